@@ -1,0 +1,189 @@
+/*
+ * codenet.h -- C ABI of the MI355X (gfx950) CodeNet coded layer step.
+ *
+ * CodeNet (arXiv 1903.01042) splits a layer's weight matrix W (N_out x N_in)
+ * into an m x n grid of blocks, encodes it once with two systematic real MDS
+ * codes into a grid of (m + r_rows) x (n + r_cols) blocks, and then runs every
+ * training step on the coded matrix: coded forward product, coded backward
+ * product, a parity check on each product that detects, locates and corrects
+ * erroneous block outputs, and a coded update that keeps the code structure
+ * without re-encoding W.  The paper's error-prone nodes are blocks of one
+ * GPU's work here; soft errors are injected by codenet_inject.
+ *
+ * Conventions
+ *  - Every function returns CODENET_OK (0) or a negative CODENET_E* code and
+ *    never throws.  codenet_strerror() names a code.
+ *  - "dev" pointers are device memory (or host memory the GPU can address,
+ *    such as pinned allocations); "host" pointers are ordinary host memory and
+ *    are only read during the call.
+ *  - All GPU work is enqueued on `stream` (a hipStream_t passed as void*;
+ *    NULL = the default stream) and is asynchronous; no call synchronises
+ *    except codenet_encode (once, at set-up) and codenet_destroy.
+ *  - Activations are batch-major, row-major, float32: X is [b][N_in],
+ *    Delta is [b][N_out], decoded S is [b][N_out], decoded C is [b][N_in],
+ *    densely packed.  W is [N_out][N_in] row-major float32.
+ *  - Block geometry.  A dimension of N entries split in `parts` equal parts
+ *    uses blocks of ceil(N / parts) entries, zero padded at the end of the
+ *    dimension; the library stores each block with a pitch B rounded up to a
+ *    multiple of 4.  Coded outputs use that geometry: the forward coded output
+ *    is [b][(m + r_rows) * B_r] with block i in columns [i*B_r, (i+1)*B_r)
+ *    (real entries first, then zeros); the backward one is
+ *    [b][(n + r_cols) * B_c].  codenet_layer_geometry() reports B_r, B_c.
+ *  - Ownership.  The caller owns W, X, Delta, the coded / decoded output
+ *    buffers and the report.  The layer owns the coded weights, the cached
+ *    coded inputs [x; x~] (from codenet_forward) and [delta; delta~] (from
+ *    codenet_backward) that codenet_update consumes, and all scratch memory,
+ *    all allocated by codenet_encode and released by codenet_destroy.
+ *  - Calls on one layer must not overlap in time (they share scratch memory).
+ */
+#ifndef CODENET_H
+#define CODENET_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CODENET_MAX_T 4          /* largest number of correctable blocks per product */
+#define CODENET_MAX_R 8          /* largest number of parity blocks per dimension    */
+#define CODENET_MAX_L 40         /* largest codeword length m + r (n + r)            */
+#define CODENET_MAX_FAULTS 64    /* faults per codenet_inject call                   */
+
+typedef struct codenet_layer codenet_layer;   /* opaque */
+
+typedef enum { CODENET_F32 = 0, CODENET_BF16_F32ACC = 1 } codenet_dtype;
+typedef enum { CODENET_FWD = 0, CODENET_BWD = 1, CODENET_WEIGHT = 2 } codenet_phase;
+typedef enum { CODENET_CLEAN = 0, CODENET_CORRECTED = 1, CODENET_UNCORRECTABLE = 2 } codenet_verdict;
+typedef enum { CODENET_NOISE_DENSE_REL = 0, CODENET_NOISE_SPARSE_ABS = 1 } codenet_noise_mode;
+
+enum {
+  CODENET_OK = 0,
+  CODENET_E_NULL = -1,      /* a required pointer is NULL                          */
+  CODENET_E_SHAPE = -2,     /* non-positive or inconsistent sizes                  */
+  CODENET_E_BATCH = -3,     /* b < 1 or b > max_batch                              */
+  CODENET_E_ORDER = -4,     /* update without a forward and a backward before it   */
+  CODENET_E_CODE = -5,      /* generator not MDS, or r / m + r beyond the limits   */
+  CODENET_E_FAULT = -6,     /* fault names a node that is not active in its phase  */
+  CODENET_E_HIP = -7,       /* a HIP runtime call failed                           */
+  CODENET_E_DTYPE = -8,     /* unknown dtype / phase / mode                        */
+  CODENET_E_ALLOC = -9      /* out of device memory                                */
+};
+
+/* Layer description (all host memory, read only during codenet_encode). */
+typedef struct {
+  int n_out, n_in;          /* logical shape of W                                              */
+  int m, n;                 /* base node grid (Section "Some Notations")                      */
+  int r_rows, r_cols;       /* parity block-rows / block-columns; the paper uses 2t of each to
+                               correct t errors per product (Theorem 1); 0 = uncoded          */
+  const double *P_r;        /* m x r_rows, row-major: parity part of G_r = [I | P_r]          */
+  const double *P_c;        /* n x r_cols, row-major: parity part of G_c = [I | P_c]          */
+  int dtype;                /* codenet_dtype: arithmetic of the three products                */
+  int max_batch;            /* largest b any later call will use                              */
+  double tau_detect;        /* a product is clean iff every relative syndrome norm is <= this */
+  double tau_resid;         /* a located support is accepted iff its relative residual <= this */
+} codenet_desc;
+
+/* Result of one check, written by the GPU to caller memory (device or pinned host). */
+typedef struct {
+  int verdict;                      /* codenet_verdict                                          */
+  int n_located;                    /* 0 .. t                                                   */
+  int located[CODENET_MAX_T];       /* ascending coded block index along the codeword
+                                       (block-row for FWD, block-column for BWD); unused = -1   */
+  float syn_rel[CODENET_MAX_R];     /* ||syndrome_k||_F / ref_k, ref_k^2 = sum_i H[k,i]^2 ||out_i||_F^2 */
+  float resid_rel;                  /* relative least-squares residual of the best support tried */
+} codenet_report;
+
+/* One soft error (Error Model 2: additive continuous noise on a node's output). */
+typedef struct {
+  int phase;                /* codenet_phase: product whose output is hit, or WEIGHT (update stage) */
+  int bi, bj;               /* node (block-row, block-column) in the coded grid                  */
+  int mode;                 /* codenet_noise_mode                                                 */
+  uint64_t seed, step;      /* noise is a pure function of (seed, step, phase, bi, bj, element)   */
+  float lo, hi;             /* magnitude range                                                    */
+  float density;            /* SPARSE_ABS only: fraction of elements hit                          */
+  int reserved;
+} codenet_fault;
+
+/*
+ * Pre-processing (Claim 1; appendix on the coding technique): build
+ * W~ = (G_r^T (x) I) W (G_c (x) I), parity x parity corner included, in float32
+ * (float64 accumulation), and allocate everything later calls need.
+ * W_dev: [n_out][n_in] float32, device.  *out receives the layer.
+ * Checks that both generators are MDS (every square minor of P non-singular).
+ * Synchronises the stream before returning.
+ */
+int codenet_encode(const codenet_desc *desc, const float *W_dev, void *stream, codenet_layer **out);
+
+/* Block pitches and coded sizes: coded_rows = (m + r_rows) * B_r, coded_cols = (n + r_cols) * B_c.
+ * Any output pointer may be NULL. */
+int codenet_layer_geometry(const codenet_layer *layer, int *B_r, int *B_c, int *coded_rows, int *coded_cols);
+
+/*
+ * Feedforward stage, steps 2-4: additional encoding x~ = (G_c^T (x) I) x (cached
+ * for the update) and the coded product s~ = W~[:, base columns] x over the
+ * active nodes (all block-rows, base block-columns), partial results summed
+ * along each grid row.  X_dev: [b][n_in].  S_coded_dev: [b][coded_rows], written.
+ */
+int codenet_forward(codenet_layer *layer, const float *X_dev, int b, float *S_coded_dev, void *stream);
+
+/*
+ * Backpropagation stage, steps 2-4: delta~ = (G_r^T (x) I) delta (cached) and
+ * c~^T = delta^T W~[base rows, :] over the active nodes (base block-rows, all
+ * block-columns), summed along each grid column.  D_dev: [b][n_out].
+ * C_coded_dev: [b][coded_cols], written.
+ */
+int codenet_backward(codenet_layer *layer, const float *D_dev, int b, float *C_coded_dev, void *stream);
+
+/*
+ * Soft-error injection (Error Models 1 / 2; the experiment's sparse law is
+ * mode SPARSE_ABS).  All faults of one call must have the same phase.
+ * FWD: node (bi, bj), bi < m + r_rows, bj < n, adds noise to block-row bi of
+ * coded_out_dev ([b][coded_rows]); BWD: node (bi < m, bj < n + r_cols) adds noise to
+ * block-column bj of coded_out_dev ([b][coded_cols]); WEIGHT: the stored block
+ * W~_{bi,bj} (not in the corner) is corrupted, coded_out_dev is ignored.
+ * DENSE_REL: every real element gets sign * U[lo, hi) * rms(clean target block);
+ * SPARSE_ABS: a fraction `density` of the elements gets U[lo, hi).
+ * faults_host: n_faults <= CODENET_MAX_FAULTS entries, host memory.
+ */
+int codenet_inject(codenet_layer *layer, const codenet_fault *faults_host, int n_faults,
+                   float *coded_out_dev, int b, void *stream);
+
+/*
+ * Error detection and decoding (General Error-Detection Method; Lemma 2 and
+ * the decoding algorithm of the appendix): syndromes (H (x) I) out with
+ * H = [P^T | -I]; clean iff all relative syndrome norms <= tau_detect;
+ * otherwise the support of at most t = floor(r/2) blocks with the smallest
+ * least-squares residual is searched by increasing cardinality and accepted
+ * if its relative residual <= tau_resid; accepted blocks are corrected in
+ * place in coded_out_dev.  More errors than t: verdict UNCORRECTABLE,
+ * coded_out_dev untouched (the caller rolls back; not an API error).
+ * phase: CODENET_FWD or CODENET_BWD.  decoded_dev: [b][n_out] (FWD) or
+ * [b][n_in] (BWD), receives the systematic part without padding; may be NULL.
+ * report_dev: written by the GPU; may be NULL.
+ */
+int codenet_detect_decode(codenet_layer *layer, int phase, float *coded_out_dev, int b,
+                          float *decoded_dev, codenet_report *report_dev, void *stream);
+
+/*
+ * Update stage (the three block rules, plus the same rule on the corner):
+ * W~ += eta * [delta; delta~] [x; x~]^T summed over the batch, using the vectors
+ * cached by the last forward and backward calls (which must have used the same b).
+ */
+int codenet_update(codenet_layer *layer, float eta, void *stream);
+
+/* Copy out the coded matrix, [coded_rows][coded_cols] float32 (drift checks, tests). */
+int codenet_export_coded(codenet_layer *layer, float *Wc_dev, void *stream);
+
+/* Copy out the systematic part without padding, [n_out][n_in] float32. */
+int codenet_export_weights(codenet_layer *layer, float *W_dev, void *stream);
+
+/* Waits for the device, frees everything the layer owns. */
+int codenet_destroy(codenet_layer *layer);
+
+const char *codenet_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CODENET_H */

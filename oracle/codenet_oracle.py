@@ -40,11 +40,17 @@ MODE_DENSE_REL, MODE_SPARSE_ABS = 0, 1
 # Code construction (Section "Some Notations": systematic (b, a) MDS generator;
 # Appendix "Error Detection and Correction Mechanism": annihilating matrix H)
 # --------------------------------------------------------------------------
-def generator(P):
-    """G = [I | P], the a x (a + r) generator of a systematic code."""
+def _parity_part(P):
+    """P as an a x r float64 matrix (r may be 0: no parity blocks)."""
     P = np.asarray(P, dtype=np.float64)
     a = P.shape[0]
-    return np.hstack([np.eye(a), P.reshape(a, -1)])
+    return P.reshape(a, -1) if P.size else np.zeros((a, 0))
+
+
+def generator(P):
+    """G = [I | P], the a x (a + r) generator of a systematic code."""
+    P = _parity_part(P)
+    return np.hstack([np.eye(P.shape[0]), P])
 
 
 def parity_check(P):
@@ -54,11 +60,8 @@ def parity_check(P):
     syndrome is "parity recomputed from the systematic blocks minus the parity
     that was actually produced".
     """
-    P = np.asarray(P, dtype=np.float64)
-    a = P.shape[0]
-    P = P.reshape(a, -1)
-    r = P.shape[1]
-    return np.hstack([P.T, -np.eye(r)])
+    P = _parity_part(P)
+    return np.hstack([P.T, -np.eye(P.shape[1])])
 
 
 def is_mds(P, tol=1e-9):
@@ -388,8 +391,8 @@ class CodedLayer:
                  tau_resid=1e-2, store_corner=True):
         W = np.asarray(W, dtype=np.float64)
         self.N_out, self.N_in = W.shape
-        self.P_r = np.asarray(P_r, dtype=np.float64).reshape(np.shape(P_r)[0], -1)
-        self.P_c = np.asarray(P_c, dtype=np.float64).reshape(np.shape(P_c)[0], -1)
+        self.P_r = _parity_part(P_r)
+        self.P_c = _parity_part(P_c)
         self.m, self.r_r = self.P_r.shape
         self.n, self.r_c = self.P_c.shape
         self.Br = block_size(self.N_out, self.m) if Br is None else Br

@@ -1,0 +1,361 @@
+// C ABI of libcodenet: argument checking, the layer object, and the order in
+// which the kernels of each call are enqueued.
+#include <cmath>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "codenet_internal.h"
+
+using namespace codenet;
+
+struct codenet_layer {
+  codenet_desc desc;            // P_r / P_c pointers are cleared after encode
+  DevCode code_r, code_c;       // host copies: rows (forward check), columns (backward check)
+  DevCode *code_r_dev = nullptr, *code_c_dev = nullptr;
+  int Mr = 0, Nc = 0;           // coded sizes
+  float *Wt = nullptr;          // [Mr][Nc]
+  float *Xt = nullptr;          // [max_batch][Nc]   cached [x; x~]
+  float *Dt = nullptr;          // [max_batch][Mr]   cached [delta; delta~]
+  float *syn = nullptr;         // [max r][max_batch][max B]
+  double *partials = nullptr;   // [kDetectParts][kMaxEntries]
+  double *fault_partials = nullptr;   // [CODENET_MAX_FAULTS][kFaultParts]
+  DevPlan *plan = nullptr;
+  int fwd_b = 0, bwd_b = 0;     // batch of the cached vectors (0 = none)
+  bool bf16 = false;
+};
+
+namespace {
+
+int map_hip(hipError_t e, const char *what) {
+  std::fprintf(stderr, "libcodenet: %s: %s\n", what, hipGetErrorString(e));
+  (void)hipGetLastError();
+  return e == hipErrorOutOfMemory ? CODENET_E_ALLOC : CODENET_E_HIP;
+}
+
+#define CN_HIP(expr)                                   \
+  do {                                                 \
+    hipError_t _e = (expr);                            \
+    if (_e != hipSuccess) return map_hip(_e, #expr);   \
+  } while (0)
+
+int round_up4(int v) { return (v + 3) & ~3; }
+
+double det_small(std::vector<double> a, int k) {   // Gaussian elimination with partial pivoting
+  double det = 1.0;
+  for (int c = 0; c < k; ++c) {
+    int piv = c;
+    for (int r = c + 1; r < k; ++r)
+      if (std::fabs(a[r * k + c]) > std::fabs(a[piv * k + c])) piv = r;
+    if (a[piv * k + c] == 0.0) return 0.0;
+    if (piv != c) {
+      for (int q = 0; q < k; ++q) std::swap(a[piv * k + q], a[c * k + q]);
+      det = -det;
+    }
+    det *= a[c * k + c];
+    for (int r = c + 1; r < k; ++r) {
+      const double f = a[r * k + c] / a[c * k + c];
+      for (int q = c; q < k; ++q) a[r * k + q] -= f * a[c * k + q];
+    }
+  }
+  return det;
+}
+
+// next k-subset of {0..n-1} in lexicographic order; false when exhausted
+bool next_subset(std::vector<int> &s, int n) {
+  const int k = (int)s.size();
+  int p = k - 1;
+  while (p >= 0 && s[p] == n - k + p) --p;
+  if (p < 0) return false;
+  ++s[p];
+  for (int q = p + 1; q < k; ++q) s[q] = s[q - 1] + 1;
+  return true;
+}
+
+// G = [I | P] is MDS iff every square minor of P is non-zero.  Orders are
+// checked smallest first until a budget of minors is spent (tiny codes are
+// checked completely).
+bool generator_is_mds(const double *P, int a, int r) {
+  const double tol = 1e-9;
+  long budget = 4000000;
+  for (int k = 1; k <= std::min(a, r); ++k) {
+    std::vector<int> rows(k), cols(k);
+    for (int q = 0; q < k; ++q) rows[q] = q;
+    do {
+      for (int q = 0; q < k; ++q) cols[q] = q;
+      do {
+        std::vector<double> sub(k * k);
+        for (int x = 0; x < k; ++x)
+          for (int y = 0; y < k; ++y) sub[x * k + y] = P[rows[x] * r + cols[y]];
+        if (!(std::fabs(det_small(sub, k)) > tol)) return false;
+        if (--budget <= 0) return true;
+      } while (next_subset(cols, r));
+    } while (next_subset(rows, a));
+  }
+  return true;
+}
+
+void fill_code(DevCode &c, int a, int r, int N, const double *P, double tau_detect, double tau_resid) {
+  std::memset(&c, 0, sizeof(c));
+  c.a = a; c.r = r; c.L = a + r; c.N = N;
+  c.B0 = (N + a - 1) / a;
+  c.B = round_up4(c.B0);
+  c.tau_detect = tau_detect; c.tau_resid = tau_resid;
+  for (int k = 0; k < r; ++k) {
+    for (int i = 0; i < a; ++i) c.H[k][i] = P[i * r + k];
+    c.H[k][a + k] = -1.0;
+    for (int i = 0; i < a + r; ++i) c.Hf[k][i] = (float)c.H[k][i];
+  }
+}
+
+int real_entries(const DevCode &c, int block) {
+  if (block >= c.a) return c.B0;
+  const int left = c.N - block * c.B0;
+  return left < 0 ? 0 : (left < c.B0 ? left : c.B0);
+}
+
+void free_layer(codenet_layer *l) {
+  if (!l) return;
+  (void)hipFree(l->Wt); (void)hipFree(l->Xt); (void)hipFree(l->Dt); (void)hipFree(l->syn);
+  (void)hipFree(l->partials); (void)hipFree(l->fault_partials); (void)hipFree(l->plan);
+  (void)hipFree(l->code_r_dev); (void)hipFree(l->code_c_dev);
+  delete l;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *codenet_strerror(int code) {
+  switch (code) {
+    case CODENET_OK: return "ok";
+    case CODENET_E_NULL: return "null pointer";
+    case CODENET_E_SHAPE: return "bad shape";
+    case CODENET_E_BATCH: return "batch out of range";
+    case CODENET_E_ORDER: return "update needs a forward and a backward call with the same batch first";
+    case CODENET_E_CODE: return "generator is not MDS or the code is too long";
+    case CODENET_E_FAULT: return "fault names an inactive node";
+    case CODENET_E_HIP: return "HIP runtime error";
+    case CODENET_E_DTYPE: return "unknown dtype, phase or mode";
+    case CODENET_E_ALLOC: return "out of device memory";
+    default: return "unknown error";
+  }
+}
+
+int codenet_encode(const codenet_desc *d, const float *W_dev, void *stream, codenet_layer **out) {
+  if (!d || !W_dev || !out) return CODENET_E_NULL;
+  *out = nullptr;
+  if (d->n_out < 1 || d->n_in < 1 || d->m < 1 || d->n < 1 || d->r_rows < 0 || d->r_cols < 0 ||
+      d->m > d->n_out || d->n > d->n_in)
+    return CODENET_E_SHAPE;
+  if (d->max_batch < 1) return CODENET_E_BATCH;
+  if (d->dtype != CODENET_F32 && d->dtype != CODENET_BF16_F32ACC) return CODENET_E_DTYPE;
+  if (d->r_rows > CODENET_MAX_R || d->r_cols > CODENET_MAX_R || d->m + d->r_rows > CODENET_MAX_L ||
+      d->n + d->r_cols > CODENET_MAX_L)
+    return CODENET_E_CODE;
+  if ((d->r_rows > 0 && !d->P_r) || (d->r_cols > 0 && !d->P_c)) return CODENET_E_NULL;
+  if (!(d->tau_detect >= 0.0) || !(d->tau_resid >= 0.0)) return CODENET_E_SHAPE;
+  if (d->r_rows > 0 && !generator_is_mds(d->P_r, d->m, d->r_rows)) return CODENET_E_CODE;
+  if (d->r_cols > 0 && !generator_is_mds(d->P_c, d->n, d->r_cols)) return CODENET_E_CODE;
+
+  codenet_layer *l = new (std::nothrow) codenet_layer();
+  if (!l) return CODENET_E_ALLOC;
+  l->desc = *d;
+  l->desc.P_r = l->desc.P_c = nullptr;
+  l->bf16 = d->dtype == CODENET_BF16_F32ACC;
+  fill_code(l->code_r, d->m, d->r_rows, d->n_out, d->P_r, d->tau_detect, d->tau_resid);
+  fill_code(l->code_c, d->n, d->r_cols, d->n_in, d->P_c, d->tau_detect, d->tau_resid);
+  l->Mr = l->code_r.L * l->code_r.B;
+  l->Nc = l->code_c.L * l->code_c.B;
+  hipStream_t s = (hipStream_t)stream;
+  const size_t mb = (size_t)d->max_batch;
+  const int rmax = std::max(std::max(d->r_rows, d->r_cols), 1);
+  const int bmax = std::max(l->code_r.B, l->code_c.B);
+  hipError_t e = hipSuccess;
+  const char *what = "hipMalloc";
+  auto alloc = [&](void **p, size_t bytes) { if (e == hipSuccess) e = hipMalloc(p, bytes ? bytes : 16); };
+  alloc((void **)&l->Wt, sizeof(float) * (size_t)l->Mr * l->Nc);
+  alloc((void **)&l->Xt, sizeof(float) * mb * l->Nc);
+  alloc((void **)&l->Dt, sizeof(float) * mb * l->Mr);
+  alloc((void **)&l->syn, sizeof(float) * (size_t)rmax * mb * bmax);
+  alloc((void **)&l->partials, sizeof(double) * (size_t)kDetectParts * kMaxEntries);
+  alloc((void **)&l->fault_partials, sizeof(double) * (size_t)CODENET_MAX_FAULTS * kFaultParts);
+  alloc((void **)&l->plan, sizeof(DevPlan));
+  alloc((void **)&l->code_r_dev, sizeof(DevCode));
+  alloc((void **)&l->code_c_dev, sizeof(DevCode));
+  if (e == hipSuccess) {
+    what = "copy of the code tables";
+    e = hipMemcpyAsync(l->code_r_dev, &l->code_r, sizeof(DevCode), hipMemcpyHostToDevice, s);
+  }
+  if (e == hipSuccess) e = hipMemcpyAsync(l->code_c_dev, &l->code_c, sizeof(DevCode), hipMemcpyHostToDevice, s);
+  if (e == hipSuccess) {
+    what = "encode kernel launch";
+    e = launch_encode_matrix(W_dev, l->Wt, l->code_r_dev, l->code_c_dev, l->Mr, l->Nc, d->n_out, d->n_in, s);
+  }
+  // the host copies of the code tables must outlive the asynchronous copies above
+  if (e == hipSuccess) {
+    what = "encode stream synchronize";
+    e = hipStreamSynchronize(s);
+  }
+  if (e != hipSuccess) {
+    const int rc = map_hip(e, what);
+    free_layer(l);
+    return rc;
+  }
+  *out = l;
+  return CODENET_OK;
+}
+
+int codenet_layer_geometry(const codenet_layer *l, int *B_r, int *B_c, int *coded_rows, int *coded_cols) {
+  if (!l) return CODENET_E_NULL;
+  if (B_r) *B_r = l->code_r.B;
+  if (B_c) *B_c = l->code_c.B;
+  if (coded_rows) *coded_rows = l->Mr;
+  if (coded_cols) *coded_cols = l->Nc;
+  return CODENET_OK;
+}
+
+int codenet_forward(codenet_layer *l, const float *X_dev, int b, float *S_coded_dev, void *stream) {
+  if (!l || !X_dev || !S_coded_dev) return CODENET_E_NULL;
+  if (b < 1 || b > l->desc.max_batch) return CODENET_E_BATCH;
+  hipStream_t s = (hipStream_t)stream;
+  l->fwd_b = 0;
+  CN_HIP(launch_encode_vector(X_dev, l->Xt, l->code_c_dev, l->code_c, b, s));
+  GemmArgs g{};
+  g.A = l->Wt; g.lda = l->Nc;                 // A[i][k] = W~[i][k], k over the base columns
+  g.B = l->Xt; g.ldb = l->Nc;                 // B[j][k] = x[j][k]
+  g.C = S_coded_dev; g.ldc = l->Mr;
+  g.I = l->Mr; g.J = b; g.K = l->code_c.a * l->code_c.B;
+  g.alpha = 1.f;
+  CN_HIP(launch_gemm(kFwd, l->bf16, g, s));
+  l->fwd_b = b;
+  return CODENET_OK;
+}
+
+int codenet_backward(codenet_layer *l, const float *D_dev, int b, float *C_coded_dev, void *stream) {
+  if (!l || !D_dev || !C_coded_dev) return CODENET_E_NULL;
+  if (b < 1 || b > l->desc.max_batch) return CODENET_E_BATCH;
+  hipStream_t s = (hipStream_t)stream;
+  l->bwd_b = 0;
+  CN_HIP(launch_encode_vector(D_dev, l->Dt, l->code_r_dev, l->code_r, b, s));
+  GemmArgs g{};
+  g.A = l->Wt; g.lda = l->Nc;                 // A[i][k] = W~[k][i], k over the base rows
+  g.B = l->Dt; g.ldb = l->Mr;                 // B[j][k] = delta[j][k]
+  g.C = C_coded_dev; g.ldc = l->Nc;
+  g.I = l->Nc; g.J = b; g.K = l->code_r.a * l->code_r.B;
+  g.alpha = 1.f;
+  CN_HIP(launch_gemm(kBwd, l->bf16, g, s));
+  l->bwd_b = b;
+  return CODENET_OK;
+}
+
+int codenet_update(codenet_layer *l, float eta, void *stream) {
+  if (!l) return CODENET_E_NULL;
+  if (l->fwd_b < 1 || l->fwd_b != l->bwd_b) return CODENET_E_ORDER;
+  hipStream_t s = (hipStream_t)stream;
+  GemmArgs g{};
+  g.A = l->Xt; g.lda = l->Nc;                 // A[i][k] = x~[k][i]     (i = coded column, k = batch)
+  g.B = l->Dt; g.ldb = l->Mr;                 // B[j][k] = delta~[k][j] (j = coded row)
+  g.C = l->Wt; g.ldc = l->Nc;
+  g.I = l->Nc; g.J = l->Mr; g.K = l->fwd_b;
+  g.alpha = eta;
+  CN_HIP(launch_gemm(kUpd, l->bf16, g, s));
+  l->fwd_b = l->bwd_b = 0;
+  return CODENET_OK;
+}
+
+int codenet_detect_decode(codenet_layer *l, int phase, float *coded_out_dev, int b, float *decoded_dev,
+                          codenet_report *report_dev, void *stream) {
+  if (!l || !coded_out_dev) return CODENET_E_NULL;
+  if (phase != CODENET_FWD && phase != CODENET_BWD) return CODENET_E_DTYPE;
+  if (b < 1 || b > l->desc.max_batch) return CODENET_E_BATCH;
+  hipStream_t s = (hipStream_t)stream;
+  const DevCode &ch = phase == CODENET_FWD ? l->code_r : l->code_c;
+  const DevCode *cd = phase == CODENET_FWD ? l->code_r_dev : l->code_c_dev;
+  int n_parts = 0;
+  if (ch.r > 0) {
+    CN_HIP(launch_detect(coded_out_dev, l->syn, l->partials, &n_parts, cd, ch, b, s));
+  }
+  // with r = 0 there is nothing to check: zero records make the decision CLEAN
+  CN_HIP(launch_decide(l->partials, n_parts, cd, ch, l->plan, report_dev, s));
+  CN_HIP(launch_correct(coded_out_dev, l->syn, l->plan, cd, ch, b, decoded_dev, s));
+  return CODENET_OK;
+}
+
+int codenet_inject(codenet_layer *l, const codenet_fault *faults, int n_faults, float *coded_out_dev, int b,
+                   void *stream) {
+  if (!l) return CODENET_E_NULL;
+  if (n_faults == 0) return CODENET_OK;
+  if (!faults) return CODENET_E_NULL;
+  if (n_faults < 0 || n_faults > CODENET_MAX_FAULTS) return CODENET_E_SHAPE;
+  const int phase = faults[0].phase;
+  if (phase != CODENET_FWD && phase != CODENET_BWD && phase != CODENET_WEIGHT) return CODENET_E_DTYPE;
+  if (phase != CODENET_WEIGHT) {
+    if (!coded_out_dev) return CODENET_E_NULL;
+    if (b < 1 || b > l->desc.max_batch) return CODENET_E_BATCH;
+  }
+  const DevCode &cr = l->code_r, &cc = l->code_c;
+  std::vector<FaultArgs> fa((size_t)n_faults);
+  for (int f = 0; f < n_faults; ++f) {
+    const codenet_fault &ft = faults[f];
+    if (ft.phase != phase) return CODENET_E_FAULT;
+    if (ft.mode != CODENET_NOISE_DENSE_REL && ft.mode != CODENET_NOISE_SPARSE_ABS) return CODENET_E_DTYPE;
+    if (ft.bi < 0 || ft.bj < 0) return CODENET_E_FAULT;
+    bool active;
+    if (phase == CODENET_FWD) active = ft.bi < cr.L && ft.bj < cc.a;
+    else if (phase == CODENET_BWD) active = ft.bi < cr.a && ft.bj < cc.L;
+    else active = ft.bi < cr.L && ft.bj < cc.L && (ft.bi < cr.a || ft.bj < cc.a);
+    if (!active) return CODENET_E_FAULT;
+    FaultArgs &a = fa[f];
+    a.key = fault_key(ft.seed, ft.step, ft.phase, ft.bi, ft.bj);
+    a.lo = ft.lo; a.hi = ft.hi; a.mode = ft.mode;
+    double hb = std::floor((double)ft.density * 4294967296.0);
+    a.hit_below = hb <= 0.0 ? 0u : (hb >= 4294967295.0 ? 4294967295u : (unsigned int)hb);
+    a.partials = l->fault_partials + (size_t)f * kFaultParts;
+    if (phase == CODENET_FWD) {
+      a.base = coded_out_dev + (size_t)ft.bi * cr.B;
+      a.stride_outer = l->Mr; a.n_outer = b; a.n_inner = real_entries(cr, ft.bi);
+      a.idx_outer = 1; a.idx_inner = (unsigned long long)b;
+    } else if (phase == CODENET_BWD) {
+      a.base = coded_out_dev + (size_t)ft.bj * cc.B;
+      a.stride_outer = l->Nc; a.n_outer = b; a.n_inner = real_entries(cc, ft.bj);
+      a.idx_outer = 1; a.idx_inner = (unsigned long long)b;
+    } else {
+      a.base = l->Wt + (size_t)ft.bi * cr.B * l->Nc + (size_t)ft.bj * cc.B;
+      a.stride_outer = l->Nc; a.n_outer = real_entries(cr, ft.bi); a.n_inner = real_entries(cc, ft.bj);
+      a.idx_outer = (unsigned long long)cc.B0; a.idx_inner = 1;
+    }
+  }
+  hipStream_t s = (hipStream_t)stream;
+  // every rms is taken from the still clean data, then the noises are added one
+  // fault after the other (two faults may hit the same block)
+  for (int f = 0; f < n_faults; ++f)
+    if (fa[f].mode == CODENET_NOISE_DENSE_REL) CN_HIP(launch_fault(fa[f], s, true));
+  for (int f = 0; f < n_faults; ++f) CN_HIP(launch_fault(fa[f], s, false));
+  return CODENET_OK;
+}
+
+int codenet_export_coded(codenet_layer *l, float *Wc_dev, void *stream) {
+  if (!l || !Wc_dev) return CODENET_E_NULL;
+  CN_HIP(hipMemcpyAsync(Wc_dev, l->Wt, sizeof(float) * (size_t)l->Mr * l->Nc, hipMemcpyDeviceToDevice,
+                        (hipStream_t)stream));
+  return CODENET_OK;
+}
+
+int codenet_export_weights(codenet_layer *l, float *W_dev, void *stream) {
+  if (!l || !W_dev) return CODENET_E_NULL;
+  CN_HIP(launch_export_weights(l->Wt, W_dev, l->code_r, l->code_c, l->Nc, l->desc.n_out, l->desc.n_in,
+                               (hipStream_t)stream));
+  return CODENET_OK;
+}
+
+int codenet_destroy(codenet_layer *l) {
+  if (!l) return CODENET_E_NULL;
+  (void)hipDeviceSynchronize();
+  free_layer(l);
+  return CODENET_OK;
+}
+
+}  // extern "C"

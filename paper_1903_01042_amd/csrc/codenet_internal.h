@@ -1,0 +1,76 @@
+// Internal declarations shared by the HIP translation units of libcodenet.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "codenet.h"
+
+namespace codenet {
+
+constexpr int kDetectParts = 512;      // most per-workgroup partial records of one check
+constexpr int kFaultParts = 32;        // partial sums of squares per fault
+constexpr int kMaxGram = CODENET_MAX_R * (CODENET_MAX_R + 1) / 2;
+constexpr int kMaxEntries = CODENET_MAX_L + kMaxGram;
+
+// One systematic (a + r, a) code as the kernels see it (device memory).
+struct DevCode {
+  int a, r, L;                                   // L = a + r
+  int B;                                         // block pitch (multiple of 4)
+  int B0;                                        // real block size ceil(N / a)
+  int N;                                         // logical length a dimension is cut from
+  double H[CODENET_MAX_R][CODENET_MAX_L];        // parity check [P^T | -I]
+  float Hf[CODENET_MAX_R][CODENET_MAX_L];        // the same, float32
+  double tau_detect, tau_resid;
+};
+
+// What the decision kernel leaves for the correction kernel.
+struct DevPlan {
+  int verdict;
+  int n_located;
+  int located[CODENET_MAX_T];
+  float coef[CODENET_MAX_T][CODENET_MAX_R];      // error block a = sum_k coef[a][k] * syndrome_k
+};
+
+struct GemmArgs {
+  const float *A; long lda;     // operand A, logical A[i][k]
+  const float *B; long ldb;     // operand B, logical B[j][k]
+  float *C; long ldc;           // C[j][i], i contiguous
+  int I, J, K;
+  float alpha;                  // accumulate variant: C += alpha * A B^T
+  int tiles_i, tiles_j;
+};
+
+enum GemmLayout { kFwd = 0, kBwd = 1, kUpd = 2 };
+// fwd: A k-contiguous, B k-contiguous, C = A B^T
+// bwd: A k-strided   , B k-contiguous, C = A B^T
+// upd: A k-strided   , B k-strided   , C += alpha A B^T
+hipError_t launch_gemm(GemmLayout layout, bool bf16, const GemmArgs &args, hipStream_t stream);
+
+struct FaultArgs {
+  float *base;                  // first element of the target payload
+  long stride_outer;            // element (outer, inner) at base[outer * stride_outer + inner]
+  int n_outer, n_inner;
+  unsigned long long idx_outer, idx_inner;   // element index = outer * idx_outer + inner * idx_inner
+  unsigned long long key;       // hash key of (seed, step, phase, bi, bj)
+  float lo, hi;
+  unsigned int hit_below;       // SPARSE_ABS: hit iff low 32 hash bits < hit_below
+  int mode;
+  double *partials;             // kFaultParts partial sums of squares of this fault
+};
+
+hipError_t launch_encode_matrix(const float *W, float *Wt, const DevCode *code_r, const DevCode *code_c,
+                                int Mr, int Nc, int n_out, int n_in, hipStream_t s);
+hipError_t launch_encode_vector(const float *V, float *Vt, const DevCode *code_dev, const DevCode &code_host,
+                                int b, hipStream_t s);
+hipError_t launch_detect(const float *out, float *syn, double *partials, int *n_parts,
+                         const DevCode *code_dev, const DevCode &code_host, int b, hipStream_t s);
+hipError_t launch_decide(const double *partials, int n_parts, const DevCode *code_dev, const DevCode &code_host,
+                         DevPlan *plan, codenet_report *report, hipStream_t s);
+hipError_t launch_correct(float *out, const float *syn, const DevPlan *plan, const DevCode *code_dev,
+                          const DevCode &code_host, int b, float *decoded, hipStream_t s);
+hipError_t launch_fault(const FaultArgs &fa, hipStream_t s, bool stats_pass);
+hipError_t launch_export_weights(const float *Wt, float *W, const DevCode &cr, const DevCode &cc,
+                                 int Nc, int n_out, int n_in, hipStream_t s);
+
+unsigned long long fault_key(unsigned long long seed, unsigned long long step, int phase, int bi, int bj);
+
+}  // namespace codenet

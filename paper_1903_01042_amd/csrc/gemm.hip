@@ -1,0 +1,310 @@
+// MFMA GEMM kernels of the coded products (O1, O2) and of the coded rank-b update (O3).
+//
+// One kernel template serves the three contractions of a layer step.  With
+// "A[i][k]" the operand whose index i is contiguous in the result and "B[j][k]"
+// the other one, the result is C[j][i] = sum_k A[i][k] B[j][k]:
+//   forward  : i = coded row of W~,    j = batch, k = base column;  A = W~ (k contiguous),
+//              B = [x; x~] batch-major (k contiguous)
+//   backward : i = coded column of W~, j = batch, k = base row;     A = W~ (k strided),
+//              B = [delta; delta~] batch-major (k contiguous)
+//   update   : i = coded column, j = coded row, k = batch;          A = [x; x~], B = [delta; delta~]
+//              (both k strided), C = W~ accumulated in place.
+// All operands are float32 in memory.  In the bf16 variant they are rounded to
+// bf16 (round to nearest even) on their way into LDS and multiplied with
+// v_mfma_f32_32x32x16_bf16; the f32 variant uses v_mfma_f32_32x32x2_f32.
+// Accumulation is float32 in both.
+//
+// Tiling: 256 threads = 4 wavefronts in a 2 x 2 arrangement, each owning
+// FM x FN MFMA tiles of 32 x 32, so a workgroup computes (64 FM) x (64 FN).
+// A k-slab is 8 chunks of 16 bytes per operand row (64 bf16 or 32 f32); LDS
+// rows are 128 bytes, chunk c of row r sits at slot c ^ swz(r), which keeps
+// both the 16-byte fragment reads (32 consecutive rows, one chunk) and the
+// transposing writes (rows 4 apart, one chunk) free of bank conflicts.
+// Global loads are staged in registers one slab ahead (double-buffered LDS,
+// one barrier per slab).  Operands stored k-strided are transposed in
+// registers between the global load and the LDS write, so no transposed copy
+// of W~ exists anywhere.
+#include "codenet_internal.h"
+
+namespace codenet {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+__device__ __forceinline__ int swz(int row) { return ((row & 7) + (row >> 3)) & 7; }
+
+__device__ __forceinline__ float f4get(const float4 &v, int e) {
+  return e == 0 ? v.x : e == 1 ? v.y : e == 2 ? v.z : v.w;
+}
+
+__device__ __forceinline__ uint4 pack_bf16x8(float a0, float a1, float a2, float a3,
+                                             float a4, float a5, float a6, float a7) {
+  bf16x8 t;
+  t[0] = (__bf16)a0; t[1] = (__bf16)a1; t[2] = (__bf16)a2; t[3] = (__bf16)a3;
+  t[4] = (__bf16)a4; t[5] = (__bf16)a5; t[6] = (__bf16)a6; t[7] = (__bf16)a7;
+  return __builtin_bit_cast(uint4, t);
+}
+
+__device__ __forceinline__ uint4 pack_f32x4(float a0, float a1, float a2, float a3) {
+  float4 t = make_float4(a0, a1, a2, a3);
+  return __builtin_bit_cast(uint4, t);
+}
+
+// Stages one operand slab (T rows x 8 chunks) from global memory to LDS.
+template <bool BF16, int T, bool KC>
+struct Loader {
+  static constexpr int EPC = BF16 ? 8 : 4;                 // elements per 16-byte chunk
+  static constexpr int NTASK = KC ? T * 8 : (T / 4) * 8;   // KC: (row, chunk); else (4 rows, chunk)
+  static constexpr int PER = (NTASK + 255) / 256;
+  static constexpr int NF4 = KC ? EPC / 4 : EPC;           // float4 loads per task
+  float4 st[PER][NF4];
+
+  __device__ __forceinline__ void load(const float *__restrict__ src, long ld, int row0, int rows,
+                                       int k0, int K, int tid) {
+#pragma unroll
+    for (int p = 0; p < PER; ++p) {
+      const int q = tid + p * 256;
+      const bool live = (NTASK % 256 == 0) || q < NTASK;
+      if (KC) {
+        const int row = q >> 3, c = q & 7;
+        const int gr = row0 + row, gk = k0 + c * EPC;
+        const bool okr = live && gr < rows;
+        const float *ptr = src + (long)gr * ld + gk;
+#pragma unroll
+        for (int f = 0; f < NF4; ++f)
+          st[p][f] = (okr && gk + 4 * f < K) ? *reinterpret_cast<const float4 *>(ptr + 4 * f)
+                                             : make_float4(0.f, 0.f, 0.f, 0.f);
+      } else {
+        const int ig = q % (T / 4), kg = q / (T / 4);
+        const int gr = row0 + ig * 4;
+        const bool okr = live && gr < rows;
+#pragma unroll
+        for (int f = 0; f < NF4; ++f) {
+          const int gk = k0 + kg * EPC + f;
+          st[p][f] = (okr && gk < K) ? *reinterpret_cast<const float4 *>(src + (long)gk * ld + gr)
+                                     : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+      }
+    }
+  }
+
+  __device__ __forceinline__ void store(uint4 *lds, int tid) const {
+#pragma unroll
+    for (int p = 0; p < PER; ++p) {
+      const int q = tid + p * 256;
+      if (!((NTASK % 256 == 0) || q < NTASK)) continue;
+      if (KC) {
+        const int row = q >> 3, c = q & 7;
+        uint4 chunk;
+        if (BF16)
+          chunk = pack_bf16x8(st[p][0].x, st[p][0].y, st[p][0].z, st[p][0].w,
+                              st[p][NF4 - 1].x, st[p][NF4 - 1].y, st[p][NF4 - 1].z, st[p][NF4 - 1].w);
+        else
+          chunk = __builtin_bit_cast(uint4, st[p][0]);
+        lds[row * 8 + (c ^ swz(row))] = chunk;
+      } else {
+        const int ig = q % (T / 4), kg = q / (T / 4);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int row = ig * 4 + e;
+          uint4 chunk;
+          if (BF16)
+            chunk = pack_bf16x8(f4get(st[p][0], e), f4get(st[p][1], e), f4get(st[p][2], e),
+                                f4get(st[p][3], e), f4get(st[p][NF4 - 4], e), f4get(st[p][NF4 - 3], e),
+                                f4get(st[p][NF4 - 2], e), f4get(st[p][NF4 - 1], e));
+          else
+            chunk = pack_f32x4(f4get(st[p][0], e), f4get(st[p][1], e), f4get(st[p][2], e),
+                               f4get(st[p][3], e));
+          lds[row * 8 + (kg ^ swz(row))] = chunk;
+        }
+      }
+    }
+  }
+};
+
+template <bool BF16, int FM, int FN, bool AKC, bool BKC, bool ACCUM>
+__global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
+  constexpr int TI = 64 * FM, TJ = 64 * FN;
+  constexpr int EPC = BF16 ? 8 : 4, KT = 8 * EPC;
+  constexpr int STAGE = (TI + TJ) * 8;                     // chunks per LDS stage
+  extern __shared__ uint4 lds[];
+
+  // Workgroup -> tile.  Consecutive workgroup ids go to different XCDs (8 of
+  // them, one L2 each); give each XCD a contiguous run of tiles so that tiles
+  // sharing an operand panel share an L2.
+  const int nt = g.tiles_i * g.tiles_j;
+  const int per = (nt + 7) >> 3;
+  const int logical = (int)(blockIdx.x & 7) * per + (int)(blockIdx.x >> 3);
+  if (logical >= nt) return;
+  const int tj = logical % g.tiles_j, ti = logical / g.tiles_j;
+  const int i0 = ti * TI, j0 = tj * TJ;
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wi = wave & 1, wj = wave >> 1;
+  const int l32 = lane & 31, h = lane >> 5;
+
+  Loader<BF16, TI, AKC> la;
+  Loader<BF16, TJ, BKC> lb;
+
+  floatx16 acc[FM][FN];
+#pragma unroll
+  for (int a = 0; a < FM; ++a)
+#pragma unroll
+    for (int b = 0; b < FN; ++b)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.f;
+
+  const int nk = (g.K + KT - 1) / KT;
+  la.load(g.A, g.lda, i0, g.I, 0, g.K, tid);
+  lb.load(g.B, g.ldb, j0, g.J, 0, g.K, tid);
+  la.store(lds, tid);
+  lb.store(lds + TI * 8, tid);
+  __syncthreads();
+
+  for (int kt = 0; kt < nk; ++kt) {
+    const int cur = kt & 1;
+    if (kt + 1 < nk) {
+      la.load(g.A, g.lda, i0, g.I, (kt + 1) * KT, g.K, tid);
+      lb.load(g.B, g.ldb, j0, g.J, (kt + 1) * KT, g.K, tid);
+    }
+    const uint4 *sa = lds + cur * STAGE;
+    const uint4 *sb = sa + TI * 8;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const int c = 2 * s + h;
+      uint4 av[FM], bv[FN];
+#pragma unroll
+      for (int a = 0; a < FM; ++a) {
+        const int row = (wi * FM + a) * 32 + l32;
+        av[a] = sa[row * 8 + (c ^ swz(row))];
+      }
+#pragma unroll
+      for (int b = 0; b < FN; ++b) {
+        const int row = (wj * FN + b) * 32 + l32;
+        bv[b] = sb[row * 8 + (c ^ swz(row))];
+      }
+#pragma unroll
+      for (int a = 0; a < FM; ++a)
+#pragma unroll
+        for (int b = 0; b < FN; ++b) {
+          if (BF16) {
+            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                __builtin_bit_cast(bf16x8, av[a]), __builtin_bit_cast(bf16x8, bv[b]), acc[a][b], 0, 0, 0);
+          } else {
+            const float4 af = __builtin_bit_cast(float4, av[a]);
+            const float4 bf = __builtin_bit_cast(float4, bv[b]);
+            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af.x, bf.x, acc[a][b], 0, 0, 0);
+            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af.y, bf.y, acc[a][b], 0, 0, 0);
+            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af.z, bf.z, acc[a][b], 0, 0, 0);
+            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af.w, bf.w, acc[a][b], 0, 0, 0);
+          }
+        }
+    }
+    if (kt + 1 < nk) {
+      uint4 *nx = lds + (cur ^ 1) * STAGE;
+      la.store(nx, tid);
+      lb.store(nx + TI * 8, tid);
+    }
+    __syncthreads();
+  }
+
+  // Accumulator element 4 g + e of a 32 x 32 tile is (i = 8 g + 4 h + e, j = lane % 32):
+  // four consecutive i per lane, stored as one float4 of C[j][i..i+3].
+#pragma unroll
+  for (int a = 0; a < FM; ++a)
+#pragma unroll
+    for (int b = 0; b < FN; ++b) {
+      const int j = j0 + (wj * FN + b) * 32 + l32;
+      if (j >= g.J) continue;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int i = i0 + (wi * FM + a) * 32 + 8 * q + 4 * h;
+        if (i >= g.I) continue;
+        float4 *dst = reinterpret_cast<float4 *>(g.C + (long)j * g.ldc + i);
+        float4 v = make_float4(acc[a][b][4 * q], acc[a][b][4 * q + 1], acc[a][b][4 * q + 2],
+                               acc[a][b][4 * q + 3]);
+        if (ACCUM) {
+          const float4 o = *dst;
+          v = make_float4(o.x + g.alpha * v.x, o.y + g.alpha * v.y, o.z + g.alpha * v.z,
+                          o.w + g.alpha * v.w);
+        }
+        *dst = v;
+      }
+    }
+}
+
+namespace {
+
+struct TileChoice { int fm, fn; double eff; };
+const TileChoice kTiles[] = {{4, 2, 1.00}, {2, 2, 0.95}, {2, 1, 0.80}, {1, 2, 0.80}, {1, 1, 0.60}};
+
+int pick_tile(const GemmArgs &g) {
+  // Cheapest estimated time: rounds of resident workgroups x tile area / tile efficiency.
+  const char *env = getenv("CODENET_GEMM_TILE");
+  if (env && env[0] >= '0' && env[0] <= '4') return env[0] - '0';
+  int best = 0;
+  double best_cost = 1e300;
+  for (int t = 0; t < 5; ++t) {
+    const int ti = 64 * kTiles[t].fm, tj = 64 * kTiles[t].fn;
+    const long nt = (long)((g.I + ti - 1) / ti) * ((g.J + tj - 1) / tj);
+    const int lds = 2 * (ti + tj) * 128;
+    const int occ = lds * 2 <= 160 * 1024 ? 2 : 1;
+    const long rounds = (nt + 256L * occ - 1) / (256L * occ);
+    const double cost = (double)rounds * occ * ti * tj / kTiles[t].eff;
+    if (cost < best_cost) { best_cost = cost; best = t; }
+  }
+  return best;
+}
+
+template <bool BF16, int FM, int FN, bool AKC, bool BKC, bool ACCUM>
+hipError_t launch_one(GemmArgs g, hipStream_t s) {
+  constexpr int TI = 64 * FM, TJ = 64 * FN;
+  constexpr int lds = 2 * (TI + TJ) * 128;
+  g.tiles_i = (g.I + TI - 1) / TI;
+  g.tiles_j = (g.J + TJ - 1) / TJ;
+  const int nt = g.tiles_i * g.tiles_j;
+  const int grid = ((nt + 7) / 8) * 8;
+  auto kern = gemm_kernel<BF16, FM, FN, AKC, BKC, ACCUM>;
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, s, g);
+  return hipGetLastError();
+}
+
+template <bool BF16, bool AKC, bool BKC, bool ACCUM>
+hipError_t launch_layout(const GemmArgs &g, hipStream_t s) {
+  switch (pick_tile(g)) {
+    case 0: return launch_one<BF16, 4, 2, AKC, BKC, ACCUM>(g, s);
+    case 1: return launch_one<BF16, 2, 2, AKC, BKC, ACCUM>(g, s);
+    case 2: return launch_one<BF16, 2, 1, AKC, BKC, ACCUM>(g, s);
+    case 3: return launch_one<BF16, 1, 2, AKC, BKC, ACCUM>(g, s);
+    default: return launch_one<BF16, 1, 1, AKC, BKC, ACCUM>(g, s);
+  }
+}
+
+template <bool BF16>
+hipError_t launch_dtype(GemmLayout layout, const GemmArgs &g, hipStream_t s) {
+  switch (layout) {
+    case kFwd: return launch_layout<BF16, true, true, false>(g, s);
+    case kBwd: return launch_layout<BF16, false, true, false>(g, s);
+    default: return launch_layout<BF16, false, false, true>(g, s);
+  }
+}
+
+}  // namespace
+
+hipError_t launch_gemm(GemmLayout layout, bool bf16, const GemmArgs &args, hipStream_t stream) {
+  // The kernels use 16-byte accesses along every contiguous dimension.
+  if ((args.lda & 3) || (args.ldb & 3) || (args.ldc & 3) || (args.I & 3)) return hipErrorInvalidValue;
+  if (layout != kUpd && (args.K & 3)) return hipErrorInvalidValue;
+  if (layout == kUpd && (args.J & 3)) return hipErrorInvalidValue;
+  return bf16 ? launch_dtype<true>(layout, args, stream) : launch_dtype<false>(layout, args, stream);
+}
+
+}  // namespace codenet

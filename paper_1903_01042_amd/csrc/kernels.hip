@@ -1,0 +1,563 @@
+// Memory-bound and tiny kernels of the coded layer step: one-time encoding of W,
+// additional encoding of the input vectors, syndrome / Gram reduction, the
+// decision (locate) kernel, the correction + decode kernel, soft-error
+// injection and weight export.
+#include "codenet_internal.h"
+
+namespace codenet {
+
+// ---------------------------------------------------------------------------
+// Pre-processing (Claim 1): W~ block (i, j) = sum_{i', j'} G_r[i'][i] G_c[j'][j] W_{i', j'}.
+// One thread per coded element, float64 accumulation, one rounding to float32.
+// G = [I | P] and H = [P^T | -I], so G[i'][a + k] = H[k][i'].
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void encode_matrix_kernel(const float *__restrict__ W, float *__restrict__ Wt,
+                                                            const DevCode *__restrict__ cr,
+                                                            const DevCode *__restrict__ cc, int Mr, int Nc,
+                                                            int n_out, int n_in) {
+  const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (long)Mr * Nc) return;
+  const int R = (int)(idx / Nc), C = (int)(idx % Nc);
+  const int i = R / cr->B, rho = R % cr->B;
+  const int j = C / cc->B, kap = C % cc->B;
+  double acc = 0.0;
+  if (rho < cr->B0 && kap < cc->B0) {
+    const int i_lo = i < cr->a ? i : 0, i_hi = i < cr->a ? i + 1 : cr->a;
+    const int j_lo = j < cc->a ? j : 0, j_hi = j < cc->a ? j + 1 : cc->a;
+    for (int i2 = i_lo; i2 < i_hi; ++i2) {
+      const int g = i2 * cr->B0 + rho;
+      if (g >= n_out) continue;
+      const double gr = i < cr->a ? 1.0 : cr->H[i - cr->a][i2];
+      for (int j2 = j_lo; j2 < j_hi; ++j2) {
+        const int hcol = j2 * cc->B0 + kap;
+        if (hcol >= n_in) continue;
+        const double gc = j < cc->a ? 1.0 : cc->H[j - cc->a][j2];
+        acc += gr * gc * (double)W[(long)g * n_in + hcol];
+      }
+    }
+  }
+  Wt[idx] = (float)acc;
+}
+
+hipError_t launch_encode_matrix(const float *W, float *Wt, const DevCode *code_r, const DevCode *code_c,
+                                int Mr, int Nc, int n_out, int n_in, hipStream_t s) {
+  const long total = (long)Mr * Nc;
+  const unsigned grid = (unsigned)((total + 255) / 256);
+  hipLaunchKernelGGL(encode_matrix_kernel, dim3(grid), dim3(256), 0, s, W, Wt, code_r, code_c, Mr, Nc,
+                     n_out, n_in);
+  return hipGetLastError();
+}
+
+// Systematic part without padding (inverse of the block padding above).
+__global__ __launch_bounds__(256) void export_weights_kernel(const float *__restrict__ Wt, float *__restrict__ W,
+                                                             int Br, int B0r, int Bc, int B0c, int Nc,
+                                                             int n_out, int n_in) {
+  const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (long)n_out * n_in) return;
+  const int g = (int)(idx / n_in), hcol = (int)(idx % n_in);
+  const int R = (g / B0r) * Br + g % B0r, C = (hcol / B0c) * Bc + hcol % B0c;
+  W[idx] = Wt[(long)R * Nc + C];
+}
+
+hipError_t launch_export_weights(const float *Wt, float *W, const DevCode &cr, const DevCode &cc, int Nc,
+                                 int n_out, int n_in, hipStream_t s) {
+  const long total = (long)n_out * n_in;
+  hipLaunchKernelGGL(export_weights_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, Wt, W,
+                     cr.B, cr.B0, cc.B, cc.B0, Nc, n_out, n_in);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Additional encoding step (step 4 of the feedforward and backpropagation
+// stages): [v; v~] = (G^T (x) I) v for every batch row.  Input is the caller's
+// dense [b][N]; output is the block-padded [b][(a + r) B] that the products and
+// the update read.  One thread per (batch row, 4 positions inside a block).
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void encode_vector_kernel(const float *__restrict__ V, float *__restrict__ Vt,
+                                                            const DevCode *__restrict__ code, int b) {
+  const int B = code->B, B0 = code->B0, a = code->a, r = code->r, N = code->N;
+  const int quads = B >> 2;
+  const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (long)b * quads) return;
+  const int beta = (int)(idx / quads), rho = (int)(idx % quads) * 4;
+  const float *src = V + (long)beta * N;
+  float *dst = Vt + (long)beta * (a + r) * B;
+  float par[CODENET_MAX_R][4];
+#pragma unroll
+  for (int k = 0; k < CODENET_MAX_R; ++k) par[k][0] = par[k][1] = par[k][2] = par[k][3] = 0.f;
+  for (int i = 0; i < a; ++i) {
+    float v[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int g = i * B0 + rho + e;
+      v[e] = (rho + e < B0 && g < N) ? src[g] : 0.f;
+    }
+    *reinterpret_cast<float4 *>(dst + i * B + rho) = make_float4(v[0], v[1], v[2], v[3]);
+#pragma unroll
+    for (int k = 0; k < CODENET_MAX_R; ++k)
+      if (k < r) {
+        const float p = code->Hf[k][i];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) par[k][e] = fmaf(p, v[e], par[k][e]);
+      }
+  }
+#pragma unroll
+  for (int k = 0; k < CODENET_MAX_R; ++k)
+    if (k < r)
+      *reinterpret_cast<float4 *>(dst + (a + k) * B + rho) = make_float4(par[k][0], par[k][1], par[k][2], par[k][3]);
+}
+
+hipError_t launch_encode_vector(const float *V, float *Vt, const DevCode *code_dev, const DevCode &code_host,
+                                int b, hipStream_t s) {
+  const long total = (long)b * (code_host.B >> 2);
+  hipLaunchKernelGGL(encode_vector_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, V, Vt,
+                     code_dev, b);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Consistency check, pass 1 (General Error-Detection Method): syndromes
+// out^_k = sum_i H[k][i] out_i for every position of a block, written out for
+// the correction pass, plus what the decision needs: ||out_i||^2 for every
+// block and the r x r Gram matrix sum_pos out^(pos) out^(pos)^T.  HBM-bound:
+// the coded output is read once.  Per-thread float32 sums over a few
+// positions, then float64 across lanes, wavefronts and workgroups in a fixed
+// order (no atomics), so the decision is reproducible.
+// ---------------------------------------------------------------------------
+template <int R>
+__global__ __launch_bounds__(256) void detect_kernel(const float *__restrict__ out, float *__restrict__ syn,
+                                                     double *__restrict__ partials,
+                                                     const DevCode *__restrict__ code, int b, int iters) {
+  const int B = code->B, L = code->L;
+  const int quads = B >> 2;
+  const long npos = (long)b * quads;
+  constexpr int NG = R * (R + 1) / 2;
+  float sq[CODENET_MAX_L];
+  float gram[NG];
+#pragma unroll
+  for (int i = 0; i < CODENET_MAX_L; ++i) sq[i] = 0.f;
+#pragma unroll
+  for (int e = 0; e < NG; ++e) gram[e] = 0.f;
+
+  for (int it = 0; it < iters; ++it) {
+    const long idx = ((long)it * gridDim.x + blockIdx.x) * 256 + threadIdx.x;
+    if (idx >= npos) break;
+    const int beta = (int)(idx / quads), rho = (int)(idx % quads) * 4;
+    const float *row = out + (long)beta * L * B + rho;
+    float4 sy[R];
+#pragma unroll
+    for (int k = 0; k < R; ++k) sy[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+    for (int i = 0; i < CODENET_MAX_L; ++i)
+      if (i < L) {
+        const float4 v = *reinterpret_cast<const float4 *>(row + i * B);
+        sq[i] += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+#pragma unroll
+        for (int k = 0; k < R; ++k) {
+          const float hk = code->Hf[k][i];
+          sy[k].x = fmaf(hk, v.x, sy[k].x);
+          sy[k].y = fmaf(hk, v.y, sy[k].y);
+          sy[k].z = fmaf(hk, v.z, sy[k].z);
+          sy[k].w = fmaf(hk, v.w, sy[k].w);
+        }
+      }
+    int e = 0;
+#pragma unroll
+    for (int k = 0; k < R; ++k) {
+      *reinterpret_cast<float4 *>(syn + ((long)k * b + beta) * B + rho) = sy[k];
+#pragma unroll
+      for (int k2 = k; k2 < R; ++k2, ++e)
+        gram[e] += sy[k].x * sy[k2].x + sy[k].y * sy[k2].y + sy[k].z * sy[k2].z + sy[k].w * sy[k2].w;
+    }
+  }
+
+  // reduce: lanes (float64 shuffles), then the 4 wavefronts through LDS
+  __shared__ double red[4][kMaxEntries];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int i = 0; i < CODENET_MAX_L; ++i)
+    if (i < L) {
+      double v = (double)sq[i];
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+      if (lane == 0) red[wave][i] = v;
+    }
+#pragma unroll
+  for (int e = 0; e < NG; ++e) {
+    double v = (double)gram[e];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+    if (lane == 0) red[wave][CODENET_MAX_L + e] = v;
+  }
+  __syncthreads();
+  const int t = threadIdx.x;
+  if (t < CODENET_MAX_L + NG && (t < L || t >= CODENET_MAX_L))
+    partials[(long)blockIdx.x * kMaxEntries + t] = red[0][t] + red[1][t] + red[2][t] + red[3][t];
+}
+
+hipError_t launch_detect(const float *out, float *syn, double *partials, int *n_parts, const DevCode *code_dev,
+                         const DevCode &ch, int b, hipStream_t s) {
+  const long npos = (long)b * (ch.B >> 2);
+  long wgs = (npos + 255) / 256;
+  int iters = 1;
+  if (wgs > kDetectParts) {
+    iters = (int)((wgs + kDetectParts - 1) / kDetectParts);
+    wgs = (npos + 256L * iters - 1) / (256L * iters);
+  }
+  *n_parts = (int)wgs;
+  dim3 grid((unsigned)wgs), block(256);
+  switch (ch.r) {
+#define CODENET_DETECT_CASE(RR) \
+  case RR: hipLaunchKernelGGL(detect_kernel<RR>, grid, block, 0, s, out, syn, partials, code_dev, b, iters); break;
+    CODENET_DETECT_CASE(1) CODENET_DETECT_CASE(2) CODENET_DETECT_CASE(3) CODENET_DETECT_CASE(4)
+    CODENET_DETECT_CASE(5) CODENET_DETECT_CASE(6) CODENET_DETECT_CASE(7) CODENET_DETECT_CASE(8)
+#undef CODENET_DETECT_CASE
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Consistency check, pass 2: the decision (decoding algorithm of the
+// appendix), one workgroup, float64.  With Gamma the Gram matrix of the
+// syndromes, the least-squares residual of a support A is
+//   ||out^||^2 - tr((H_A^T H_A)^-1 H_A^T Gamma H_A),
+// so the search over supports touches only a few dozen scalars.
+// ---------------------------------------------------------------------------
+struct Support {
+  int k;
+  int idx[CODENET_MAX_T];
+};
+
+// k-subset number `rank` of {0..L-1} in lexicographic order
+__device__ void unrank_support(long rank, int L, int k, int *idx) {
+  int x = 0;
+  for (int pos = 0; pos < k; ++pos) {
+    for (;; ++x) {
+      // subsets that keep x at this position: C(L - x - 1, k - pos - 1)
+      long c = 1;
+      const int nn = L - x - 1, kk = k - pos - 1;
+      if (kk > nn) c = 0;
+      else for (int q = 1; q <= kk; ++q) c = c * (nn - kk + q) / q;
+      if (rank < c) break;
+      rank -= c;
+    }
+    idx[pos] = x++;
+  }
+}
+
+__device__ long n_choose_k(int n, int k) {
+  if (k > n) return 0;
+  long c = 1;
+  for (int q = 1; q <= k; ++q) c = c * (n - k + q) / q;
+  return c;
+}
+
+// Cholesky factor of M = H_A^T H_A (k x k, lower), returns false if not positive definite
+__device__ bool support_factor(const DevCode *code, const int *idx, int k, double Lo[CODENET_MAX_T][CODENET_MAX_T]) {
+  const int r = code->r;
+  for (int p = 0; p < k; ++p)
+    for (int q = 0; q <= p; ++q) {
+      double m = 0.0;
+      for (int c = 0; c < r; ++c) m += code->H[c][idx[p]] * code->H[c][idx[q]];
+      for (int u = 0; u < q; ++u) m -= Lo[p][u] * Lo[q][u];
+      if (p == q) {
+        if (m <= 1e-300) return false;
+        Lo[p][p] = sqrt(m);
+      } else {
+        Lo[p][q] = m / Lo[q][q];
+      }
+    }
+  return true;
+}
+
+__device__ double support_residual2(const DevCode *code, const double (*G)[CODENET_MAX_R], double trG,
+                                    const int *idx, int k) {
+  const int r = code->r;
+  double Lo[CODENET_MAX_T][CODENET_MAX_T];
+  if (!support_factor(code, idx, k, Lo)) return trG;
+  // N = H_A^T Gamma H_A
+  double T[CODENET_MAX_R][CODENET_MAX_T];
+  for (int c = 0; c < r; ++c)
+    for (int p = 0; p < k; ++p) {
+      double v = 0.0;
+      for (int d = 0; d < r; ++d) v += G[c][d] * code->H[d][idx[p]];
+      T[c][p] = v;
+    }
+  double N[CODENET_MAX_T][CODENET_MAX_T];
+  for (int p = 0; p < k; ++p)
+    for (int q = 0; q < k; ++q) {
+      double v = 0.0;
+      for (int c = 0; c < r; ++c) v += code->H[c][idx[p]] * T[c][q];
+      N[p][q] = v;
+    }
+  // tr(M^-1 N) = tr(Lo^-1 N Lo^-T): forward-substitute rows, then columns
+  double Y[CODENET_MAX_T][CODENET_MAX_T];
+  for (int q = 0; q < k; ++q)
+    for (int p = 0; p < k; ++p) {
+      double v = N[p][q];
+      for (int u = 0; u < p; ++u) v -= Lo[p][u] * Y[u][q];
+      Y[p][q] = v / Lo[p][p];
+    }
+  double tr = 0.0;
+  for (int p = 0; p < k; ++p) {
+    // (Y Lo^-T)[p][p]: solve z Lo^T = Y[p][:] up to column p
+    double z[CODENET_MAX_T];
+    for (int q = 0; q <= p; ++q) {
+      double v = Y[p][q];
+      for (int u = 0; u < q; ++u) v -= z[u] * Lo[q][u];
+      z[q] = v / Lo[q][q];
+    }
+    tr += z[p];
+  }
+  const double res = trG - tr;
+  return res > 0.0 ? res : 0.0;
+}
+
+__global__ __launch_bounds__(256) void decide_kernel(const double *__restrict__ partials, int n_parts,
+                                                     const DevCode *__restrict__ code, DevPlan *__restrict__ plan,
+                                                     codenet_report *__restrict__ report) {
+  __shared__ double tot[kMaxEntries];
+  __shared__ double G[CODENET_MAX_R][CODENET_MAX_R];
+  __shared__ double best_res[256];
+  __shared__ long best_rank[256];
+  __shared__ int s_verdict, s_k;
+  __shared__ long s_rank;
+  __shared__ double s_resid, s_trG;
+  const int t = threadIdx.x;
+  const int L = code->L, r = code->r;
+  const int tcap = r / 2 < CODENET_MAX_T ? r / 2 : CODENET_MAX_T;
+
+  if (t < kMaxEntries) {
+    double v = 0.0;
+    if (t < L || (t >= CODENET_MAX_L && t < CODENET_MAX_L + r * (r + 1) / 2))
+      for (int p = 0; p < n_parts; ++p) v += partials[(long)p * kMaxEntries + t];
+    tot[t] = v;
+  }
+  __syncthreads();
+  if (t == 0) {
+    int e = CODENET_MAX_L;
+    double trG = 0.0;
+    for (int k = 0; k < r; ++k)
+      for (int k2 = k; k2 < r; ++k2, ++e) G[k][k2] = G[k2][k] = tot[e];
+    bool clean = true;
+    for (int k = 0; k < r; ++k) {
+      trG += G[k][k];
+      double ref2 = 0.0;
+      for (int i = 0; i < L; ++i) ref2 += code->H[k][i] * code->H[k][i] * tot[i];
+      const double rel = ref2 > 0.0 ? sqrt(G[k][k] / ref2) : 0.0;
+      if (report) report->syn_rel[k] = (float)rel;
+      // a non-finite ratio (NaN / Inf in the output) must not pass as clean
+      if (!(rel <= code->tau_detect)) clean = false;
+    }
+    if (report)
+      for (int k = r; k < CODENET_MAX_R; ++k) report->syn_rel[k] = 0.f;
+    s_trG = trG;
+    s_verdict = clean ? CODENET_CLEAN : CODENET_UNCORRECTABLE;
+    s_k = 0;
+    s_rank = -1;
+    s_resid = 0.0;
+  }
+  __syncthreads();
+
+  if (s_verdict != CODENET_CLEAN && isfinite(s_trG) && s_trG > 0.0) {
+    for (int k = 1; k <= tcap; ++k) {
+      const long count = n_choose_k(L, k);
+      double my_res = 1e300;
+      long my_rank = -1;
+      for (long rank = t; rank < count; rank += 256) {
+        int idx[CODENET_MAX_T];
+        unrank_support(rank, L, k, idx);
+        const double res2 = support_residual2(code, G, s_trG, idx, k);
+        if (res2 < my_res) { my_res = res2; my_rank = rank; }
+      }
+      best_res[t] = my_res;
+      best_rank[t] = my_rank;
+      __syncthreads();
+      if (t == 0) {
+        double br = 1e300;
+        long bk = -1;
+        for (int u = 0; u < 256; ++u)
+          if (best_rank[u] >= 0 && (best_res[u] < br || (best_res[u] == br && best_rank[u] < bk))) {
+            br = best_res[u];
+            bk = best_rank[u];
+          }
+        const double rel = bk >= 0 ? sqrt(br / s_trG) : 1e300;
+        s_resid = rel;
+        if (bk >= 0 && rel <= code->tau_resid) {
+          s_verdict = CODENET_CORRECTED;
+          s_k = k;
+          s_rank = bk;
+        }
+      }
+      __syncthreads();
+      if (s_verdict == CODENET_CORRECTED) break;
+    }
+  }
+
+  if (t == 0) {
+    int idx[CODENET_MAX_T];
+    for (int p = 0; p < CODENET_MAX_T; ++p) idx[p] = -1;
+    const int k = s_verdict == CODENET_CORRECTED ? s_k : 0;
+    if (k > 0) {
+      unrank_support(s_rank, L, k, idx);
+      // error block p = sum_c pinv[p][c] syndrome_c with pinv = (H_A^T H_A)^-1 H_A^T
+      double Lo[CODENET_MAX_T][CODENET_MAX_T];
+      support_factor(code, idx, k, Lo);
+      for (int c = 0; c < r; ++c) {
+        double y[CODENET_MAX_T], x[CODENET_MAX_T];
+        for (int p = 0; p < k; ++p) {
+          double v = code->H[c][idx[p]];
+          for (int u = 0; u < p; ++u) v -= Lo[p][u] * y[u];
+          y[p] = v / Lo[p][p];
+        }
+        for (int p = k - 1; p >= 0; --p) {
+          double v = y[p];
+          for (int u = p + 1; u < k; ++u) v -= Lo[u][p] * x[u];
+          x[p] = v / Lo[p][p];
+        }
+        for (int p = 0; p < k; ++p) plan->coef[p][c] = (float)x[p];
+      }
+    }
+    plan->verdict = s_verdict;
+    plan->n_located = k;
+    for (int p = 0; p < CODENET_MAX_T; ++p) plan->located[p] = idx[p];
+    if (report) {
+      report->verdict = s_verdict;
+      report->n_located = k;
+      for (int p = 0; p < CODENET_MAX_T; ++p) report->located[p] = idx[p];
+      report->resid_rel = (float)(s_resid < 3e38 ? s_resid : 3e38);
+    }
+  }
+}
+
+hipError_t launch_decide(const double *partials, int n_parts, const DevCode *code_dev, const DevCode &,
+                         DevPlan *plan, codenet_report *report, hipStream_t s) {
+  hipLaunchKernelGGL(decide_kernel, dim3(1), dim3(256), 0, s, partials, n_parts, code_dev, plan, report);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Consistency check, pass 3: subtract the reconstructed error blocks on the
+// accepted support and emit the decoded (systematic, unpadded) output.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void correct_kernel(float *__restrict__ out, const float *__restrict__ syn,
+                                                      const DevPlan *__restrict__ plan,
+                                                      const DevCode *__restrict__ code, int b,
+                                                      float *__restrict__ decoded) {
+  const int corrected = plan->verdict == CODENET_CORRECTED ? plan->n_located : 0;
+  if (corrected == 0 && decoded == nullptr) return;
+  const int B = code->B, B0 = code->B0, L = code->L, a = code->a, r = code->r, N = code->N;
+  const int quads = B >> 2;
+  const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (long)b * quads) return;
+  const int beta = (int)(idx / quads), rho = (int)(idx % quads) * 4;
+  float *row = out + (long)beta * L * B + rho;
+
+  for (int p = 0; p < corrected; ++p) {
+    float4 e = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int c = 0; c < r; ++c) {
+      const float4 s = *reinterpret_cast<const float4 *>(syn + ((long)c * b + beta) * B + rho);
+      const float w = plan->coef[p][c];
+      e.x = fmaf(w, s.x, e.x); e.y = fmaf(w, s.y, e.y); e.z = fmaf(w, s.z, e.z); e.w = fmaf(w, s.w, e.w);
+    }
+    const int i = plan->located[p];
+    float4 v = *reinterpret_cast<float4 *>(row + i * B);
+    v.x -= e.x; v.y -= e.y; v.z -= e.z; v.w -= e.w;
+    *reinterpret_cast<float4 *>(row + i * B) = v;
+  }
+  if (decoded == nullptr) return;
+  float *dst = decoded + (long)beta * N;
+  for (int i = 0; i < a; ++i) {
+    const float4 v = *reinterpret_cast<const float4 *>(row + i * B);   // own writes above are visible to this thread
+    const float vv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int g = i * B0 + rho + e;
+      if (rho + e < B0 && g < N) dst[g] = vv[e];
+    }
+  }
+}
+
+hipError_t launch_correct(float *out, const float *syn, const DevPlan *plan, const DevCode *code_dev,
+                          const DevCode &ch, int b, float *decoded, hipStream_t s) {
+  const long total = (long)b * (ch.B >> 2);
+  hipLaunchKernelGGL(correct_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, out, syn, plan,
+                     code_dev, b, decoded);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Soft-error injection.  Noise element idx of a fault is a pure function of
+// (seed, step, phase, bi, bj, idx) through the SplitMix64 output function
+// (Steele, Lea, Flood 2014): z = mix(key + idx); bits 0..31 decide a sparse
+// hit, bits 32..55 give u in [0, 1) in steps of 2^-24, bit 63 the sign.
+// ---------------------------------------------------------------------------
+__host__ __device__ inline unsigned long long mix64(unsigned long long x) {
+  unsigned long long z = x + 0x9E3779B97F4A7C15ull;
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+
+unsigned long long fault_key(unsigned long long seed, unsigned long long step, int phase, int bi, int bj) {
+  unsigned long long k = mix64(seed);
+  k = mix64(k ^ step);
+  return mix64(k ^ (((unsigned long long)phase << 40) | ((unsigned long long)bi << 20) | (unsigned long long)bj));
+}
+
+// sum of squares of the (still clean) target payload, kFaultParts partial sums
+__global__ __launch_bounds__(256) void fault_stats_kernel(FaultArgs fa) {
+  const long total = (long)fa.n_outer * fa.n_inner;
+  double acc = 0.0;
+  for (long e = (long)blockIdx.x * 256 + threadIdx.x; e < total; e += (long)gridDim.x * 256) {
+    const long o = e / fa.n_inner, in = e % fa.n_inner;
+    const float v = fa.base[o * fa.stride_outer + in];
+    acc += (double)v * (double)v;
+  }
+  __shared__ double red[4];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) acc += __shfl_down(acc, off, 64);
+  if (lane == 0) red[wave] = acc;
+  __syncthreads();
+  if (threadIdx.x == 0) fa.partials[blockIdx.x] = red[0] + red[1] + red[2] + red[3];
+}
+
+__global__ __launch_bounds__(256) void fault_apply_kernel(FaultArgs fa) {
+  const long total = (long)fa.n_outer * fa.n_inner;
+  const long e = (long)blockIdx.x * 256 + threadIdx.x;
+  if (e >= total) return;
+  float scale = 1.f;
+  if (fa.mode == CODENET_NOISE_DENSE_REL) {
+    double ss = 0.0;
+    for (int p = 0; p < kFaultParts; ++p) ss += fa.partials[p];
+    scale = (float)sqrt(ss / (double)total);
+  }
+  const long o = e / fa.n_inner, in = e % fa.n_inner;
+  const unsigned long long idx = (unsigned long long)o * fa.idx_outer + (unsigned long long)in * fa.idx_inner;
+  const unsigned long long z = mix64(fa.key + idx);
+  const float u = (float)((z >> 32) & 0xFFFFFFull) * (1.0f / 16777216.0f);
+  float val = fa.lo + (fa.hi - fa.lo) * u;
+  if (fa.mode == CODENET_NOISE_DENSE_REL) {
+    val *= scale;
+    if (z >> 63) val = -val;
+  } else if ((unsigned int)(z & 0xFFFFFFFFull) >= fa.hit_below) {
+    return;
+  }
+  float *p = fa.base + o * fa.stride_outer + in;
+  *p += val;
+}
+
+hipError_t launch_fault(const FaultArgs &fa, hipStream_t s, bool stats_pass) {
+  const long total = (long)fa.n_outer * fa.n_inner;
+  if (total <= 0) return hipSuccess;
+  if (stats_pass) {
+    hipLaunchKernelGGL(fault_stats_kernel, dim3(kFaultParts), dim3(256), 0, s, fa);
+  } else {
+    hipLaunchKernelGGL(fault_apply_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, fa);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace codenet

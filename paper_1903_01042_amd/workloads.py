@@ -197,7 +197,7 @@ WORKLOADS = {
                      "gaussian", input_law="uniform01", fault_law="bernoulli", fault_p=0.05),
     # one 4096x4096 layer, bf16 inputs / fp32 accumulate, 8x8 grid + 2 parity rows/cols
     "cfg3": Workload("cfg3-4096-8x8+2-bf16", (4096, 4096), (8, 8), 2, 512, 50, "bf16",
-                     "vandermonde", fault_law="upto2", tau_detect=2e-2, tau_resid=1e-1),
+                     "vandermonde", fault_law="upto2", tau_detect=2e-2, tau_resid=2e-2),
     # 8-layer width-8192 MLP, 8x8 grid + 2 parity rows/cols, faults in fwd, bwd and update
     "cfg4": Workload("cfg4-mlp8192x8-8x8+2", (8192,) * 9, (8, 8), 2, 1024, 20, "f32",
                      "vandermonde", fault_law="bernoulli", fault_p=0.02, weight_faults=True),

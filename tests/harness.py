@@ -1,0 +1,108 @@
+"""Drives the HIP library and the float64 oracle side by side on the same seeded
+inputs and compares them.  Test infrastructure only."""
+import numpy as np
+
+from oracle import codenet_oracle as O
+from paper_1903_01042_amd import workloads as WL
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}          # relative Frobenius error on values
+MARGIN = 5.0                               # every threshold decision must clear its tau by this factor
+
+
+def rel_fro(a, b):
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    den = np.linalg.norm(b)
+    return float(np.linalg.norm(a - b) / den) if den > 0 else float(np.linalg.norm(a))
+
+
+def to_np(t):
+    return t.detach().cpu().numpy().astype(np.float64)
+
+
+class Pair:
+    """One layer on the GPU and in the oracle."""
+
+    def __init__(self, W, P_r, P_c, dtype="f32", max_batch=16, tau_detect=1e-3, tau_resid=1e-2):
+        import torch
+        from paper_1903_01042_amd import binding as B
+        self.B = B
+        self.dtype = dtype
+        self.tol = TOL[dtype]
+        self.tau_detect, self.tau_resid = tau_detect, tau_resid
+        self.dev = torch.device("cuda:0")
+        Wd = torch.from_numpy(np.ascontiguousarray(W, dtype=np.float32)).to(self.dev)
+        self.gpu = B.CodedLayer(Wd, P_r, P_c, dtype=B.BF16_F32ACC if dtype == "bf16" else B.F32,
+                                max_batch=max_batch, tau_detect=tau_detect, tau_resid=tau_resid)
+        self.ora = O.CodedLayer(np.asarray(W, dtype=np.float32), P_r, P_c, Br=self.gpu.B_r, Bc=self.gpu.B_c,
+                                tau_detect=tau_detect, tau_resid=tau_resid)
+        self.report = self.gpu.new_report()
+        self.log = []
+
+    def dev_tensor(self, a):
+        import torch
+        return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(self.dev)
+
+    def check_weights(self, tol=None):
+        err = rel_fro(to_np(self.gpu.export_coded()), self.ora.Wt)
+        assert err <= (tol or self.tol), "coded weights differ: rel %.3e" % err
+        return err
+
+    def product(self, phase, V, faults=(), check_margins=True):
+        """One coded product + injection + check on both sides; V is batch-major [b][N]."""
+        B = self.B
+        Vd = self.dev_tensor(V)
+        if phase == B.FWD:
+            out_g = self.gpu.forward(Vd)
+            out_o = self.ora.forward(np.asarray(V, dtype=np.float32).T.astype(np.float64))
+        else:
+            out_g = self.gpu.backward(Vd)
+            out_o = self.ora.backward(np.asarray(V, dtype=np.float32).T.astype(np.float64))
+        err = rel_fro(to_np(out_g).T, out_o)
+        assert err <= self.tol, "coded product differs: rel %.3e (phase %d)" % (err, phase)
+        faults = list(faults)
+        if faults:
+            self.gpu.inject(faults, out_g)
+            out_o = self.ora.inject(faults, out_o)
+            err = rel_fro(to_np(out_g).T, out_o)
+            assert err <= self.tol, "injected output differs: rel %.3e" % err
+        dec_g = self.gpu.detect_decode(phase, out_g, report=self.report)
+        rep = self.gpu.read_report(self.report)
+        res = self.ora.detect_decode(phase, out_o)
+        self.log.append((phase, [(f["bi"], f["bj"]) for f in faults], rep["verdict"], rep["located"]))
+        assert rep["verdict"] == res["verdict"], (rep, res["verdict"], res["located"], res["syn_rel"], res["resid_rel"])
+        assert rep["located"] == res["located"], (rep, res["located"])
+        if check_margins and (self.ora.r_r if phase == B.FWD else self.ora.r_c) > 0:
+            self._margins(rep, res, self.ora.r_r if phase == B.FWD else self.ora.r_c)
+        if rep["verdict"] != B.UNCORRECTABLE:
+            err = rel_fro(to_np(dec_g).T, res["decoded"])
+            assert err <= self.tol, "decoded output differs: rel %.3e" % err
+            err = rel_fro(to_np(out_g).T, res["out"])
+            assert err <= self.tol, "corrected coded output differs: rel %.3e" % err
+        return dec_g, rep, res
+
+    def _margins(self, rep, res, r):
+        """Both sides' thresholded quantities must sit a factor MARGIN away from the
+        thresholds, so that float32/bf16 rounding cannot flip a decision silently."""
+        for side, syn, resid in (("gpu", max(rep["syn_rel"]), rep["resid_rel"]),
+                                 ("oracle", float(np.max(res["syn_rel"])), res["resid_rel"])):
+            if res["verdict"] == O.CLEAN:
+                assert syn * MARGIN <= self.tau_detect, (side, "clean but close to tau_detect", syn)
+            else:
+                assert syn >= MARGIN * self.tau_detect, (side, "detected but close to tau_detect", syn)
+            if res["verdict"] == O.CORRECTED:
+                assert resid * MARGIN <= self.tau_resid, (side, "accepted but close to tau_resid", resid)
+            elif res["verdict"] == O.UNCORRECTABLE and r >= 2:
+                assert resid >= MARGIN * self.tau_resid, (side, "rejected but close to tau_resid", resid)
+
+    def update(self, eta):
+        self.gpu.update(eta)
+        self.ora.update(eta)
+
+    def inject_weights(self, faults):
+        if faults:
+            self.gpu.inject(list(faults))
+            self.ora.inject(list(faults))
+
+    def close(self):
+        self.gpu.destroy()

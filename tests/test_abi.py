@@ -1,0 +1,66 @@
+"""The C-ABI library loads and exports every symbol the header declares; argument
+checks that need no GPU answer with the documented codes (no compute calls)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_1903_01042_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "codenet.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(codenet_[a-z_]+)\s*\(", text)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(B.LIB_PATH):
+        from paper_1903_01042_amd import build
+        build.build_library(verbose=False)
+    return B.load_library()
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = _declared()
+    assert set(names) == set(B.EXPORTS), (names, B.EXPORTS)
+    for name in names:
+        assert getattr(lib, name) is not None
+
+
+def test_struct_layouts_match_the_header():
+    # codenet_report: 2 ints + MAX_T ints + MAX_R floats + 1 float; codenet_fault: 4 ints, 2 u64, 3 floats, 1 int
+    assert ctypes.sizeof(B.Report) == 4 * (2 + B.MAX_T + B.MAX_R + 1)
+    assert ctypes.sizeof(B.Fault) == 48
+    assert B.Fault.seed.offset == 16 and B.Fault.lo.offset == 32
+    text = open(os.path.join(ROOT, "include", "codenet.h")).read()
+    for name, val in (("CODENET_MAX_T", B.MAX_T), ("CODENET_MAX_R", B.MAX_R), ("CODENET_MAX_L", B.MAX_L),
+                      ("CODENET_MAX_FAULTS", B.MAX_FAULTS)):
+        assert re.search(r"#define\s+%s\s+%d\b" % (name, val), text), name
+
+
+def test_argument_errors_without_a_gpu(lib):
+    h = ctypes.c_void_p(0)
+    assert lib.codenet_encode(None, None, None, ctypes.byref(h)) == B.E_NULL
+    d = B.Desc(0, 8, 2, 2, 0, 0, None, None, B.F32, 4, 1e-3, 1e-2)
+    fake = ctypes.c_void_p(16)          # never dereferenced: the shape check comes first
+    assert lib.codenet_encode(ctypes.byref(d), fake, None, ctypes.byref(h)) == B.E_SHAPE
+    d = B.Desc(8, 8, 2, 2, 0, 0, None, None, 7, 4, 1e-3, 1e-2)
+    assert lib.codenet_encode(ctypes.byref(d), fake, None, ctypes.byref(h)) == B.E_DTYPE
+    d = B.Desc(8, 8, 2, 2, 0, 0, None, None, B.F32, 0, 1e-3, 1e-2)
+    assert lib.codenet_encode(ctypes.byref(d), fake, None, ctypes.byref(h)) == B.E_BATCH
+    d = B.Desc(8, 8, 2, 2, 9, 0, None, None, B.F32, 4, 1e-3, 1e-2)
+    assert lib.codenet_encode(ctypes.byref(d), fake, None, ctypes.byref(h)) == B.E_CODE
+    # rows 0 and 1 of P are equal: a zero 2x2 minor, not MDS
+    P = (ctypes.c_double * 6)(1.0, 2.0, 1.0, 2.0, 1.0, 3.0)
+    d = B.Desc(9, 9, 3, 3, 2, 2, P, P, B.F32, 4, 1e-3, 1e-2)
+    assert lib.codenet_encode(ctypes.byref(d), fake, None, ctypes.byref(h)) == B.E_CODE
+    assert lib.codenet_forward(None, None, 1, None, None) == B.E_NULL
+    assert lib.codenet_update(None, 0.1, None) == B.E_NULL
+    assert lib.codenet_destroy(None) == B.E_NULL
+    assert lib.codenet_strerror(B.E_CODE).decode().startswith("generator")
+    assert lib.codenet_strerror(0).decode() == "ok"

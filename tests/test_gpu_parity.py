@@ -1,0 +1,223 @@
+"""GPU parity: the HIP path, called through the C ABI, against the float64 oracle
+on the same seeded inputs.  Located block sets and verdicts must be identical;
+values within 1e-4 (f32) / 2e-2 (bf16 inputs) relative Frobenius error."""
+import itertools
+import sys
+
+import numpy as np
+import pytest
+
+from paper_1903_01042_amd import workloads as WL
+from harness import Pair, rel_fro, to_np
+
+pytestmark = pytest.mark.gpu
+
+FWD, BWD, WEIGHT = WL.PHASE_FWD, WL.PHASE_BWD, WL.PHASE_WEIGHT
+CLEAN, CORRECTED, UNCORRECTABLE = 0, 1, 2
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+def layer_step(pair, wl, step, layer=0, n_out=None, n_in=None):
+    """forward -> inject -> check, backward -> inject -> check, update (-> weight faults)."""
+    b = wl.batch
+    X = WL.normal((b, n_in), WL.SEED_INPUTS + step) if wl.input_law == "normal" else \
+        WL.uniform01((b, n_in), WL.SEED_INPUTS + step)
+    D = WL.normal((b, n_out), WL.SEED_DELTAS + step)
+    _, rf, _ = pair.product(FWD, X, wl.product_faults(FWD, step, layer))
+    _, rb, _ = pair.product(BWD, D, wl.product_faults(BWD, step, layer))
+    pair.update(wl.eta)
+    return rf, rb
+
+
+# ------------------------------------------------------------------ worked example
+def test_paper_example_grid_every_single_block_error():
+    """m = n = 2, t = 1 with the paper's generators on a 256 x 256 layer: every
+    single erroneous block-row / block-column is located and corrected."""
+    P_r, P_c = WL.paper_example_generators()
+    W = WL.layer_weights(256, 256)
+    pair = Pair(W, P_r, P_c, "f32", max_batch=16)
+    pair.check_weights(1e-6)
+    X, D = WL.normal((16, 256), 1), WL.normal((16, 256), 2)
+    for bi in range(4):
+        say("paper grid fwd fault row", bi)
+        _, rep, _ = pair.product(FWD, X, [WL.make_fault(FWD, bi, 1, step=bi)])
+        assert rep["verdict"] == CORRECTED and rep["located"] == [bi]
+    for bj in range(4):
+        say("paper grid bwd fault col", bj)
+        _, rep, _ = pair.product(BWD, D, [WL.make_fault(BWD, 0, bj, step=bj)])
+        assert rep["verdict"] == CORRECTED and rep["located"] == [bj]
+    _, rep, _ = pair.product(FWD, X, [WL.make_fault(FWD, 0, 0, 9), WL.make_fault(FWD, 3, 1, 9)])
+    assert rep["verdict"] == UNCORRECTABLE
+    _, rep, _ = pair.product(FWD, X)
+    assert rep["verdict"] == CLEAN
+    pair.product(BWD, D)
+    pair.update(0.01)
+    pair.check_weights()
+    assert rel_fro(to_np(pair.gpu.export_weights()), pair.ora.weights()) < 1e-5
+    pair.close()
+
+
+# ------------------------------------------------------------------- cfg1, full size
+def test_cfg1_full():
+    wl = WL.WORKLOADS["cfg1"]
+    P_r, P_c = wl.generators()
+    pair = Pair(WL.layer_weights(256, 256), P_r, P_c, "f32", wl.batch, wl.tau_detect, wl.tau_resid)
+    seen = set()
+    for step in range(wl.steps):
+        say("cfg1 step", step)
+        rf, rb = layer_step(pair, wl, step, n_out=256, n_in=256)
+        seen.update([rf["verdict"], rb["verdict"]])
+        pair.check_weights()
+    # one parity block only detects: every corrupted product is flagged, none located
+    assert seen == {CLEAN, UNCORRECTABLE}
+    pair.close()
+
+
+# ------------------------------------------------------------- ragged / odd shapes
+@pytest.mark.parametrize("n_out,n_in,m,n,r,b,dtype", [
+    (10, 1024, 4, 4, 1, 128, "f32"),      # cfg2's last layer: 10 outputs on 4 block-rows
+    (100, 52, 3, 5, 2, 7, "f32"),         # nothing divides anything
+    (300, 200, 5, 4, 2, 33, "bf16"),
+    (130, 70, 2, 2, 4, 5, "f32"),         # t = 2
+    (64, 64, 2, 2, 0, 8, "f32"),          # uncoded baseline path (r = 0)
+])
+def test_ragged_shapes(n_out, n_in, m, n, r, b, dtype):
+    say("ragged", n_out, n_in, m, n, r, b, dtype)
+    P_r = WL.vandermonde_like(m, r) if r in (0, 2) else WL.gaussian_generator(m, r, 3)
+    P_c = WL.vandermonde_like(n, r) if r in (0, 2) else WL.gaussian_generator(n, r, 4)
+    tau = (1e-3, 1e-2) if dtype == "f32" else (2e-2, 2e-2)
+    pair = Pair(WL.layer_weights(n_out, n_in), P_r, P_c, dtype, b, *tau)
+    pair.check_weights(1e-6)
+    X, D = WL.normal((b, n_in), 11), WL.normal((b, n_out), 12)
+    pair.product(FWD, X)
+    pair.product(BWD, D)
+    pair.update(0.02)
+    pair.check_weights()
+    if r >= 2:
+        _, rep, _ = pair.product(FWD, X, [WL.make_fault(FWD, m - 1, 0, 1)])   # last, partly padded block-row
+        assert rep["verdict"] == CORRECTED and rep["located"] == [m - 1]
+        _, rep, _ = pair.product(BWD, D, [WL.make_fault(BWD, 0, n + r - 1, 1)])
+        assert rep["verdict"] == CORRECTED and rep["located"] == [n + r - 1]
+    if r >= 4:
+        _, rep, _ = pair.product(FWD, X, [WL.make_fault(FWD, 0, 0, 2), WL.make_fault(FWD, m + 1, 1, 2)])
+        assert rep["verdict"] == CORRECTED and rep["located"] == [0, m + 1]
+    if r == 1:
+        _, rep, _ = pair.product(FWD, X, [WL.make_fault(FWD, 1, 0, 1)])
+        assert rep["verdict"] == UNCORRECTABLE and rep["located"] == []
+    pair.product(FWD, X)
+    pair.product(BWD, D)
+    pair.update(0.02)
+    pair.check_weights()
+    assert rel_fro(to_np(pair.gpu.export_weights()), pair.ora.weights()) < pair.tol
+    pair.close()
+
+
+# ------------------------------------------------------------ exhaustive campaigns
+@pytest.mark.parametrize("m,r,dtype", [(4, 2, "f32"), (8, 2, "bf16"), (3, 4, "f32")])
+def test_every_error_pattern_on_a_small_grid(m, r, dtype):
+    """All supports up to size r: within capability (<= t) located exactly and
+    corrected, beyond it UNCORRECTABLE -- identical to the oracle every time."""
+    t, L = r // 2, m + r
+    P = WL.vandermonde_like(m, r) if r <= 2 else WL.gaussian_generator(m, r, 8)
+    n_out = n_in = 64 * m
+    tau = (1e-3, 1e-2) if dtype == "f32" else (2e-2, 2e-2)
+    pair = Pair(WL.layer_weights(n_out, n_in), P, P, dtype, 24, *tau)
+    X = WL.normal((24, n_in), 5)
+    D = WL.normal((24, n_out), 6)
+    count = 0
+    for k in range(1, min(r, t + 1) + 1):
+        for A in itertools.combinations(range(L), k):
+            say("campaign", m, r, dtype, "support", A)
+            faults = [WL.make_fault(FWD, i, (i + k) % m, step=count) for i in A]
+            # a random r = 4 generator has some nearly dependent column pairs: no 5x margin asked there
+            _, rep, _ = pair.product(FWD, X, faults, check_margins=(r <= 2))
+            assert rep["verdict"] == (CORRECTED if k <= t else UNCORRECTABLE)
+            assert rep["located"] == (list(A) if k <= t else [])
+            if k == 1:
+                faults = [WL.make_fault(BWD, (A[0] + 1) % m, A[0], step=count)]
+                _, rep, _ = pair.product(BWD, D, faults, check_margins=(r <= 2))
+                assert rep["verdict"] == CORRECTED and rep["located"] == list(A)
+            count += 1
+    pair.close()
+
+
+# --------------------------------------------------------- multi-step, scaled copies
+@pytest.mark.parametrize("name,block,steps", [("cfg3", 64, 12), ("cfg5", 32, 12), ("cfg4", 32, 8)])
+def test_multi_step_on_a_width_scaled_copy(name, block, steps):
+    """Same grid, parity count, dtype, thresholds and fault law as the full
+    workload with blocks of `block`: the oracle follows every step."""
+    wl = WL.WORKLOADS[name].scaled(block, batch=min(WL.WORKLOADS[name].batch, 96))
+    P_r, P_c = wl.generators()
+    n_in, n_out = wl.widths[0], wl.widths[1]
+    pair = Pair(WL.layer_weights(n_out, n_in), P_r, P_c, wl.dtype, wl.batch, wl.tau_detect, wl.tau_resid)
+    verdicts = []
+    for step in range(steps):
+        say(name, "scaled step", step)
+        rf, rb = layer_step(pair, wl, step, n_out=n_out, n_in=n_in)
+        verdicts += [rf["verdict"], rb["verdict"]]
+        pair.check_weights()
+    say(name, "verdicts", verdicts)
+    pair.close()
+
+
+def test_weight_fault_shows_up_in_the_next_products():
+    """An update-stage error corrupts a stored block; it is seen at the next
+    forward product (block-row bi) and, for a base-row block, at the next
+    backward product (block-column bj)."""
+    m = n = 4
+    P = WL.vandermonde_like(m, 2)
+    pair = Pair(WL.layer_weights(256, 256), P, P, "f32", 32)
+    X, D = WL.normal((32, 256), 21), WL.normal((32, 256), 22)
+    pair.product(FWD, X)
+    pair.product(BWD, D)
+    pair.update(0.01)
+    pair.inject_weights([WL.make_fault(WEIGHT, 2, 1, step=0)])
+    pair.check_weights()
+    _, rep, _ = pair.product(FWD, X)
+    assert rep["verdict"] == CORRECTED and rep["located"] == [2]
+    _, rep, _ = pair.product(BWD, D)
+    assert rep["verdict"] == CORRECTED and rep["located"] == [1]
+    # the paper's sparse law on a parity-column block: only the backward product sees it
+    pair.inject_weights([WL.make_fault(WEIGHT, 0, 5, step=1, lo=-5.0, hi=5.0, mode=WL.MODE_SPARSE_ABS, density=0.005)])
+    pair.check_weights()
+    _, rep, _ = pair.product(BWD, D, check_margins=False)
+    assert rep["verdict"] == UNCORRECTABLE        # columns 1 and 5 are now both erroneous, t = 1
+    pair.close()
+
+
+# ------------------------------------------------------------------ API error paths
+def test_api_errors_on_the_gpu():
+    import torch
+    from paper_1903_01042_amd import binding as B
+    P = WL.vandermonde_like(2, 2)
+    W = torch.zeros((64, 64), device="cuda")
+    lay = B.CodedLayer(W, P, P, max_batch=8)
+    with pytest.raises(B.CodenetError) as e:
+        lay.update(0.1)
+    assert e.value.code == B.E_ORDER
+    with pytest.raises(B.CodenetError) as e:
+        lay.forward(torch.zeros((9, 64), device="cuda"))
+    assert e.value.code == B.E_BATCH
+    S = lay.forward(torch.zeros((8, 64), device="cuda"))
+    with pytest.raises(B.CodenetError) as e:
+        lay.update(0.1)                      # forward only
+    assert e.value.code == B.E_ORDER
+    lay.backward(torch.zeros((4, 64), device="cuda"))
+    with pytest.raises(B.CodenetError) as e:
+        lay.update(0.1)                      # batches differ
+    assert e.value.code == B.E_ORDER
+    with pytest.raises(B.CodenetError) as e:
+        lay.inject([WL.make_fault(FWD, 1, 2, 0)], S)      # column 2 is a parity column: inactive in forward
+    assert e.value.code == B.E_FAULT
+    with pytest.raises(B.CodenetError) as e:
+        lay.inject([WL.make_fault(WEIGHT, 3, 3, 0)])      # corner holds no node
+    assert e.value.code == B.E_FAULT
+    with pytest.raises(B.CodenetError) as e:
+        B.CodedLayer(W, np.array([[1.0, 2.0], [1.0, 2.0]]), P, max_batch=8)
+    assert e.value.code == B.E_CODE
+    torch.cuda.synchronize()
+    lay.destroy()
