@@ -1,0 +1,273 @@
+#!/usr/bin/env python3
+"""Benchmark of the coded layer step on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input:
+coded forward product, fault injection, check + decode, coded backward product,
+fault injection, check + decode, coded update.  Inputs are resident in HBM
+before the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3]
+"""
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg3", "cfg5"])
+    ap.add_argument("--cpu-steps", type=int, default=12, help="oracle layer-steps timed for cpu_baseline (0 = skip)")
+    ap.add_argument("--no-faults", action="store_true", help="run the coded path without injecting faults")
+    ap.add_argument("--coded-only", action="store_true", help="skip the uncoded baseline and the CPU oracle (profiling runs)")
+    ap.add_argument("--eager", action="store_true", help="launch every call from Python instead of replaying hipGraphs")
+    return ap.parse_args()
+
+
+class Runner:
+    """Pre-marshalled calls of one single-layer workload (coded or uncoded)."""
+
+    RING = 8
+
+    def __init__(self, wl, coded, faults_on, total_steps):
+        import torch
+        from paper_1903_01042_amd import binding as B
+        from paper_1903_01042_amd import workloads as WL
+        self.torch, self.B, self.wl = torch, B, wl
+        self.lib = B.load_library()
+        dev = torch.device("cuda:0")
+        n_in, n_out = wl.widths[0], wl.widths[1]
+        m, n = wl.grid
+        self.b = wl.batch
+        self.coded = coded
+        W = torch.from_numpy(WL.layer_weights(n_out, n_in)).to(dev)
+        if coded:
+            P_r, P_c = wl.generators()
+        else:
+            P_r, P_c = np.zeros((m, 0)), np.zeros((n, 0))
+        self.layer = B.CodedLayer(W, P_r, P_c, dtype=B.BF16_F32ACC if wl.dtype == "bf16" else B.F32,
+                                  max_batch=wl.batch, tau_detect=wl.tau_detect, tau_resid=wl.tau_resid)
+        L = self.layer
+        self.X = [torch.from_numpy(wl.inputs(s)).to(dev) for s in range(self.RING)]
+        self.D = [torch.from_numpy(wl.deltas(s)).to(dev) for s in range(self.RING)]
+        self.St = torch.empty((self.b, L.coded_rows), dtype=torch.float32, device=dev)
+        self.Ct = torch.empty((self.b, L.coded_cols), dtype=torch.float32, device=dev)
+        self.S = torch.empty((self.b, n_out), dtype=torch.float32, device=dev)
+        self.C = torch.empty((self.b, n_in), dtype=torch.float32, device=dev)
+        self.reports = torch.zeros((total_steps, 2, B.REPORT_BYTES), dtype=torch.uint8, device=dev)
+        self.faults = []
+        for s in range(total_steps):
+            ff = wl.product_faults(WL.PHASE_FWD, s) if (coded and faults_on) else []
+            fb = wl.product_faults(WL.PHASE_BWD, s) if (coded and faults_on) else []
+            self.faults.append(((B.pack_faults(ff), len(ff)), (B.pack_faults(fb), len(fb))))
+        self.h = L._h
+        vp = ctypes.c_void_p
+        self.pX = [vp(t.data_ptr()) for t in self.X]
+        self.pD = [vp(t.data_ptr()) for t in self.D]
+        self.pSt, self.pCt, self.pS, self.pC = (vp(t.data_ptr()) for t in (self.St, self.Ct, self.S, self.C))
+        self.eta = ctypes.c_float(wl.eta)
+        self.flops = dict(fwd=2.0 * L.coded_rows * (n * L.B_c) * self.b,
+                          bwd=2.0 * (m * L.B_r) * L.coded_cols * self.b,
+                          upd=2.0 * L.coded_rows * L.coded_cols * self.b)
+        self.weight_bytes = 4.0 * L.coded_rows * L.coded_cols
+
+    def pre_update(self, s, stream):
+        """forward, faults, check, backward, faults, check of step s (everything but the update)."""
+        lib, h, b = self.lib, self.h, self.b
+        k = s % self.RING
+        rc = lib.codenet_forward(h, self.pX[k], b, self.pSt, stream)
+        if self.coded:
+            (ff, nf), (fb, nb) = self.faults[s]
+            if nf:
+                rc |= lib.codenet_inject(h, ff, nf, self.pSt, b, stream)
+            rc |= lib.codenet_detect_decode(h, 0, self.pSt, b, self.pS,
+                                            ctypes.c_void_p(self.reports[s, 0].data_ptr()), stream)
+        rc |= lib.codenet_backward(h, self.pD[k], b, self.pCt, stream)
+        if self.coded:
+            if nb:
+                rc |= lib.codenet_inject(h, fb, nb, self.pCt, b, stream)
+            rc |= lib.codenet_detect_decode(h, 1, self.pCt, b, self.pC,
+                                            ctypes.c_void_p(self.reports[s, 1].data_ptr()), stream)
+        if rc:
+            raise RuntimeError("a codenet call failed in step %d (rc=%d)" % (s, rc))
+
+    def update(self, stream):
+        rc = self.lib.codenet_update(self.h, self.eta, stream)
+        if rc:
+            raise RuntimeError("codenet_update failed (rc=%d)" % rc)
+
+    def capture(self, total_steps):
+        """One hipGraph per step for everything before the update, one for the update
+        (a single kernel, so that events around its replay time exactly that kernel).
+        The library only enqueues kernels, so its calls can be captured as they are."""
+        torch = self.torch
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):          # first use outside capture (function attributes are set once)
+            st = ctypes.c_void_p(side.cuda_stream)
+            self.pre_update(0, st)
+            self.update(st)
+        side.synchronize()
+        self.graphs = []
+        for s in range(total_steps):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                self.pre_update(s, ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+            self.graphs.append(g)
+        # forward/backward must have run (eagerly or in a replay) before the update is captured
+        self.upd_graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(self.upd_graph, stream=side):
+            self.update(ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+        torch.cuda.synchronize()
+
+    def run(self, steps, warmup, eager):
+        torch = self.torch
+        stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+        if not eager:
+            self.capture(steps + warmup)
+
+        def one(s, ev=None):
+            if eager:
+                self.pre_update(s, stream)
+            else:
+                self.graphs[s].replay()
+            if ev is not None:
+                ev[0].record()
+            if eager:
+                self.update(stream)
+            else:
+                self.upd_graph.replay()
+            if ev is not None:
+                ev[1].record()
+
+        for s in range(warmup):
+            one(s)
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for s in range(steps):
+            one(warmup + s, evs[s])
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        upd_ms = float(np.mean([a.elapsed_time(c) for a, c in evs]))
+        return (t1 - t0) * 1e3 / steps, upd_ms
+
+    def verdict_counts(self, lo, hi):
+        B = self.B
+        raw = self.reports[lo:hi].cpu().numpy()
+        counts = {"clean": 0, "corrected": 0, "uncorrectable": 0}
+        for s in range(raw.shape[0]):
+            for p in range(2):
+                v = B.Report.from_buffer_copy(raw[s, p].tobytes()).verdict
+                counts[["clean", "corrected", "uncorrectable"][v]] += 1
+        return counts
+
+
+def cpu_baseline(wl, steps):
+    """The float64 oracle as it stands, timed on the host for a few layer-steps of
+    the same workload (encoding excluded, as on the GPU)."""
+    from oracle import codenet_oracle as O
+    from paper_1903_01042_amd import workloads as WL
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    n_in, n_out = wl.widths[0], wl.widths[1]
+    P_r, P_c = wl.generators()
+    lay = O.CodedLayer(WL.layer_weights(n_out, n_in), P_r, P_c, tau_detect=wl.tau_detect, tau_resid=wl.tau_resid)
+    t0 = time.perf_counter()
+    for s in range(steps):
+        X = wl.inputs(s).T.astype(np.float64)
+        D = wl.deltas(s).T.astype(np.float64)
+        out = lay.inject(wl.product_faults(WL.PHASE_FWD, s), lay.forward(X))
+        lay.detect_decode(O.PHASE_FWD, out)
+        out = lay.inject(wl.product_faults(WL.PHASE_BWD, s), lay.backward(D))
+        lay.detect_decode(O.PHASE_BWD, out)
+        lay.update(wl.eta)
+    dt = time.perf_counter() - t0
+    return {"value": steps / dt, "unit": "coded layer-steps/s", "cores": int(cores), "kind": "oracle",
+            "sample": "%d full-size layer-steps of %s (float64 numpy, encoding excluded)" % (steps, wl.name)}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the path has no cross-GPU part); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_1903_01042_amd import workloads as WL
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    wl = WL.WORKLOADS[args.workload]
+    total = args.steps + args.warmup
+
+    coded = Runner(wl, True, not args.no_faults, total)
+    ms_coded, upd_ms = coded.run(args.steps, args.warmup, args.eager)
+    counts = coded.verdict_counts(args.warmup, total)
+    if args.coded_only:
+        print(json.dumps({"ms_per_step": ms_coded, "update_kernel_ms": upd_ms, "verdicts": counts, "workload": wl.name}))
+        return
+    uncoded = Runner(wl, False, False, total)
+    ms_uncoded, upd_ms_unc = uncoded.run(args.steps, args.warmup, args.eager)
+
+    L = coded.layer
+    flops_step = sum(coded.flops.values())
+    m, n = wl.grid
+    floor = sum(coded.flops.values()) / sum(uncoded.flops.values()) - 1.0
+    # dominant kernel: the update, a read-modify-write of the whole fp32 coded matrix.
+    # algorithmic bytes per launch: read + write W~ (2 * 4 B per element), the bf16 operand copies
+    # of W~ that the two products read (bf16 mode: 2 * 2 B per element), both coded vectors once
+    elem = 2.0 if wl.dtype == "bf16" else 4.0
+    upd_bytes = 2.0 * coded.weight_bytes + elem * coded.b * (L.coded_rows + L.coded_cols)
+    if wl.dtype == "bf16":
+        upd_bytes += coded.weight_bytes
+    achieved = upd_bytes / (upd_ms * 1e-3) / 1e9
+    out = {
+        "metric": "coded layer-steps/s (fwd+bwd+detect/decode+update)",
+        "value": 1e3 / ms_coded,
+        "unit": "coded layer-steps/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_coded,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": wl.name, "layer": "%dx%d" % (wl.widths[1], wl.widths[0]),
+                   "grid": "%dx%d+%d" % (m, n, wl.r), "batch": wl.batch, "fault_law": wl.fault_law,
+                   "launch": "eager, one stream" if args.eager else "hipGraph replay (one graph per step + update), one stream"},
+        "tflops": flops_step / (ms_coded * 1e-3) / 1e12,
+        "mfma_frac_of_peak_whole_step": flops_step / (ms_coded * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS[wl.dtype],
+        "uncoded_ms_per_step": ms_uncoded,
+        "coding_overhead": ms_coded / ms_uncoded - 1.0,
+        "algorithmic_overhead_floor": floor,
+        "verdicts": counts,
+        "update_kernel_ms_uncoded": upd_ms_unc,
+        "roofline": {"kernel": "update2_kernel (W~ += eta [d;d~][x;x~]^T, fp32 RMW + bf16 operand copies)"
+                     if wl.dtype == "bf16" else "gemm_kernel (update, W~ += eta [d;d~][x;x~]^T)", "bound": "hbm",
+                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "avg_launch_ms": upd_ms, "algorithmic_bytes": upd_bytes,
+                     "tflops": coded.flops["upd"] / (upd_ms * 1e-3) / 1e12},
+    }
+    coded.layer.destroy()
+    uncoded.layer.destroy()
+    if args.cpu_steps > 0:
+        out["cpu_baseline"] = cpu_baseline(wl, args.cpu_steps)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -23,6 +23,16 @@ struct codenet_layer {
   double *partials = nullptr;   // [kDetectParts][kMaxEntries]
   double *fault_partials = nullptr;   // [CODENET_MAX_FAULTS][kFaultParts]
   DevPlan *plan = nullptr;
+  // bf16 mode only: k-contiguous bf16 operands of the two products
+  __bf16 *Wb = nullptr;         // [Mr][ldWb]   row-major copy of W~ (forward)
+  __bf16 *WTb = nullptr;        // [Nc][ldWTb]  transposed copy of W~ (backward)
+  __bf16 *Xb = nullptr;         // [max_batch][KpX]  x, zero beyond the base columns
+  __bf16 *Db = nullptr;         // [max_batch][KpD]  delta, zero beyond the base rows
+  __bf16 *XTb = nullptr;        // [Nc][bpad]   feature-major [x; x~] (update)
+  __bf16 *DTb = nullptr;        // [Mr][bpad]   feature-major [delta; delta~] (update)
+  float *part = nullptr;        // split-k partial results: [kMaxSplits][max_batch][max(Mr, Nc)]
+  long ldWb = 0, ldWTb = 0;
+  int KpX = 0, KpD = 0, bpad = 0;
   int fwd_b = 0, bwd_b = 0;     // batch of the cached vectors (0 = none)
   bool bf16 = false;
 };
@@ -121,6 +131,8 @@ void free_layer(codenet_layer *l) {
   (void)hipFree(l->Wt); (void)hipFree(l->Xt); (void)hipFree(l->Dt); (void)hipFree(l->syn);
   (void)hipFree(l->partials); (void)hipFree(l->fault_partials); (void)hipFree(l->plan);
   (void)hipFree(l->code_r_dev); (void)hipFree(l->code_c_dev);
+  (void)hipFree(l->Wb); (void)hipFree(l->WTb); (void)hipFree(l->Xb); (void)hipFree(l->Db);
+  (void)hipFree(l->XTb); (void)hipFree(l->DTb); (void)hipFree(l->part);
   delete l;
 }
 
@@ -185,6 +197,29 @@ int codenet_encode(const codenet_desc *d, const float *W_dev, void *stream, code
   alloc((void **)&l->plan, sizeof(DevPlan));
   alloc((void **)&l->code_r_dev, sizeof(DevCode));
   alloc((void **)&l->code_c_dev, sizeof(DevCode));
+  if (l->bf16) {
+    auto up64 = [](long v) { return (v + 63) & ~63L; };
+    l->ldWb = up64(l->Nc);
+    l->ldWTb = up64(l->Mr);
+    l->KpX = (int)up64((long)l->code_c.a * l->code_c.B);
+    l->KpD = (int)up64((long)l->code_r.a * l->code_r.B);
+    const size_t szWb = 2 * (size_t)l->Mr * l->ldWb, szWTb = 2 * (size_t)l->Nc * l->ldWTb;
+    const size_t szXb = 2 * mb * l->KpX, szDb = 2 * mb * l->KpD;
+    l->bpad = (int)up64((long)mb);
+    alloc((void **)&l->XTb, 2 * (size_t)l->Nc * l->bpad);
+    alloc((void **)&l->DTb, 2 * (size_t)l->Mr * l->bpad);
+    alloc((void **)&l->part, sizeof(float) * (size_t)kMaxSplits * mb * std::max(l->Mr, l->Nc));
+    alloc((void **)&l->Wb, szWb);
+    alloc((void **)&l->WTb, szWTb);
+    alloc((void **)&l->Xb, szXb);
+    alloc((void **)&l->Db, szDb);
+    // pitch padding and the tails beyond the base blocks stay zero for the layer's life
+    what = "clearing the bf16 operands";
+    if (e == hipSuccess) e = hipMemsetAsync(l->Wb, 0, szWb, s);
+    if (e == hipSuccess) e = hipMemsetAsync(l->WTb, 0, szWTb, s);
+    if (e == hipSuccess) e = hipMemsetAsync(l->Xb, 0, szXb, s);
+    if (e == hipSuccess) e = hipMemsetAsync(l->Db, 0, szDb, s);
+  }
   if (e == hipSuccess) {
     what = "copy of the code tables";
     e = hipMemcpyAsync(l->code_r_dev, &l->code_r, sizeof(DevCode), hipMemcpyHostToDevice, s);
@@ -193,6 +228,10 @@ int codenet_encode(const codenet_desc *d, const float *W_dev, void *stream, code
   if (e == hipSuccess) {
     what = "encode kernel launch";
     e = launch_encode_matrix(W_dev, l->Wt, l->code_r_dev, l->code_c_dev, l->Mr, l->Nc, d->n_out, d->n_in, s);
+  }
+  if (e == hipSuccess && l->bf16) {
+    what = "bf16 copies of the coded matrix";
+    e = launch_shadow(l->Wt, l->Mr, l->Nc, l->Wb, l->ldWb, l->WTb, l->ldWTb, s);
   }
   // the host copies of the code tables must outlive the asynchronous copies above
   if (e == hipSuccess) {
@@ -222,7 +261,22 @@ int codenet_forward(codenet_layer *l, const float *X_dev, int b, float *S_coded_
   if (b < 1 || b > l->desc.max_batch) return CODENET_E_BATCH;
   hipStream_t s = (hipStream_t)stream;
   l->fwd_b = 0;
-  CN_HIP(launch_encode_vector(X_dev, l->Xt, l->code_c_dev, l->code_c, b, s));
+  if (l->bf16) {
+    int tile = 0, splits = 1;
+    plan_gemm2(l->Mr, b, l->KpX, kMaxSplits, &tile, &splits);
+    CN_HIP(launch_encode_vector(X_dev, l->Xt, l->code_c_dev, l->code_c, b, l->Xb, l->KpX, nullptr, 0, s));
+    Gemm2Args g2{};
+    g2.A = l->Wb; g2.lda = l->ldWb;
+    g2.B = l->Xb; g2.ldb = l->KpX;
+    g2.C = S_coded_dev; g2.ldc = l->Mr;
+    g2.I = l->Mr; g2.J = b; g2.K = l->KpX; g2.splits = splits;
+    CN_HIP(launch_gemm2(g2, tile, l->part, s));
+    // feature-major bf16 copy of [x; x~] for the update
+    CN_HIP(launch_transpose_bf16(l->Xt, l->Nc, b, l->Nc, l->XTb, l->bpad, (b + 63) & ~63, s));
+    l->fwd_b = b;
+    return CODENET_OK;
+  }
+  CN_HIP(launch_encode_vector(X_dev, l->Xt, l->code_c_dev, l->code_c, b, nullptr, 0, nullptr, 0, s));
   GemmArgs g{};
   g.A = l->Wt; g.lda = l->Nc;                 // A[i][k] = W~[i][k], k over the base columns
   g.B = l->Xt; g.ldb = l->Nc;                 // B[j][k] = x[j][k]
@@ -239,7 +293,21 @@ int codenet_backward(codenet_layer *l, const float *D_dev, int b, float *C_coded
   if (b < 1 || b > l->desc.max_batch) return CODENET_E_BATCH;
   hipStream_t s = (hipStream_t)stream;
   l->bwd_b = 0;
-  CN_HIP(launch_encode_vector(D_dev, l->Dt, l->code_r_dev, l->code_r, b, s));
+  if (l->bf16) {
+    int tile = 0, splits = 1;
+    plan_gemm2(l->Nc, b, l->KpD, kMaxSplits, &tile, &splits);
+    CN_HIP(launch_encode_vector(D_dev, l->Dt, l->code_r_dev, l->code_r, b, l->Db, l->KpD, nullptr, 0, s));
+    Gemm2Args g2{};
+    g2.A = l->WTb; g2.lda = l->ldWTb;
+    g2.B = l->Db; g2.ldb = l->KpD;
+    g2.C = C_coded_dev; g2.ldc = l->Nc;
+    g2.I = l->Nc; g2.J = b; g2.K = l->KpD; g2.splits = splits;
+    CN_HIP(launch_gemm2(g2, tile, l->part, s));
+    CN_HIP(launch_transpose_bf16(l->Dt, l->Mr, b, l->Mr, l->DTb, l->bpad, (b + 63) & ~63, s));
+    l->bwd_b = b;
+    return CODENET_OK;
+  }
+  CN_HIP(launch_encode_vector(D_dev, l->Dt, l->code_r_dev, l->code_r, b, nullptr, 0, nullptr, 0, s));
   GemmArgs g{};
   g.A = l->Wt; g.lda = l->Nc;                 // A[i][k] = W~[k][i], k over the base rows
   g.B = l->Dt; g.ldb = l->Mr;                 // B[j][k] = delta[j][k]
@@ -255,13 +323,26 @@ int codenet_update(codenet_layer *l, float eta, void *stream) {
   if (!l) return CODENET_E_NULL;
   if (l->fwd_b < 1 || l->fwd_b != l->bwd_b) return CODENET_E_ORDER;
   hipStream_t s = (hipStream_t)stream;
+  if (l->bf16) {
+    const int bp = (l->fwd_b + 63) & ~63;
+    Update2Args u{};
+    u.XT = l->XTb; u.ldx = l->bpad;
+    u.DT = l->DTb; u.ldd = l->bpad;
+    u.W = l->Wt; u.ldw = l->Nc;
+    u.Wb = l->Wb; u.ldWb = l->ldWb;
+    u.WTb = l->WTb; u.ldWTb = l->ldWTb;
+    u.I = l->Nc; u.J = l->Mr; u.K = bp; u.eta = eta;
+    CN_HIP(launch_update2(u, s));
+    l->fwd_b = l->bwd_b = 0;
+    return CODENET_OK;
+  }
   GemmArgs g{};
   g.A = l->Xt; g.lda = l->Nc;                 // A[i][k] = x~[k][i]     (i = coded column, k = batch)
   g.B = l->Dt; g.ldb = l->Mr;                 // B[j][k] = delta~[k][j] (j = coded row)
   g.C = l->Wt; g.ldc = l->Nc;
   g.I = l->Nc; g.J = l->Mr; g.K = l->fwd_b;
   g.alpha = eta;
-  CN_HIP(launch_gemm(kUpd, l->bf16, g, s));
+  CN_HIP(launch_gemm(kUpd, false, g, s));
   l->fwd_b = l->bwd_b = 0;
   return CODENET_OK;
 }
@@ -334,6 +415,8 @@ int codenet_inject(codenet_layer *l, const codenet_fault *faults, int n_faults, 
   for (int f = 0; f < n_faults; ++f)
     if (fa[f].mode == CODENET_NOISE_DENSE_REL) CN_HIP(launch_fault(fa[f], s, true));
   for (int f = 0; f < n_faults; ++f) CN_HIP(launch_fault(fa[f], s, false));
+  if (phase == CODENET_WEIGHT && l->bf16)
+    CN_HIP(launch_shadow(l->Wt, l->Mr, l->Nc, l->Wb, l->ldWb, l->WTb, l->ldWTb, s));
   return CODENET_OK;
 }
 

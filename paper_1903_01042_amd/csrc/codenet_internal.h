@@ -7,7 +7,7 @@
 namespace codenet {
 
 constexpr int kDetectParts = 512;      // most per-workgroup partial records of one check
-constexpr int kFaultParts = 32;        // partial sums of squares per fault
+constexpr int kFaultParts = 128;       // partial sums of squares per fault
 constexpr int kMaxGram = CODENET_MAX_R * (CODENET_MAX_R + 1) / 2;
 constexpr int kMaxEntries = CODENET_MAX_L + kMaxGram;
 
@@ -45,6 +45,34 @@ enum GemmLayout { kFwd = 0, kBwd = 1, kUpd = 2 };
 // upd: A k-strided   , B k-strided   , C += alpha A B^T
 hipError_t launch_gemm(GemmLayout layout, bool bf16, const GemmArgs &args, hipStream_t stream);
 
+// bf16 operands, k contiguous and zero padded to a multiple of 64; C[j][i] fp32
+struct Gemm2Args {
+  const __bf16 *A; long lda;
+  const __bf16 *B; long ldb;
+  float *C; long ldc;
+  int I, J, K;
+  int tiles_i, tiles_j, splits;
+  long split_stride;
+};
+struct Update2Args {
+  const __bf16 *XT; long ldx;    // [I = coded columns][batch padded to 64]
+  const __bf16 *DT; long ldd;    // [J = coded rows][batch padded to 64]
+  float *W; long ldw;            // fp32 coded matrix [J][I]
+  __bf16 *Wb; long ldWb;         // its bf16 copy, row-major
+  __bf16 *WTb; long ldWTb;       // its bf16 copy, transposed
+  int I, J, K;
+  float eta;
+  int tiles_i, tiles_j;
+};
+constexpr int kMaxSplits = 8;
+void plan_gemm2(int I, int J, int K, int max_splits, int *tile, int *splits);
+hipError_t launch_gemm2(Gemm2Args g, int tile, float *workspace, hipStream_t s);
+hipError_t launch_update2(Update2Args g, hipStream_t s);
+hipError_t launch_transpose_bf16(const float *in, long ld_in, int R, int C, void *out, long ld_out, int Rpad,
+                                 hipStream_t s);
+hipError_t launch_shadow(const float *Wt, int Mr, int Nc, void *Wb, long ldWb, void *WTb, long ldWTb,
+                         hipStream_t s);
+
 struct FaultArgs {
   float *base;                  // first element of the target payload
   long stride_outer;            // element (outer, inner) at base[outer * stride_outer + inner]
@@ -59,8 +87,10 @@ struct FaultArgs {
 
 hipError_t launch_encode_matrix(const float *W, float *Wt, const DevCode *code_r, const DevCode *code_c,
                                 int Mr, int Nc, int n_out, int n_in, hipStream_t s);
+// Vb (optional): bf16 batch-major copy of the systematic part, pitch ldVb.
+// zero (optional): zero_count4 float4 of a buffer to clear in the same pass.
 hipError_t launch_encode_vector(const float *V, float *Vt, const DevCode *code_dev, const DevCode &code_host,
-                                int b, hipStream_t s);
+                                int b, void *Vb, long ldVb, float *zero, long zero_count4, hipStream_t s);
 hipError_t launch_detect(const float *out, float *syn, double *partials, int *n_parts,
                          const DevCode *code_dev, const DevCode &code_host, int b, hipStream_t s);
 hipError_t launch_decide(const double *partials, int n_parts, const DevCode *code_dev, const DevCode &code_host,

@@ -1,0 +1,591 @@
+// bf16 MFMA kernels of the coded products (O1, O2) and of the coded update (O3) for gfx950.
+//
+// C[j][i] (+)= sum_k A[i][k] B[j][k] with A and B bf16 in memory, k contiguous
+// ("shadow" copies of the fp32 coded matrix and of the coded vectors, k padded
+// with zeros to a multiple of 64), fp32 accumulation, fp32 result.
+//
+// What bounds this contraction at the benchmark shape (5120 x 512 x 4096) is not
+// the MFMA rate but how fast operand slabs reach LDS: a 64-deep slab must be in
+// flight for about one HBM latency.  So:
+//  * slabs go global -> LDS directly (global_load_lds_dwordx4, no VGPR staging),
+//    NS stages deep; a stage is consumed NS-1 iterations after it was requested;
+//  * completion is tracked by hand: s_waitcnt vmcnt(n) leaves the younger
+//    slabs in flight, one s_barrier per slab;
+//  * fragments are read from LDS with ds_read_b128 issued from inline asm one
+//    k-step ahead of the MFMAs that use them (the compiler would otherwise
+//    drain every outstanding direct-to-LDS load before each LDS read);
+//  * LDS rows are 128 bytes (64 bf16); 16-byte chunk c of row r sits at slot
+//    c ^ (r & 7): fragment reads (32 consecutive rows, one chunk) touch every
+//    bank once; the direct-to-LDS writes are linear per wavefront, and the
+//    swizzle is applied by choosing which global chunk each lane fetches;
+//  * a workgroup (4 wavefronts, 2 x 2) computes a (64 FM) x (64 FN) tile over a
+//    contiguous range of slabs (split-k); with more than one split every split
+//    stores its partial tile to a workspace and a second kernel adds the
+//    partial results in a fixed order (fp32 atomics at L2 were measured to be
+//    several times slower than the whole product, and are order dependent).
+//  * workgroup ids are dealt to the 8 XCDs round-robin by the hardware; the
+//    id -> tile map gives every XCD a contiguous run of tiles so that tiles
+//    sharing an A panel share an L2.
+#include "codenet_internal.h"
+
+namespace codenet {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+#define CN_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
+
+// The inline asm below only exists in the device pass: the host pass must still
+// be able to instantiate the kernel template to emit its launch stub.
+#if defined(__HIP_DEVICE_COMPILE__)
+#define CN_DEVICE_ASM 1
+#else
+#define CN_DEVICE_ASM 0
+#endif
+
+template <int OFF>
+__device__ __forceinline__ u32x4 lds_read16(unsigned addr) {
+  u32x4 v = {0u, 0u, 0u, 0u};
+#if CN_DEVICE_ASM
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
+#endif
+  return v;
+}
+
+// N fragments of 32 rows each (4096 bytes apart) at the same chunk slot
+template <int N>
+__device__ __forceinline__ void read_frags(u32x4 (&f)[N], unsigned addr) {
+  f[0] = lds_read16<0>(addr);
+  if constexpr (N > 1) f[1] = lds_read16<4096>(addr);
+  if constexpr (N > 2) f[2] = lds_read16<8192>(addr);
+  if constexpr (N > 3) f[3] = lds_read16<12288>(addr);
+}
+
+template <int N>
+__device__ __forceinline__ void wait_lgkm() {
+#if CN_DEVICE_ASM
+  asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N) : "memory");
+#endif
+}
+template <int N>
+__device__ __forceinline__ void wait_vm() {
+#if CN_DEVICE_ASM
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+#endif
+}
+// orders the consumers of v after every asm statement issued before this one
+__device__ __forceinline__ void pin(u32x4 &v) {
+#if CN_DEVICE_ASM
+  asm volatile("" : "+v"(v));
+#endif
+}
+
+// Main loop shared by the product and the update kernels: acc[a][b] += A-tile x B-tile^T
+// over slabs [kb, kb + nk) of 64.  acc rows (MFMA row index) run over j (B rows),
+// acc columns (lane % 32) over i (A rows): the B-side fragment is the first MFMA operand.
+template <int FM, int FN, int NS, int DBG = 0>
+__device__ __forceinline__ void mainloop(const __bf16 *__restrict__ A, long lda, const __bf16 *__restrict__ B,
+                                         long ldb, int I, int J, int i0, int j0, int kb, int nk, char *lds_c,
+                                         floatx16 (&acc)[FM][FN]) {
+  constexpr int TI = 64 * FM, TJ = 64 * FN;
+  constexpr int STAGE = (TI + TJ) * 128;              // bytes per stage
+  constexpr int LA = TI / 32, LB = TJ / 32;           // direct-to-LDS loads per lane and slab
+  constexpr int LPS = LA + LB;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wi = wave & 1, wj = wave >> 1;
+  const int l32 = lane & 31, h = lane >> 5;
+
+  // per-lane sources: lane l of load u fetches chunk (l & 7) ^ (l >> 3) of row 8 (4 u + wave) + (l >> 3)
+  const int lrow = lane >> 3;
+  const int chunk = (lane & 7) ^ lrow;
+  const __bf16 *srcA[LA];
+  const __bf16 *srcB[LB];
+#pragma unroll
+  for (int u = 0; u < LA; ++u) {
+    int row = i0 + 8 * (4 * u + wave) + lrow;
+    row = row < I ? row : I - 1;
+    srcA[u] = A + (long)row * lda + (long)kb * 64 + chunk * 8;
+  }
+#pragma unroll
+  for (int u = 0; u < LB; ++u) {
+    int row = j0 + 8 * (4 * u + wave) + lrow;
+    row = row < J ? row : J - 1;
+    srcB[u] = B + (long)row * ldb + (long)kb * 64 + chunk * 8;
+  }
+
+  // load u (0 .. LPS-1) of slab kt: A rows first, then B rows
+  auto issue_one = [&](int kt, int u) {
+#if CN_DEVICE_ASM
+    char *sbase = lds_c + (kt % NS) * STAGE;
+    if (u < LA)
+      __builtin_amdgcn_global_load_lds(srcA[u] + (long)kt * 64, CN_LDS_PTR(sbase + (4 * u + wave) * 1024), 16, 0, 0);
+    else
+      __builtin_amdgcn_global_load_lds(srcB[u - LA] + (long)kt * 64,
+                                       CN_LDS_PTR(sbase + TI * 128 + (4 * (u - LA) + wave) * 1024), 16, 0, 0);
+#else
+    (void)kt; (void)u;
+#endif
+  };
+  auto issue = [&](int kt) {
+#pragma unroll
+    for (int u = 0; u < LPS; ++u) issue_one(kt, u);
+  };
+
+  // fragment read addresses (bytes inside a stage) for the 4 k-steps of a slab
+  unsigned offA[4], offB[4];
+#pragma unroll
+  for (int s = 0; s < 4; ++s) {
+    const unsigned slot = (unsigned)(((2 * s + h) ^ (l32 & 7)) * 16);
+    offA[s] = (unsigned)((wi * FM * 32 + l32) * 128) + slot;
+    offB[s] = (unsigned)(TI * 128 + (wj * FN * 32 + l32) * 128) + slot;
+  }
+
+#pragma unroll
+  for (int s = 0; s < NS - 1; ++s)
+    if (s < nk && !(DBG & 1)) issue(s);
+
+  for (int kt = 0; kt < nk; ++kt) {
+    // slab kt must have landed; up to NS-2 younger slabs stay in flight
+    const int later = nk - 1 - kt;
+    if (NS >= 4 && later >= 2) wait_vm<2 * LPS>();
+    else if (NS >= 3 && later >= 1) wait_vm<LPS>();
+    else wait_vm<0>();
+    __builtin_amdgcn_s_barrier();
+    // The loads of slab kt + NS - 1 are issued a few at a time between the MFMAs
+    // of this slab: a wavefront issues in order, and a burst of direct-to-LDS
+    // loads would hold back its own MFMAs while the memory pipeline accepts them.
+    const bool prefetch = kt + NS - 1 < nk && !(DBG & 1);
+
+    const unsigned sb = (unsigned)((kt % NS) * STAGE);
+    u32x4 fa[2][FM], fb[2][FN];
+    if (DBG & 2) {
+#pragma unroll
+      for (int a = 0; a < FM; ++a) fa[0][a] = fa[1][a] = u32x4{(unsigned)kt, 1u, 2u, 3u};
+#pragma unroll
+      for (int b = 0; b < FN; ++b) fb[0][b] = fb[1][b] = u32x4{(unsigned)kt, 1u, 2u, 3u};
+    } else {
+      read_frags<FM>(fa[0], sb + offA[0]);
+      read_frags<FN>(fb[0], sb + offB[0]);
+    }
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const int cur = s & 1, nxt = cur ^ 1;
+      if (DBG & 2) {
+      } else if (s < 3) {
+        read_frags<FM>(fa[nxt], sb + offA[s + 1]);
+        read_frags<FN>(fb[nxt], sb + offB[s + 1]);
+        wait_lgkm<FM + FN>();      // LDS returns in order: the older step's fragments are in
+      } else {
+        wait_lgkm<0>();
+      }
+#pragma unroll
+      for (int a = 0; a < FM; ++a) pin(fa[cur][a]);
+#pragma unroll
+      for (int b = 0; b < FN; ++b) pin(fb[cur][b]);
+      if (DBG & 4) {
+#pragma unroll
+        for (int a = 0; a < FM; ++a) acc[a][0][0] += __builtin_bit_cast(float, fa[cur][a][0]);
+#pragma unroll
+        for (int b = 0; b < FN; ++b) acc[0][b][1] += __builtin_bit_cast(float, fb[cur][b][0]);
+        continue;
+      }
+      constexpr int LQ = LPS / 4;            // loads issued during one k-step
+      constexpr int MPL = (FM * FN) / LQ;    // MFMAs between two loads
+#pragma unroll
+      for (int a = 0; a < FM; ++a)
+#pragma unroll
+        for (int b = 0; b < FN; ++b) {
+          const int m = a * FN + b;
+          if (m % MPL == 0 && m / MPL < LQ) {
+            if (prefetch) issue_one(kt + NS - 1, s * LQ + m / MPL);
+            __builtin_amdgcn_sched_barrier(0);
+          }
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fb[cur][b]),
+                                                              __builtin_bit_cast(bf16x8, fa[cur][a]), acc[a][b], 0, 0, 0);
+        }
+    }
+  }
+}
+
+// workgroup id -> (tile, split): consecutive ids land on different XCDs, so give
+// every XCD a contiguous run of logical tiles (tiles sharing an A panel share an L2)
+__device__ __forceinline__ int logical_workgroup(int total) {
+  const int per = (total + 7) >> 3;
+  const int logical = (int)(blockIdx.x & 7) * per + (int)(blockIdx.x >> 3);
+  return logical < total ? logical : -1;
+}
+
+template <int FM, int FN, int NS, int DBG = 0>
+__global__ __launch_bounds__(256) void gemm2_kernel(Gemm2Args g) {
+  constexpr int TI = 64 * FM, TJ = 64 * FN;
+  extern __shared__ uint4 lds[];
+  const int logical = logical_workgroup(g.tiles_i * g.tiles_j * g.splits);
+  if (logical < 0) return;
+  const int tj = logical % g.tiles_j;
+  const int rest = logical / g.tiles_j;
+  const int split = rest % g.splits, ti = rest / g.splits;
+  const int i0 = ti * TI, j0 = tj * TJ;
+  const int kslabs = g.K >> 6;
+  const int kb = (int)((long)split * kslabs / g.splits);
+  const int ke = (int)((long)(split + 1) * kslabs / g.splits);
+
+  floatx16 acc[FM][FN];
+#pragma unroll
+  for (int a = 0; a < FM; ++a)
+#pragma unroll
+    for (int b = 0; b < FN; ++b)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.f;
+  mainloop<FM, FN, NS, DBG>(g.A, g.lda, g.B, g.ldb, g.I, g.J, i0, j0, kb, ke - kb, reinterpret_cast<char *>(lds), acc);
+
+  // Accumulator element 4 q + e of a 32 x 32 tile is (j = 8 q + 4 h + e, i = lane % 32):
+  // for one (q, e) the 32 lanes of a half-wavefront write 128 contiguous bytes of a row.
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int wi = wave & 1, wj = wave >> 1, l32 = lane & 31, h = lane >> 5;
+  float *C = g.C + (long)split * g.split_stride;
+#pragma unroll
+  for (int a = 0; a < FM; ++a)
+#pragma unroll
+    for (int b = 0; b < FN; ++b) {
+      const int i = i0 + (wi * FM + a) * 32 + l32;
+      if (i >= g.I) continue;
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int j = j0 + (wj * FN + b) * 32 + 8 * q + 4 * h + e;
+          if (j < g.J) C[(long)j * g.ldc + i] = acc[a][b][4 * q + e];
+        }
+    }
+}
+
+// out = sum over splits of the partial results, in split order
+__global__ __launch_bounds__(256) void reduce_partials_kernel(const float4 *__restrict__ part, long stride4,
+                                                              int splits, float4 *__restrict__ out, long count4) {
+  const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= count4) return;
+  float4 v = part[idx];
+  for (int s = 1; s < splits; ++s) {
+    const float4 w = part[(long)s * stride4 + idx];
+    v.x += w.x; v.y += w.y; v.z += w.z; v.w += w.w;
+  }
+  out[idx] = v;
+}
+
+// ---------------------------------------------------------------------------
+// Coded update (O3 with the three block rules, corner included):
+//   W~[j][i] += eta * sum_k delta~[j][k] x~[i][k]      (j coded row, i coded column, k batch)
+// Operands are the feature-major bf16 copies of the cached coded vectors.  The
+// epilogue reads-modifies-writes the fp32 matrix with fully coalesced dword
+// accesses and refreshes both bf16 copies of it: the row-major one and the
+// transposed one are staged through LDS so that they leave as 16-byte stores.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ unsigned pack2_bf16(float lo, float hi) {
+  const __bf16 a = (__bf16)lo, b = (__bf16)hi;
+  return (unsigned)__builtin_bit_cast(unsigned short, a) | ((unsigned)__builtin_bit_cast(unsigned short, b) << 16);
+}
+
+template <int FM, int FN, int NS>
+__global__ __launch_bounds__(256) void update2_kernel(Update2Args g) {
+  constexpr int TI = 64 * FM, TJ = 64 * FN;
+  constexpr int PT = TJ * 2 + 16;       // pitch of the transposed staging tile [i][j], bytes
+  constexpr int PR = TI * 2 + 16;       // pitch of the row-major staging tile [j][i], bytes
+  constexpr int ST = TI * PT;           // the row-major tile follows the transposed one
+  extern __shared__ uint4 lds[];
+  char *const lds_c = reinterpret_cast<char *>(lds);
+  const int logical = logical_workgroup(g.tiles_i * g.tiles_j);
+  if (logical < 0) return;
+  const int ti = logical % g.tiles_i, tj = logical / g.tiles_i;
+  const int i0 = ti * TI, j0 = tj * TJ;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wi = wave & 1, wj = wave >> 1, l32 = lane & 31, h = lane >> 5;
+
+  // The fp32 tile this workgroup will read-modify-write is requested before the
+  // main loop, so that its HBM latency is hidden behind the contraction.  Element
+  // x of fragment (a, b) is (j = 8 (x / 4) + 4 h + x % 4, i = lane % 32): for one x
+  // a half-wavefront touches 128 contiguous bytes of a row.
+  float old[FM][FN][16];
+#pragma unroll
+  for (int a = 0; a < FM; ++a)
+#pragma unroll
+    for (int b = 0; b < FN; ++b) {
+      const int i = i0 + (wi * FM + a) * 32 + l32;
+#pragma unroll
+      for (int x = 0; x < 16; ++x) {
+        const int j = j0 + (wj * FN + b) * 32 + 8 * (x >> 2) + 4 * h + (x & 3);
+        old[a][b][x] = (i < g.I && j < g.J) ? g.W[(long)j * g.ldw + i] : 0.f;
+      }
+    }
+
+  floatx16 acc[FM][FN];
+#pragma unroll
+  for (int a = 0; a < FM; ++a)
+#pragma unroll
+    for (int b = 0; b < FN; ++b)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.f;
+  mainloop<FM, FN, NS>(g.XT, g.ldx, g.DT, g.ldd, g.I, g.J, i0, j0, 0, g.K >> 6, lds_c, acc);
+
+  __syncthreads();                       // every wavefront is done with the operand stages
+#pragma unroll
+  for (int a = 0; a < FM; ++a)
+#pragma unroll
+    for (int b = 0; b < FN; ++b) {
+      const int il = (wi * FM + a) * 32 + l32;
+      const int i = i0 + il;
+      // 1. fp32 matrix: w = W~ + eta * acc, written back; entries outside the matrix become 0
+#pragma unroll
+      for (int x = 0; x < 16; ++x) {
+        const int j = j0 + (wj * FN + b) * 32 + 8 * (x >> 2) + 4 * h + (x & 3);
+        const bool in = i < g.I && j < g.J;
+        const float w = in ? fmaf(g.eta, acc[a][b][x], old[a][b][x]) : 0.f;
+        if (in) g.W[(long)j * g.ldw + i] = w;
+        acc[a][b][x] = w;
+      }
+      // 2. stage the bf16 value of w twice: transposed [i][j] and row-major [j][i]
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int jl = (wj * FN + b) * 32 + 8 * q + 4 * h;
+        uint2 pk;
+        pk.x = pack2_bf16(acc[a][b][4 * q], acc[a][b][4 * q + 1]);
+        pk.y = pack2_bf16(acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]);
+        *reinterpret_cast<uint2 *>(lds_c + il * PT + jl * 2) = pk;
+        *reinterpret_cast<unsigned short *>(lds_c + ST + (jl + 0) * PR + il * 2) = (unsigned short)(pk.x & 0xffffu);
+        *reinterpret_cast<unsigned short *>(lds_c + ST + (jl + 1) * PR + il * 2) = (unsigned short)(pk.x >> 16);
+        *reinterpret_cast<unsigned short *>(lds_c + ST + (jl + 2) * PR + il * 2) = (unsigned short)(pk.y & 0xffffu);
+        *reinterpret_cast<unsigned short *>(lds_c + ST + (jl + 3) * PR + il * 2) = (unsigned short)(pk.y >> 16);
+      }
+    }
+  __syncthreads();
+  // 3. both bf16 copies leave as rows of 16-byte chunks (the pitches are multiples
+  //    of 64 elements: whole chunks fit, and entries beyond the matrix are zeros)
+  for (int id = tid; id < TI * (TJ / 8); id += 256) {
+    const int row = id / (TJ / 8), cj = id % (TJ / 8);
+    const int i = i0 + row, j = j0 + cj * 8;
+    if (i < g.I && j < g.ldWTb)
+      *reinterpret_cast<uint4 *>(g.WTb + (long)i * g.ldWTb + j) = *reinterpret_cast<const uint4 *>(lds_c + row * PT + cj * 16);
+  }
+  for (int id = tid; id < TJ * (TI / 8); id += 256) {
+    const int row = id / (TI / 8), ci = id % (TI / 8);
+    const int j = j0 + row, i = i0 + ci * 8;
+    if (j < g.J && i < g.ldWb)
+      *reinterpret_cast<uint4 *>(g.Wb + (long)j * g.ldWb + i) = *reinterpret_cast<const uint4 *>(lds_c + ST + row * PR + ci * 16);
+  }
+}
+
+// out[c][r] = bf16(in[r][c]) for r < R, 0 for R <= r < Rpad (feature-major copy of a batch-major block)
+__global__ __launch_bounds__(256) void transpose_bf16_kernel(const float *__restrict__ in, long ld_in, int R, int C,
+                                                             __bf16 *__restrict__ out, long ld_out, int Rpad) {
+  __shared__ unsigned short tile[64][66];
+  const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+  const int t = threadIdx.x;
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    const int r = (t >> 4) + 16 * p, c = (t & 15) * 4;
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (r0 + r < R && c0 + c < C) v = *reinterpret_cast<const float4 *>(in + (long)(r0 + r) * ld_in + c0 + c);
+    const __bf16 b0 = (__bf16)v.x, b1 = (__bf16)v.y, b2 = (__bf16)v.z, b3 = (__bf16)v.w;
+    tile[r][c] = __builtin_bit_cast(unsigned short, b0);
+    tile[r][c + 1] = __builtin_bit_cast(unsigned short, b1);
+    tile[r][c + 2] = __builtin_bit_cast(unsigned short, b2);
+    tile[r][c + 3] = __builtin_bit_cast(unsigned short, b3);
+  }
+  __syncthreads();
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    const int c = (t >> 4) + 16 * p, r = (t & 15) * 4;
+    if (c0 + c < C && r0 + r < Rpad) {
+      uint2 pk;
+      pk.x = (unsigned)tile[r][c] | ((unsigned)tile[r + 1][c] << 16);
+      pk.y = (unsigned)tile[r + 2][c] | ((unsigned)tile[r + 3][c] << 16);
+      *reinterpret_cast<uint2 *>(out + (long)(c0 + c) * ld_out + r0 + r) = pk;
+    }
+  }
+}
+
+namespace {
+
+struct Tile2 { int fm, fn, ns; };
+const Tile2 kTiles2[] = {{4, 2, 3}, {2, 2, 4}, {2, 2, 2}, {4, 4, 2}, {2, 4, 3}};
+constexpr int kNumTiles2 = 5;
+
+template <typename K>
+hipError_t set_lds(K kern, int lds, bool *done) {
+  if (*done) return hipSuccess;
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+  if (e == hipSuccess) *done = true;
+  return e;
+}
+
+template <int FM, int FN, int NS, int DBG = 0>
+hipError_t launch2(Gemm2Args g, hipStream_t s) {
+  constexpr int lds = NS * (64 * FM + 64 * FN) * 128;
+  const int nt = g.tiles_i * g.tiles_j * g.splits;
+  const int grid = ((nt + 7) / 8) * 8;
+  static bool attr_done = false;
+  hipError_t e = set_lds(gemm2_kernel<FM, FN, NS, DBG>, lds, &attr_done);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((gemm2_kernel<FM, FN, NS, DBG>), dim3(grid), dim3(256), lds, s, g);
+  return hipGetLastError();
+}
+
+template <int FM, int FN, int NS>
+hipError_t launch_upd2(Update2Args g, hipStream_t s) {
+  constexpr int TI = 64 * FM, TJ = 64 * FN;
+  constexpr int stage = NS * (TI + TJ) * 128, st = TI * (TJ * 2 + 16) + TJ * (TI * 2 + 16);
+  constexpr int lds = stage > st ? stage : st;
+  static_assert(lds <= 160 * 1024, "staging tiles do not fit in LDS");
+  g.tiles_i = (g.I + TI - 1) / TI;
+  g.tiles_j = (g.J + TJ - 1) / TJ;
+  const int nt = g.tiles_i * g.tiles_j;
+  const int grid = ((nt + 7) / 8) * 8;
+  static bool attr_done = false;
+  hipError_t e = set_lds(update2_kernel<FM, FN, NS>, lds, &attr_done);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL((update2_kernel<FM, FN, NS>), dim3(grid), dim3(256), lds, s, g);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+// Picks tile and split count for an (I x J x K) product.  Measured on MI355X at
+// 5120 x 512 x 4096: 128 x 128 tiles, 4 stages, no split 41 us; 256 x 128 tiles
+// with 3 splits 34 us + 7 us for the ordered reduction.  The fixed cost of a
+// workgroup (launch, 64 barriers, epilogue) is of the order of the contraction
+// itself at this size, so splitting buys nothing: one split unless asked.
+void plan_gemm2(int I, int J, int K, int max_splits, int *tile, int *splits) {
+  (void)I; (void)J;
+  int best = 1, best_sp = 1;
+  const int kslabs = K / 64;
+  const char *env = getenv("CODENET_GEMM2");    // "tile,splits" override for tuning runs
+  if (env && env[0] >= '0' && env[0] < '0' + kNumTiles2) {
+    best = env[0] - '0';
+    if (env[1] == ',' && atoi(env + 2) > 0) best_sp = atoi(env + 2);
+    if (best_sp > kslabs) best_sp = kslabs;
+    if (best_sp > max_splits) best_sp = max_splits;
+  }
+  *tile = best;
+  *splits = best_sp;
+}
+
+// C = A B^T.  With g.splits > 1 the partial results go to `workspace`
+// (splits x J x ldc floats) and are then added into g.C in split order.
+hipError_t launch_gemm2(Gemm2Args g, int tile, float *workspace, hipStream_t s) {
+  if ((g.K & 63) || (g.lda & 7) || (g.ldb & 7) || (g.ldc & 3) || (g.I & 3) || g.splits < 1 || g.I < 1 || g.J < 1)
+    return hipErrorInvalidValue;
+  const int ti = 64 * kTiles2[tile].fm, tj = 64 * kTiles2[tile].fn;
+  g.tiles_i = (g.I + ti - 1) / ti;
+  g.tiles_j = (g.J + tj - 1) / tj;
+  float *final_out = g.C;
+  g.split_stride = 0;
+  if (g.splits > 1) {
+    if (workspace == nullptr) return hipErrorInvalidValue;
+    g.split_stride = (long)g.J * g.ldc;
+    g.C = workspace;
+  }
+  hipError_t e;
+#ifdef CODENET_ABLATION
+  const char *dbg_env = getenv("CODENET_GEMM2_DBG");
+  const int dbg = dbg_env ? atoi(dbg_env) : 0;
+  if (dbg && tile <= 1) {
+    switch (tile * 8 + dbg) {
+      case 1: return launch2<4, 2, 3, 1>(g, s);
+      case 2: return launch2<4, 2, 3, 2>(g, s);
+      case 3: return launch2<4, 2, 3, 3>(g, s);
+      case 4: return launch2<4, 2, 3, 4>(g, s);
+      case 6: return launch2<4, 2, 3, 6>(g, s);
+      case 7: return launch2<4, 2, 3, 7>(g, s);
+      case 9: return launch2<2, 2, 4, 1>(g, s);
+      case 10: return launch2<2, 2, 4, 2>(g, s);
+      case 11: return launch2<2, 2, 4, 3>(g, s);
+      case 12: return launch2<2, 2, 4, 4>(g, s);
+      case 14: return launch2<2, 2, 4, 6>(g, s);
+      case 15: return launch2<2, 2, 4, 7>(g, s);
+      default: break;
+    }
+  }
+#endif
+  switch (tile) {
+    case 0: e = launch2<4, 2, 3>(g, s); break;
+    case 1: e = launch2<2, 2, 4>(g, s); break;
+    case 2: e = launch2<2, 2, 2>(g, s); break;
+    case 3: e = launch2<4, 4, 2>(g, s); break;
+    default: e = launch2<2, 4, 3>(g, s); break;
+  }
+  if (e != hipSuccess || g.splits == 1) return e;
+  const long count4 = g.split_stride / 4;
+  hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((count4 + 255) / 256)), dim3(256), 0, s,
+                     reinterpret_cast<const float4 *>(workspace), count4, g.splits,
+                     reinterpret_cast<float4 *>(final_out), count4);
+  return hipGetLastError();
+}
+
+hipError_t launch_update2(Update2Args g, hipStream_t s) {
+  if ((g.K & 63) || (g.ldx & 7) || (g.ldd & 7) || (g.ldWb & 63) || (g.ldWTb & 63) || g.I < 1 || g.J < 1)
+    return hipErrorInvalidValue;
+  const char *env = getenv("CODENET_UPD2");
+  const int which = env ? atoi(env) : 0;
+  if (which == 1) return launch_upd2<2, 2, 2>(g, s);
+  return launch_upd2<4, 2, 2>(g, s);
+}
+
+hipError_t launch_transpose_bf16(const float *in, long ld_in, int R, int C, void *out, long ld_out, int Rpad,
+                                 hipStream_t s) {
+  dim3 grid((unsigned)((C + 63) / 64), (unsigned)((Rpad + 63) / 64));
+  hipLaunchKernelGGL(transpose_bf16_kernel, grid, dim3(256), 0, s, in, ld_in, R, C, (__bf16 *)out, ld_out, Rpad);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Shadow refresh: bf16 copies of the fp32 coded matrix, row-major (forward
+// product) and transposed (backward product), 64 x 64 tiles through LDS.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void shadow_kernel(const float *__restrict__ Wt, int Mr, int Nc,
+                                                     __bf16 *__restrict__ Wb, long ldWb,
+                                                     __bf16 *__restrict__ WTb, long ldWTb) {
+  __shared__ unsigned short tile[64][66];
+  const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+  const int t = threadIdx.x;
+  // 64 rows x 16 float4: thread t handles float4 (t & 15) of rows (t >> 4) + 16 p
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    const int r = (t >> 4) + 16 * p, c = (t & 15) * 4;
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (r0 + r < Mr && c0 + c < Nc) v = *reinterpret_cast<const float4 *>(Wt + (long)(r0 + r) * Nc + c0 + c);
+    const __bf16 b0 = (__bf16)v.x, b1 = (__bf16)v.y, b2 = (__bf16)v.z, b3 = (__bf16)v.w;
+    const unsigned short u0 = __builtin_bit_cast(unsigned short, b0), u1 = __builtin_bit_cast(unsigned short, b1),
+                         u2 = __builtin_bit_cast(unsigned short, b2), u3 = __builtin_bit_cast(unsigned short, b3);
+    tile[r][c] = u0; tile[r][c + 1] = u1; tile[r][c + 2] = u2; tile[r][c + 3] = u3;
+    if (r0 + r < Mr && c0 + c < Nc) {
+      uint2 pk;
+      pk.x = (unsigned)u0 | ((unsigned)u1 << 16);
+      pk.y = (unsigned)u2 | ((unsigned)u3 << 16);
+      *reinterpret_cast<uint2 *>(Wb + (long)(r0 + r) * ldWb + c0 + c) = pk;
+    }
+  }
+  __syncthreads();
+  // transposed: thread t writes 4 consecutive rows (t & 15) * 4 .. of column (t >> 4) + 16 p
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    const int c = (t >> 4) + 16 * p, r = (t & 15) * 4;
+    if (c0 + c < Nc && r0 + r < Mr) {
+      uint2 pk;
+      pk.x = (unsigned)tile[r][c] | ((unsigned)tile[r + 1][c] << 16);
+      pk.y = (unsigned)tile[r + 2][c] | ((unsigned)tile[r + 3][c] << 16);
+      *reinterpret_cast<uint2 *>(WTb + (long)(c0 + c) * ldWTb + r0 + r) = pk;
+    }
+  }
+}
+
+hipError_t launch_shadow(const float *Wt, int Mr, int Nc, void *Wb, long ldWb, void *WTb, long ldWTb,
+                         hipStream_t s) {
+  dim3 grid((unsigned)((Nc + 63) / 64), (unsigned)((Mr + 63) / 64));
+  hipLaunchKernelGGL(shadow_kernel, grid, dim3(256), 0, s, Wt, Mr, Nc, (__bf16 *)Wb, ldWb, (__bf16 *)WTb, ldWTb);
+  return hipGetLastError();
+}
+
+}  // namespace codenet

@@ -74,14 +74,38 @@ hipError_t launch_export_weights(const float *Wt, float *W, const DevCode &cr, c
 // the update read.  One thread per (batch row, 4 positions inside a block).
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void encode_vector_kernel(const float *__restrict__ V, float *__restrict__ Vt,
-                                                            const DevCode *__restrict__ code, int b) {
+                                                            const DevCode *__restrict__ code, int b,
+                                                            __bf16 *__restrict__ Vb, long ldVb,
+                                                            float4 *__restrict__ zero, long zero_count4) {
   const int B = code->B, B0 = code->B0, a = code->a, r = code->r, N = code->N;
   const int quads = B >> 2;
   const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+  const int job = blockIdx.y;            // 0 .. a-1: copy systematic block `job`; a: the r parity blocks
+  if (zero != nullptr && job == 0)
+    for (long z = idx; z < zero_count4; z += (long)gridDim.x * 256) zero[z] = make_float4(0.f, 0.f, 0.f, 0.f);
   if (idx >= (long)b * quads) return;
   const int beta = (int)(idx / quads), rho = (int)(idx % quads) * 4;
   const float *src = V + (long)beta * N;
   float *dst = Vt + (long)beta * (a + r) * B;
+  if (job < a) {
+    const int i = job;
+    float v[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int g = i * B0 + rho + e;
+      v[e] = (rho + e < B0 && g < N) ? src[g] : 0.f;
+    }
+    *reinterpret_cast<float4 *>(dst + i * B + rho) = make_float4(v[0], v[1], v[2], v[3]);
+    if (Vb != nullptr) {
+      const __bf16 b0 = (__bf16)v[0], b1 = (__bf16)v[1], b2 = (__bf16)v[2], b3 = (__bf16)v[3];
+      uint2 pk;
+      pk.x = (unsigned)__builtin_bit_cast(unsigned short, b0) | ((unsigned)__builtin_bit_cast(unsigned short, b1) << 16);
+      pk.y = (unsigned)__builtin_bit_cast(unsigned short, b2) | ((unsigned)__builtin_bit_cast(unsigned short, b3) << 16);
+      *reinterpret_cast<uint2 *>(Vb + (long)beta * ldVb + i * B + rho) = pk;
+    }
+    return;
+  }
+  if (r == 0) return;
   float par[CODENET_MAX_R][4];
 #pragma unroll
   for (int k = 0; k < CODENET_MAX_R; ++k) par[k][0] = par[k][1] = par[k][2] = par[k][3] = 0.f;
@@ -92,7 +116,6 @@ __global__ __launch_bounds__(256) void encode_vector_kernel(const float *__restr
       const int g = i * B0 + rho + e;
       v[e] = (rho + e < B0 && g < N) ? src[g] : 0.f;
     }
-    *reinterpret_cast<float4 *>(dst + i * B + rho) = make_float4(v[0], v[1], v[2], v[3]);
 #pragma unroll
     for (int k = 0; k < CODENET_MAX_R; ++k)
       if (k < r) {
@@ -108,10 +131,11 @@ __global__ __launch_bounds__(256) void encode_vector_kernel(const float *__restr
 }
 
 hipError_t launch_encode_vector(const float *V, float *Vt, const DevCode *code_dev, const DevCode &code_host,
-                                int b, hipStream_t s) {
+                                int b, void *Vb, long ldVb, float *zero, long zero_count4, hipStream_t s) {
   const long total = (long)b * (code_host.B >> 2);
-  hipLaunchKernelGGL(encode_vector_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, V, Vt,
-                     code_dev, b);
+  dim3 grid((unsigned)((total + 255) / 256), (unsigned)(code_host.a + 1));
+  hipLaunchKernelGGL(encode_vector_kernel, grid, dim3(256), 0, s, V, Vt, code_dev, b, (__bf16 *)Vb, ldVb,
+                     reinterpret_cast<float4 *>(zero), zero_count4);
   return hipGetLastError();
 }
 
@@ -192,7 +216,7 @@ __global__ __launch_bounds__(256) void detect_kernel(const float *__restrict__ o
   __syncthreads();
   const int t = threadIdx.x;
   if (t < CODENET_MAX_L + NG && (t < L || t >= CODENET_MAX_L))
-    partials[(long)blockIdx.x * kMaxEntries + t] = red[0][t] + red[1][t] + red[2][t] + red[3][t];
+    partials[(long)t * kDetectParts + blockIdx.x] = red[0][t] + red[1][t] + red[2][t] + red[3][t];
 }
 
 hipError_t launch_detect(const float *out, float *syn, double *partials, int *n_parts, const DevCode *code_dev,
@@ -254,12 +278,12 @@ __device__ long n_choose_k(int n, int k) {
 }
 
 // Cholesky factor of M = H_A^T H_A (k x k, lower), returns false if not positive definite
-__device__ bool support_factor(const DevCode *code, const int *idx, int k, double Lo[CODENET_MAX_T][CODENET_MAX_T]) {
-  const int r = code->r;
+__device__ bool support_factor(const double (*H)[CODENET_MAX_L], int r, const int *idx, int k,
+                               double Lo[CODENET_MAX_T][CODENET_MAX_T]) {
   for (int p = 0; p < k; ++p)
     for (int q = 0; q <= p; ++q) {
       double m = 0.0;
-      for (int c = 0; c < r; ++c) m += code->H[c][idx[p]] * code->H[c][idx[q]];
+      for (int c = 0; c < r; ++c) m += H[c][idx[p]] * H[c][idx[q]];
       for (int u = 0; u < q; ++u) m -= Lo[p][u] * Lo[q][u];
       if (p == q) {
         if (m <= 1e-300) return false;
@@ -271,24 +295,23 @@ __device__ bool support_factor(const DevCode *code, const int *idx, int k, doubl
   return true;
 }
 
-__device__ double support_residual2(const DevCode *code, const double (*G)[CODENET_MAX_R], double trG,
-                                    const int *idx, int k) {
-  const int r = code->r;
+__device__ double support_residual2(const double (*H)[CODENET_MAX_L], int r, const double (*G)[CODENET_MAX_R],
+                                    double trG, const int *idx, int k) {
   double Lo[CODENET_MAX_T][CODENET_MAX_T];
-  if (!support_factor(code, idx, k, Lo)) return trG;
+  if (!support_factor(H, r, idx, k, Lo)) return trG;
   // N = H_A^T Gamma H_A
   double T[CODENET_MAX_R][CODENET_MAX_T];
   for (int c = 0; c < r; ++c)
     for (int p = 0; p < k; ++p) {
       double v = 0.0;
-      for (int d = 0; d < r; ++d) v += G[c][d] * code->H[d][idx[p]];
+      for (int d = 0; d < r; ++d) v += G[c][d] * H[d][idx[p]];
       T[c][p] = v;
     }
   double N[CODENET_MAX_T][CODENET_MAX_T];
   for (int p = 0; p < k; ++p)
     for (int q = 0; q < k; ++q) {
       double v = 0.0;
-      for (int c = 0; c < r; ++c) v += code->H[c][idx[p]] * T[c][q];
+      for (int c = 0; c < r; ++c) v += H[c][idx[p]] * T[c][q];
       N[p][q] = v;
     }
   // tr(M^-1 N) = tr(Lo^-1 N Lo^-T): forward-substitute rows, then columns
@@ -319,20 +342,53 @@ __global__ __launch_bounds__(256) void decide_kernel(const double *__restrict__ 
                                                      codenet_report *__restrict__ report) {
   __shared__ double tot[kMaxEntries];
   __shared__ double G[CODENET_MAX_R][CODENET_MAX_R];
-  __shared__ double best_res[256];
-  __shared__ long best_rank[256];
+  __shared__ double best_res[4];
+  __shared__ long best_rank[4];
   __shared__ int s_verdict, s_k;
   __shared__ long s_rank;
   __shared__ double s_resid, s_trG;
   const int t = threadIdx.x;
   const int L = code->L, r = code->r;
   const int tcap = r / 2 < CODENET_MAX_T ? r / 2 : CODENET_MAX_T;
+  // the parity-check matrix is read many times by single threads below: keep it in LDS
+  __shared__ double H[CODENET_MAX_R][CODENET_MAX_L];
+  for (int idx = t; idx < CODENET_MAX_R * CODENET_MAX_L; idx += 256)
+    H[idx / CODENET_MAX_L][idx % CODENET_MAX_L] = code->H[idx / CODENET_MAX_L][idx % CODENET_MAX_L];
+  const double tau_detect = code->tau_detect, tau_resid = code->tau_resid;
 
+  // Totals of the per-workgroup records (stored entry-major), live entries only:
+  // thread t takes records t and t + 256 of eight entries at a time (independent
+  // loads), a shuffle tree adds the lanes, LDS the four wavefronts -- the same
+  // arithmetic on every run.
+  __shared__ double red[4][kMaxEntries];
+  const int n_live = L + r * (r + 1) / 2;
+  {
+    const int lane = t & 63, wave = t >> 6;
+    for (int k0 = 0; k0 < n_live; k0 += 8) {
+      double v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int k = k0 + u;
+        const int e = k < L ? k : CODENET_MAX_L + (k - L);
+        double a = 0.0, b2 = 0.0;
+        if (k < n_live && t < n_parts) a = partials[(long)e * kDetectParts + t];
+        if (k < n_live && t + 256 < n_parts) b2 = partials[(long)e * kDetectParts + t + 256];
+        v[u] = a + b2;
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        double w = v[u];
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) w += __shfl_down(w, off, 64);
+        const int k = k0 + u;
+        if (lane == 0 && k < n_live) red[wave][k < L ? k : CODENET_MAX_L + (k - L)] = w;
+      }
+    }
+  }
+  __syncthreads();
   if (t < kMaxEntries) {
-    double v = 0.0;
-    if (t < L || (t >= CODENET_MAX_L && t < CODENET_MAX_L + r * (r + 1) / 2))
-      for (int p = 0; p < n_parts; ++p) v += partials[(long)p * kMaxEntries + t];
-    tot[t] = v;
+    const bool live = t < L || (t >= CODENET_MAX_L && t < CODENET_MAX_L + r * (r + 1) / 2);
+    tot[t] = live ? (red[0][t] + red[1][t]) + (red[2][t] + red[3][t]) : 0.0;
   }
   __syncthreads();
   if (t == 0) {
@@ -344,11 +400,11 @@ __global__ __launch_bounds__(256) void decide_kernel(const double *__restrict__ 
     for (int k = 0; k < r; ++k) {
       trG += G[k][k];
       double ref2 = 0.0;
-      for (int i = 0; i < L; ++i) ref2 += code->H[k][i] * code->H[k][i] * tot[i];
+      for (int i = 0; i < L; ++i) ref2 += H[k][i] * H[k][i] * tot[i];
       const double rel = ref2 > 0.0 ? sqrt(G[k][k] / ref2) : 0.0;
       if (report) report->syn_rel[k] = (float)rel;
       // a non-finite ratio (NaN / Inf in the output) must not pass as clean
-      if (!(rel <= code->tau_detect)) clean = false;
+      if (!(rel <= tau_detect)) clean = false;
     }
     if (report)
       for (int k = r; k < CODENET_MAX_R; ++k) report->syn_rel[k] = 0.f;
@@ -366,25 +422,52 @@ __global__ __launch_bounds__(256) void decide_kernel(const double *__restrict__ 
       double my_res = 1e300;
       long my_rank = -1;
       for (long rank = t; rank < count; rank += 256) {
-        int idx[CODENET_MAX_T];
-        unrank_support(rank, L, k, idx);
-        const double res2 = support_residual2(code, G, s_trG, idx, k);
+        double res2;
+        if (k == 1) {
+          // one block i: residual^2 = tr(Gamma) - (h^T Gamma h) / (h^T h), h = H[:, i]
+          double hh = 0.0, hgh = 0.0;
+          for (int c = 0; c < r; ++c) {
+            const double hc = H[c][rank];
+            hh += hc * hc;
+            double gh = 0.0;
+            for (int d = 0; d < r; ++d) gh += G[c][d] * H[d][rank];
+            hgh += hc * gh;
+          }
+          res2 = hh > 0.0 ? s_trG - hgh / hh : s_trG;
+          if (res2 < 0.0) res2 = 0.0;
+        } else {
+          int idx[CODENET_MAX_T];
+          unrank_support(rank, L, k, idx);
+          res2 = support_residual2(H, r, G, s_trG, idx, k);
+        }
         if (res2 < my_res) { my_res = res2; my_rank = rank; }
       }
-      best_res[t] = my_res;
-      best_rank[t] = my_rank;
+      // smallest (residual, rank) pair: shuffle tree inside a wavefront, then the four leaders
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) {
+        const double o_res = __shfl_down(my_res, off, 64);
+        const long o_rank = __shfl_down(my_rank, off, 64);
+        if (o_rank >= 0 && (my_rank < 0 || o_res < my_res || (o_res == my_res && o_rank < my_rank))) {
+          my_res = o_res;
+          my_rank = o_rank;
+        }
+      }
+      if ((t & 63) == 0) {
+        best_res[t >> 6] = my_res;
+        best_rank[t >> 6] = my_rank;
+      }
       __syncthreads();
       if (t == 0) {
         double br = 1e300;
         long bk = -1;
-        for (int u = 0; u < 256; ++u)
-          if (best_rank[u] >= 0 && (best_res[u] < br || (best_res[u] == br && best_rank[u] < bk))) {
+        for (int u = 0; u < 4; ++u)
+          if (best_rank[u] >= 0 && (bk < 0 || best_res[u] < br || (best_res[u] == br && best_rank[u] < bk))) {
             br = best_res[u];
             bk = best_rank[u];
           }
         const double rel = bk >= 0 ? sqrt(br / s_trG) : 1e300;
         s_resid = rel;
-        if (bk >= 0 && rel <= code->tau_resid) {
+        if (bk >= 0 && rel <= tau_resid) {
           s_verdict = CODENET_CORRECTED;
           s_k = k;
           s_rank = bk;
@@ -399,15 +482,20 @@ __global__ __launch_bounds__(256) void decide_kernel(const double *__restrict__ 
     int idx[CODENET_MAX_T];
     for (int p = 0; p < CODENET_MAX_T; ++p) idx[p] = -1;
     const int k = s_verdict == CODENET_CORRECTED ? s_k : 0;
-    if (k > 0) {
+    if (k == 1) {
+      idx[0] = (int)s_rank;
+      double hh = 0.0;
+      for (int c = 0; c < r; ++c) hh += H[c][idx[0]] * H[c][idx[0]];
+      for (int c = 0; c < r; ++c) plan->coef[0][c] = (float)(H[c][idx[0]] / hh);
+    } else if (k > 1) {
       unrank_support(s_rank, L, k, idx);
       // error block p = sum_c pinv[p][c] syndrome_c with pinv = (H_A^T H_A)^-1 H_A^T
       double Lo[CODENET_MAX_T][CODENET_MAX_T];
-      support_factor(code, idx, k, Lo);
+      support_factor(H, r, idx, k, Lo);
       for (int c = 0; c < r; ++c) {
         double y[CODENET_MAX_T], x[CODENET_MAX_T];
         for (int p = 0; p < k; ++p) {
-          double v = code->H[c][idx[p]];
+          double v = H[c][idx[p]];
           for (int u = 0; u < p; ++u) v -= Lo[p][u] * y[u];
           y[p] = v / Lo[p][p];
         }
@@ -527,20 +615,25 @@ __global__ __launch_bounds__(256) void fault_stats_kernel(FaultArgs fa) {
 __global__ __launch_bounds__(256) void fault_apply_kernel(FaultArgs fa) {
   const long total = (long)fa.n_outer * fa.n_inner;
   const long e = (long)blockIdx.x * 256 + threadIdx.x;
-  if (e >= total) return;
-  float scale = 1.f;
-  if (fa.mode == CODENET_NOISE_DENSE_REL) {
-    double ss = 0.0;
-    for (int p = 0; p < kFaultParts; ++p) ss += fa.partials[p];
-    scale = (float)sqrt(ss / (double)total);
+  __shared__ float s_scale;
+  if (threadIdx.x == 0) {
+    float scale = 1.f;
+    if (fa.mode == CODENET_NOISE_DENSE_REL) {
+      double ss = 0.0;
+      for (int p = 0; p < kFaultParts; ++p) ss += fa.partials[p];
+      scale = (float)sqrt(ss / (double)total);
+    }
+    s_scale = scale;
   }
+  __syncthreads();
+  if (e >= total) return;
   const long o = e / fa.n_inner, in = e % fa.n_inner;
   const unsigned long long idx = (unsigned long long)o * fa.idx_outer + (unsigned long long)in * fa.idx_inner;
   const unsigned long long z = mix64(fa.key + idx);
   const float u = (float)((z >> 32) & 0xFFFFFFull) * (1.0f / 16777216.0f);
   float val = fa.lo + (fa.hi - fa.lo) * u;
   if (fa.mode == CODENET_NOISE_DENSE_REL) {
-    val *= scale;
+    val *= s_scale;
     if (z >> 63) val = -val;
   } else if ((unsigned int)(z & 0xFFFFFFFFull) >= fa.hit_below) {
     return;
