@@ -106,3 +106,67 @@ class Pair:
 
     def close(self):
         self.gpu.destroy()
+
+
+# ---------------------------------------------------------------------------------
+# Multi-layer driver (feedforward l = 1..L, backpropagation l = L..1, update), the
+# per-iteration schedule of the decentralized algorithm, on both sides.  Activation
+# f = ReLU, g(x) = 1[x > 0]; loss head: mean softmax cross-entropy, delta^L = (Y - p) / b
+# (delta is minus the gradient, so the update adds eta * delta x^T).  An UNCORRECTABLE
+# product is recomputed once without replaying the fault (transient output errors).
+# ---------------------------------------------------------------------------------
+class MlpPair:
+    def __init__(self, wl, max_layers=None):
+        self.wl = wl
+        widths = wl.widths if max_layers is None else wl.widths[: max_layers + 1]
+        self.layers = []
+        for l in range(len(widths) - 1):
+            P_r, P_c = wl.generators(l)
+            W = WL.layer_weights(widths[l + 1], widths[l], l)
+            self.layers.append(Pair(W, P_r, P_c, wl.dtype, wl.batch, wl.tau_detect, wl.tau_resid))
+        self.widths = widths
+        self.counts = {0: 0, 1: 0, 2: 0}
+
+    def _product(self, l, phase, V, faults):
+        pair = self.layers[l]
+        dec, rep, res = pair.product(phase, V, faults)
+        self.counts[rep["verdict"]] += 1
+        if rep["verdict"] == O.UNCORRECTABLE:
+            dec, rep, res = pair.product(phase, V, ())          # roll back = recompute the product
+            assert rep["verdict"] == O.CLEAN
+        return to_np(dec).astype(np.float32), res["decoded"].T.astype(np.float32)
+
+    def step(self, step, labels=None):
+        wl, L = self.wl, len(self.layers)
+        b = wl.batch
+        X = wl.inputs(step)[:, : self.widths[0]]
+        xs_g, xs_o = [X], [X]
+        for l in range(L):
+            s_g, s_o = self._product(l, WL.PHASE_FWD, xs_g[-1], wl.product_faults(WL.PHASE_FWD, step, l))
+            assert rel_fro(s_g, s_o) <= self.layers[l].tol
+            if l < L - 1:
+                s_g, s_o = np.maximum(s_g, 0), np.maximum(s_o, 0)
+            # both sides continue from the GPU activations: the comparison is per product
+            xs_g.append(s_g)
+            xs_o.append(s_g)
+        logits = xs_g[-1].astype(np.float64)
+        if labels is None:
+            labels = np.random.default_rng(WL.SEED_DELTAS + step).integers(0, logits.shape[1], size=b)
+        p = np.exp(logits - logits.max(axis=1, keepdims=True))
+        p /= p.sum(axis=1, keepdims=True)
+        Y = np.zeros_like(p)
+        Y[np.arange(b), labels] = 1.0
+        delta = ((Y - p) / b).astype(np.float32)
+        loss = float(-np.mean(np.log(p[np.arange(b), labels] + 1e-30)))
+        for l in range(L - 1, -1, -1):
+            c_g, c_o = self._product(l, WL.PHASE_BWD, delta, wl.product_faults(WL.PHASE_BWD, step, l))
+            assert rel_fro(c_g, c_o) <= self.layers[l].tol
+            if l > 0:
+                delta = (c_g * (xs_g[l] > 0)).astype(np.float32)
+        for l in range(L):
+            self.layers[l].update(wl.eta)
+        return loss
+
+    def close(self):
+        for p in self.layers:
+            p.close()
