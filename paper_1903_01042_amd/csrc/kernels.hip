@@ -76,7 +76,8 @@ hipError_t launch_export_weights(const float *Wt, float *W, const DevCode &cr, c
 __global__ __launch_bounds__(256) void encode_vector_kernel(const float *__restrict__ V, float *__restrict__ Vt,
                                                             const DevCode *__restrict__ code, int b,
                                                             __bf16 *__restrict__ Vb, long ldVb,
-                                                            float4 *__restrict__ zero, long zero_count4) {
+                                                            float4 *__restrict__ zero, long zero_count4,
+                                                            int aligned) {
   const int B = code->B, B0 = code->B0, a = code->a, r = code->r, N = code->N;
   const int quads = B >> 2;
   const long idx = (long)blockIdx.x * 256 + threadIdx.x;
@@ -90,10 +91,16 @@ __global__ __launch_bounds__(256) void encode_vector_kernel(const float *__restr
   if (job < a) {
     const int i = job;
     float v[4];
+    if (aligned) {        // N and B0 multiples of 4, V 16-byte aligned: whole quads are real or padding
+      const int g = i * B0 + rho;
+      const float4 q = g < N ? *reinterpret_cast<const float4 *>(src + g) : make_float4(0.f, 0.f, 0.f, 0.f);
+      v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+    } else {
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const int g = i * B0 + rho + e;
-      v[e] = (rho + e < B0 && g < N) ? src[g] : 0.f;
+      for (int e = 0; e < 4; ++e) {
+        const int g = i * B0 + rho + e;
+        v[e] = (rho + e < B0 && g < N) ? src[g] : 0.f;
+      }
     }
     *reinterpret_cast<float4 *>(dst + i * B + rho) = make_float4(v[0], v[1], v[2], v[3]);
     if (Vb != nullptr) {
@@ -109,12 +116,19 @@ __global__ __launch_bounds__(256) void encode_vector_kernel(const float *__restr
   float par[CODENET_MAX_R][4];
 #pragma unroll
   for (int k = 0; k < CODENET_MAX_R; ++k) par[k][0] = par[k][1] = par[k][2] = par[k][3] = 0.f;
+#pragma unroll 4
   for (int i = 0; i < a; ++i) {
     float v[4];
+    if (aligned) {
+      const int g = i * B0 + rho;
+      const float4 q = g < N ? *reinterpret_cast<const float4 *>(src + g) : make_float4(0.f, 0.f, 0.f, 0.f);
+      v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+    } else {
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const int g = i * B0 + rho + e;
-      v[e] = (rho + e < B0 && g < N) ? src[g] : 0.f;
+      for (int e = 0; e < 4; ++e) {
+        const int g = i * B0 + rho + e;
+        v[e] = (rho + e < B0 && g < N) ? src[g] : 0.f;
+      }
     }
 #pragma unroll
     for (int k = 0; k < CODENET_MAX_R; ++k)
@@ -134,110 +148,9 @@ hipError_t launch_encode_vector(const float *V, float *Vt, const DevCode *code_d
                                 int b, void *Vb, long ldVb, float *zero, long zero_count4, hipStream_t s) {
   const long total = (long)b * (code_host.B >> 2);
   dim3 grid((unsigned)((total + 255) / 256), (unsigned)(code_host.a + 1));
+  const int aligned = (code_host.N % 4 == 0) && (code_host.B0 % 4 == 0) && ((reinterpret_cast<uintptr_t>(V) & 15) == 0);
   hipLaunchKernelGGL(encode_vector_kernel, grid, dim3(256), 0, s, V, Vt, code_dev, b, (__bf16 *)Vb, ldVb,
-                     reinterpret_cast<float4 *>(zero), zero_count4);
-  return hipGetLastError();
-}
-
-// ---------------------------------------------------------------------------
-// Consistency check, pass 1 (General Error-Detection Method): syndromes
-// out^_k = sum_i H[k][i] out_i for every position of a block, written out for
-// the correction pass, plus what the decision needs: ||out_i||^2 for every
-// block and the r x r Gram matrix sum_pos out^(pos) out^(pos)^T.  HBM-bound:
-// the coded output is read once.  Per-thread float32 sums over a few
-// positions, then float64 across lanes, wavefronts and workgroups in a fixed
-// order (no atomics), so the decision is reproducible.
-// ---------------------------------------------------------------------------
-template <int R>
-__global__ __launch_bounds__(256) void detect_kernel(const float *__restrict__ out, float *__restrict__ syn,
-                                                     double *__restrict__ partials,
-                                                     const DevCode *__restrict__ code, int b, int iters) {
-  const int B = code->B, L = code->L;
-  const int quads = B >> 2;
-  const long npos = (long)b * quads;
-  constexpr int NG = R * (R + 1) / 2;
-  float sq[CODENET_MAX_L];
-  float gram[NG];
-#pragma unroll
-  for (int i = 0; i < CODENET_MAX_L; ++i) sq[i] = 0.f;
-#pragma unroll
-  for (int e = 0; e < NG; ++e) gram[e] = 0.f;
-
-  for (int it = 0; it < iters; ++it) {
-    const long idx = ((long)it * gridDim.x + blockIdx.x) * 256 + threadIdx.x;
-    if (idx >= npos) break;
-    const int beta = (int)(idx / quads), rho = (int)(idx % quads) * 4;
-    const float *row = out + (long)beta * L * B + rho;
-    float4 sy[R];
-#pragma unroll
-    for (int k = 0; k < R; ++k) sy[k] = make_float4(0.f, 0.f, 0.f, 0.f);
-#pragma unroll
-    for (int i = 0; i < CODENET_MAX_L; ++i)
-      if (i < L) {
-        const float4 v = *reinterpret_cast<const float4 *>(row + i * B);
-        sq[i] += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
-#pragma unroll
-        for (int k = 0; k < R; ++k) {
-          const float hk = code->Hf[k][i];
-          sy[k].x = fmaf(hk, v.x, sy[k].x);
-          sy[k].y = fmaf(hk, v.y, sy[k].y);
-          sy[k].z = fmaf(hk, v.z, sy[k].z);
-          sy[k].w = fmaf(hk, v.w, sy[k].w);
-        }
-      }
-    int e = 0;
-#pragma unroll
-    for (int k = 0; k < R; ++k) {
-      *reinterpret_cast<float4 *>(syn + ((long)k * b + beta) * B + rho) = sy[k];
-#pragma unroll
-      for (int k2 = k; k2 < R; ++k2, ++e)
-        gram[e] += sy[k].x * sy[k2].x + sy[k].y * sy[k2].y + sy[k].z * sy[k2].z + sy[k].w * sy[k2].w;
-    }
-  }
-
-  // reduce: lanes (float64 shuffles), then the 4 wavefronts through LDS
-  __shared__ double red[4][kMaxEntries];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-#pragma unroll
-  for (int i = 0; i < CODENET_MAX_L; ++i)
-    if (i < L) {
-      double v = (double)sq[i];
-#pragma unroll
-      for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
-      if (lane == 0) red[wave][i] = v;
-    }
-#pragma unroll
-  for (int e = 0; e < NG; ++e) {
-    double v = (double)gram[e];
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
-    if (lane == 0) red[wave][CODENET_MAX_L + e] = v;
-  }
-  __syncthreads();
-  const int t = threadIdx.x;
-  if (t < CODENET_MAX_L + NG && (t < L || t >= CODENET_MAX_L))
-    partials[(long)t * kDetectParts + blockIdx.x] = red[0][t] + red[1][t] + red[2][t] + red[3][t];
-}
-
-hipError_t launch_detect(const float *out, float *syn, double *partials, int *n_parts, const DevCode *code_dev,
-                         const DevCode &ch, int b, hipStream_t s) {
-  const long npos = (long)b * (ch.B >> 2);
-  long wgs = (npos + 255) / 256;
-  int iters = 1;
-  if (wgs > kDetectParts) {
-    iters = (int)((wgs + kDetectParts - 1) / kDetectParts);
-    wgs = (npos + 256L * iters - 1) / (256L * iters);
-  }
-  *n_parts = (int)wgs;
-  dim3 grid((unsigned)wgs), block(256);
-  switch (ch.r) {
-#define CODENET_DETECT_CASE(RR) \
-  case RR: hipLaunchKernelGGL(detect_kernel<RR>, grid, block, 0, s, out, syn, partials, code_dev, b, iters); break;
-    CODENET_DETECT_CASE(1) CODENET_DETECT_CASE(2) CODENET_DETECT_CASE(3) CODENET_DETECT_CASE(4)
-    CODENET_DETECT_CASE(5) CODENET_DETECT_CASE(6) CODENET_DETECT_CASE(7) CODENET_DETECT_CASE(8)
-#undef CODENET_DETECT_CASE
-    default: return hipErrorInvalidValue;
-  }
+                     reinterpret_cast<float4 *>(zero), zero_count4, aligned);
   return hipGetLastError();
 }
 
@@ -337,9 +250,11 @@ __device__ double support_residual2(const double (*H)[CODENET_MAX_L], int r, con
   return res > 0.0 ? res : 0.0;
 }
 
-__global__ __launch_bounds__(256) void decide_kernel(const double *__restrict__ partials, int n_parts,
-                                                     const DevCode *__restrict__ code, DevPlan *__restrict__ plan,
-                                                     codenet_report *__restrict__ report) {
+// Executed by all 256 threads of one workgroup.  GENERIC = supports of two or more
+// blocks may be needed (r >= 4); without it the kernel needs no private scratch.
+template <bool GENERIC>
+__device__ void decide_body(const double *partials, int n_parts, const DevCode *__restrict__ code,
+                            DevPlan *__restrict__ plan, codenet_report *__restrict__ report) {
   __shared__ double tot[kMaxEntries];
   __shared__ double G[CODENET_MAX_R][CODENET_MAX_R];
   __shared__ double best_res[4];
@@ -435,10 +350,12 @@ __global__ __launch_bounds__(256) void decide_kernel(const double *__restrict__ 
           }
           res2 = hh > 0.0 ? s_trG - hgh / hh : s_trG;
           if (res2 < 0.0) res2 = 0.0;
-        } else {
+        } else if constexpr (GENERIC) {
           int idx[CODENET_MAX_T];
           unrank_support(rank, L, k, idx);
           res2 = support_residual2(H, r, G, s_trG, idx, k);
+        } else {
+          res2 = s_trG;
         }
         if (res2 < my_res) { my_res = res2; my_rank = rank; }
       }
@@ -487,7 +404,7 @@ __global__ __launch_bounds__(256) void decide_kernel(const double *__restrict__ 
       double hh = 0.0;
       for (int c = 0; c < r; ++c) hh += H[c][idx[0]] * H[c][idx[0]];
       for (int c = 0; c < r; ++c) plan->coef[0][c] = (float)(H[c][idx[0]] / hh);
-    } else if (k > 1) {
+    } else if (GENERIC && k > 1) {
       unrank_support(s_rank, L, k, idx);
       // error block p = sum_c pinv[p][c] syndrome_c with pinv = (H_A^T H_A)^-1 H_A^T
       double Lo[CODENET_MAX_T][CODENET_MAX_T];
@@ -519,9 +436,125 @@ __global__ __launch_bounds__(256) void decide_kernel(const double *__restrict__ 
   }
 }
 
-hipError_t launch_decide(const double *partials, int n_parts, const DevCode *code_dev, const DevCode &,
+template <bool GENERIC>
+__global__ __launch_bounds__(256) void decide_kernel(const double *partials, int n_parts,
+                                                     const DevCode *__restrict__ code, DevPlan *__restrict__ plan,
+                                                     codenet_report *__restrict__ report) {
+  decide_body<GENERIC>(partials, n_parts, code, plan, report);
+}
+
+// ---------------------------------------------------------------------------
+// Consistency check, pass 1 (General Error-Detection Method): syndromes
+// out^_k = sum_i H[k][i] out_i for every position of a block, written out for
+// the correction pass, plus what the decision needs: ||out_i||^2 for every
+// block and the r x r Gram matrix sum_pos out^(pos) out^(pos)^T.  HBM-bound:
+// the coded output is read once.  (Letting the last workgroup to finish take the
+// decision in the same kernel was tried: the device-scope fence it needs writes
+// back the L2 of every XCD and cost 25 us; a second tiny kernel costs 3-10 us.)
+// Per-thread float32 sums over a few
+// positions, then float64 across lanes, wavefronts and workgroups in a fixed
+// order (no atomics), so the decision is reproducible.
+// ---------------------------------------------------------------------------
+template <int R>
+__global__ __launch_bounds__(256) void detect_kernel(const float *__restrict__ out, float *__restrict__ syn,
+                                                     double *__restrict__ partials,
+                                                     const DevCode *__restrict__ code, int b, int iters) {
+  const int B = code->B, L = code->L;
+  const int quads = B >> 2;
+  const long npos = (long)b * quads;
+  constexpr int NG = R * (R + 1) / 2;
+  float sq[CODENET_MAX_L];
+  float gram[NG];
+#pragma unroll
+  for (int i = 0; i < CODENET_MAX_L; ++i) sq[i] = 0.f;
+#pragma unroll
+  for (int e = 0; e < NG; ++e) gram[e] = 0.f;
+
+  for (int it = 0; it < iters; ++it) {
+    const long idx = ((long)it * gridDim.x + blockIdx.x) * 256 + threadIdx.x;
+    if (idx >= npos) break;
+    const int beta = (int)(idx / quads), rho = (int)(idx % quads) * 4;
+    const float *row = out + (long)beta * L * B + rho;
+    float4 sy[R];
+#pragma unroll
+    for (int k = 0; k < R; ++k) sy[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+    for (int i = 0; i < CODENET_MAX_L; ++i)
+      if (i < L) {
+        const float4 v = *reinterpret_cast<const float4 *>(row + i * B);
+        sq[i] += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+#pragma unroll
+        for (int k = 0; k < R; ++k) {
+          const float hk = code->Hf[k][i];
+          sy[k].x = fmaf(hk, v.x, sy[k].x);
+          sy[k].y = fmaf(hk, v.y, sy[k].y);
+          sy[k].z = fmaf(hk, v.z, sy[k].z);
+          sy[k].w = fmaf(hk, v.w, sy[k].w);
+        }
+      }
+    int e = 0;
+#pragma unroll
+    for (int k = 0; k < R; ++k) {
+      *reinterpret_cast<float4 *>(syn + ((long)k * b + beta) * B + rho) = sy[k];
+#pragma unroll
+      for (int k2 = k; k2 < R; ++k2, ++e)
+        gram[e] += sy[k].x * sy[k2].x + sy[k].y * sy[k2].y + sy[k].z * sy[k2].z + sy[k].w * sy[k2].w;
+    }
+  }
+
+  // reduce: lanes (float64 shuffles), then the 4 wavefronts through LDS
+  __shared__ double red[4][kMaxEntries];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int i = 0; i < CODENET_MAX_L; ++i)
+    if (i < L) {
+      double v = (double)sq[i];
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+      if (lane == 0) red[wave][i] = v;
+    }
+#pragma unroll
+  for (int e = 0; e < NG; ++e) {
+    double v = (double)gram[e];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
+    if (lane == 0) red[wave][CODENET_MAX_L + e] = v;
+  }
+  __syncthreads();
+  const int t = threadIdx.x;
+  if (t < CODENET_MAX_L + NG && (t < L || t >= CODENET_MAX_L))
+    partials[(long)t * kDetectParts + blockIdx.x] = red[0][t] + red[1][t] + red[2][t] + red[3][t];
+
+}
+
+hipError_t launch_detect(const float *out, float *syn, double *partials, int *n_parts, const DevCode *code_dev,
+                         const DevCode &ch, int b, hipStream_t s) {
+  const long npos = (long)b * (ch.B >> 2);
+  long wgs = (npos + 255) / 256;
+  int iters = 1;
+  if (wgs > kDetectParts) {
+    iters = (int)((wgs + kDetectParts - 1) / kDetectParts);
+    wgs = (npos + 256L * iters - 1) / (256L * iters);
+  }
+  *n_parts = (int)wgs;
+  dim3 grid((unsigned)wgs), block(256);
+  switch (ch.r) {
+#define CODENET_DETECT_CASE(RR) \
+  case RR: hipLaunchKernelGGL(detect_kernel<RR>, grid, block, 0, s, out, syn, partials, code_dev, b, iters); break;
+    CODENET_DETECT_CASE(1) CODENET_DETECT_CASE(2) CODENET_DETECT_CASE(3) CODENET_DETECT_CASE(4)
+    CODENET_DETECT_CASE(5) CODENET_DETECT_CASE(6) CODENET_DETECT_CASE(7) CODENET_DETECT_CASE(8)
+#undef CODENET_DETECT_CASE
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_decide(const double *partials, int n_parts, const DevCode *code_dev, const DevCode &ch,
                          DevPlan *plan, codenet_report *report, hipStream_t s) {
-  hipLaunchKernelGGL(decide_kernel, dim3(1), dim3(256), 0, s, partials, n_parts, code_dev, plan, report);
+  if (ch.r >= 4)
+    hipLaunchKernelGGL(decide_kernel<true>, dim3(1), dim3(256), 0, s, partials, n_parts, code_dev, plan, report);
+  else
+    hipLaunchKernelGGL(decide_kernel<false>, dim3(1), dim3(256), 0, s, partials, n_parts, code_dev, plan, report);
   return hipGetLastError();
 }
 
@@ -532,7 +565,7 @@ hipError_t launch_decide(const double *partials, int n_parts, const DevCode *cod
 __global__ __launch_bounds__(256) void correct_kernel(float *__restrict__ out, const float *__restrict__ syn,
                                                       const DevPlan *__restrict__ plan,
                                                       const DevCode *__restrict__ code, int b,
-                                                      float *__restrict__ decoded) {
+                                                      float *__restrict__ decoded, int aligned) {
   const int corrected = plan->verdict == CODENET_CORRECTED ? plan->n_located : 0;
   if (corrected == 0 && decoded == nullptr) return;
   const int B = code->B, B0 = code->B0, L = code->L, a = code->a, r = code->r, N = code->N;
@@ -558,6 +591,11 @@ __global__ __launch_bounds__(256) void correct_kernel(float *__restrict__ out, c
   float *dst = decoded + (long)beta * N;
   for (int i = 0; i < a; ++i) {
     const float4 v = *reinterpret_cast<const float4 *>(row + i * B);   // own writes above are visible to this thread
+    if (aligned) {
+      const int g = i * B0 + rho;
+      if (g < N) *reinterpret_cast<float4 *>(dst + g) = v;
+      continue;
+    }
     const float vv[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
@@ -570,8 +608,9 @@ __global__ __launch_bounds__(256) void correct_kernel(float *__restrict__ out, c
 hipError_t launch_correct(float *out, const float *syn, const DevPlan *plan, const DevCode *code_dev,
                           const DevCode &ch, int b, float *decoded, hipStream_t s) {
   const long total = (long)b * (ch.B >> 2);
+  const int aligned = (ch.N % 4 == 0) && (ch.B0 % 4 == 0) && ((reinterpret_cast<uintptr_t>(decoded) & 15) == 0);
   hipLaunchKernelGGL(correct_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, out, syn, plan,
-                     code_dev, b, decoded);
+                     code_dev, b, decoded, aligned);
   return hipGetLastError();
 }
 
