@@ -360,8 +360,7 @@ int codenet_detect_decode(codenet_layer *l, int phase, float *coded_out_dev, int
     CN_HIP(launch_detect(coded_out_dev, l->syn, l->partials, &n_parts, cd, ch, b, s));
   }
   // with r = 0 there is nothing to check: zero records make the decision CLEAN
-  CN_HIP(launch_decide(l->partials, n_parts, cd, ch, l->plan, report_dev, s));
-  CN_HIP(launch_correct(coded_out_dev, l->syn, l->plan, cd, ch, b, decoded_dev, s));
+  CN_HIP(launch_finish(coded_out_dev, l->syn, l->partials, n_parts, cd, ch, b, decoded_dev, report_dev, s));
   return CODENET_OK;
 }
 

@@ -93,10 +93,10 @@ hipError_t launch_encode_vector(const float *V, float *Vt, const DevCode *code_d
                                 int b, void *Vb, long ldVb, float *zero, long zero_count4, hipStream_t s);
 hipError_t launch_detect(const float *out, float *syn, double *partials, int *n_parts,
                          const DevCode *code_dev, const DevCode &code_host, int b, hipStream_t s);
-hipError_t launch_decide(const double *partials, int n_parts, const DevCode *code_dev, const DevCode &code_host,
-                         DevPlan *plan, codenet_report *report, hipStream_t s);
-hipError_t launch_correct(float *out, const float *syn, const DevPlan *plan, const DevCode *code_dev,
-                          const DevCode &code_host, int b, float *decoded, hipStream_t s);
+// passes 2 + 3 of a check: decision (every workgroup, from the pass-1 records), correction, decoded output
+hipError_t launch_finish(float *out, const float *syn, const double *partials, int n_parts,
+                         const DevCode *code_dev, const DevCode &code_host, int b, float *decoded,
+                         codenet_report *report, hipStream_t s);
 hipError_t launch_fault(const FaultArgs &fa, hipStream_t s, bool stats_pass);
 hipError_t launch_export_weights(const float *Wt, float *W, const DevCode &cr, const DevCode &cc,
                                  int Nc, int n_out, int n_in, hipStream_t s);

@@ -287,8 +287,8 @@ __device__ __forceinline__ unsigned pack2_bf16(float lo, float hi) {
   return (unsigned)__builtin_bit_cast(unsigned short, a) | ((unsigned)__builtin_bit_cast(unsigned short, b) << 16);
 }
 
-template <int FM, int FN, int NS>
-__global__ __launch_bounds__(256) void update2_kernel(Update2Args g) {
+template <int FM, int FN, int NS, int DBG = 0>
+__global__ __launch_bounds__(256, (FM * FN <= 4 ? 2 : 1)) void update2_kernel(Update2Args g) {
   constexpr int TI = 64 * FM, TJ = 64 * FN;
   constexpr int PT = TJ * 2 + 16;       // pitch of the transposed staging tile [i][j], bytes
   constexpr int PR = TI * 2 + 16;       // pitch of the row-major staging tile [j][i], bytes
@@ -316,7 +316,7 @@ __global__ __launch_bounds__(256) void update2_kernel(Update2Args g) {
 #pragma unroll
       for (int x = 0; x < 16; ++x) {
         const int j = j0 + (wj * FN + b) * 32 + 8 * (x >> 2) + 4 * h + (x & 3);
-        old[a][b][x] = (i < g.I && j < g.J) ? g.W[(long)j * g.ldw + i] : 0.f;
+        old[a][b][x] = (i < g.I && j < g.J && !(DBG & 1)) ? g.W[(long)j * g.ldw + i] : 0.f;
       }
     }
 
@@ -327,7 +327,7 @@ __global__ __launch_bounds__(256) void update2_kernel(Update2Args g) {
     for (int b = 0; b < FN; ++b)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.f;
-  mainloop<FM, FN, NS>(g.XT, g.ldx, g.DT, g.ldd, g.I, g.J, i0, j0, 0, g.K >> 6, lds_c, acc);
+  if (!(DBG & 8)) mainloop<FM, FN, NS>(g.XT, g.ldx, g.DT, g.ldd, g.I, g.J, i0, j0, 0, g.K >> 6, lds_c, acc);
 
   __syncthreads();                       // every wavefront is done with the operand stages
 #pragma unroll
@@ -342,7 +342,7 @@ __global__ __launch_bounds__(256) void update2_kernel(Update2Args g) {
         const int j = j0 + (wj * FN + b) * 32 + 8 * (x >> 2) + 4 * h + (x & 3);
         const bool in = i < g.I && j < g.J;
         const float w = in ? fmaf(g.eta, acc[a][b][x], old[a][b][x]) : 0.f;
-        if (in) g.W[(long)j * g.ldw + i] = w;
+        if (in && !(DBG & 2)) g.W[(long)j * g.ldw + i] = w;
         acc[a][b][x] = w;
       }
       // 2. stage the bf16 value of w twice: transposed [i][j] and row-major [j][i]
@@ -360,6 +360,7 @@ __global__ __launch_bounds__(256) void update2_kernel(Update2Args g) {
       }
     }
   __syncthreads();
+  if (DBG & 4) return;
   // 3. both bf16 copies leave as rows of 16-byte chunks (the pitches are multiples
   //    of 64 elements: whole chunks fit, and entries beyond the matrix are zeros)
   for (int id = tid; id < TI * (TJ / 8); id += 256) {
@@ -433,7 +434,7 @@ hipError_t launch2(Gemm2Args g, hipStream_t s) {
   return hipGetLastError();
 }
 
-template <int FM, int FN, int NS>
+template <int FM, int FN, int NS, int DBG = 0>
 hipError_t launch_upd2(Update2Args g, hipStream_t s) {
   constexpr int TI = 64 * FM, TJ = 64 * FN;
   constexpr int stage = NS * (TI + TJ) * 128, st = TI * (TJ * 2 + 16) + TJ * (TI * 2 + 16);
@@ -444,9 +445,9 @@ hipError_t launch_upd2(Update2Args g, hipStream_t s) {
   const int nt = g.tiles_i * g.tiles_j;
   const int grid = ((nt + 7) / 8) * 8;
   static bool attr_done = false;
-  hipError_t e = set_lds(update2_kernel<FM, FN, NS>, lds, &attr_done);
+  hipError_t e = set_lds(update2_kernel<FM, FN, NS, DBG>, lds, &attr_done);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((update2_kernel<FM, FN, NS>), dim3(grid), dim3(256), lds, s, g);
+  hipLaunchKernelGGL((update2_kernel<FM, FN, NS, DBG>), dim3(grid), dim3(256), lds, s, g);
   return hipGetLastError();
 }
 
@@ -530,6 +531,20 @@ hipError_t launch_update2(Update2Args g, hipStream_t s) {
   const char *env = getenv("CODENET_UPD2");
   const int which = env ? atoi(env) : 0;
   if (which == 1) return launch_upd2<2, 2, 2>(g, s);
+#ifdef CODENET_ABLATION
+  const char *denv = getenv("CODENET_UPD2_DBG");
+  switch (denv ? atoi(denv) : 0) {
+    case 1: return launch_upd2<4, 2, 2, 1>(g, s);
+    case 2: return launch_upd2<4, 2, 2, 2>(g, s);
+    case 3: return launch_upd2<4, 2, 2, 3>(g, s);
+    case 4: return launch_upd2<4, 2, 2, 4>(g, s);
+    case 7: return launch_upd2<4, 2, 2, 7>(g, s);
+    case 8: return launch_upd2<4, 2, 2, 8>(g, s);
+    case 12: return launch_upd2<4, 2, 2, 12>(g, s);
+    case 15: return launch_upd2<4, 2, 2, 15>(g, s);
+    default: break;
+  }
+#endif
   return launch_upd2<4, 2, 2>(g, s);
 }
 

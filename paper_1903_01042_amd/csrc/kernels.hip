@@ -436,13 +436,6 @@ __device__ void decide_body(const double *partials, int n_parts, const DevCode *
   }
 }
 
-template <bool GENERIC>
-__global__ __launch_bounds__(256) void decide_kernel(const double *partials, int n_parts,
-                                                     const DevCode *__restrict__ code, DevPlan *__restrict__ plan,
-                                                     codenet_report *__restrict__ report) {
-  decide_body<GENERIC>(partials, n_parts, code, plan, report);
-}
-
 // ---------------------------------------------------------------------------
 // Consistency check, pass 1 (General Error-Detection Method): syndromes
 // out^_k = sum_i H[k][i] out_i for every position of a block, written out for
@@ -549,24 +542,24 @@ hipError_t launch_detect(const float *out, float *syn, double *partials, int *n_
   return hipGetLastError();
 }
 
-hipError_t launch_decide(const double *partials, int n_parts, const DevCode *code_dev, const DevCode &ch,
-                         DevPlan *plan, codenet_report *report, hipStream_t s) {
-  if (ch.r >= 4)
-    hipLaunchKernelGGL(decide_kernel<true>, dim3(1), dim3(256), 0, s, partials, n_parts, code_dev, plan, report);
-  else
-    hipLaunchKernelGGL(decide_kernel<false>, dim3(1), dim3(256), 0, s, partials, n_parts, code_dev, plan, report);
-  return hipGetLastError();
-}
-
 // ---------------------------------------------------------------------------
-// Consistency check, pass 3: subtract the reconstructed error blocks on the
-// accepted support and emit the decoded (systematic, unpadded) output.
+// Consistency check, passes 2 + 3 in one kernel: every workgroup first takes the
+// decision from the pass-1 records (the same deterministic arithmetic in each of
+// them -- cheaper than a single-workgroup kernel in between, whose chain of
+// dependent loads cost 8-10 us), then subtracts the reconstructed error blocks on
+// the accepted support and emits the decoded (systematic, unpadded) output.
+// Workgroup 0 writes the report.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void correct_kernel(float *__restrict__ out, const float *__restrict__ syn,
-                                                      const DevPlan *__restrict__ plan,
-                                                      const DevCode *__restrict__ code, int b,
-                                                      float *__restrict__ decoded, int aligned) {
-  const int corrected = plan->verdict == CODENET_CORRECTED ? plan->n_located : 0;
+template <bool GENERIC>
+__global__ __launch_bounds__(256) void finish_kernel(float *__restrict__ out, const float *__restrict__ syn,
+                                                     const double *__restrict__ partials, int n_parts,
+                                                     const DevCode *__restrict__ code, int b,
+                                                     float *__restrict__ decoded, int aligned,
+                                                     codenet_report *__restrict__ report) {
+  __shared__ DevPlan plan;
+  decide_body<GENERIC>(partials, n_parts, code, &plan, blockIdx.x == 0 ? report : nullptr);
+  __syncthreads();
+  const int corrected = plan.verdict == CODENET_CORRECTED ? plan.n_located : 0;
   if (corrected == 0 && decoded == nullptr) return;
   const int B = code->B, B0 = code->B0, L = code->L, a = code->a, r = code->r, N = code->N;
   const int quads = B >> 2;
@@ -579,10 +572,10 @@ __global__ __launch_bounds__(256) void correct_kernel(float *__restrict__ out, c
     float4 e = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int c = 0; c < r; ++c) {
       const float4 s = *reinterpret_cast<const float4 *>(syn + ((long)c * b + beta) * B + rho);
-      const float w = plan->coef[p][c];
+      const float w = plan.coef[p][c];
       e.x = fmaf(w, s.x, e.x); e.y = fmaf(w, s.y, e.y); e.z = fmaf(w, s.z, e.z); e.w = fmaf(w, s.w, e.w);
     }
-    const int i = plan->located[p];
+    const int i = plan.located[p];
     float4 v = *reinterpret_cast<float4 *>(row + i * B);
     v.x -= e.x; v.y -= e.y; v.z -= e.z; v.w -= e.w;
     *reinterpret_cast<float4 *>(row + i * B) = v;
@@ -605,12 +598,17 @@ __global__ __launch_bounds__(256) void correct_kernel(float *__restrict__ out, c
   }
 }
 
-hipError_t launch_correct(float *out, const float *syn, const DevPlan *plan, const DevCode *code_dev,
-                          const DevCode &ch, int b, float *decoded, hipStream_t s) {
+hipError_t launch_finish(float *out, const float *syn, const double *partials, int n_parts, const DevCode *code_dev,
+                         const DevCode &ch, int b, float *decoded, codenet_report *report, hipStream_t s) {
   const long total = (long)b * (ch.B >> 2);
   const int aligned = (ch.N % 4 == 0) && (ch.B0 % 4 == 0) && ((reinterpret_cast<uintptr_t>(decoded) & 15) == 0);
-  hipLaunchKernelGGL(correct_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, out, syn, plan,
-                     code_dev, b, decoded, aligned);
+  dim3 grid((unsigned)((total + 255) / 256)), block(256);
+  if (ch.r >= 4)
+    hipLaunchKernelGGL(finish_kernel<true>, grid, block, 0, s, out, syn, partials, n_parts, code_dev, b, decoded,
+                       aligned, report);
+  else
+    hipLaunchKernelGGL(finish_kernel<false>, grid, block, 0, s, out, syn, partials, n_parts, code_dev, b, decoded,
+                       aligned, report);
   return hipGetLastError();
 }
 
