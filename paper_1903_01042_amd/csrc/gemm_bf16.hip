@@ -33,6 +33,7 @@ namespace codenet {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 #define CN_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
 
@@ -72,6 +73,13 @@ template <int N>
 __device__ __forceinline__ void wait_vm() {
 #if CN_DEVICE_ASM
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+#endif
+}
+// LDS traffic of this wavefront complete, then the workgroup barrier; one asm
+// statement with a memory clobber, so no LDS access is moved across it
+__device__ __forceinline__ void lds_barrier() {
+#if CN_DEVICE_ASM
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 #endif
 }
 // orders the consumers of v after every asm statement issued before this one
@@ -377,6 +385,284 @@ __global__ __launch_bounds__(256, (FM * FN <= 4 ? 2 : 1)) void update2_kernel(Up
   }
 }
 
+// ---------------------------------------------------------------------------
+// Coded update, persistent and wave-specialised (batch of at least 256).
+//
+// update2_kernel spends 40 us in its contraction and 54 us streaming the fp32
+// matrix and its bf16 copies, one after the other.  Here a workgroup of 8
+// wavefronts stays resident and walks over 128 x 128 tiles, with three roles
+// that meet only at the per-slab workgroup barriers (every wavefront executes
+// the same number of s_barrier: one per slab, one at the end of a tile):
+//  * wavefronts 0-3 (MMA) run one flat slab pipeline across all tiles of the
+//    workgroup (direct-to-LDS loads three stages deep, MFMAs); their vmcnt only
+//    ever counts those loads.  At the end of a tile they add eta * acc to the
+//    fp32 tile that waits in LDS, in place;
+//  * wavefronts 4-5 (loaders) fetch the fp32 tile of the matrix from HBM into
+//    registers a whole tile period ahead and drop it into LDS during slab 2,
+//    once the storers have released the buffer; no other wavefront ever waits
+//    on HBM;
+//  * wavefronts 6-7 (storers) work one tile behind: during slab 0 they read the
+//    updated tile row-wise and store the matrix and its row-major bf16 copy,
+//    during slab 1 they read it column-wise and store the transposed copy.  They
+//    only ever issue stores, so they never wait for memory.
+// On gfx9 one counter covers loads and stores and stores return out of order:
+// a wavefront that mixes the two can only wait for everything, which is why
+// the roles are split this way.  Tiles are dealt so that the workgroups of one
+// XCD work on an 8 x TJX block of tiles at a time (operand panels of about
+// 1.5 MB stay in that XCD's L2).  Streaming accesses stay ordinary cached ones:
+// the matrix and its copies largely live in the 256 MB memory-side cache from
+// one step to the next, and non-temporal stores forfeit that (150 us vs 84 us).
+// ---------------------------------------------------------------------------
+struct TileWalk {
+  int tiles_i, tiles_j, tjx, span, total, x, step, q;
+  __device__ void init(int ti, int tj) {
+    tiles_i = ti; tiles_j = tj;
+    tjx = (tj + 7) >> 3;                      // tile rows per XCD
+    span = 8 * tjx;                           // tiles in one block of 8 tile columns
+    total = span * ((ti + 7) >> 3);
+    x = blockIdx.x & 7;
+    step = gridDim.x >> 3;
+    q = (int)(blockIdx.x >> 3) - step;
+  }
+  // next valid tile of this workgroup; false when there is none
+  __device__ bool next(int &ti, int &tj) {
+    for (q += step; q < total; q += step) {
+      const int blk = q / span, w = q % span;
+      ti = 8 * blk + (w & 7);
+      tj = x * tjx + (w >> 3);
+      if (ti < tiles_i && tj < tiles_j) return true;
+    }
+    return false;
+  }
+};
+
+// DBG (ablation builds): 1 loaders and storers idle, 2 MMA role idles, 4 no stores at all,
+// 8 no transposed-copy stores, 16 no row-major-copy stores, 32 no fp32 stores
+template <int DBG = 0>
+__global__ __launch_bounds__(512) void update3_kernel(Update2Args g) {
+  constexpr int STAGE = 256 * 128;            // bytes: 128 A rows + 128 B rows of 128 bytes
+  constexpr int TILE = 3 * STAGE;             // fp32 tile [128 j][128 i] of the matrix, pitch 512 bytes; 160 KB in all
+  extern __shared__ uint4 lds[];
+  char *const lds_c = reinterpret_cast<char *>(lds);
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int KS = g.K >> 6;                    // slabs per tile (>= 4)
+
+  TileWalk walk;
+  walk.init(g.tiles_i, g.tiles_j);
+  int ti, tj;
+  if (!walk.next(ti, tj)) return;             // uniform: nothing for this workgroup
+
+  if (wave < 4) {
+    // ---------------------------------------------------------------------- MMA
+    const int wi = wave & 1, wj = wave >> 1;
+    const int l32 = lane & 31, h = lane >> 5;
+    const int lrow = lane >> 3, chunk = (lane & 7) ^ lrow;
+    unsigned offA[4], offB[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const unsigned slot = (unsigned)(((2 * s + h) ^ (l32 & 7)) * 16);
+      offA[s] = (unsigned)((wi * 64 + l32) * 128) + slot;
+      offB[s] = (unsigned)(128 * 128 + (wj * 64 + l32) * 128) + slot;
+    }
+    const __bf16 *src[8];                     // 4 A loads then 4 B loads of the slab being requested
+    auto point_at = [&](int pti, int ptj) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        int row = pti * 128 + 8 * (4 * u + wave) + lrow;
+        row = row < g.I ? row : g.I - 1;
+        src[u] = g.XT + (long)row * g.ldx + chunk * 8;
+        row = ptj * 128 + 8 * (4 * u + wave) + lrow;
+        row = row < g.J ? row : g.J - 1;
+        src[4 + u] = g.DT + (long)row * g.ldd + chunk * 8;
+      }
+    };
+    auto issue_one = [&](int kslab, int stage, int u) {
+#if CN_DEVICE_ASM
+      char *dst = lds_c + stage * STAGE + (u < 4 ? 0 : 128 * 128) + (4 * (u & 3) + wave) * 1024;
+      __builtin_amdgcn_global_load_lds(src[u] + (long)kslab * 64, CN_LDS_PTR(dst), 16, 0, 0);
+#else
+      (void)kslab; (void)stage; (void)u;
+#endif
+    };
+    floatx16 acc[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.f;
+
+    point_at(ti, tj);
+    if (!(DBG & 2)) {
+#pragma unroll
+      for (int u = 0; u < 8; ++u) issue_one(0, 0, u);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) issue_one(1, 1, u);
+    }
+    int nti = 0, ntj = 0;
+    bool more = walk.next(nti, ntj);
+    int stage = 0;                            // stage of the slab being consumed; the pipeline is flat across tiles
+    for (;;) {
+      for (int kt = 0; kt < KS; ++kt) {
+        // the slab after this one was requested one round ago and may still be in flight
+        if (kt + 1 < KS || more) wait_vm<8>();
+        else wait_vm<0>();
+        lds_barrier();
+        if (DBG & 2) continue;
+        // requested during this slab: two slabs ahead, in this tile or at the start of the next one
+        const bool wraps = kt + 2 >= KS;
+        const bool prefetch = !wraps || more;
+        if (kt + 2 == KS && more) point_at(nti, ntj);
+        const int pk = wraps ? kt + 2 - KS : kt + 2;
+        const int pstage = stage == 0 ? 2 : stage - 1;
+        const unsigned sb = (unsigned)(stage * STAGE);
+        stage = stage == 2 ? 0 : stage + 1;
+        u32x4 fa[2][2], fb[2][2];
+        read_frags<2>(fa[0], sb + offA[0]);
+        read_frags<2>(fb[0], sb + offB[0]);
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          const int cur = s & 1, nxt = cur ^ 1;
+          if (s < 3) {
+            read_frags<2>(fa[nxt], sb + offA[s + 1]);
+            read_frags<2>(fb[nxt], sb + offB[s + 1]);
+            wait_lgkm<4>();
+          } else {
+            wait_lgkm<0>();
+          }
+          pin(fa[cur][0]); pin(fa[cur][1]); pin(fb[cur][0]); pin(fb[cur][1]);
+#pragma unroll
+          for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int b = 0; b < 2; ++b) {
+              const int m = a * 2 + b;
+              if ((m & 1) == 0) {
+                if (prefetch) issue_one(pk, pstage, s * 2 + (m >> 1));
+                __builtin_amdgcn_sched_barrier(0);
+              }
+              acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fb[cur][b]),
+                                                                  __builtin_bit_cast(bf16x8, fa[cur][a]), acc[a][b], 0, 0, 0);
+            }
+        }
+      }
+      // end of the tile: the loaders' fp32 tile is in; add eta * acc in place.
+      // Element x of fragment (a, b) is (j = 8 (x / 4) + 4 h + x % 4, i = lane % 32).
+      lds_barrier();
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+          const int il = (wi * 2 + a) * 32 + l32;
+#pragma unroll
+          for (int x = 0; x < 16; ++x) {
+            const int jl = (wj * 2 + b) * 32 + 8 * (x >> 2) + 4 * h + (x & 3);
+            float *cell = reinterpret_cast<float *>(lds_c + TILE + jl * 512 + il * 4);
+            *cell += g.eta * acc[a][b][x];
+            acc[a][b][x] = 0.f;
+          }
+        }
+      if (!more) break;
+      ti = nti; tj = ntj;
+      more = walk.next(nti, ntj);
+    }
+    // two more rounds let the storers finish the last tile
+    lds_barrier();
+    lds_barrier();
+    return;
+  }
+
+  if (wave < 6) {
+    // ------------------------------------------------------------------ loaders
+    const int v = tid - 256;                  // 0 .. 127: item n is row 4 n + v / 32, columns 4 (v % 32) .. + 3
+    f32x4 old[32];                            // native vectors: an array of HIP's float4 struct ends up in scratch here
+    bool first = true, have = true;
+    while (have) {
+      if (!(DBG & 1)) {
+        const int col = ti * 128 + (v & 31) * 4;
+        const float *src = g.W + (col < g.I ? col : g.I - 4);
+#pragma unroll
+        for (int n = 0; n < 32; ++n) {
+          int row = tj * 128 + 4 * n + (v >> 5);
+          row = row < g.J ? row : g.J - 1;
+          old[n] = *reinterpret_cast<const f32x4 *>(src + (long)row * g.ldw);
+        }
+      }
+      if (!first) {
+        for (int kt = 3; kt < KS; ++kt) lds_barrier();
+        lds_barrier();                                    // end of the tile before
+      }
+      first = false;
+      lds_barrier(); lds_barrier(); lds_barrier();        // slabs 0-2: the storers are done with the tile buffer
+      if (!(DBG & 1)) {
+#pragma unroll
+        for (int n = 0; n < 32; ++n)
+          *reinterpret_cast<f32x4 *>(lds_c + TILE + (4 * n + (v >> 5)) * 512 + (v & 31) * 16) = old[n];
+      }
+      have = walk.next(ti, tj);
+    }
+    for (int kt = 3; kt < KS; ++kt) lds_barrier();
+    lds_barrier();                                        // end of the last tile
+    lds_barrier();
+    lds_barrier();
+    return;
+  }
+
+  // -------------------------------------------------------------------- storers
+  const int v = tid - 384;                    // 0 .. 127
+  int pti = 0, ptj = 0;                       // tile being stored (one behind the MMA role)
+  bool have_prev = false, more = true;
+  for (;;) {
+    lds_barrier();
+    if (have_prev && !(DBG & 1)) {
+      // rows: item k is row 8 k + v / 16, columns 8 (v % 16) .. + 7
+#pragma unroll 4
+      for (int k = 0; k < 16; ++k) {
+        const int rl = 8 * k + (v >> 4), cl = (v & 15) * 8;
+        const int j = ptj * 128 + rl, i = pti * 128 + cl;
+        float4 w0 = *reinterpret_cast<const float4 *>(lds_c + TILE + rl * 512 + cl * 4);
+        float4 w1 = *reinterpret_cast<const float4 *>(lds_c + TILE + rl * 512 + cl * 4 + 16);
+        const bool in0 = j < g.J && i < g.I, in1 = j < g.J && i + 4 < g.I;
+        if (!in0) w0 = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (!in1) w1 = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (in0 && !(DBG & 36)) *reinterpret_cast<float4 *>(g.W + (long)j * g.ldw + i) = w0;
+        if (in1 && !(DBG & 36)) *reinterpret_cast<float4 *>(g.W + (long)j * g.ldw + i + 4) = w1;
+        uint4 pk;
+        pk.x = pack2_bf16(w0.x, w0.y); pk.y = pack2_bf16(w0.z, w0.w);
+        pk.z = pack2_bf16(w1.x, w1.y); pk.w = pack2_bf16(w1.z, w1.w);
+        if (j < g.J && i < g.ldWb && (!(DBG & 20) || pk.x == 0x12345u))
+          *reinterpret_cast<uint4 *>(g.Wb + (long)j * g.ldWb + i) = pk;
+      }
+    }
+    lds_barrier();
+    if (have_prev && !(DBG & 1)) {
+      // columns: column v, eight consecutive j per item -> 16-byte pieces of the transposed copy
+      const int i = pti * 128 + v;
+#pragma unroll 4
+      for (int k = 0; k < 16; ++k) {
+        float c[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          c[e] = *reinterpret_cast<const float *>(lds_c + TILE + (8 * k + e) * 512 + v * 4);
+          if (ptj * 128 + 8 * k + e >= g.J) c[e] = 0.f;
+        }
+        uint4 pk;
+        pk.x = pack2_bf16(c[0], c[1]); pk.y = pack2_bf16(c[2], c[3]);
+        pk.z = pack2_bf16(c[4], c[5]); pk.w = pack2_bf16(c[6], c[7]);
+        const int j = ptj * 128 + 8 * k;
+        if (i < g.I && j < g.ldWTb && (!(DBG & 12) || pk.x == 0x12345u))
+          *reinterpret_cast<uint4 *>(g.WTb + (long)i * g.ldWTb + j) = pk;
+      }
+    }
+    if (!more) break;
+    for (int kt = 2; kt < KS; ++kt) lds_barrier();
+    lds_barrier();                                        // end of tile
+    pti = ti; ptj = tj;
+    have_prev = true;
+    more = walk.next(ti, tj);
+  }
+}
+
 // out[c][r] = bf16(in[r][c]) for r < R, 0 for R <= r < Rpad (feature-major copy of a batch-major block)
 __global__ __launch_bounds__(256) void transpose_bf16_kernel(const float *__restrict__ in, long ld_in, int R, int C,
                                                              __bf16 *__restrict__ out, long ld_out, int Rpad) {
@@ -525,9 +811,42 @@ hipError_t launch_gemm2(Gemm2Args g, int tile, float *workspace, hipStream_t s) 
   return hipGetLastError();
 }
 
+template <int DBG = 0>
+hipError_t launch_upd3(Update2Args g, hipStream_t s) {
+  constexpr int lds = 3 * 256 * 128 + 128 * 128 * 4;   // 160 KB
+  g.tiles_i = (g.I + 127) / 128;
+  g.tiles_j = (g.J + 127) / 128;
+  static bool attr_done = false;
+  hipError_t e = set_lds(update3_kernel<DBG>, lds, &attr_done);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(update3_kernel<DBG>, dim3(256), dim3(512), lds, s, g);
+  return hipGetLastError();
+}
+
+hipError_t launch_update3(Update2Args g, hipStream_t s) {
+#ifdef CODENET_ABLATION
+  const char *denv = getenv("CODENET_UPD3_DBG");
+  switch (denv ? atoi(denv) : 0) {
+    case 1: return launch_upd3<1>(g, s);
+    case 2: return launch_upd3<2>(g, s);
+    case 3: return launch_upd3<3>(g, s);
+    case 4: return launch_upd3<4>(g, s);
+    case 6: return launch_upd3<6>(g, s);
+    case 8: return launch_upd3<8>(g, s);
+    case 16: return launch_upd3<16>(g, s);
+    case 24: return launch_upd3<24>(g, s);
+    case 32: return launch_upd3<32>(g, s);
+    default: break;
+  }
+#endif
+  return launch_upd3<0>(g, s);
+}
+
 hipError_t launch_update2(Update2Args g, hipStream_t s) {
   if ((g.K & 63) || (g.ldx & 7) || (g.ldd & 7) || (g.ldWb & 63) || (g.ldWTb & 63) || g.I < 1 || g.J < 1)
     return hipErrorInvalidValue;
+  const char *env3 = getenv("CODENET_UPD3");
+  if (g.K >= 256 && (g.I & 3) == 0 && !(env3 && env3[0] == '0')) return launch_update3(g, s);
   const char *env = getenv("CODENET_UPD2");
   const int which = env ? atoi(env) : 0;
   if (which == 1) return launch_upd2<2, 2, 2>(g, s);
