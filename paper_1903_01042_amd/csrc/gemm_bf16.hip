@@ -401,10 +401,12 @@ __global__ __launch_bounds__(256, (FM * FN <= 4 ? 2 : 1)) void update2_kernel(Up
 //    registers a whole tile period ahead and drop it into LDS during slab 2,
 //    once the storers have released the buffer; no other wavefront ever waits
 //    on HBM;
-//  * wavefronts 6-7 (storers) work one tile behind: during slab 0 they read the
-//    updated tile row-wise and store the matrix and its row-major bf16 copy,
-//    during slab 1 they read it column-wise and store the transposed copy.  They
-//    only ever issue stores, so they never wait for memory.
+//  * wavefronts 6-7 (storers) work one tile behind: during slab 0 they gather
+//    rows of the matrix from the (transposed) LDS tile and store them and the
+//    row-major bf16 copy, during slab 1 they store the transposed copy; every
+//    store instruction writes whole 64-byte segments (the L2 request rate, not
+//    its bandwidth, is what this kernel runs into).  They only ever issue
+//    stores, so they never wait for memory.
 // On gfx9 one counter covers loads and stores and stores return out of order:
 // a wavefront that mixes the two can only wait for everything, which is why
 // the roles are split this way.  Tiles are dealt so that the workgroups of one
@@ -441,9 +443,17 @@ struct TileWalk {
 template <int DBG = 0>
 __global__ __launch_bounds__(512) void update3_kernel(Update2Args g) {
   constexpr int STAGE = 256 * 128;            // bytes: 128 A rows + 128 B rows of 128 bytes
-  constexpr int TILE = 3 * STAGE;             // fp32 tile [128 j][128 i] of the matrix, pitch 512 bytes; 160 KB in all
+  constexpr int TILE = 3 * STAGE;             // fp32 tile of the matrix, 64 KB: 160 KB in all
   extern __shared__ uint4 lds[];
   char *const lds_c = reinterpret_cast<char *>(lds);
+  // The fp32 tile is kept transposed, [i][j] with 512-byte rows, because an MMA lane
+  // owns four consecutive j of one i.  The 16-byte piece j / 4 of row i sits at
+  // piece (j / 4) ^ f(i), f(i) = (i ^ i / 32) % 32: the MMA lanes (32 consecutive i),
+  // the loaders (i = 4 c + e over 32 c) and the column readers (i = 8 c + e over 16 c)
+  // all spread over the banks with at most two-way conflicts.
+  auto cell = [&](int il, int jl) -> char * {
+    return lds_c + TILE + il * 512 + ((((jl >> 2) ^ il ^ (il >> 5)) & 31) << 4) + ((jl & 3) << 2);
+  };
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
   const int KS = g.K >> 6;                    // slabs per tile (>= 4)
@@ -546,8 +556,8 @@ __global__ __launch_bounds__(512) void update3_kernel(Update2Args g) {
             }
         }
       }
-      // end of the tile: the loaders' fp32 tile is in; add eta * acc in place.
-      // Element x of fragment (a, b) is (j = 8 (x / 4) + 4 h + x % 4, i = lane % 32).
+      // end of the tile: the loaders' fp32 tile is in; add eta * acc in place.  Elements
+      // 4 q .. 4 q + 3 of fragment (a, b) are j = 8 q + 4 h .. + 3 of column i = lane % 32.
       lds_barrier();
 #pragma unroll
       for (int a = 0; a < 2; ++a)
@@ -555,55 +565,102 @@ __global__ __launch_bounds__(512) void update3_kernel(Update2Args g) {
         for (int b = 0; b < 2; ++b) {
           const int il = (wi * 2 + a) * 32 + l32;
 #pragma unroll
-          for (int x = 0; x < 16; ++x) {
-            const int jl = (wj * 2 + b) * 32 + 8 * (x >> 2) + 4 * h + (x & 3);
-            float *cell = reinterpret_cast<float *>(lds_c + TILE + jl * 512 + il * 4);
-            *cell += g.eta * acc[a][b][x];
-            acc[a][b][x] = 0.f;
+          for (int q = 0; q < 4; ++q) {
+            f32x4 *p = reinterpret_cast<f32x4 *>(cell(il, (wj * 2 + b) * 32 + 8 * q + 4 * h));
+            f32x4 w = *p;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              w[e] += g.eta * acc[a][b][4 * q + e];
+              acc[a][b][4 * q + e] = 0.f;
+            }
+            *p = w;
           }
         }
       if (!more) break;
       ti = nti; tj = ntj;
       more = walk.next(nti, ntj);
     }
-    // two more rounds let the storers finish the last tile
-    lds_barrier();
+    // the storers finish the last tile after this one
     lds_barrier();
     return;
   }
 
+  // Schedule of the other two roles inside a tile period (barriers B0 .. B(KS-1), then
+  // the end-of-tile barrier).  With 8 slabs or more: the storers empty the tile buffer
+  // in four quarters after B0 .. B3 and the loaders refill it in four groups after
+  // B4 .. B7; with fewer slabs the quarters pair up after B0, B1 and the groups after
+  // B2, B3.  No piece is long enough to hold the MMA wavefronts up at the next barrier.
+  const bool wide = KS >= 8;
+
   if (wave < 6) {
     // ------------------------------------------------------------------ loaders
-    const int v = tid - 256;                  // 0 .. 127: item n is row 4 n + v / 32, columns 4 (v % 32) .. + 3
+    // Lane v holds, as item n, the values of row j = 4 n + v / 32, columns i = 4 (v % 32) .. + 3;
+    // group q is items 8 q .. 8 q + 7.  As soon as a group is in LDS, the same registers
+    // request that group of the next tile: the HBM latency has a whole tile period.
+    const int v = tid - 256;
     f32x4 old[32];                            // native vectors: an array of HIP's float4 struct ends up in scratch here
-    bool first = true, have = true;
-    while (have) {
-      if (!(DBG & 1)) {
-        const int col = ti * 128 + (v & 31) * 4;
-        const float *src = g.W + (col < g.I ? col : g.I - 4);
+    if (DBG & 128)
+      for (int n = 0; n < 32; ++n) old[n] = f32x4{0.f, 0.f, 0.f, 0.f};
+    char *rowbase[4];
+    int fe[4];
 #pragma unroll
-        for (int n = 0; n < 32; ++n) {
-          int row = tj * 128 + 4 * n + (v >> 5);
-          row = row < g.J ? row : g.J - 1;
-          old[n] = *reinterpret_cast<const f32x4 *>(src + (long)row * g.ldw);
-        }
-      }
-      if (!first) {
-        for (int kt = 3; kt < KS; ++kt) lds_barrier();
-        lds_barrier();                                    // end of the tile before
-      }
-      first = false;
-      lds_barrier(); lds_barrier(); lds_barrier();        // slabs 0-2: the storers are done with the tile buffer
-      if (!(DBG & 1)) {
-#pragma unroll
-        for (int n = 0; n < 32; ++n)
-          *reinterpret_cast<f32x4 *>(lds_c + TILE + (4 * n + (v >> 5)) * 512 + (v & 31) * 16) = old[n];
-      }
-      have = walk.next(ti, tj);
+    for (int e = 0; e < 4; ++e) {
+      const int il = 4 * (v & 31) + e;
+      rowbase[e] = lds_c + TILE + il * 512 + ((v >> 5) << 2);
+      fe[e] = (il ^ (il >> 5)) & 31;
     }
-    for (int kt = 3; kt < KS; ++kt) lds_barrier();
-    lds_barrier();                                        // end of the last tile
-    lds_barrier();
+    auto request_group = [&](int gq, int rti, int rtj) {
+      if (DBG & 129) return;
+      if ((rti + 1) * 128 <= g.I && (rtj + 1) * 128 <= g.J) {
+        // whole tile inside the matrix: one base address, uniform strides
+        const float *src = g.W + (long)(rtj * 128 + (v >> 5)) * g.ldw + rti * 128 + (v & 31) * 4;
+#pragma unroll
+        for (int n8 = 0; n8 < 8; ++n8) {
+          const int n = gq * 8 + n8;
+          old[n] = *reinterpret_cast<const f32x4 *>(src + (long)(4 * n) * g.ldw);
+        }
+        return;
+      }
+      const int col = rti * 128 + (v & 31) * 4;
+      const float *src = g.W + (col < g.I ? col : g.I - 4);
+#pragma unroll
+      for (int n8 = 0; n8 < 8; ++n8) {
+        const int n = gq * 8 + n8;
+        int row = rtj * 128 + 4 * n + (v >> 5);
+        row = row < g.J ? row : g.J - 1;
+        old[n] = *reinterpret_cast<const f32x4 *>(src + (long)row * g.ldw);
+      }
+    };
+    auto write_group = [&](int gq) {
+      if (DBG & 257) return;
+#if CN_DEVICE_ASM
+      // recompute the 32 addresses of a group here: hoisted out of the tile loop they cost 128 registers
+#pragma unroll
+      for (int e = 0; e < 4; ++e) asm volatile("" : "+v"(fe[e]));
+#endif
+#pragma unroll
+      for (int n8 = 0; n8 < 8; ++n8)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int n = gq * 8 + n8;
+          *reinterpret_cast<float *>(rowbase[e] + ((n ^ fe[e]) << 4)) = old[n][e];
+        }
+    };
+#pragma unroll
+    for (int gq = 0; gq < 4; ++gq) request_group(gq, ti, tj);
+    bool have = true;
+    while (have) {
+      for (int e = wide ? 5 : 3; e > 0; --e) lds_barrier();
+      have = walk.next(ti, tj);
+#pragma unroll
+      for (int gq = 0; gq < 4; ++gq) {
+        if (gq > 0 && (wide || gq == 2)) lds_barrier();
+        write_group(gq);
+        if (have) request_group(gq, ti, tj);
+      }
+      for (int e = KS - (wide ? 8 : 4); e > 0; --e) lds_barrier();
+      lds_barrier();                                      // end of the tile
+    }
     lds_barrier();
     return;
   }
@@ -611,56 +668,134 @@ __global__ __launch_bounds__(512) void update3_kernel(Update2Args g) {
   // -------------------------------------------------------------------- storers
   const int v = tid - 384;                    // 0 .. 127
   int pti = 0, ptj = 0;                       // tile being stored (one behind the MMA role)
-  bool have_prev = false, more = true;
-  for (;;) {
-    lds_barrier();
-    if (have_prev && !(DBG & 1)) {
-      // rows: item k is row 8 k + v / 16, columns 8 (v % 16) .. + 7
-#pragma unroll 4
-      for (int k = 0; k < 16; ++k) {
-        const int rl = 8 * k + (v >> 4), cl = (v & 15) * 8;
-        const int j = ptj * 128 + rl, i = pti * 128 + cl;
-        float4 w0 = *reinterpret_cast<const float4 *>(lds_c + TILE + rl * 512 + cl * 4);
-        float4 w1 = *reinterpret_cast<const float4 *>(lds_c + TILE + rl * 512 + cl * 4 + 16);
+  // quarters 0, 1: fp32 matrix and row-major copy; item k is row j = 8 k + v / 16, columns i = 8 (v % 16) .. + 7
+  char *rowA[8];
+  int feA[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const int il = 8 * (v & 15) + e;
+    rowA[e] = lds_c + TILE + il * 512 + (((v >> 4) & 3) << 2);
+    feA[e] = ((((il ^ (il >> 5)) & 31) ^ (v >> 6)) << 4);
+  }
+  // quarters 2, 3: transposed copy; item k is row i = 8 k + v / 16, columns j = 8 (v % 16) .. + 7
+  char *const rowB = lds_c + TILE + (v >> 4) * 512;
+  int baseB = ((2 * (v & 15)) ^ (v >> 4)) << 4;
+  auto quarter = [&](int qt) {
+    if (DBG & 513) return;
+    if ((DBG & 1024) && qt < 2) return;
+    if ((DBG & 2048) && qt >= 2) return;
+    // a tile that lies inside the matrix takes the branch-free path: all LDS reads of the
+    // quarter first, then the stores; an edge tile masks every access
+    const bool interior = (pti + 1) * 128 <= g.I && (ptj + 1) * 128 <= g.J;
+    if (qt < 2) {
+#if CN_DEVICE_ASM
+#pragma unroll
+      for (int e = 0; e < 8; ++e) asm volatile("" : "+v"(feA[e]));
+#endif
+      const int j0 = ptj * 128 + (v >> 4), i = pti * 128 + (v & 15) * 8;
+      float *const pw = g.W + (long)j0 * g.ldw + i;
+      __bf16 *const pb = g.Wb + (long)j0 * g.ldWb + i;
+      if (interior) {
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+          float c[4][8];
+#pragma unroll
+          for (int k4 = 0; k4 < 4; ++k4)
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+              c[k4][e] = *reinterpret_cast<const float *>(rowA[e] + (feA[e] ^ (32 * (qt * 8 + half * 4 + k4))));
+#pragma unroll
+          for (int k4 = 0; k4 < 4; ++k4) {
+            const int k = qt * 8 + half * 4 + k4;
+            const f32x4 w0 = {c[k4][0], c[k4][1], c[k4][2], c[k4][3]}, w1 = {c[k4][4], c[k4][5], c[k4][6], c[k4][7]};
+            const u32x4 pk = {pack2_bf16(w0[0], w0[1]), pack2_bf16(w0[2], w0[3]), pack2_bf16(w1[0], w1[1]), pack2_bf16(w1[2], w1[3])};
+            if (!(DBG & 36)) {
+              *reinterpret_cast<f32x4 *>(pw + (long)(8 * k) * g.ldw) = w0;
+              *reinterpret_cast<f32x4 *>(pw + (long)(8 * k) * g.ldw + 4) = w1;
+            }
+            if (!(DBG & 20) || pk[0] == 0x12345u) *reinterpret_cast<u32x4 *>(pb + (long)(8 * k) * g.ldWb) = pk;
+          }
+        }
+        return;
+      }
+#pragma unroll 2
+      for (int k8 = 0; k8 < 8; ++k8) {
+        const int k = qt * 8 + k8;
+        float c[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) c[e] = *reinterpret_cast<const float *>(rowA[e] + (feA[e] ^ (32 * k)));
+        float4 w0 = make_float4(c[0], c[1], c[2], c[3]), w1 = make_float4(c[4], c[5], c[6], c[7]);
+        const int j = j0 + 8 * k;
         const bool in0 = j < g.J && i < g.I, in1 = j < g.J && i + 4 < g.I;
         if (!in0) w0 = make_float4(0.f, 0.f, 0.f, 0.f);
         if (!in1) w1 = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (in0 && !(DBG & 36)) *reinterpret_cast<float4 *>(g.W + (long)j * g.ldw + i) = w0;
-        if (in1 && !(DBG & 36)) *reinterpret_cast<float4 *>(g.W + (long)j * g.ldw + i + 4) = w1;
+        if (in0 && !(DBG & 36)) *reinterpret_cast<float4 *>(pw + (long)(8 * k) * g.ldw) = w0;
+        if (in1 && !(DBG & 36)) *reinterpret_cast<float4 *>(pw + (long)(8 * k) * g.ldw + 4) = w1;
         uint4 pk;
         pk.x = pack2_bf16(w0.x, w0.y); pk.y = pack2_bf16(w0.z, w0.w);
         pk.z = pack2_bf16(w1.x, w1.y); pk.w = pack2_bf16(w1.z, w1.w);
         if (j < g.J && i < g.ldWb && (!(DBG & 20) || pk.x == 0x12345u))
-          *reinterpret_cast<uint4 *>(g.Wb + (long)j * g.ldWb + i) = pk;
+          *reinterpret_cast<uint4 *>(pb + (long)(8 * k) * g.ldWb) = pk;
       }
-    }
-    lds_barrier();
-    if (have_prev && !(DBG & 1)) {
-      // columns: column v, eight consecutive j per item -> 16-byte pieces of the transposed copy
-      const int i = pti * 128 + v;
-#pragma unroll 4
-      for (int k = 0; k < 16; ++k) {
-        float c[8];
+    } else {
+#if CN_DEVICE_ASM
+      asm volatile("" : "+v"(baseB));
+#endif
+      const int i0 = pti * 128 + (v >> 4), j = ptj * 128 + (v & 15) * 8;
+      __bf16 *const pt = g.WTb + (long)i0 * g.ldWTb + j;
+      // f(8 k + r) = 8 (k % 4) ^ r ^ k / 4 for r < 8
+      if (interior) {
+        f32x4 c[8][2];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          c[e] = *reinterpret_cast<const float *>(lds_c + TILE + (8 * k + e) * 512 + v * 4);
-          if (ptj * 128 + 8 * k + e >= g.J) c[e] = 0.f;
+        for (int k8 = 0; k8 < 8; ++k8) {
+          const int k = (qt - 2) * 8 + k8;
+          const int ck = ((8 * (k & 3)) ^ (k >> 2)) << 4;
+          c[k8][0] = *reinterpret_cast<const f32x4 *>(rowB + 4096 * k + (baseB ^ ck));
+          c[k8][1] = *reinterpret_cast<const f32x4 *>(rowB + 4096 * k + (baseB ^ ck ^ 16));
         }
+#pragma unroll
+        for (int k8 = 0; k8 < 8; ++k8) {
+          const int k = (qt - 2) * 8 + k8;
+          const u32x4 pk = {pack2_bf16(c[k8][0][0], c[k8][0][1]), pack2_bf16(c[k8][0][2], c[k8][0][3]),
+                            pack2_bf16(c[k8][1][0], c[k8][1][1]), pack2_bf16(c[k8][1][2], c[k8][1][3])};
+          if (!(DBG & 12) || pk[0] == 0x12345u) *reinterpret_cast<u32x4 *>(pt + (long)(8 * k) * g.ldWTb) = pk;
+        }
+        return;
+      }
+#pragma unroll 2
+      for (int k8 = 0; k8 < 8; ++k8) {
+        const int k = (qt - 2) * 8 + k8;
+        const int ck = ((8 * (k & 3)) ^ (k >> 2)) << 4;
+        f32x4 c0 = *reinterpret_cast<const f32x4 *>(rowB + 4096 * k + (baseB ^ ck));
+        f32x4 c1 = *reinterpret_cast<const f32x4 *>(rowB + 4096 * k + (baseB ^ ck ^ 16));
+        if (j >= g.J) c0 = f32x4{0.f, 0.f, 0.f, 0.f};       // J is a multiple of 4
+        if (j + 4 >= g.J) c1 = f32x4{0.f, 0.f, 0.f, 0.f};
         uint4 pk;
-        pk.x = pack2_bf16(c[0], c[1]); pk.y = pack2_bf16(c[2], c[3]);
-        pk.z = pack2_bf16(c[4], c[5]); pk.w = pack2_bf16(c[6], c[7]);
-        const int j = ptj * 128 + 8 * k;
-        if (i < g.I && j < g.ldWTb && (!(DBG & 12) || pk.x == 0x12345u))
-          *reinterpret_cast<uint4 *>(g.WTb + (long)i * g.ldWTb + j) = pk;
+        pk.x = pack2_bf16(c0[0], c0[1]); pk.y = pack2_bf16(c0[2], c0[3]);
+        pk.z = pack2_bf16(c1[0], c1[1]); pk.w = pack2_bf16(c1[2], c1[3]);
+        if (i0 + 8 * k < g.I && j < g.ldWTb && (!(DBG & 12) || pk.x == 0x12345u))
+          *reinterpret_cast<uint4 *>(pt + (long)(8 * k) * g.ldWTb) = pk;
       }
     }
-    if (!more) break;
-    for (int kt = 2; kt < KS; ++kt) lds_barrier();
-    lds_barrier();                                        // end of tile
+  };
+  bool have_prev = false, more = true;
+  while (more) {
+    lds_barrier();
+    if (have_prev) quarter(0);
+    if (wide) lds_barrier();
+    if (have_prev) quarter(1);
+    lds_barrier();
+    if (have_prev) quarter(2);
+    if (wide) lds_barrier();
+    if (have_prev) quarter(3);
+    for (int e = KS - (wide ? 4 : 2); e > 0; --e) lds_barrier();
+    lds_barrier();                                        // end of the tile
     pti = ti; ptj = tj;
     have_prev = true;
     more = walk.next(ti, tj);
   }
+  lds_barrier();
+  quarter(0); quarter(1); quarter(2); quarter(3);
 }
 
 // out[c][r] = bf16(in[r][c]) for r < R, 0 for R <= r < Rpad (feature-major copy of a batch-major block)
@@ -836,6 +971,12 @@ hipError_t launch_update3(Update2Args g, hipStream_t s) {
     case 16: return launch_upd3<16>(g, s);
     case 24: return launch_upd3<24>(g, s);
     case 32: return launch_upd3<32>(g, s);
+    case 68: return launch_upd3<68>(g, s);
+    case 132: return launch_upd3<132>(g, s);
+    case 388: return launch_upd3<388>(g, s);
+    case 644: return launch_upd3<644>(g, s);
+    case 1156: return launch_upd3<1156>(g, s);
+    case 2180: return launch_upd3<2180>(g, s);
     default: break;
   }
 #endif
@@ -846,7 +987,7 @@ hipError_t launch_update2(Update2Args g, hipStream_t s) {
   if ((g.K & 63) || (g.ldx & 7) || (g.ldd & 7) || (g.ldWb & 63) || (g.ldWTb & 63) || g.I < 1 || g.J < 1)
     return hipErrorInvalidValue;
   const char *env3 = getenv("CODENET_UPD3");
-  if (g.K >= 256 && (g.I & 3) == 0 && !(env3 && env3[0] == '0')) return launch_update3(g, s);
+  if (g.K >= 256 && (g.I & 3) == 0 && (g.J & 3) == 0 && !(env3 && env3[0] == '0')) return launch_update3(g, s);
   const char *env = getenv("CODENET_UPD2");
   const int which = env ? atoi(env) : 0;
   if (which == 1) return launch_upd2<2, 2, 2>(g, s);
