@@ -264,15 +264,14 @@ int codenet_forward(codenet_layer *l, const float *X_dev, int b, float *S_coded_
   if (l->bf16) {
     int tile = 0, splits = 1;
     plan_gemm2(l->Mr, b, l->KpX, kMaxSplits, &tile, &splits);
-    CN_HIP(launch_encode_vector(X_dev, l->Xt, l->code_c_dev, l->code_c, b, l->Xb, l->KpX, nullptr, 0, s));
+    // coded input: fp32, batch-major bf16 (product operand) and feature-major bf16 [x; x~] (update operand)
+    CN_HIP(launch_encode_vector_bf16(X_dev, l->Xt, l->code_c_dev, l->code_c, b, l->Xb, l->KpX, l->XTb, l->bpad, s));
     Gemm2Args g2{};
     g2.A = l->Wb; g2.lda = l->ldWb;
     g2.B = l->Xb; g2.ldb = l->KpX;
     g2.C = S_coded_dev; g2.ldc = l->Mr;
     g2.I = l->Mr; g2.J = b; g2.K = l->KpX; g2.splits = splits;
     CN_HIP(launch_gemm2(g2, tile, l->part, s));
-    // feature-major bf16 copy of [x; x~] for the update
-    CN_HIP(launch_transpose_bf16(l->Xt, l->Nc, b, l->Nc, l->XTb, l->bpad, (b + 63) & ~63, s));
     l->fwd_b = b;
     return CODENET_OK;
   }
@@ -296,14 +295,13 @@ int codenet_backward(codenet_layer *l, const float *D_dev, int b, float *C_coded
   if (l->bf16) {
     int tile = 0, splits = 1;
     plan_gemm2(l->Nc, b, l->KpD, kMaxSplits, &tile, &splits);
-    CN_HIP(launch_encode_vector(D_dev, l->Dt, l->code_r_dev, l->code_r, b, l->Db, l->KpD, nullptr, 0, s));
+    CN_HIP(launch_encode_vector_bf16(D_dev, l->Dt, l->code_r_dev, l->code_r, b, l->Db, l->KpD, l->DTb, l->bpad, s));
     Gemm2Args g2{};
     g2.A = l->WTb; g2.lda = l->ldWTb;
     g2.B = l->Db; g2.ldb = l->KpD;
     g2.C = C_coded_dev; g2.ldc = l->Nc;
     g2.I = l->Nc; g2.J = b; g2.K = l->KpD; g2.splits = splits;
     CN_HIP(launch_gemm2(g2, tile, l->part, s));
-    CN_HIP(launch_transpose_bf16(l->Dt, l->Mr, b, l->Mr, l->DTb, l->bpad, (b + 63) & ~63, s));
     l->bwd_b = b;
     return CODENET_OK;
   }

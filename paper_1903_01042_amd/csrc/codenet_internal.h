@@ -68,8 +68,6 @@ constexpr int kMaxSplits = 8;
 void plan_gemm2(int I, int J, int K, int max_splits, int *tile, int *splits);
 hipError_t launch_gemm2(Gemm2Args g, int tile, float *workspace, hipStream_t s);
 hipError_t launch_update2(Update2Args g, hipStream_t s);
-hipError_t launch_transpose_bf16(const float *in, long ld_in, int R, int C, void *out, long ld_out, int Rpad,
-                                 hipStream_t s);
 hipError_t launch_shadow(const float *Wt, int Mr, int Nc, void *Wb, long ldWb, void *WTb, long ldWTb,
                          hipStream_t s);
 
@@ -91,6 +89,8 @@ hipError_t launch_encode_matrix(const float *W, float *Wt, const DevCode *code_r
 // zero (optional): zero_count4 float4 of a buffer to clear in the same pass.
 hipError_t launch_encode_vector(const float *V, float *Vt, const DevCode *code_dev, const DevCode &code_host,
                                 int b, void *Vb, long ldVb, float *zero, long zero_count4, hipStream_t s);
+hipError_t launch_encode_vector_bf16(const float *V, float *Vt, const DevCode *code_dev, const DevCode &code_host,
+                                     int b, void *Vb, long ldVb, void *VTb, long ldVT, hipStream_t s);
 hipError_t launch_detect(const float *out, float *syn, double *partials, int *n_parts,
                          const DevCode *code_dev, const DevCode &code_host, int b, hipStream_t s);
 // passes 2 + 3 of a check: decision (every workgroup, from the pass-1 records), correction, decoded output

@@ -798,36 +798,6 @@ __global__ __launch_bounds__(512) void update3_kernel(Update2Args g) {
   quarter(0); quarter(1); quarter(2); quarter(3);
 }
 
-// out[c][r] = bf16(in[r][c]) for r < R, 0 for R <= r < Rpad (feature-major copy of a batch-major block)
-__global__ __launch_bounds__(256) void transpose_bf16_kernel(const float *__restrict__ in, long ld_in, int R, int C,
-                                                             __bf16 *__restrict__ out, long ld_out, int Rpad) {
-  __shared__ unsigned short tile[64][66];
-  const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
-  const int t = threadIdx.x;
-#pragma unroll
-  for (int p = 0; p < 4; ++p) {
-    const int r = (t >> 4) + 16 * p, c = (t & 15) * 4;
-    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (r0 + r < R && c0 + c < C) v = *reinterpret_cast<const float4 *>(in + (long)(r0 + r) * ld_in + c0 + c);
-    const __bf16 b0 = (__bf16)v.x, b1 = (__bf16)v.y, b2 = (__bf16)v.z, b3 = (__bf16)v.w;
-    tile[r][c] = __builtin_bit_cast(unsigned short, b0);
-    tile[r][c + 1] = __builtin_bit_cast(unsigned short, b1);
-    tile[r][c + 2] = __builtin_bit_cast(unsigned short, b2);
-    tile[r][c + 3] = __builtin_bit_cast(unsigned short, b3);
-  }
-  __syncthreads();
-#pragma unroll
-  for (int p = 0; p < 4; ++p) {
-    const int c = (t >> 4) + 16 * p, r = (t & 15) * 4;
-    if (c0 + c < C && r0 + r < Rpad) {
-      uint2 pk;
-      pk.x = (unsigned)tile[r][c] | ((unsigned)tile[r + 1][c] << 16);
-      pk.y = (unsigned)tile[r + 2][c] | ((unsigned)tile[r + 3][c] << 16);
-      *reinterpret_cast<uint2 *>(out + (long)(c0 + c) * ld_out + r0 + r) = pk;
-    }
-  }
-}
-
 namespace {
 
 struct Tile2 { int fm, fn, ns; };
@@ -1006,13 +976,6 @@ hipError_t launch_update2(Update2Args g, hipStream_t s) {
   }
 #endif
   return launch_upd2<4, 2, 2>(g, s);
-}
-
-hipError_t launch_transpose_bf16(const float *in, long ld_in, int R, int C, void *out, long ld_out, int Rpad,
-                                 hipStream_t s) {
-  dim3 grid((unsigned)((C + 63) / 64), (unsigned)((Rpad + 63) / 64));
-  hipLaunchKernelGGL(transpose_bf16_kernel, grid, dim3(256), 0, s, in, ld_in, R, C, (__bf16 *)out, ld_out, Rpad);
-  return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------

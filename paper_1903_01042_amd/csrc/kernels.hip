@@ -154,6 +154,90 @@ hipError_t launch_encode_vector(const float *V, float *Vt, const DevCode *code_d
   return hipGetLastError();
 }
 
+// The same encoding for the bf16 mode, one 64 (batch) x 64 (positions) tile of one
+// output block per workgroup: besides the fp32 coded vector it writes the two bf16
+// copies that the MFMA kernels read, the batch-major one (operand of the product)
+// and, through an LDS transposition, the feature-major one (operand of the update);
+// batch columns b .. Rpad-1 of the latter are written as zeros.  Jobs 0 .. a-1 copy
+// a systematic block, job a + k computes parity block k.
+__global__ __launch_bounds__(256) void encode_vector_bf16_kernel(const float *__restrict__ V, float *__restrict__ Vt,
+                                                                 const DevCode *__restrict__ code, int b,
+                                                                 __bf16 *__restrict__ Vb, long ldVb,
+                                                                 __bf16 *__restrict__ VTb, long ldVT, int Rpad,
+                                                                 int aligned) {
+  __shared__ unsigned short tile[64][66];
+  const int B = code->B, B0 = code->B0, a = code->a, r = code->r, N = code->N;
+  const int rho0 = blockIdx.x * 64, beta0 = blockIdx.y * 64, job = blockIdx.z;
+  const int t = threadIdx.x;
+  const int c = (t & 15) * 4, rho = rho0 + c;
+  auto fetch = [&](const float *src, int i, float (&v)[4]) {
+    if (aligned) {        // N and B0 multiples of 4, V 16-byte aligned: whole quads are real or padding
+      const int g = i * B0 + rho;
+      const float4 q = (rho < B0 && g < N) ? *reinterpret_cast<const float4 *>(src + g) : make_float4(0.f, 0.f, 0.f, 0.f);
+      v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int g = i * B0 + rho + e;
+        v[e] = (rho + e < B0 && g < N) ? src[g] : 0.f;
+      }
+    }
+  };
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    const int rr = (t >> 4) + 16 * p, beta = beta0 + rr;
+    float v[4] = {0.f, 0.f, 0.f, 0.f};
+    if (beta < b && rho < B) {
+      const float *src = V + (long)beta * N;
+      if (job < a) {
+        fetch(src, job, v);
+      } else {
+        const int k = job - a;
+        for (int i = 0; i < a; ++i) {
+          float x[4];
+          fetch(src, i, x);
+          const float h = code->Hf[k][i];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[e] = fmaf(h, x[e], v[e]);
+        }
+      }
+      *reinterpret_cast<float4 *>(Vt + (long)beta * (a + r) * B + (long)job * B + rho) = make_float4(v[0], v[1], v[2], v[3]);
+    }
+    const __bf16 b0 = (__bf16)v[0], b1 = (__bf16)v[1], b2 = (__bf16)v[2], b3 = (__bf16)v[3];
+    const unsigned short u0 = __builtin_bit_cast(unsigned short, b0), u1 = __builtin_bit_cast(unsigned short, b1),
+                         u2 = __builtin_bit_cast(unsigned short, b2), u3 = __builtin_bit_cast(unsigned short, b3);
+    tile[rr][c] = u0; tile[rr][c + 1] = u1; tile[rr][c + 2] = u2; tile[rr][c + 3] = u3;
+    if (job < a && beta < b && rho < B) {
+      uint2 pk;
+      pk.x = (unsigned)u0 | ((unsigned)u1 << 16);
+      pk.y = (unsigned)u2 | ((unsigned)u3 << 16);
+      *reinterpret_cast<uint2 *>(Vb + (long)beta * ldVb + (long)job * B + rho) = pk;
+    }
+  }
+  __syncthreads();
+  // feature-major: thread t writes batch rows 4 (t % 16) .. + 3 of positions t / 16 + 16 p
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    const int cc = (t >> 4) + 16 * p, rr = (t & 15) * 4;
+    if (rho0 + cc < B && beta0 + rr < Rpad) {
+      uint2 pk;
+      pk.x = (unsigned)tile[rr][cc] | ((unsigned)tile[rr + 1][cc] << 16);
+      pk.y = (unsigned)tile[rr + 2][cc] | ((unsigned)tile[rr + 3][cc] << 16);
+      *reinterpret_cast<uint2 *>(VTb + ((long)job * B + rho0 + cc) * ldVT + beta0 + rr) = pk;
+    }
+  }
+}
+
+hipError_t launch_encode_vector_bf16(const float *V, float *Vt, const DevCode *code_dev, const DevCode &code_host,
+                                     int b, void *Vb, long ldVb, void *VTb, long ldVT, hipStream_t s) {
+  const int Rpad = (b + 63) & ~63;
+  dim3 grid((unsigned)((code_host.B + 63) / 64), (unsigned)(Rpad / 64), (unsigned)(code_host.a + code_host.r));
+  const int aligned = (code_host.N % 4 == 0) && (code_host.B0 % 4 == 0) && ((reinterpret_cast<uintptr_t>(V) & 15) == 0);
+  hipLaunchKernelGGL(encode_vector_bf16_kernel, grid, dim3(256), 0, s, V, Vt, code_dev, b, (__bf16 *)Vb, ldVb,
+                     (__bf16 *)VTb, ldVT, Rpad, aligned);
+  return hipGetLastError();
+}
+
 // ---------------------------------------------------------------------------
 // Consistency check, pass 2: the decision (decoding algorithm of the
 // appendix), one workgroup, float64.  With Gamma the Gram matrix of the
