@@ -169,8 +169,28 @@ int codenet_detect_decode(codenet_layer *layer, int phase, float *coded_out_dev,
  * Update stage (the three block rules, plus the same rule on the corner):
  * W~ += eta * [delta; delta~] [x; x~]^T summed over the batch, using the vectors
  * cached by the last forward and backward calls (which must have used the same b).
+ * The cached vectors stay valid until the next forward / backward call replaces
+ * them: a second update applies the same gradient again.  (The check is made
+ * when the call is enqueued; forward and backward calls replayed from a captured
+ * graph refresh the vectors on the device without the host noticing.)
  */
 int codenet_update(codenet_layer *layer, float eta, void *stream);
+
+/*
+ * Regeneration of the stored data at located nodes (Sec. "Errors in the update
+ * stage" and the regeneration step of the per-layer algorithm; the worked
+ * example W_{1,0} = W~_{2,0} - W_{0,0}).  report_dev is the report that
+ * codenet_detect_decode left on the device for `phase`.  If its verdict is
+ * CORRECTED, every stored block of the located block-rows (FWD) or
+ * block-columns (BWD) is rebuilt from good blocks of the same grid column
+ * (row): the good systematic blocks plus as many good parity blocks as there are
+ * located systematic ones.  Any other verdict leaves the matrix untouched.  The
+ * report is read on the device: the call never synchronises with the host.  In
+ * the bf16 mode the bf16 copies of the rebuilt blocks are refreshed as well.
+ * The cached vectors [x; x~], [delta; delta~] need no regeneration here: they
+ * are re-encoded from the caller's inputs on every forward / backward call.
+ */
+int codenet_regenerate(codenet_layer *layer, int phase, const codenet_report *report_dev, void *stream);
 
 /* Copy out the coded matrix, [coded_rows][coded_cols] float32 (drift checks, tests). */
 int codenet_export_coded(codenet_layer *layer, float *Wc_dev, void *stream);

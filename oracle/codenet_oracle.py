@@ -262,19 +262,30 @@ def update(Wt, Dt, Xt, eta, m, n, Br, Bc, store_corner=True):
     return Wn
 
 
-def regenerate_block_row(Wt, i_bad, P_r, m, Br):
-    """Regeneration: rebuild every stored block of block-row i_bad from the
-    other block-rows of the same grid column (any m good blocks of a column
-    determine the column; here the least-squares solve over all of them)."""
-    G = generator(P_r)                       # m x L
+def regenerate_blocks(Wt, bad, P, B, axis=0):
+    """Regeneration: rebuild every stored block of the block-rows (axis 0) or
+    block-columns (axis 1) listed in `bad` from the other blocks of the same
+    grid column (row).  Any a good blocks of a line determine it (MDS); this is
+    the least-squares solve over all the good ones, which is the same thing
+    when they are consistent."""
+    if axis == 1:
+        return regenerate_blocks(Wt.T, bad, P, B, 0).T
+    G = generator(P)                         # a x L
     L = G.shape[1]
-    good = [i for i in range(L) if i != i_bad]
+    bad = sorted(set(int(i) for i in bad))
+    good = [i for i in range(L) if i not in bad]
     Wn = Wt.copy()
     cols = Wt.shape[1]
-    stack = np.stack([Wt[i * Br:(i + 1) * Br].reshape(-1) for i in good])   # (L-1) x (Br cols)
-    sys, *_ = np.linalg.lstsq(G[:, good].T, stack, rcond=None)             # m x (Br cols)
-    Wn[i_bad * Br:(i_bad + 1) * Br] = (G[:, i_bad] @ sys).reshape(Br, cols)
+    stack = np.stack([Wt[i * B:(i + 1) * B].reshape(-1) for i in good])     # |good| x (B cols)
+    sys, *_ = np.linalg.lstsq(G[:, good].T, stack, rcond=None)              # a x (B cols)
+    for i in bad:
+        Wn[i * B:(i + 1) * B] = (G[:, i] @ sys).reshape(B, cols)
     return Wn
+
+
+def regenerate_block_row(Wt, i_bad, P_r, m, Br):
+    """One block-row, as in the paper's worked example."""
+    return regenerate_blocks(Wt, [i_bad], P_r, Br, 0)
 
 
 # --------------------------------------------------------------------------
@@ -434,6 +445,16 @@ class CodedLayer:
             res = detect_decode(coded_out, self.P_c, self.Bc, self.tau_detect, self.tau_resid)
             res["decoded"] = unpad_blocks(res["out"][: self.n * self.Bc], self.N_in, self.n, self.Bc)
         return res
+
+    def regenerate(self, phase, located):
+        """Rebuild the stored blocks at the nodes located in `phase`'s product:
+        block-rows for the forward product, block-columns for the backward one."""
+        if len(located) == 0:
+            return
+        if phase == PHASE_FWD:
+            self.Wt = regenerate_blocks(self.Wt, located, self.P_r, self.Br, 0)
+        else:
+            self.Wt = regenerate_blocks(self.Wt, located, self.P_c, self.Bc, 1)
 
     def update(self, eta):
         self.Wt = update(self.Wt, self.Dt, self.Xt, eta, self.m, self.n,

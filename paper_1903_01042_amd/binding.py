@@ -20,7 +20,7 @@ DENSE_REL, SPARSE_ABS = 0, 1
 E_NULL, E_SHAPE, E_BATCH, E_ORDER, E_CODE, E_FAULT, E_HIP, E_DTYPE, E_ALLOC = range(-1, -10, -1)
 
 EXPORTS = ["codenet_encode", "codenet_layer_geometry", "codenet_forward", "codenet_backward",
-           "codenet_inject", "codenet_detect_decode", "codenet_update", "codenet_export_coded",
+           "codenet_inject", "codenet_detect_decode", "codenet_update", "codenet_regenerate", "codenet_export_coded",
            "codenet_export_weights", "codenet_destroy", "codenet_strerror"]
 
 
@@ -69,6 +69,7 @@ def load_library(path=LIB_PATH):
     lib.codenet_inject.argtypes = [vp, ctypes.POINTER(Fault), ci, vp, ci, vp]
     lib.codenet_detect_decode.argtypes = [vp, ci, vp, ci, vp, vp, vp]
     lib.codenet_update.argtypes = [vp, cf, vp]
+    lib.codenet_regenerate.argtypes = [vp, ci, vp, vp]
     lib.codenet_export_coded.argtypes = [vp, vp, vp]
     lib.codenet_export_weights.argtypes = [vp, vp, vp]
     lib.codenet_destroy.argtypes = [vp]
@@ -198,6 +199,14 @@ class CodedLayer:
 
     def update(self, eta):
         _check(load_library().codenet_update(self._h, float(eta), _stream()), "codenet_update")
+
+    def regenerate(self, phase, report):
+        """Rebuild the stored blocks of the block-rows (FWD) / block-columns (BWD) that the device-side
+        `report` of that phase's detect_decode lists as located; a no-op for any other verdict."""
+        import torch
+        if report is None or report.dtype != torch.uint8 or report.numel() < REPORT_BYTES or not report.is_cuda:
+            raise ValueError("report must be the uint8 CUDA tensor that detect_decode filled")
+        _check(load_library().codenet_regenerate(self._h, int(phase), _ptr(report), _stream()), "codenet_regenerate")
 
     # ---- inspection ----------------------------------------------------------------------
     def export_coded(self):

@@ -331,7 +331,6 @@ int codenet_update(codenet_layer *l, float eta, void *stream) {
     u.WTb = l->WTb; u.ldWTb = l->ldWTb;
     u.I = l->Nc; u.J = l->Mr; u.K = bp; u.eta = eta;
     CN_HIP(launch_update2(u, s));
-    l->fwd_b = l->bwd_b = 0;
     return CODENET_OK;
   }
   GemmArgs g{};
@@ -341,7 +340,6 @@ int codenet_update(codenet_layer *l, float eta, void *stream) {
   g.I = l->Nc; g.J = l->Mr; g.K = l->fwd_b;
   g.alpha = eta;
   CN_HIP(launch_gemm(kUpd, false, g, s));
-  l->fwd_b = l->bwd_b = 0;
   return CODENET_OK;
 }
 
@@ -414,6 +412,21 @@ int codenet_inject(codenet_layer *l, const codenet_fault *faults, int n_faults, 
   for (int f = 0; f < n_faults; ++f) CN_HIP(launch_fault(fa[f], s, false));
   if (phase == CODENET_WEIGHT && l->bf16)
     CN_HIP(launch_shadow(l->Wt, l->Mr, l->Nc, l->Wb, l->ldWb, l->WTb, l->ldWTb, s));
+  return CODENET_OK;
+}
+
+int codenet_regenerate(codenet_layer *l, int phase, const codenet_report *report_dev, void *stream) {
+  if (!l || !report_dev) return CODENET_E_NULL;
+  if (phase != CODENET_FWD && phase != CODENET_BWD) return CODENET_E_SHAPE;
+  RegenArgs g{};
+  g.W = l->Wt; g.Mr = l->Mr; g.Nc = l->Nc;
+  g.Wb = l->bf16 ? l->Wb : nullptr; g.ldWb = l->ldWb;
+  g.WTb = l->bf16 ? l->WTb : nullptr; g.ldWTb = l->ldWTb;
+  g.axis = phase == CODENET_FWD ? 0 : 1;
+  // the forward output is checked by the code along the rows, so its located nodes are block-rows
+  const bool rows = phase == CODENET_FWD;
+  CN_HIP(launch_regen(g, rows ? l->code_r_dev : l->code_c_dev, rows ? l->code_r : l->code_c, report_dev,
+                      (hipStream_t)stream));
   return CODENET_OK;
 }
 

@@ -71,6 +71,16 @@ hipError_t launch_update2(Update2Args g, hipStream_t s);
 hipError_t launch_shadow(const float *Wt, int Mr, int Nc, void *Wb, long ldWb, void *WTb, long ldWTb,
                          hipStream_t s);
 
+// Regeneration of located blocks: axis 0 = block-rows (code along the rows), 1 = block-columns
+struct RegenArgs {
+  float *W; int Mr, Nc;          // fp32 coded matrix [Mr][Nc]
+  __bf16 *Wb; long ldWb;         // bf16 copies (null in the f32 mode)
+  __bf16 *WTb; long ldWTb;
+  int axis;
+};
+hipError_t launch_regen(RegenArgs g, const DevCode *code_dev, const DevCode &code_host, const codenet_report *report,
+                        hipStream_t s);
+
 struct FaultArgs {
   float *base;                  // first element of the target payload
   long stride_outer;            // element (outer, inner) at base[outer * stride_outer + inner]

@@ -697,6 +697,150 @@ hipError_t launch_finish(float *out, const float *syn, const double *partials, i
 }
 
 // ---------------------------------------------------------------------------
+// Regeneration of the stored blocks at located nodes.  Along the axis of the
+// phase's code, the L blocks of every line of the coded matrix form a codeword:
+// parity block q is sum_i P[i][q] block_i.  The k <= t located blocks are
+// rebuilt from a good systematic blocks' worth of others: the good systematic
+// blocks and, for ks located systematic blocks, the first ks good parity blocks
+// (a ks x ks system in the entries of P, nonsingular for an MDS generator).
+// Every workgroup derives the k x L coefficient table itself (float64, one
+// thread, a few hundred flops) from the report that the decision left on the
+// device: no host round trip, and nothing happens unless the verdict is
+// CORRECTED.  One workgroup rebuilds a 64 x 64 tile of one located block:
+// fp32 matrix, row-major bf16 copy and, through LDS, transposed bf16 copy.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void regen_kernel(RegenArgs g, const DevCode *__restrict__ code,
+                                                    const codenet_report *__restrict__ report) {
+  __shared__ float coef[CODENET_MAX_L];
+  __shared__ int s_target;
+  __shared__ unsigned short tile[64][66];
+  const int t = threadIdx.x;
+  const int slot = blockIdx.z;
+  if (report->verdict != CODENET_CORRECTED || slot >= report->n_located) return;
+  const int a = code->a, r = code->r, L = code->L;
+  if (t == 0) {
+    const int k = report->n_located;
+    bool bad[CODENET_MAX_L];
+    for (int i = 0; i < L; ++i) bad[i] = false;
+    int As[CODENET_MAX_T], ks = 0;
+    for (int p = 0; p < k; ++p) {
+      const int i = report->located[p];
+      bad[i] = true;
+      if (i < a) As[ks++] = i;
+    }
+    int Q[CODENET_MAX_T], nq = 0;
+    for (int q = 0; q < r && nq < ks; ++q)
+      if (!bad[a + q]) Q[nq++] = q;
+    // M[x][y] = P[As[y]][Q[x]] = H[Q[x]][As[y]]; Gauss-Jordan with partial pivoting -> Minv
+    double M[CODENET_MAX_T][2 * CODENET_MAX_T];
+    for (int x = 0; x < ks; ++x)
+      for (int y = 0; y < ks; ++y) {
+        M[x][y] = code->H[Q[x]][As[y]];
+        M[x][ks + y] = x == y ? 1.0 : 0.0;
+      }
+    for (int c = 0; c < ks; ++c) {
+      int piv = c;
+      for (int x = c + 1; x < ks; ++x)
+        if (fabs(M[x][c]) > fabs(M[piv][c])) piv = x;
+      for (int y = 0; y < 2 * ks; ++y) { const double tmp = M[c][y]; M[c][y] = M[piv][y]; M[piv][y] = tmp; }
+      const double inv = 1.0 / M[c][c];
+      for (int y = 0; y < 2 * ks; ++y) M[c][y] *= inv;
+      for (int x = 0; x < ks; ++x)
+        if (x != c) {
+          const double f = M[x][c];
+          for (int y = 0; y < 2 * ks; ++y) M[x][y] -= f * M[c][y];
+        }
+    }
+    // located systematic block As[y] = sum_x Minv[y][x] (parity_Q[x] - sum_{good i'} P[i'][Q[x]] block_i')
+    double cs[CODENET_MAX_T][CODENET_MAX_L];
+    for (int y = 0; y < ks; ++y) {
+      for (int i = 0; i < L; ++i) cs[y][i] = 0.0;
+      for (int x = 0; x < ks; ++x) {
+        const double mi = M[y][ks + x];
+        cs[y][a + Q[x]] += mi;
+        for (int i = 0; i < a; ++i)
+          if (!bad[i]) cs[y][i] -= mi * code->H[Q[x]][i];
+      }
+    }
+    const int target = report->located[slot];
+    s_target = target;
+    if (target < a) {
+      int y = 0;
+      while (As[y] != target) ++y;
+      for (int i = 0; i < L; ++i) coef[i] = (float)cs[y][i];
+    } else {
+      const int q = target - a;
+      for (int i = 0; i < L; ++i) {
+        double c = (i < a && !bad[i]) ? code->H[q][i] : 0.0;
+        for (int y = 0; y < ks; ++y) c += code->H[q][As[y]] * cs[y][i];
+        coef[i] = (float)c;
+      }
+    }
+  }
+  __syncthreads();
+  const int target = s_target;
+  const int B = code->B;
+  // tile (r0, c0) of the located block; along the code's axis the block offset is target * B
+  const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+  const int rows = g.axis == 0 ? B : g.Mr, cols = g.axis == 0 ? g.Nc : B;
+  const long blk = g.axis == 0 ? (long)B * g.Nc : (long)B;      // distance between consecutive blocks of a line
+  const int gr0 = g.axis == 0 ? target * B + r0 : r0;           // row / column of the tile in the coded matrix
+  const int gc0 = g.axis == 0 ? c0 : target * B + c0;
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    const int rr = (t >> 4) + 16 * p, cc = (t & 15) * 4;
+    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+    const bool in = r0 + rr < rows && c0 + cc < cols;
+    if (in) {
+      const float *first = g.W + (long)(g.axis == 0 ? r0 + rr : gr0 + rr) * g.Nc + (g.axis == 0 ? gc0 + cc : c0 + cc);
+      for (int i = 0; i < L; ++i) {
+        const float w = coef[i];
+        if (w == 0.f) continue;
+        const float4 x = *reinterpret_cast<const float4 *>(first + i * blk);
+        v.x = fmaf(w, x.x, v.x); v.y = fmaf(w, x.y, v.y); v.z = fmaf(w, x.z, v.z); v.w = fmaf(w, x.w, v.w);
+      }
+      *reinterpret_cast<float4 *>(g.W + (long)(gr0 + rr) * g.Nc + gc0 + cc) = v;
+    }
+    if (g.Wb != nullptr) {
+      const __bf16 b0 = (__bf16)v.x, b1 = (__bf16)v.y, b2 = (__bf16)v.z, b3 = (__bf16)v.w;
+      const unsigned short u0 = __builtin_bit_cast(unsigned short, b0), u1 = __builtin_bit_cast(unsigned short, b1),
+                           u2 = __builtin_bit_cast(unsigned short, b2), u3 = __builtin_bit_cast(unsigned short, b3);
+      tile[rr][cc] = u0; tile[rr][cc + 1] = u1; tile[rr][cc + 2] = u2; tile[rr][cc + 3] = u3;
+      if (in) {
+        uint2 pk;
+        pk.x = (unsigned)u0 | ((unsigned)u1 << 16);
+        pk.y = (unsigned)u2 | ((unsigned)u3 << 16);
+        *reinterpret_cast<uint2 *>(g.Wb + (long)(gr0 + rr) * g.ldWb + gc0 + cc) = pk;
+      }
+    }
+  }
+  if (g.Wb == nullptr) return;
+  __syncthreads();
+  // transposed copy: thread t writes rows 4 (t % 16) .. + 3 of column t / 16 + 16 p
+  // (the matrix has a multiple of 4 rows and the block pitch is one too)
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    const int cc = (t >> 4) + 16 * p, rr = (t & 15) * 4;
+    if (c0 + cc < cols && r0 + rr < rows) {
+      uint2 pk;
+      pk.x = (unsigned)tile[rr][cc] | ((unsigned)tile[rr + 1][cc] << 16);
+      pk.y = (unsigned)tile[rr + 2][cc] | ((unsigned)tile[rr + 3][cc] << 16);
+      *reinterpret_cast<uint2 *>(g.WTb + (long)(gc0 + cc) * g.ldWTb + gr0 + rr) = pk;
+    }
+  }
+}
+
+hipError_t launch_regen(RegenArgs g, const DevCode *code_dev, const DevCode &ch, const codenet_report *report,
+                        hipStream_t s) {
+  const int tcap = ch.r / 2 < CODENET_MAX_T ? ch.r / 2 : CODENET_MAX_T;
+  if (tcap < 1) return hipSuccess;
+  const int rows = g.axis == 0 ? ch.B : g.Mr, cols = g.axis == 0 ? g.Nc : ch.B;
+  dim3 grid((unsigned)((cols + 63) / 64), (unsigned)((rows + 63) / 64), (unsigned)tcap);
+  hipLaunchKernelGGL(regen_kernel, grid, dim3(256), 0, s, g, code_dev, report);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
 // Soft-error injection.  Noise element idx of a fault is a pure function of
 // (seed, step, phase, bi, bj, idx) through the SplitMix64 output function
 // (Steele, Lea, Flood 2014): z = mix(key + idx); bits 0..31 decide a sparse

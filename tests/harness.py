@@ -99,6 +99,12 @@ class Pair:
         self.gpu.update(eta)
         self.ora.update(eta)
 
+    def regenerate(self, phase, res):
+        """GPU: from the device-side report of the last product of `phase`; oracle: from its located set."""
+        self.gpu.regenerate(phase, self.report)
+        if res["verdict"] == O.CORRECTED:
+            self.ora.regenerate(phase, res["located"])
+
     def inject_weights(self, faults):
         if faults:
             self.gpu.inject(list(faults))

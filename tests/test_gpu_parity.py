@@ -121,6 +121,19 @@ def test_full_size_layer_step(name):
     say(name, "update")
     pair.update(wl.eta)
     pair.check_weights()
+    say(name, "weight faults on block-row 1, located by the next forward product, regenerated")
+    coded, coded_gpu = pair.ora.Wt.copy(), to_np(pair.gpu.export_coded())
+    pair.inject_weights([WL.make_fault(WEIGHT, 1, j, 1) for j in range(n)])
+    _, rep, res = pair.product(FWD, wl.inputs(1))
+    assert rep["verdict"] == CORRECTED and rep["located"] == [1]
+    pair.regenerate(FWD, res)
+    assert rel_fro(pair.ora.Wt, coded) <= 1e-9
+    # after an update with bf16 operands the stored parity blocks follow the systematic ones only to
+    # bf16 accuracy of the increment, so the rebuilt row matches the lost one to that accuracy
+    pair.check_weights()
+    assert rel_fro(to_np(pair.gpu.export_coded()), coded_gpu) <= (1e-5 if wl.dtype == "f32" else pair.tol)
+    _, rep, _ = pair.product(FWD, wl.inputs(2))
+    assert rep["verdict"] == CLEAN
     pair.close()
 
 
@@ -129,6 +142,8 @@ def test_full_size_layer_step(name):
     (10, 1024, 4, 4, 1, 128, "f32"),      # cfg2's last layer: 10 outputs on 4 block-rows
     (100, 52, 3, 5, 2, 7, "f32"),         # nothing divides anything
     (300, 200, 5, 4, 2, 33, "bf16"),
+    (300, 200, 5, 4, 2, 260, "bf16"),     # batch of 256 or more: the persistent update kernel on edge tiles
+    (700, 452, 3, 7, 2, 512, "bf16"),     # the same with several tiles per side and 8 slabs
     (130, 70, 2, 2, 4, 5, "f32"),         # t = 2
     (64, 64, 2, 2, 0, 8, "f32"),          # uncoded baseline path (r = 0)
 ])
@@ -233,6 +248,58 @@ def test_weight_fault_shows_up_in_the_next_products():
     pair.check_weights()
     _, rep, _ = pair.product(BWD, D, check_margins=False)
     assert rep["verdict"] == UNCORRECTABLE        # columns 1 and 5 are now both erroneous, t = 1
+    pair.close()
+
+
+# ------------------------------------------------------------------ regeneration of located blocks
+@pytest.mark.parametrize("N_out,N_in,m,n,r,b,dtype,bad", [
+    (96, 80, 4, 4, 2, 8, "f32", [(FWD, [1])]),                 # a systematic block-row
+    (96, 80, 4, 4, 2, 8, "f32", [(FWD, [5])]),                 # a parity block-row
+    (96, 80, 4, 4, 2, 8, "f32", [(BWD, [2])]),                 # a systematic block-column
+    (300, 200, 5, 4, 2, 33, "bf16", [(FWD, [0]), (BWD, [4])]),   # ragged, bf16 copies refreshed, both axes in turn
+    (130, 70, 3, 3, 4, 5, "f32", [(FWD, [0, 2])]),             # two systematic block-rows (t = 2)
+    (130, 70, 3, 3, 4, 5, "f32", [(BWD, [1, 5])]),             # a systematic and a parity block-column
+    (1024, 1024, 8, 8, 2, 64, "bf16", [(FWD, [3]), (BWD, [9])]),   # several 64 x 64 tiles per block
+])
+def test_regeneration_restores_the_stored_code(N_out, N_in, m, n, r, b, dtype, bad):
+    """Weight faults on several nodes of one block-row (column) persist: the next
+    product locates that row (column), the regeneration rebuilds its stored blocks, and
+    the stored matrix is the clean code again on both sides; the following products are
+    clean.  A regeneration call after a CLEAN verdict changes nothing, bit for bit."""
+    import torch
+    P_r = WL.vandermonde_like(m, r) if r <= 2 else WL.gaussian_generator(m, r, seed=5)
+    P_c = WL.vandermonde_like(n, r) if r <= 2 else WL.gaussian_generator(n, r, seed=6)
+    tau = (2e-2, 2e-2) if dtype == "bf16" else (1e-3, 1e-2)
+    pair = Pair(WL.layer_weights(N_out, N_in), P_r, P_c, dtype, b, *tau)
+    clean = pair.ora.Wt.copy()
+    step = 0
+    for phase, lines in bad:
+        # corrupt every stored block of the chosen block-rows (columns) that a product of this phase reads
+        faults = []
+        for line in lines:
+            others = range(n) if phase == FWD else range(m)
+            for o in others:
+                bi, bj = (line, o) if phase == FWD else (o, line)
+                faults.append(WL.make_fault(WL.PHASE_WEIGHT, bi, bj, step))
+        pair.inject_weights(faults)
+        pair.check_weights(1e-5)
+        V = WL.normal((b, N_in if phase == FWD else N_out), seed=100 + step)
+        _, rep, res = pair.product(phase, V)
+        assert rep["verdict"] == CORRECTED and rep["located"] == sorted(lines), rep
+        pair.regenerate(phase, res)
+        assert rel_fro(pair.ora.Wt, clean) <= 1e-9
+        err = pair.check_weights(1e-5)
+        assert rel_fro(to_np(pair.gpu.export_coded()), clean) <= 1e-5
+        # the copies that the bf16 products read were refreshed too: both products are clean again
+        for ph in (FWD, BWD):
+            V = WL.normal((b, N_in if ph == FWD else N_out), seed=200 + step + ph)
+            _, rep, res = pair.product(ph, V)
+            assert rep["verdict"] == CLEAN, rep
+        before = pair.gpu.export_coded().clone()
+        pair.regenerate(BWD, res)              # verdict CLEAN: nothing to do
+        torch.cuda.synchronize()
+        assert torch.equal(before, pair.gpu.export_coded())
+        step += 1
     pair.close()
 
 

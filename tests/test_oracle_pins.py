@@ -370,6 +370,60 @@ def test_regeneration_of_worked_example(worked_example):
     assert np.allclose(O.regenerate_block_row(bad, 1, P_r, 2, B), Wt, atol=1e-12)
 
 
+@pytest.mark.parametrize("axis", [0, 1])
+@pytest.mark.parametrize("r", [1, 2, 4])
+def test_regeneration_restores_any_r_blocks_of_a_codeword(axis, r):
+    """Every block-column (block-row) of the coded matrix is a codeword of an
+    (a + r, a) MDS code, so up to r erased blocks of a line are determined by
+    the rest: regenerating any set of at most r corrupted block-rows (columns)
+    must give back the encoded matrix, whatever was stored in them."""
+    m, n, B = 4, 3, 5
+    P_r, P_c = WL.gaussian_generator(m, r, seed=41), WL.gaussian_generator(n, r, seed=42)
+    W = rng.standard_normal((m * B, n * B))
+    Wt = O.encode(W, P_r, P_c)
+    P, L = (P_r, m + r) if axis == 0 else (P_c, n + r)
+    for k in range(1, r + 1):
+        for bad in itertools.combinations(range(L), k):
+            hit = Wt.copy()
+            for i in bad:
+                if axis == 0:
+                    hit[i * B:(i + 1) * B] = rng.standard_normal((B, Wt.shape[1])) * 10
+                else:
+                    hit[:, i * B:(i + 1) * B] = rng.standard_normal((Wt.shape[0], B)) * 10
+            assert np.allclose(O.regenerate_blocks(hit, bad, P, B, axis), Wt, atol=1e-9), (axis, bad)
+
+
+def test_regeneration_of_a_parity_block_is_reencoding():
+    """Special case with a textbook form: a lost parity block-row q is the
+    encoding of the systematic ones, sum_i P[i][q] W~_i."""
+    m, n, r, B = 3, 3, 2, 4
+    P_r, P_c = WL.vandermonde_like(m, r), WL.vandermonde_like(n, r)
+    Wt = O.encode(rng.standard_normal((m * B, n * B)), P_r, P_c)
+    hit = Wt.copy()
+    hit[(m + 1) * B:(m + 2) * B] = 0.0
+    want = sum(P_r[i, 1] * Wt[i * B:(i + 1) * B] for i in range(m))
+    got = O.regenerate_blocks(hit, [m + 1], P_r, B, 0)
+    assert np.allclose(got[(m + 1) * B:(m + 2) * B], want, atol=1e-12)
+    assert np.allclose(got, Wt, atol=1e-12)
+
+
+def test_layer_regeneration_after_a_weight_fault_gives_clean_products():
+    """Oracle layer: a weight fault at node (i, j) makes block-row i of every
+    later forward product erroneous; after regenerating the located row the
+    stored matrix is the clean code again."""
+    N, m, r, b = 12, 3, 2, 4
+    P = WL.vandermonde_like(m, r)
+    lay = O.CodedLayer(rng.standard_normal((N, N)), P, P)
+    clean = lay.Wt.copy()
+    lay.inject([WL.make_fault(WL.PHASE_WEIGHT, 1, 2, 7)])
+    assert not np.allclose(lay.Wt, clean)
+    res = lay.detect_decode(O.PHASE_FWD, lay.forward(rng.standard_normal((N, b))))
+    assert res["verdict"] == O.CORRECTED and list(res["located"]) == [1]
+    lay.regenerate(O.PHASE_FWD, res["located"])
+    assert np.allclose(lay.Wt, clean, atol=1e-10)
+    assert lay.detect_decode(O.PHASE_FWD, lay.forward(rng.standard_normal((N, b))))["verdict"] == O.CLEAN
+
+
 # ------------------------------------------------------------------ geometry
 def test_results_do_not_depend_on_block_pitch():
     N_out, N_in, m, n, r, b = 10, 9, 4, 3, 2, 3
