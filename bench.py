@@ -47,7 +47,7 @@ class Runner:
         import torch
         from paper_1903_01042_amd import binding as B
         from paper_1903_01042_amd import workloads as WL
-        self.torch, self.B, self.wl = torch, B, wl
+        self.torch, self.B, self.wl, self.WL = torch, B, wl, WL
         self.lib = B.load_library()
         dev = torch.device("cuda:0")
         n_in, n_out = wl.widths[0], wl.widths[1]
@@ -159,6 +159,39 @@ class Runner:
         t1 = time.perf_counter()
         upd_ms = float(np.mean([a.elapsed_time(c) for a, c in evs]))
         return (t1 - t0) * 1e3 / steps, upd_ms
+
+    def time_regeneration(self, reps=10):
+        """Weight faults on every stored block of block-row 1 that the forward product reads,
+        one forward product that locates the row, then `reps` regenerations of it (each rebuilds
+        the same row from the same good blocks) between two events."""
+        torch, B, WL, L = self.torch, self.B, self.WL, self.layer
+        n = self.wl.grid[1]
+        L.inject([WL.make_fault(WL.PHASE_WEIGHT, 1, j, 10 ** 6) for j in range(n)])
+        out = L.forward(self.X[0])
+        rep = L.new_report()
+        L.detect_decode(B.FWD, out, report=rep, want_decoded=False)
+        got = L.read_report(rep)
+        if got["verdict"] != B.CORRECTED or got["located"] != [1]:
+            raise RuntimeError("regeneration set-up: the corrupted block-row was not located: %r" % (got,))
+        L.regenerate(B.FWD, rep)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            L.regenerate(B.FWD, rep)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        L.detect_decode(B.FWD, L.forward(self.X[1]), report=rep, want_decoded=False)
+        after = L.read_report(rep)["verdict"]
+        m_sys = self.wl.grid[0]
+        # reads the m good systematic block-rows, writes one block-row (+ its two bf16 copies)
+        row_bytes = 4.0 * L.B_r * L.coded_cols
+        nbytes = row_bytes * (m_sys + 1) + (row_bytes if self.wl.dtype == "bf16" else 0.0)
+        return {"ms": ms, "algorithmic_bytes": nbytes, "GB/s": nbytes / (ms * 1e-3) / 1e9,
+                "frac_of_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                "verdict_of_next_product": ["clean", "corrected", "uncorrectable"][after],
+                "what": "one located block-row of the coded matrix rebuilt from the good systematic rows and a parity row"}
 
     def verdict_counts(self, lo, hi):
         B = self.B
@@ -275,6 +308,7 @@ def main():
                      "avg_launch_ms": upd_ms, "algorithmic_bytes": upd_bytes,
                      "tflops": coded.flops["upd"] / (upd_ms * 1e-3) / 1e12},
     }
+    out["regeneration"] = coded.time_regeneration()
     coded.layer.destroy()
     uncoded.layer.destroy()
     if args.cpu_steps > 0:

@@ -26,13 +26,14 @@ struct codenet_layer {
   // bf16 mode only: k-contiguous bf16 operands of the two products
   __bf16 *Wb = nullptr;         // [Mr][ldWb]   row-major copy of W~ (forward)
   __bf16 *WTb = nullptr;        // [Nc][ldWTb]  transposed copy of W~ (backward)
-  __bf16 *Xb = nullptr;         // [max_batch][KpX]  x, zero beyond the base columns
-  __bf16 *Db = nullptr;         // [max_batch][KpD]  delta, zero beyond the base rows
-  __bf16 *XTb = nullptr;        // [Nc][bpad]   feature-major [x; x~] (update)
-  __bf16 *DTb = nullptr;        // [Mr][bpad]   feature-major [delta; delta~] (update)
+  __bf16 *Xb = nullptr;         // [max_batch][ldXb]  x, zero beyond the base columns
+  __bf16 *Db = nullptr;         // [max_batch][ldDb]  delta, zero beyond the base rows
+  __bf16 *XTb = nullptr;        // [Nc][ldT]    feature-major [x; x~] (update)
+  __bf16 *DTb = nullptr;        // [Mr][ldT]    feature-major [delta; delta~] (update)
   float *part = nullptr;        // split-k partial results: [kMaxSplits][max_batch][max(Mr, Nc)]
   long ldWb = 0, ldWTb = 0;
-  int KpX = 0, KpD = 0, bpad = 0;
+  int KpX = 0, KpD = 0, bpad = 0;   // contraction lengths (multiples of 64): base columns, base rows, batch
+  long ldXb = 0, ldDb = 0, ldT = 0; // pitches of Xb, Db and of XTb / DTb
   int fwd_b = 0, bwd_b = 0;     // batch of the cached vectors (0 = none)
   bool bf16 = false;
 };
@@ -199,15 +200,24 @@ int codenet_encode(const codenet_desc *d, const float *W_dev, void *stream, code
   alloc((void **)&l->code_c_dev, sizeof(DevCode));
   if (l->bf16) {
     auto up64 = [](long v) { return (v + 63) & ~63L; };
-    l->ldWb = up64(l->Nc);
-    l->ldWTb = up64(l->Mr);
+    // A row pitch that is a multiple of 2 KB puts the same 128-byte column of every row of an
+    // operand tile on one L2 channel, and all workgroups of an XCD walk those columns together:
+    // such pitches get one more line (64 elements), so that consecutive rows change channel.
+    const char *skew_env = getenv("CODENET_SKEW");
+    const bool skew_on = !(skew_env && skew_env[0] == '0');
+    auto pitch = [&](long v) { v = up64(v); return (skew_on && (v * 2) % 2048 == 0) ? v + 64 : v; };
+    l->ldWb = pitch(l->Nc);
+    l->ldWTb = pitch(l->Mr);
     l->KpX = (int)up64((long)l->code_c.a * l->code_c.B);
     l->KpD = (int)up64((long)l->code_r.a * l->code_r.B);
+    l->ldXb = pitch(l->KpX);
+    l->ldDb = pitch(l->KpD);
     const size_t szWb = 2 * (size_t)l->Mr * l->ldWb, szWTb = 2 * (size_t)l->Nc * l->ldWTb;
-    const size_t szXb = 2 * mb * l->KpX, szDb = 2 * mb * l->KpD;
+    const size_t szXb = 2 * mb * l->ldXb, szDb = 2 * mb * l->ldDb;
     l->bpad = (int)up64((long)mb);
-    alloc((void **)&l->XTb, 2 * (size_t)l->Nc * l->bpad);
-    alloc((void **)&l->DTb, 2 * (size_t)l->Mr * l->bpad);
+    l->ldT = pitch(l->bpad);
+    alloc((void **)&l->XTb, 2 * (size_t)l->Nc * l->ldT);
+    alloc((void **)&l->DTb, 2 * (size_t)l->Mr * l->ldT);
     alloc((void **)&l->part, sizeof(float) * (size_t)kMaxSplits * mb * std::max(l->Mr, l->Nc));
     alloc((void **)&l->Wb, szWb);
     alloc((void **)&l->WTb, szWTb);
@@ -265,10 +275,10 @@ int codenet_forward(codenet_layer *l, const float *X_dev, int b, float *S_coded_
     int tile = 0, splits = 1;
     plan_gemm2(l->Mr, b, l->KpX, kMaxSplits, &tile, &splits);
     // coded input: fp32, batch-major bf16 (product operand) and feature-major bf16 [x; x~] (update operand)
-    CN_HIP(launch_encode_vector_bf16(X_dev, l->Xt, l->code_c_dev, l->code_c, b, l->Xb, l->KpX, l->XTb, l->bpad, s));
+    CN_HIP(launch_encode_vector_bf16(X_dev, l->Xt, l->code_c_dev, l->code_c, b, l->Xb, l->ldXb, l->XTb, l->ldT, s));
     Gemm2Args g2{};
     g2.A = l->Wb; g2.lda = l->ldWb;
-    g2.B = l->Xb; g2.ldb = l->KpX;
+    g2.B = l->Xb; g2.ldb = l->ldXb;
     g2.C = S_coded_dev; g2.ldc = l->Mr;
     g2.I = l->Mr; g2.J = b; g2.K = l->KpX; g2.splits = splits;
     CN_HIP(launch_gemm2(g2, tile, l->part, s));
@@ -295,10 +305,10 @@ int codenet_backward(codenet_layer *l, const float *D_dev, int b, float *C_coded
   if (l->bf16) {
     int tile = 0, splits = 1;
     plan_gemm2(l->Nc, b, l->KpD, kMaxSplits, &tile, &splits);
-    CN_HIP(launch_encode_vector_bf16(D_dev, l->Dt, l->code_r_dev, l->code_r, b, l->Db, l->KpD, l->DTb, l->bpad, s));
+    CN_HIP(launch_encode_vector_bf16(D_dev, l->Dt, l->code_r_dev, l->code_r, b, l->Db, l->ldDb, l->DTb, l->ldT, s));
     Gemm2Args g2{};
     g2.A = l->WTb; g2.lda = l->ldWTb;
-    g2.B = l->Db; g2.ldb = l->KpD;
+    g2.B = l->Db; g2.ldb = l->ldDb;
     g2.C = C_coded_dev; g2.ldc = l->Nc;
     g2.I = l->Nc; g2.J = b; g2.K = l->KpD; g2.splits = splits;
     CN_HIP(launch_gemm2(g2, tile, l->part, s));
@@ -324,8 +334,8 @@ int codenet_update(codenet_layer *l, float eta, void *stream) {
   if (l->bf16) {
     const int bp = (l->fwd_b + 63) & ~63;
     Update2Args u{};
-    u.XT = l->XTb; u.ldx = l->bpad;
-    u.DT = l->DTb; u.ldd = l->bpad;
+    u.XT = l->XTb; u.ldx = l->ldT;
+    u.DT = l->DTb; u.ldd = l->ldT;
     u.W = l->Wt; u.ldw = l->Nc;
     u.Wb = l->Wb; u.ldWb = l->ldWb;
     u.WTb = l->WTb; u.ldWTb = l->ldWTb;

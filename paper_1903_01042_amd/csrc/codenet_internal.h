@@ -52,6 +52,7 @@ struct Gemm2Args {
   float *C; long ldc;
   int I, J, K;
   int tiles_i, tiles_j, splits;
+  int prefetch;                  // gemm3_kernel: run the L2 prefetch wavefront
   long split_stride;
 };
 struct Update2Args {

@@ -89,6 +89,15 @@ __device__ __forceinline__ void pin(u32x4 &v) {
 #endif
 }
 
+// LDS layout of an operand tile: row r (128 bytes = eight 16-byte chunks of k) keeps its
+// chunk c at slot c ^ swizzle_of_row(r).  A ds_read_b128 serves 16 lanes at a time; the 16
+// rows they read (same chunk) must cover the sixteen 16-byte bank groups: the group is
+// 8 (r % 2) + slot, so the swizzle has to take its three bits from r / 2 (with r % 8, rows
+// r and r + 8 collide: half of all LDS cycles were bank conflicts).  Every row group that
+// a direct-to-LDS load fills starts at a multiple of 8 rows, and 8 * (4 u + wave) or
+// 8 * (8 u + wave) differ from 8 * wave by a multiple of 16: one formula serves all loads.
+__device__ __forceinline__ int swizzle_of_row(int r) { return (r >> 1) & 7; }
+
 // Main loop shared by the product and the update kernels: acc[a][b] += A-tile x B-tile^T
 // over slabs [kb, kb + nk) of 64.  acc rows (MFMA row index) run over j (B rows),
 // acc columns (lane % 32) over i (A rows): the B-side fragment is the first MFMA operand.
@@ -105,9 +114,9 @@ __device__ __forceinline__ void mainloop(const __bf16 *__restrict__ A, long lda,
   const int wi = wave & 1, wj = wave >> 1;
   const int l32 = lane & 31, h = lane >> 5;
 
-  // per-lane sources: lane l of load u fetches chunk (l & 7) ^ (l >> 3) of row 8 (4 u + wave) + (l >> 3)
+  // per-lane sources: lane l of load u fetches, for slot l & 7 of row 8 (4 u + wave) + (l >> 3), the chunk that belongs there
   const int lrow = lane >> 3;
-  const int chunk = (lane & 7) ^ lrow;
+  const int chunk = (lane & 7) ^ swizzle_of_row(8 * wave + lrow);
   const __bf16 *srcA[LA];
   const __bf16 *srcB[LB];
 #pragma unroll
@@ -145,7 +154,7 @@ __device__ __forceinline__ void mainloop(const __bf16 *__restrict__ A, long lda,
   unsigned offA[4], offB[4];
 #pragma unroll
   for (int s = 0; s < 4; ++s) {
-    const unsigned slot = (unsigned)(((2 * s + h) ^ (l32 & 7)) * 16);
+    const unsigned slot = (unsigned)(((2 * s + h) ^ swizzle_of_row(l32)) * 16);
     offA[s] = (unsigned)((wi * FM * 32 + l32) * 128) + slot;
     offB[s] = (unsigned)(TI * 128 + (wj * FN * 32 + l32) * 128) + slot;
   }
@@ -267,6 +276,151 @@ __global__ __launch_bounds__(256) void gemm2_kernel(Gemm2Args g) {
           if (j < g.J) C[(long)j * g.ldc + i] = acc[a][b][4 * q + e];
         }
     }
+}
+
+// ---------------------------------------------------------------------------
+// Product kernel with two wavefronts per SIMD: the same 128 x 128 x 64 slabs and
+// four-stage direct-to-LDS pipeline as gemm2_kernel<2, 2, 4>, but eight
+// wavefronts of 64 (i) x 32 (j) each.  A wavefront issues in order, so with one
+// wavefront per SIMD its MFMAs stop whenever it waits for LDS or at the barrier;
+// with two, the other one's MFMAs fill those gaps.  The price is 1.5 KB of LDS
+// reads per MFMA instead of 1 KB, still below what the LDS delivers.
+//
+// A ninth wavefront only touches one dword of every 128-byte line of the slabs PD ahead
+// (a slab row is one line): the lines are then in this XCD's L2 when the MMA wavefronts'
+// direct-to-LDS loads ask for them.  It never waits for its loads, so HBM latency is
+// nobody's critical path; it keeps pace through the same per-slab barriers.
+__global__ __launch_bounds__(576) void gemm3_kernel(Gemm2Args g) {
+  constexpr int NS = 4;
+  constexpr int PD = 10;                      // prefetch distance in slabs
+  constexpr int STAGE = 256 * 128;            // 128 A rows + 128 B rows of 128 bytes
+  extern __shared__ uint4 lds[];
+  char *const lds_c = reinterpret_cast<char *>(lds);
+  const int logical = logical_workgroup(g.tiles_i * g.tiles_j);
+  if (logical < 0) return;
+  const int tj = logical % g.tiles_j, ti = logical / g.tiles_j;
+  const int i0 = ti * 128, j0 = tj * 128;
+  const int nk = g.K >> 6;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  if (wave == 8) {
+    if (!g.prefetch) return;              // a wavefront that has ended is no longer expected at the barriers
+    // lane l: A rows i0 + l and i0 + 64 + l, B rows j0 + l and j0 + 64 + l
+    const __bf16 *rows[4];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      int row = i0 + 64 * u + lane;
+      row = row < g.I ? row : g.I - 1;
+      rows[u] = g.A + (long)row * g.lda;
+      row = j0 + 64 * u + lane;
+      row = row < g.J ? row : g.J - 1;
+      rows[2 + u] = g.B + (long)row * g.ldb;
+    }
+    // The touched dwords go straight to a spare 256 bytes of LDS that nobody reads: a load into a
+    // register that is never waited for would land after the compiler has reused that register.
+    auto touch = [&](int kt) {
+#if CN_DEVICE_ASM
+      if (kt < nk) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+          __builtin_amdgcn_global_load_lds(rows[u] + (long)kt * 64, CN_LDS_PTR(lds_c + NS * STAGE), 4, 0, 0);
+      }
+#else
+      (void)kt;
+#endif
+    };
+    for (int kt = NS - 1; kt < PD; ++kt) touch(kt);
+    for (int kt = 0; kt < nk; ++kt) {
+      __builtin_amdgcn_s_barrier();
+      touch(kt + PD);
+    }
+    return;
+  }
+  const int wi = wave & 1, wj = wave >> 1;    // 2 x 4 wavefronts over (i, j)
+  const int l32 = lane & 31, h = lane >> 5;
+  const int lrow = lane >> 3, chunk = (lane & 7) ^ swizzle_of_row(8 * wave + lrow);
+
+  // loads 0, 1: A rows 8 (8 u + wave) + lane / 8; loads 2, 3: B rows likewise
+  const __bf16 *src[4];
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    int row = i0 + 8 * (8 * u + wave) + lrow;
+    row = row < g.I ? row : g.I - 1;
+    src[u] = g.A + (long)row * g.lda + chunk * 8;
+    row = j0 + 8 * (8 * u + wave) + lrow;
+    row = row < g.J ? row : g.J - 1;
+    src[2 + u] = g.B + (long)row * g.ldb + chunk * 8;
+  }
+  auto issue_one = [&](int kt, int u) {
+#if CN_DEVICE_ASM
+    char *dst = lds_c + (kt % NS) * STAGE + (u < 2 ? 0 : 128 * 128) + (8 * (u & 1) + wave) * 1024;
+    __builtin_amdgcn_global_load_lds(src[u] + (long)kt * 64, CN_LDS_PTR(dst), 16, 0, 0);
+#else
+    (void)kt; (void)u;
+#endif
+  };
+  unsigned offA[4], offB[4];
+#pragma unroll
+  for (int s = 0; s < 4; ++s) {
+    const unsigned slot = (unsigned)(((2 * s + h) ^ swizzle_of_row(l32)) * 16);
+    offA[s] = (unsigned)((wi * 64 + l32) * 128) + slot;
+    offB[s] = (unsigned)(128 * 128 + (wj * 32 + l32) * 128) + slot;
+  }
+  floatx16 acc[2];
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[a][e] = 0.f;
+
+#pragma unroll
+  for (int s = 0; s < NS - 1; ++s)
+    if (s < nk) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) issue_one(s, u);
+    }
+  for (int kt = 0; kt < nk; ++kt) {
+    const int later = nk - 1 - kt;
+    if (later >= 2) wait_vm<8>();
+    else if (later >= 1) wait_vm<4>();
+    else wait_vm<0>();
+    __builtin_amdgcn_s_barrier();
+    const bool prefetch = kt + NS - 1 < nk;
+    const unsigned sb = (unsigned)((kt % NS) * STAGE);
+    u32x4 fa[2][2], fb[2][1];
+    read_frags<2>(fa[0], sb + offA[0]);
+    read_frags<1>(fb[0], sb + offB[0]);
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const int cur = s & 1, nxt = cur ^ 1;
+      if (s < 3) {
+        read_frags<2>(fa[nxt], sb + offA[s + 1]);
+        read_frags<1>(fb[nxt], sb + offB[s + 1]);
+        wait_lgkm<3>();
+      } else {
+        wait_lgkm<0>();
+      }
+      pin(fa[cur][0]); pin(fa[cur][1]); pin(fb[cur][0]);
+      if (prefetch) issue_one(kt + NS - 1, s);
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+        acc[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fb[cur][0]),
+                                                         __builtin_bit_cast(bf16x8, fa[cur][a]), acc[a], 0, 0, 0);
+    }
+  }
+  // element 4 q + e of fragment a is (j = 8 q + 4 h + e, i = lane % 32)
+#pragma unroll
+  for (int a = 0; a < 2; ++a) {
+    const int i = i0 + (wi * 2 + a) * 32 + l32;
+    if (i >= g.I) continue;
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int j = j0 + wj * 32 + 8 * q + 4 * h + e;
+        if (j < g.J) g.C[(long)j * g.ldc + i] = acc[a][4 * q + e];
+      }
+  }
 }
 
 // out = sum over splits of the partial results, in split order
@@ -467,11 +621,11 @@ __global__ __launch_bounds__(512) void update3_kernel(Update2Args g) {
     // ---------------------------------------------------------------------- MMA
     const int wi = wave & 1, wj = wave >> 1;
     const int l32 = lane & 31, h = lane >> 5;
-    const int lrow = lane >> 3, chunk = (lane & 7) ^ lrow;
+    const int lrow = lane >> 3, chunk = (lane & 7) ^ swizzle_of_row(8 * wave + lrow);
     unsigned offA[4], offB[4];
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
-      const unsigned slot = (unsigned)(((2 * s + h) ^ (l32 & 7)) * 16);
+      const unsigned slot = (unsigned)(((2 * s + h) ^ swizzle_of_row(l32)) * 16);
       offA[s] = (unsigned)((wi * 64 + l32) * 128) + slot;
       offB[s] = (unsigned)(128 * 128 + (wj * 64 + l32) * 128) + slot;
     }
@@ -880,6 +1034,21 @@ hipError_t launch_gemm2(Gemm2Args g, int tile, float *workspace, hipStream_t s) 
     g.C = workspace;
   }
   hipError_t e;
+  {
+    const char *env3 = getenv("CODENET_GEMM3");
+    if (tile == 1 && g.splits == 1 && !(env3 && env3[0] == '0')) {
+      constexpr int lds = 4 * 256 * 128 + 256;       // four stages and the prefetch wavefront's sink
+      static bool attr_done = false;
+      e = set_lds(gemm3_kernel, lds, &attr_done);
+      if (e != hipSuccess) return e;
+      g.tiles_i = (g.I + 127) / 128;
+      g.tiles_j = (g.J + 127) / 128;
+      const int total = g.tiles_i * g.tiles_j;
+      g.prefetch = env3 && env3[0] == '2';
+      hipLaunchKernelGGL(gemm3_kernel, dim3((unsigned)(((total + 7) / 8) * 8)), dim3(576), lds, s, g);
+      return hipGetLastError();
+    }
+  }
 #ifdef CODENET_ABLATION
   const char *dbg_env = getenv("CODENET_GEMM2_DBG");
   const int dbg = dbg_env ? atoi(dbg_env) : 0;
