@@ -105,60 +105,88 @@ class Runner:
         if rc:
             raise RuntimeError("a codenet call failed in step %d (rc=%d)" % (s, rc))
 
-    def update(self, stream):
-        rc = self.lib.codenet_update(self.h, self.eta, stream)
+    STAMP_EVERY = 4     # steps whose update kernel is bracketed by two device time stamps
+
+    def update(self, s, stream):
+        """The update of step s; on every STAMP_EVERY-th step between two device time stamps."""
+        stamped = s % self.STAMP_EVERY == 0
+        rc = 0
+        if stamped:
+            rc |= self.lib.codenet_timestamp(ctypes.c_void_p(self.stamps[s, 0].data_ptr()), stream,
+                                             ctypes.byref(self.ticks_per_us))
+        rc |= self.lib.codenet_update(self.h, self.eta, stream)
+        if stamped:
+            rc |= self.lib.codenet_timestamp(ctypes.c_void_p(self.stamps[s, 1].data_ptr()), stream, None)
         if rc:
             raise RuntimeError("codenet_update failed (rc=%d)" % rc)
 
     def capture(self, total_steps):
-        """One hipGraph per step for everything before the update.  The update, a single
-        kernel, is launched directly between two events, so that their difference is that
-        kernel's duration and not a graph launch.  The library only enqueues kernels, so
-        its calls can be captured as they are."""
+        """One hipGraph per step.  The library only enqueues kernels, so its calls can be captured
+        as they are.  Host-recorded events cannot stamp a kernel inside a graph, and splitting the
+        step into two launches with an event in between costs about 19 us of launch gaps per step:
+        the update kernel is timed by device time stamps inside the graph instead."""
         torch = self.torch
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
         with torch.cuda.stream(side):          # first use outside capture (function attributes are set once)
             st = ctypes.c_void_p(side.cuda_stream)
             self.pre_update(0, st)
-            self.update(st)
+            self.update(0, st)
         side.synchronize()
         self.graphs = []
         for s in range(total_steps):
             g = torch.cuda.CUDAGraph()
             with torch.cuda.graph(g, stream=side):
-                self.pre_update(s, ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+                st = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+                self.pre_update(s, st)
+                self.update(s, st)
             self.graphs.append(g)
         torch.cuda.synchronize()
 
     def run(self, steps, warmup, eager):
         torch = self.torch
         stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+        self.stamps = torch.zeros((steps + warmup, 2), dtype=torch.int64, device="cuda:0")
+        self.ticks_per_us = ctypes.c_int(0)
         if not eager:
             self.capture(steps + warmup)
 
-        def one(s, ev=None):
+        def one(s):
             if eager:
                 self.pre_update(s, stream)
+                self.update(s, stream)
             else:
                 self.graphs[s].replay()
-            if ev is not None:
-                ev[0].record()
-            self.update(stream)
-            if ev is not None:
-                ev[1].record()
 
         for s in range(warmup):
             one(s)
-        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for s in range(steps):
-            one(warmup + s, evs[s])
+            one(warmup + s)
         torch.cuda.synchronize()
         t1 = time.perf_counter()
-        upd_ms = float(np.mean([a.elapsed_time(c) for a, c in evs]))
+        st = self.stamps[warmup:].cpu().numpy()
+        st = st[st[:, 0] != 0]
+        upd_ms = float(np.mean(st[:, 1] - st[:, 0])) / self.ticks_per_us.value * 1e-3
         return (t1 - t0) * 1e3 / steps, upd_ms
+
+    def update_by_events(self, reps=50):
+        """The same update kernel launched `reps` times back to back between two HIP events."""
+        torch = self.torch
+        stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for _ in range(3):
+            self.lib.codenet_update(self.h, self.eta, stream)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            rc = self.lib.codenet_update(self.h, self.eta, stream)
+        e1.record()
+        torch.cuda.synchronize()
+        if rc:
+            raise RuntimeError("codenet_update failed (rc=%d)" % rc)
+        return e0.elapsed_time(e1) / reps
 
     def time_regeneration(self, reps=10):
         """Weight faults on every stored block of block-row 1 that the forward product reads,
@@ -272,6 +300,8 @@ def main():
     ms_uncoded, upd_ms_unc = uncoded.run(args.steps, args.warmup, args.eager)
 
     L = coded.layer
+    upd_events_ms = coded.update_by_events()
+    upd_events_ms_unc = uncoded.update_by_events()
     flops_step = sum(coded.flops.values())
     m, n = wl.grid
     floor = sum(coded.flops.values()) / sum(uncoded.flops.values()) - 1.0
@@ -282,7 +312,7 @@ def main():
     upd_bytes = 2.0 * coded.weight_bytes + elem * coded.b * (L.coded_rows + L.coded_cols)
     if wl.dtype == "bf16":
         upd_bytes += coded.weight_bytes
-    achieved = upd_bytes / (upd_ms * 1e-3) / 1e9
+    achieved = upd_bytes / (upd_events_ms * 1e-3) / 1e9
     out = {
         "metric": "coded layer-steps/s (fwd+bwd+detect/decode+update)",
         "value": 1e3 / ms_coded,
@@ -293,20 +323,25 @@ def main():
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": wl.name, "layer": "%dx%d" % (wl.widths[1], wl.widths[0]),
                    "grid": "%dx%d+%d" % (m, n, wl.r), "batch": wl.batch, "fault_law": wl.fault_law,
-                   "launch": "eager, one stream" if args.eager else "hipGraph replay of each step up to the update, update kernel launched directly; one stream"},
+                   "launch": "eager, one stream" if args.eager else "hipGraph replay, one graph per step, one stream"},
         "tflops": flops_step / (ms_coded * 1e-3) / 1e12,
         "mfma_frac_of_peak_whole_step": flops_step / (ms_coded * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS[wl.dtype],
         "uncoded_ms_per_step": ms_uncoded,
         "coding_overhead": ms_coded / ms_uncoded - 1.0,
         "algorithmic_overhead_floor": floor,
         "verdicts": counts,
-        "update_kernel_ms_uncoded": upd_ms_unc,
+        "update_kernel_ms_uncoded": upd_events_ms_unc,
         "roofline": {"kernel": "update3_kernel (W~ += eta [d;d~][x;x~]^T, fp32 RMW + bf16 operand copies)"
                      if wl.dtype == "bf16" else "gemm_kernel (update, W~ += eta [d;d~][x;x~]^T)", "bound": "hbm",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(args.workload),
-                     "avg_launch_ms": upd_ms, "algorithmic_bytes": upd_bytes,
-                     "tflops": coded.flops["upd"] / (upd_ms * 1e-3) / 1e12},
+                     "avg_launch_ms": upd_events_ms,
+                     "avg_launch_ms_by": "HIP events around 50 back-to-back launches after the timed region",
+                     "in_graph_ms": upd_ms,
+                     "in_graph_ms_by": "device time stamps before and after the kernel inside the graph of every "
+                     "%d-th timed step (adds two kernel boundaries)" % Runner.STAMP_EVERY,
+                     "algorithmic_bytes": upd_bytes,
+                     "tflops": coded.flops["upd"] / (upd_events_ms * 1e-3) / 1e12},
     }
     out["regeneration"] = coded.time_regeneration()
     coded.layer.destroy()

@@ -201,6 +201,17 @@ int codenet_export_weights(codenet_layer *layer, float *W_dev, void *stream);
 /* Waits for the device, frees everything the layer owns. */
 int codenet_destroy(codenet_layer *layer);
 
+/*
+ * Time stamp on the device: when `stream` reaches this point, the GPU's
+ * constant-rate wall clock is written to *dst_dev (one 64-bit count).
+ * *ticks_per_us, if not NULL, receives the clock's rate during the call.  A
+ * kernel like the others: it can be captured into a hipGraph together with the
+ * calls above, where host-recorded events cannot stamp individual kernels.
+ * The difference of two stamps around a call is that call's time on the GPU
+ * plus one kernel boundary.
+ */
+int codenet_timestamp(uint64_t *dst_dev, void *stream, int *ticks_per_us);
+
 const char *codenet_strerror(int code);
 
 #ifdef __cplusplus

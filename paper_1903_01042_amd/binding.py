@@ -21,7 +21,7 @@ E_NULL, E_SHAPE, E_BATCH, E_ORDER, E_CODE, E_FAULT, E_HIP, E_DTYPE, E_ALLOC = ra
 
 EXPORTS = ["codenet_encode", "codenet_layer_geometry", "codenet_forward", "codenet_backward",
            "codenet_inject", "codenet_detect_decode", "codenet_update", "codenet_regenerate", "codenet_export_coded",
-           "codenet_export_weights", "codenet_destroy", "codenet_strerror"]
+           "codenet_export_weights", "codenet_destroy", "codenet_timestamp", "codenet_strerror"]
 
 
 class Desc(ctypes.Structure):
@@ -73,12 +73,22 @@ def load_library(path=LIB_PATH):
     lib.codenet_export_coded.argtypes = [vp, vp, vp]
     lib.codenet_export_weights.argtypes = [vp, vp, vp]
     lib.codenet_destroy.argtypes = [vp]
+    lib.codenet_timestamp.argtypes = [vp, vp, pi]
     lib.codenet_strerror.argtypes = [ci]
     lib.codenet_strerror.restype = ctypes.c_char_p
     for name in EXPORTS[:-1]:
         getattr(lib, name).restype = ci
     _lib = lib
     return lib
+
+
+def timestamp(dst, index=0):
+    """Enqueue a device time stamp into element `index` of the int64 CUDA tensor `dst` on the current
+    stream; returns the clock rate in ticks per microsecond."""
+    rate = ctypes.c_int(0)
+    _check(load_library().codenet_timestamp(ctypes.c_void_p(dst.data_ptr() + 8 * int(index)), _stream(),
+                                            ctypes.byref(rate)), "codenet_timestamp")
+    return int(rate.value)
 
 
 class CodenetError(RuntimeError):

@@ -461,4 +461,16 @@ int codenet_destroy(codenet_layer *l) {
   return CODENET_OK;
 }
 
+int codenet_timestamp(uint64_t *dst_dev, void *stream, int *ticks_per_us) {
+  if (!dst_dev) return CODENET_E_NULL;
+  if (ticks_per_us) {
+    int dev = 0, khz = 0;
+    CN_HIP(hipGetDevice(&dev));
+    CN_HIP(hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev));
+    *ticks_per_us = khz / 1000;
+  }
+  CN_HIP(launch_timestamp(reinterpret_cast<unsigned long long *>(dst_dev), (hipStream_t)stream));
+  return CODENET_OK;
+}
+
 }  // extern "C"

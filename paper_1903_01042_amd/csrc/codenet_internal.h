@@ -52,7 +52,6 @@ struct Gemm2Args {
   float *C; long ldc;
   int I, J, K;
   int tiles_i, tiles_j, splits;
-  int prefetch;                  // gemm3_kernel: run the L2 prefetch wavefront
   long split_stride;
 };
 struct Update2Args {
@@ -81,6 +80,8 @@ struct RegenArgs {
 };
 hipError_t launch_regen(RegenArgs g, const DevCode *code_dev, const DevCode &code_host, const codenet_report *report,
                         hipStream_t s);
+
+hipError_t launch_timestamp(unsigned long long *dst, hipStream_t s);
 
 struct FaultArgs {
   float *base;                  // first element of the target payload

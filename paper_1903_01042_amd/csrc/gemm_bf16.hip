@@ -286,13 +286,14 @@ __global__ __launch_bounds__(256) void gemm2_kernel(Gemm2Args g) {
 // with two, the other one's MFMAs fill those gaps.  The price is 1.5 KB of LDS
 // reads per MFMA instead of 1 KB, still below what the LDS delivers.
 //
-// A ninth wavefront only touches one dword of every 128-byte line of the slabs PD ahead
-// (a slab row is one line): the lines are then in this XCD's L2 when the MMA wavefronts'
-// direct-to-LDS loads ask for them.  It never waits for its loads, so HBM latency is
-// nobody's critical path; it keeps pace through the same per-slab barriers.
-__global__ __launch_bounds__(576) void gemm3_kernel(Gemm2Args g) {
+// Tried and dropped, both slower at 5120 x 512 x 4096: an extra wavefront that touches every
+// line of the slabs ten ahead so that they wait in this XCD's L2 (46 us against 39: the
+// address unit is the busier resource, HBM latency was not the limit), and filling LDS through
+// registers instead of direct-to-LDS loads (47 us).  hipBLASLt's own kernel for this shape
+// (160 x 64 x 128 tiles) takes 32 us.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(512) void gemm3_kernel(Gemm2Args g) {
   constexpr int NS = 4;
-  constexpr int PD = 10;                      // prefetch distance in slabs
   constexpr int STAGE = 256 * 128;            // 128 A rows + 128 B rows of 128 bytes
   extern __shared__ uint4 lds[];
   char *const lds_c = reinterpret_cast<char *>(lds);
@@ -303,39 +304,6 @@ __global__ __launch_bounds__(576) void gemm3_kernel(Gemm2Args g) {
   const int nk = g.K >> 6;
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
-  if (wave == 8) {
-    if (!g.prefetch) return;              // a wavefront that has ended is no longer expected at the barriers
-    // lane l: A rows i0 + l and i0 + 64 + l, B rows j0 + l and j0 + 64 + l
-    const __bf16 *rows[4];
-#pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      int row = i0 + 64 * u + lane;
-      row = row < g.I ? row : g.I - 1;
-      rows[u] = g.A + (long)row * g.lda;
-      row = j0 + 64 * u + lane;
-      row = row < g.J ? row : g.J - 1;
-      rows[2 + u] = g.B + (long)row * g.ldb;
-    }
-    // The touched dwords go straight to a spare 256 bytes of LDS that nobody reads: a load into a
-    // register that is never waited for would land after the compiler has reused that register.
-    auto touch = [&](int kt) {
-#if CN_DEVICE_ASM
-      if (kt < nk) {
-#pragma unroll
-        for (int u = 0; u < 4; ++u)
-          __builtin_amdgcn_global_load_lds(rows[u] + (long)kt * 64, CN_LDS_PTR(lds_c + NS * STAGE), 4, 0, 0);
-      }
-#else
-      (void)kt;
-#endif
-    };
-    for (int kt = NS - 1; kt < PD; ++kt) touch(kt);
-    for (int kt = 0; kt < nk; ++kt) {
-      __builtin_amdgcn_s_barrier();
-      touch(kt + PD);
-    }
-    return;
-  }
   const int wi = wave & 1, wj = wave >> 1;    // 2 x 4 wavefronts over (i, j)
   const int l32 = lane & 31, h = lane >> 5;
   const int lrow = lane >> 3, chunk = (lane & 7) ^ swizzle_of_row(8 * wave + lrow);
@@ -1037,15 +1005,14 @@ hipError_t launch_gemm2(Gemm2Args g, int tile, float *workspace, hipStream_t s) 
   {
     const char *env3 = getenv("CODENET_GEMM3");
     if (tile == 1 && g.splits == 1 && !(env3 && env3[0] == '0')) {
-      constexpr int lds = 4 * 256 * 128 + 256;       // four stages and the prefetch wavefront's sink
+      constexpr int lds = 4 * 256 * 128;
       static bool attr_done = false;
       e = set_lds(gemm3_kernel, lds, &attr_done);
       if (e != hipSuccess) return e;
       g.tiles_i = (g.I + 127) / 128;
       g.tiles_j = (g.J + 127) / 128;
       const int total = g.tiles_i * g.tiles_j;
-      g.prefetch = env3 && env3[0] == '2';
-      hipLaunchKernelGGL(gemm3_kernel, dim3((unsigned)(((total + 7) / 8) * 8)), dim3(576), lds, s, g);
+      hipLaunchKernelGGL(gemm3_kernel, dim3((unsigned)(((total + 7) / 8) * 8)), dim3(512), lds, s, g);
       return hipGetLastError();
     }
   }

@@ -840,6 +840,16 @@ hipError_t launch_regen(RegenArgs g, const DevCode *code_dev, const DevCode &ch,
   return hipGetLastError();
 }
 
+// One lane stores the constant-rate wall clock (s_memrealtime) with an ordinary vector store.
+__global__ void timestamp_kernel(unsigned long long *dst) {
+  if (threadIdx.x == 0) *dst = wall_clock64();
+}
+
+hipError_t launch_timestamp(unsigned long long *dst, hipStream_t s) {
+  hipLaunchKernelGGL(timestamp_kernel, dim3(1), dim3(64), 0, s, dst);
+  return hipGetLastError();
+}
+
 // ---------------------------------------------------------------------------
 // Soft-error injection.  Noise element idx of a fault is a pure function of
 // (seed, step, phase, bi, bj, idx) through the SplitMix64 output function

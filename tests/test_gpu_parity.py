@@ -303,6 +303,27 @@ def test_regeneration_restores_the_stored_code(N_out, N_in, m, n, r, b, dtype, b
     pair.close()
 
 
+def test_device_time_stamps_bracket_a_call():
+    """Two stamps around an update: a positive, plausible number of ticks of a clock whose
+    rate the call reports; NULL destination is refused."""
+    import torch
+    from paper_1903_01042_amd import binding as B
+    P = WL.vandermonde_like(4, 2)
+    lay = B.CodedLayer(torch.zeros((512, 512), device="cuda"), P, P, max_batch=64)
+    lay.forward(torch.zeros((64, 512), device="cuda"))
+    lay.backward(torch.zeros((64, 512), device="cuda"))
+    stamps = torch.zeros(2, dtype=torch.int64, device="cuda")
+    rate = B.timestamp(stamps, 0)
+    lay.update(0.1)
+    B.timestamp(stamps, 1)
+    torch.cuda.synchronize()
+    a, b = (int(v) for v in stamps.cpu())
+    assert rate >= 1 and a > 0
+    assert 0 < (b - a) / rate < 5000.0, (a, b, rate)        # microseconds
+    assert B.load_library().codenet_timestamp(None, None, None) == B.E_NULL
+    lay.destroy()
+
+
 # ------------------------------------------------------------------ API error paths
 def test_api_errors_on_the_gpu():
     import torch
