@@ -415,11 +415,23 @@ int codenet_inject(codenet_layer *l, const codenet_fault *faults, int n_faults, 
     }
   }
   hipStream_t s = (hipStream_t)stream;
-  // every rms is taken from the still clean data, then the noises are added one
-  // fault after the other (two faults may hit the same block)
-  for (int f = 0; f < n_faults; ++f)
-    if (fa[f].mode == CODENET_NOISE_DENSE_REL) CN_HIP(launch_fault(fa[f], s, true));
-  for (int f = 0; f < n_faults; ++f) CN_HIP(launch_fault(fa[f], s, false));
+  // Every rms is taken from the still clean data, then the noises are added in the order
+  // given.  Faults go to the GPU in batches of up to kFaultBatch, one launch per batch; a
+  // fault whose target block is already in the batch starts a new one, so that two noises
+  // on one block are still added one after the other.
+  for (int pass = 0; pass < 2; ++pass) {
+    FaultBatch fb{};
+    for (int f = 0; f < n_faults; ++f) {
+      bool clash = false;
+      for (int q = 0; q < fb.n; ++q) clash = clash || fb.f[q].base == fa[f].base;
+      if (fb.n == kFaultBatch || (pass == 1 && clash)) {
+        CN_HIP(launch_faults(fb, s, pass == 0));
+        fb.n = 0;
+      }
+      if (pass == 1 || fa[f].mode == CODENET_NOISE_DENSE_REL) fb.f[fb.n++] = fa[f];
+    }
+    CN_HIP(launch_faults(fb, s, pass == 0));
+  }
   if (phase == CODENET_WEIGHT && l->bf16)
     CN_HIP(launch_shadow(l->Wt, l->Mr, l->Nc, l->Wb, l->ldWb, l->WTb, l->ldWTb, s));
   return CODENET_OK;

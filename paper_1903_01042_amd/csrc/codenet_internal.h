@@ -94,6 +94,11 @@ struct FaultArgs {
   int mode;
   double *partials;             // kFaultParts partial sums of squares of this fault
 };
+constexpr int kFaultBatch = 8;
+struct FaultBatch {
+  int n;
+  FaultArgs f[kFaultBatch];
+};
 
 hipError_t launch_encode_matrix(const float *W, float *Wt, const DevCode *code_r, const DevCode *code_c,
                                 int Mr, int Nc, int n_out, int n_in, hipStream_t s);
@@ -109,7 +114,7 @@ hipError_t launch_detect(const float *out, float *syn, double *partials, int *n_
 hipError_t launch_finish(float *out, const float *syn, const double *partials, int n_parts,
                          const DevCode *code_dev, const DevCode &code_host, int b, float *decoded,
                          codenet_report *report, hipStream_t s);
-hipError_t launch_fault(const FaultArgs &fa, hipStream_t s, bool stats_pass);
+hipError_t launch_faults(const FaultBatch &fb, hipStream_t s, bool stats_pass);
 hipError_t launch_export_weights(const float *Wt, float *W, const DevCode &cr, const DevCode &cc,
                                  int Nc, int n_out, int n_in, hipStream_t s);
 

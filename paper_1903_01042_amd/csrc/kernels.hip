@@ -870,7 +870,9 @@ unsigned long long fault_key(unsigned long long seed, unsigned long long step, i
 }
 
 // sum of squares of the (still clean) target payload, kFaultParts partial sums
-__global__ __launch_bounds__(256) void fault_stats_kernel(FaultArgs fa) {
+__global__ __launch_bounds__(256) void fault_stats_kernel(FaultBatch fb) {
+  const FaultArgs &fa = fb.f[blockIdx.y];
+  if (fa.mode != CODENET_NOISE_DENSE_REL) return;
   const long total = (long)fa.n_outer * fa.n_inner;
   double acc = 0.0;
   for (long e = (long)blockIdx.x * 256 + threadIdx.x; e < total; e += (long)gridDim.x * 256) {
@@ -887,7 +889,8 @@ __global__ __launch_bounds__(256) void fault_stats_kernel(FaultArgs fa) {
   if (threadIdx.x == 0) fa.partials[blockIdx.x] = red[0] + red[1] + red[2] + red[3];
 }
 
-__global__ __launch_bounds__(256) void fault_apply_kernel(FaultArgs fa) {
+__global__ __launch_bounds__(256) void fault_apply_kernel(FaultBatch fb) {
+  const FaultArgs &fa = fb.f[blockIdx.y];
   const long total = (long)fa.n_outer * fa.n_inner;
   const long e = (long)blockIdx.x * 256 + threadIdx.x;
   __shared__ float s_scale;
@@ -917,13 +920,18 @@ __global__ __launch_bounds__(256) void fault_apply_kernel(FaultArgs fa) {
   *p += val;
 }
 
-hipError_t launch_fault(const FaultArgs &fa, hipStream_t s, bool stats_pass) {
-  const long total = (long)fa.n_outer * fa.n_inner;
-  if (total <= 0) return hipSuccess;
+// One launch per batch of faults with pairwise distinct targets (grid.y = fault)
+hipError_t launch_faults(const FaultBatch &fb, hipStream_t s, bool stats_pass) {
+  if (fb.n < 1) return hipSuccess;
   if (stats_pass) {
-    hipLaunchKernelGGL(fault_stats_kernel, dim3(kFaultParts), dim3(256), 0, s, fa);
+    hipLaunchKernelGGL(fault_stats_kernel, dim3(kFaultParts, (unsigned)fb.n), dim3(256), 0, s, fb);
   } else {
-    hipLaunchKernelGGL(fault_apply_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, fa);
+    long most = 1;
+    for (int f = 0; f < fb.n; ++f) {
+      const long total = (long)fb.f[f].n_outer * fb.f[f].n_inner;
+      most = total > most ? total : most;
+    }
+    hipLaunchKernelGGL(fault_apply_kernel, dim3((unsigned)((most + 255) / 256), (unsigned)fb.n), dim3(256), 0, s, fb);
   }
   return hipGetLastError();
 }
