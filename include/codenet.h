@@ -166,6 +166,23 @@ int codenet_detect_decode(codenet_layer *layer, int phase, float *coded_out_dev,
                           float *decoded_dev, codenet_report *report_dev, void *stream);
 
 /*
+ * The same with the elementwise primary step that follows the product applied
+ * to the decoded output on its way out (the per-layer algorithm's "generate
+ * x^{l+1} = f(s^l)" in the feedforward stage and the diagonal post-multiplication
+ * delta^{l-1} = g(x^l) (.) c^l in the backpropagation stage, with g(f(u)) = f'(u)):
+ *   CODENET_EPI_RELU      decoded = max(decoded, 0)                  (f = ReLU)
+ *   CODENET_EPI_MASK_POS  decoded = aux > 0 ? decoded : 0            (g of ReLU; aux = x^l)
+ *   CODENET_EPI_MUL       decoded = decoded * aux                    (any f', supplied by the caller)
+ * aux_dev has the shape of decoded_dev ([b][n_out] for FWD, [b][n_in] for BWD) and
+ * is required by the last two; decoded_dev is required by all three.  The coded
+ * output buffer keeps the (corrected) values before the elementwise step.
+ */
+typedef enum { CODENET_EPI_NONE = 0, CODENET_EPI_RELU = 1, CODENET_EPI_MASK_POS = 2, CODENET_EPI_MUL = 3 } codenet_epilogue;
+int codenet_detect_decode_act(codenet_layer *layer, int phase, float *coded_out_dev, int b,
+                              float *decoded_dev, codenet_report *report_dev, int epilogue,
+                              const float *aux_dev, void *stream);
+
+/*
  * Update stage (the three block rules, plus the same rule on the corner):
  * W~ += eta * [delta; delta~] [x; x~]^T summed over the batch, using the vectors
  * cached by the last forward and backward calls (which must have used the same b).

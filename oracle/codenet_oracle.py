@@ -289,6 +289,19 @@ def regenerate_block_row(Wt, i_bad, P_r, m, Br):
 
 
 # --------------------------------------------------------------------------
+# Elementwise primary steps (C1: x^{l+1} = f(s^l); C2: delta^{l-1} = g(x^l) (.) c^l,
+# with g chosen such that g(f(u)) = f'(u)), for f = ReLU
+# --------------------------------------------------------------------------
+def relu(s):
+    return np.maximum(s, 0.0)
+
+
+def relu_backward(c, x):
+    """g(x) (.) c with g(x) = 1[x > 0]: for x = relu(u), g(x) = relu'(u)."""
+    return np.where(x > 0, c, 0.0)
+
+
+# --------------------------------------------------------------------------
 # Soft-error injection (Error Model 2: additive, every element of the
 # erroneous block drawn independently from a continuous law; the experiment's
 # sparse additive law is mode 1)

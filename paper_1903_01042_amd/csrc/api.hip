@@ -355,7 +355,16 @@ int codenet_update(codenet_layer *l, float eta, void *stream) {
 
 int codenet_detect_decode(codenet_layer *l, int phase, float *coded_out_dev, int b, float *decoded_dev,
                           codenet_report *report_dev, void *stream) {
+  return codenet_detect_decode_act(l, phase, coded_out_dev, b, decoded_dev, report_dev, CODENET_EPI_NONE, nullptr,
+                                   stream);
+}
+
+int codenet_detect_decode_act(codenet_layer *l, int phase, float *coded_out_dev, int b, float *decoded_dev,
+                              codenet_report *report_dev, int epilogue, const float *aux_dev, void *stream) {
   if (!l || !coded_out_dev) return CODENET_E_NULL;
+  if (epilogue < CODENET_EPI_NONE || epilogue > CODENET_EPI_MUL) return CODENET_E_DTYPE;
+  if (epilogue != CODENET_EPI_NONE && !decoded_dev) return CODENET_E_NULL;
+  if ((epilogue == CODENET_EPI_MASK_POS || epilogue == CODENET_EPI_MUL) && !aux_dev) return CODENET_E_NULL;
   if (phase != CODENET_FWD && phase != CODENET_BWD) return CODENET_E_DTYPE;
   if (b < 1 || b > l->desc.max_batch) return CODENET_E_BATCH;
   hipStream_t s = (hipStream_t)stream;
@@ -366,7 +375,8 @@ int codenet_detect_decode(codenet_layer *l, int phase, float *coded_out_dev, int
     CN_HIP(launch_detect(coded_out_dev, l->syn, l->partials, &n_parts, cd, ch, b, s));
   }
   // with r = 0 there is nothing to check: zero records make the decision CLEAN
-  CN_HIP(launch_finish(coded_out_dev, l->syn, l->partials, n_parts, cd, ch, b, decoded_dev, report_dev, s));
+  CN_HIP(launch_finish(coded_out_dev, l->syn, l->partials, n_parts, cd, ch, b, decoded_dev, report_dev, epilogue,
+                       aux_dev, s));
   return CODENET_OK;
 }
 

@@ -113,7 +113,7 @@ hipError_t launch_detect(const float *out, float *syn, double *partials, int *n_
 // passes 2 + 3 of a check: decision (every workgroup, from the pass-1 records), correction, decoded output
 hipError_t launch_finish(float *out, const float *syn, const double *partials, int n_parts,
                          const DevCode *code_dev, const DevCode &code_host, int b, float *decoded,
-                         codenet_report *report, hipStream_t s);
+                         codenet_report *report, int epilogue, const float *aux, hipStream_t s);
 hipError_t launch_faults(const FaultBatch &fb, hipStream_t s, bool stats_pass);
 hipError_t launch_export_weights(const float *Wt, float *W, const DevCode &cr, const DevCode &cc,
                                  int Nc, int n_out, int n_in, hipStream_t s);

@@ -639,7 +639,8 @@ __global__ __launch_bounds__(256) void finish_kernel(float *__restrict__ out, co
                                                      const double *__restrict__ partials, int n_parts,
                                                      const DevCode *__restrict__ code, int b,
                                                      float *__restrict__ decoded, int aligned,
-                                                     codenet_report *__restrict__ report) {
+                                                     codenet_report *__restrict__ report, int epi,
+                                                     const float *__restrict__ aux) {
   __shared__ DevPlan plan;
   decide_body<GENERIC>(partials, n_parts, code, &plan, blockIdx.x == 0 ? report : nullptr);
   __syncthreads();
@@ -666,33 +667,49 @@ __global__ __launch_bounds__(256) void finish_kernel(float *__restrict__ out, co
   }
   if (decoded == nullptr) return;
   float *dst = decoded + (long)beta * N;
+  const float *ax = aux ? aux + (long)beta * N : nullptr;
+  // the elementwise primary step that follows the product, applied to the decoded copy only:
+  // activation f = ReLU (feedforward), or the diagonal post-multiplication by g(x) (backpropagation)
+  auto act = [&](float v, int g) -> float {
+    if (epi == CODENET_EPI_RELU) return v > 0.f ? v : 0.f;
+    if (epi == CODENET_EPI_MASK_POS) return ax[g] > 0.f ? v : 0.f;
+    if (epi == CODENET_EPI_MUL) return v * ax[g];
+    return v;
+  };
   for (int i = 0; i < a; ++i) {
     const float4 v = *reinterpret_cast<const float4 *>(row + i * B);   // own writes above are visible to this thread
-    if (aligned) {
+    if (aligned && epi == CODENET_EPI_NONE) {
       const int g = i * B0 + rho;
       if (g < N) *reinterpret_cast<float4 *>(dst + g) = v;
       continue;
     }
     const float vv[4] = {v.x, v.y, v.z, v.w};
+    if (aligned) {
+      const int g = i * B0 + rho;
+      if (g < N)
+        *reinterpret_cast<float4 *>(dst + g) = make_float4(act(vv[0], g), act(vv[1], g + 1), act(vv[2], g + 2), act(vv[3], g + 3));
+      continue;
+    }
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       const int g = i * B0 + rho + e;
-      if (rho + e < B0 && g < N) dst[g] = vv[e];
+      if (rho + e < B0 && g < N) dst[g] = act(vv[e], g);
     }
   }
 }
 
 hipError_t launch_finish(float *out, const float *syn, const double *partials, int n_parts, const DevCode *code_dev,
-                         const DevCode &ch, int b, float *decoded, codenet_report *report, hipStream_t s) {
+                         const DevCode &ch, int b, float *decoded, codenet_report *report, int epi, const float *aux,
+                         hipStream_t s) {
   const long total = (long)b * (ch.B >> 2);
   const int aligned = (ch.N % 4 == 0) && (ch.B0 % 4 == 0) && ((reinterpret_cast<uintptr_t>(decoded) & 15) == 0);
   dim3 grid((unsigned)((total + 255) / 256)), block(256);
   if (ch.r >= 4)
     hipLaunchKernelGGL(finish_kernel<true>, grid, block, 0, s, out, syn, partials, n_parts, code_dev, b, decoded,
-                       aligned, report);
+                       aligned, report, epi, aux);
   else
     hipLaunchKernelGGL(finish_kernel<false>, grid, block, 0, s, out, syn, partials, n_parts, code_dev, b, decoded,
-                       aligned, report);
+                       aligned, report, epi, aux);
   return hipGetLastError();
 }
 

@@ -48,8 +48,9 @@ class Pair:
         assert err <= (tol or self.tol), "coded weights differ: rel %.3e" % err
         return err
 
-    def product(self, phase, V, faults=(), check_margins=True):
-        """One coded product + injection + check on both sides; V is batch-major [b][N]."""
+    def product(self, phase, V, faults=(), check_margins=True, epilogue=0, aux=None):
+        """One coded product + injection + check on both sides; V is batch-major [b][N].
+        epilogue / aux (batch-major numpy): the elementwise step fused into the GPU's check."""
         B = self.B
         Vd = self.dev_tensor(V)
         if phase == B.FWD:
@@ -66,9 +67,16 @@ class Pair:
             out_o = self.ora.inject(faults, out_o)
             err = rel_fro(to_np(out_g).T, out_o)
             assert err <= self.tol, "injected output differs: rel %.3e" % err
-        dec_g = self.gpu.detect_decode(phase, out_g, report=self.report)
+        dec_g = self.gpu.detect_decode(phase, out_g, report=self.report, epilogue=epilogue,
+                                       aux=None if aux is None else self.dev_tensor(aux))
         rep = self.gpu.read_report(self.report)
         res = self.ora.detect_decode(phase, out_o)
+        if epilogue == B.EPI_RELU:
+            res["decoded"] = O.relu(res["decoded"])
+        elif epilogue == B.EPI_MASK_POS:
+            res["decoded"] = O.relu_backward(res["decoded"], np.asarray(aux, dtype=np.float64).T)
+        elif epilogue == B.EPI_MUL:
+            res["decoded"] = res["decoded"] * np.asarray(aux, dtype=np.float64).T
         self.log.append((phase, [(f["bi"], f["bj"]) for f in faults], rep["verdict"], rep["located"]))
         assert rep["verdict"] == res["verdict"], (rep, res["verdict"], res["located"], res["syn_rel"], res["resid_rel"])
         assert rep["located"] == res["located"], (rep, res["located"])
@@ -122,6 +130,8 @@ class Pair:
 # product is recomputed once without replaying the fault (transient output errors).
 # ---------------------------------------------------------------------------------
 class MlpPair:
+    EPI_RELU, EPI_MASK_POS = 1, 2
+
     def __init__(self, wl, max_layers=None):
         self.wl = wl
         widths = wl.widths if max_layers is None else wl.widths[: max_layers + 1]
@@ -133,12 +143,12 @@ class MlpPair:
         self.widths = widths
         self.counts = {0: 0, 1: 0, 2: 0}
 
-    def _product(self, l, phase, V, faults):
+    def _product(self, l, phase, V, faults, epilogue=0, aux=None):
         pair = self.layers[l]
-        dec, rep, res = pair.product(phase, V, faults)
+        dec, rep, res = pair.product(phase, V, faults, epilogue=epilogue, aux=aux)
         self.counts[rep["verdict"]] += 1
         if rep["verdict"] == O.UNCORRECTABLE:
-            dec, rep, res = pair.product(phase, V, ())          # roll back = recompute the product
+            dec, rep, res = pair.product(phase, V, (), epilogue=epilogue, aux=aux)   # roll back = recompute the product
             assert rep["verdict"] == O.CLEAN
         return to_np(dec).astype(np.float32), res["decoded"].T.astype(np.float32)
 
@@ -148,10 +158,12 @@ class MlpPair:
         X = wl.inputs(step)[:, : self.widths[0]]
         xs_g, xs_o = [X], [X]
         for l in range(L):
-            s_g, s_o = self._product(l, WL.PHASE_FWD, xs_g[-1], wl.product_faults(WL.PHASE_FWD, step, l))
+            # the activation is fused into the check on the GPU side (all layers but the last)
+            s_g, s_o = self._product(l, WL.PHASE_FWD, xs_g[-1], wl.product_faults(WL.PHASE_FWD, step, l),
+                                     epilogue=self.EPI_RELU if l < L - 1 else 0)
             assert rel_fro(s_g, s_o) <= self.layers[l].tol
             if l < L - 1:
-                s_g, s_o = np.maximum(s_g, 0), np.maximum(s_o, 0)
+                assert (s_g >= 0).all()
             # both sides continue from the GPU activations: the comparison is per product
             xs_g.append(s_g)
             xs_o.append(s_g)
@@ -165,10 +177,12 @@ class MlpPair:
         delta = ((Y - p) / b).astype(np.float32)
         loss = float(-np.mean(np.log(p[np.arange(b), labels] + 1e-30)))
         for l in range(L - 1, -1, -1):
-            c_g, c_o = self._product(l, WL.PHASE_BWD, delta, wl.product_faults(WL.PHASE_BWD, step, l))
+            # delta^{l-1} = g(x^l) (.) c^l, fused into the check of the backward product
+            c_g, c_o = self._product(l, WL.PHASE_BWD, delta, wl.product_faults(WL.PHASE_BWD, step, l),
+                                     epilogue=self.EPI_MASK_POS if l > 0 else 0, aux=xs_g[l] if l > 0 else None)
             assert rel_fro(c_g, c_o) <= self.layers[l].tol
             if l > 0:
-                delta = (c_g * (xs_g[l] > 0)).astype(np.float32)
+                delta = c_g.astype(np.float32)
         for l in range(L):
             self.layers[l].update(wl.eta)
         return loss

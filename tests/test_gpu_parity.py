@@ -324,6 +324,41 @@ def test_device_time_stamps_bracket_a_call():
     lay.destroy()
 
 
+# ------------------------------------------------------------------ elementwise step fused into the check
+@pytest.mark.parametrize("n_out,n_in,m,n,r,b,dtype", [
+    (512, 384, 4, 4, 2, 64, "f32"),       # aligned: float4 path
+    (100, 52, 3, 5, 2, 7, "f32"),         # nothing divides anything: scalar path
+    (300, 200, 5, 4, 2, 33, "bf16"),
+])
+def test_activation_fused_into_the_check(n_out, n_in, m, n, r, b, dtype):
+    """ReLU on the decoded forward output, g(x) (.) c and a general multiplier on the decoded
+    backward output, with and without a corrected fault; the coded buffer keeps the values
+    before the elementwise step."""
+    from paper_1903_01042_amd import binding as B
+    P_r, P_c = WL.vandermonde_like(m, r), WL.vandermonde_like(n, r)
+    tau = (1e-3, 1e-2) if dtype == "f32" else (2e-2, 2e-2)
+    pair = Pair(WL.layer_weights(n_out, n_in), P_r, P_c, dtype, b, *tau)
+    X, D = WL.normal((b, n_in), 21), WL.normal((b, n_out), 22)
+    for faults_f, faults_b in (((), ()), ([WL.make_fault(FWD, 1, 0, 3)], [WL.make_fault(BWD, 0, n, 3)])):
+        dec, rep, res = pair.product(FWD, X, faults_f, epilogue=B.EPI_RELU)
+        assert rep["verdict"] == (CORRECTED if faults_f else CLEAN)
+        got = to_np(dec)
+        assert (got >= 0).all() and (got == 0).any() and (got > 0).any()
+        dec, rep, _ = pair.product(BWD, D, faults_b, epilogue=B.EPI_MASK_POS, aux=X)
+        assert rep["verdict"] == (CORRECTED if faults_b else CLEAN)
+        assert (to_np(dec)[X <= 0] == 0).all()
+        pair.product(BWD, D, faults_b, epilogue=B.EPI_MUL, aux=WL.normal((b, n_in), 23))
+    lay = pair.gpu
+    out = lay.forward(pair.dev_tensor(X))
+    lib, vp = B.load_library(), __import__("ctypes").c_void_p
+    dec = pair.dev_tensor(np.zeros((b, n_out)))
+    args = (lay._h, B.FWD, vp(out.data_ptr()), b)
+    assert lib.codenet_detect_decode_act(*args, vp(dec.data_ptr()), None, B.EPI_MUL, None, None) == B.E_NULL
+    assert lib.codenet_detect_decode_act(*args, None, None, B.EPI_RELU, None, None) == B.E_NULL
+    assert lib.codenet_detect_decode_act(*args, vp(dec.data_ptr()), None, 7, None, None) == B.E_DTYPE
+    pair.close()
+
+
 # ------------------------------------------------------------------ API error paths
 def test_api_errors_on_the_gpu():
     import torch

@@ -424,6 +424,18 @@ def test_layer_regeneration_after_a_weight_fault_gives_clean_products():
     assert lay.detect_decode(O.PHASE_FWD, lay.forward(rng.standard_normal((N, b))))["verdict"] == O.CLEAN
 
 
+def test_relu_steps_are_the_function_and_its_derivative():
+    """C1 / C2 for f = ReLU: g(f(u)) = f'(u), checked against a central difference away from 0."""
+    u = rng.standard_normal(1000)
+    u = u[np.abs(u) > 1e-3]
+    x = O.relu(u)
+    assert np.array_equal(x, np.where(u > 0, u, 0.0))
+    h = 1e-6
+    fprime = (O.relu(u + h) - O.relu(u - h)) / (2 * h)
+    c = rng.standard_normal(u.shape)
+    assert np.allclose(O.relu_backward(c, x), c * fprime, atol=1e-9)
+
+
 # ------------------------------------------------------------------ geometry
 def test_results_do_not_depend_on_block_pitch():
     N_out, N_in, m, n, r, b = 10, 9, 4, 3, 2, 3
