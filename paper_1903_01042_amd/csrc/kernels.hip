@@ -154,6 +154,11 @@ hipError_t launch_encode_vector(const float *V, float *Vt, const DevCode *code_d
   return hipGetLastError();
 }
 
+// Block geometry by value: kernels that take it need no dependent load from the code table
+// before they can form their first address.
+struct Geometry { int B, B0, a, r, L, N; };
+static inline Geometry geometry_of(const DevCode &c) { return Geometry{c.B, c.B0, c.a, c.r, c.L, c.N}; }
+
 // The same encoding for the bf16 mode, one 64 (batch) x 64 (positions) tile of one
 // output block per workgroup: besides the fp32 coded vector it writes the two bf16
 // copies that the MFMA kernels read, the batch-major one (operand of the product)
@@ -164,9 +169,9 @@ __global__ __launch_bounds__(256) void encode_vector_bf16_kernel(const float *__
                                                                  const DevCode *__restrict__ code, int b,
                                                                  __bf16 *__restrict__ Vb, long ldVb,
                                                                  __bf16 *__restrict__ VTb, long ldVT, int Rpad,
-                                                                 int aligned) {
+                                                                 int aligned, Geometry geo) {
   __shared__ unsigned short tile[64][66];
-  const int B = code->B, B0 = code->B0, a = code->a, r = code->r, N = code->N;
+  const int B = geo.B, B0 = geo.B0, a = geo.a, r = geo.r, N = geo.N;
   const int rho0 = blockIdx.x * 64, beta0 = blockIdx.y * 64, job = blockIdx.z;
   const int t = threadIdx.x;
   const int c = (t & 15) * 4, rho = rho0 + c;
@@ -234,7 +239,7 @@ hipError_t launch_encode_vector_bf16(const float *V, float *Vt, const DevCode *c
   dim3 grid((unsigned)((code_host.B + 63) / 64), (unsigned)(Rpad / 64), (unsigned)(code_host.a + code_host.r));
   const int aligned = (code_host.N % 4 == 0) && (code_host.B0 % 4 == 0) && ((reinterpret_cast<uintptr_t>(V) & 15) == 0);
   hipLaunchKernelGGL(encode_vector_bf16_kernel, grid, dim3(256), 0, s, V, Vt, code_dev, b, (__bf16 *)Vb, ldVb,
-                     (__bf16 *)VTb, ldVT, Rpad, aligned);
+                     (__bf16 *)VTb, ldVT, Rpad, aligned, geometry_of(code_host));
   return hipGetLastError();
 }
 
@@ -355,41 +360,44 @@ __device__ void decide_body(const double *partials, int n_parts, const DevCode *
     H[idx / CODENET_MAX_L][idx % CODENET_MAX_L] = code->H[idx / CODENET_MAX_L][idx % CODENET_MAX_L];
   const double tau_detect = code->tau_detect, tau_resid = code->tau_resid;
 
-  // Totals of the per-workgroup records (stored entry-major), live entries only:
-  // thread t takes records t and t + 256 of eight entries at a time (independent
-  // loads), a shuffle tree adds the lanes, LDS the four wavefronts -- the same
-  // arithmetic on every run.
-  __shared__ double red[4][kMaxEntries];
+  // Totals of the per-workgroup records (stored entry-major), live entries only, 16 entries at
+  // a time: thread t adds records t and t + 256 of each (independent loads), then a 16 x 16
+  // tree through LDS per entry -- the same arithmetic on every run and in every workgroup.
+  __shared__ double red[16][256];
+  __shared__ double red2[16][16];
   const int n_live = L + r * (r + 1) / 2;
-  {
-    const int lane = t & 63, wave = t >> 6;
-    for (int k0 = 0; k0 < n_live; k0 += 8) {
-      double v[8];
+  if (t < kMaxEntries) tot[t] = 0.0;
+  for (int c0 = 0; c0 < n_live; c0 += 16) {
+    double v[16];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const int k = k0 + u;
-        const int e = k < L ? k : CODENET_MAX_L + (k - L);
-        double a = 0.0, b2 = 0.0;
-        if (k < n_live && t < n_parts) a = partials[(long)e * kDetectParts + t];
-        if (k < n_live && t + 256 < n_parts) b2 = partials[(long)e * kDetectParts + t + 256];
-        v[u] = a + b2;
-      }
-#pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        double w = v[u];
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) w += __shfl_down(w, off, 64);
-        const int k = k0 + u;
-        if (lane == 0 && k < n_live) red[wave][k < L ? k : CODENET_MAX_L + (k - L)] = w;
-      }
+    for (int u = 0; u < 16; ++u) {
+      const int k = c0 + u;
+      const int e = k < L ? k : CODENET_MAX_L + (k - L);
+      double a = 0.0, b2 = 0.0;
+      if (k < n_live && t < n_parts) a = partials[(long)e * kDetectParts + t];
+      if (k < n_live && t + 256 < n_parts) b2 = partials[(long)e * kDetectParts + t + 256];
+      v[u] = a + b2;
     }
+#pragma unroll
+    for (int u = 0; u < 16; ++u) red[u][t] = v[u];
+    __syncthreads();
+    {
+      const int u = t >> 4, part = t & 15;
+      double acc = 0.0;
+#pragma unroll
+      for (int q = 0; q < 16; ++q) acc += red[u][part + 16 * q];
+      red2[u][part] = acc;
+    }
+    __syncthreads();
+    if (t < 16 && c0 + t < n_live) {
+      double acc = 0.0;
+#pragma unroll
+      for (int q = 0; q < 16; ++q) acc += red2[t][q];
+      const int k = c0 + t;
+      tot[k < L ? k : CODENET_MAX_L + (k - L)] = acc;
+    }
+    __syncthreads();
   }
-  __syncthreads();
-  if (t < kMaxEntries) {
-    const bool live = t < L || (t >= CODENET_MAX_L && t < CODENET_MAX_L + r * (r + 1) / 2);
-    tot[t] = live ? (red[0][t] + red[1][t]) + (red[2][t] + red[3][t]) : 0.0;
-  }
-  __syncthreads();
   if (t == 0) {
     int e = CODENET_MAX_L;
     double trG = 0.0;
@@ -444,6 +452,7 @@ __device__ void decide_body(const double *partials, int n_parts, const DevCode *
         if (res2 < my_res) { my_res = res2; my_rank = rank; }
       }
       // smallest (residual, rank) pair: shuffle tree inside a wavefront, then the four leaders
+      // (an LDS tree as for the sums was no faster here)
 #pragma unroll
       for (int off = 32; off > 0; off >>= 1) {
         const double o_res = __shfl_down(my_res, off, 64);
@@ -535,8 +544,9 @@ __device__ void decide_body(const double *partials, int n_parts, const DevCode *
 template <int R>
 __global__ __launch_bounds__(256) void detect_kernel(const float *__restrict__ out, float *__restrict__ syn,
                                                      double *__restrict__ partials,
-                                                     const DevCode *__restrict__ code, int b, int iters) {
-  const int B = code->B, L = code->L;
+                                                     const DevCode *__restrict__ code, int b, int iters,
+                                                     Geometry geo) {
+  const int B = geo.B, L = geo.L;
   const int quads = B >> 2;
   const long npos = (long)b * quads;
   constexpr int NG = R * (R + 1) / 2;
@@ -579,29 +589,45 @@ __global__ __launch_bounds__(256) void detect_kernel(const float *__restrict__ o
     }
   }
 
-  // reduce: lanes (float64 shuffles), then the 4 wavefronts through LDS
-  __shared__ double red[4][kMaxEntries];
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-#pragma unroll
-  for (int i = 0; i < CODENET_MAX_L; ++i)
-    if (i < L) {
-      double v = (double)sq[i];
-#pragma unroll
-      for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
-      if (lane == 0) red[wave][i] = v;
-    }
-#pragma unroll
-  for (int e = 0; e < NG; ++e) {
-    double v = (double)gram[e];
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_down(v, off, 64);
-    if (lane == 0) red[wave][CODENET_MAX_L + e] = v;
-  }
-  __syncthreads();
+  // Reduce over the 256 threads, 16 entries at a time, through LDS: a 16 x 16 tree per entry
+  // (each thread adds 16 values a fixed stride apart, then 16 threads add the 16 partial sums).
+  // Float64, fixed order.  (Shuffle trees of doubles cost about 2 us here: two ds_bpermute
+  // and their address arithmetic per step, 6 steps, 13 entries.)  Live entries are numbered
+  // Gram first (their count is a compile-time constant), then the L block norms.
+  __shared__ double red[16][256];
+  __shared__ double red2[16][16];
   const int t = threadIdx.x;
-  if (t < CODENET_MAX_L + NG && (t < L || t >= CODENET_MAX_L))
-    partials[(long)t * kDetectParts + blockIdx.x] = red[0][t] + red[1][t] + red[2][t] + red[3][t];
-
+  const int n_live = NG + L;
+#pragma unroll
+  for (int c0 = 0; c0 < NG + CODENET_MAX_L; c0 += 16) {
+    if (c0 >= n_live) break;
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      const int k = c0 + u;
+      float v = 0.f;
+      if (k < NG) v = gram[k < NG ? k : 0];
+      else if (k - NG < CODENET_MAX_L && k - NG < L) v = sq[k - NG < CODENET_MAX_L ? k - NG : 0];
+      red[u][t] = (double)v;
+    }
+    __syncthreads();
+    {
+      const int u = t >> 4, part = t & 15;
+      double acc = 0.0;
+#pragma unroll
+      for (int q = 0; q < 16; ++q) acc += red[u][part + 16 * q];
+      red2[u][part] = acc;
+    }
+    __syncthreads();
+    if (t < 16 && c0 + t < n_live) {
+      double acc = 0.0;
+#pragma unroll
+      for (int q = 0; q < 16; ++q) acc += red2[t][q];
+      const int k = c0 + t;
+      const int e = k < NG ? CODENET_MAX_L + k : k - NG;
+      partials[(long)e * kDetectParts + blockIdx.x] = acc;
+    }
+    __syncthreads();
+  }
 }
 
 hipError_t launch_detect(const float *out, float *syn, double *partials, int *n_parts, const DevCode *code_dev,
@@ -617,7 +643,7 @@ hipError_t launch_detect(const float *out, float *syn, double *partials, int *n_
   dim3 grid((unsigned)wgs), block(256);
   switch (ch.r) {
 #define CODENET_DETECT_CASE(RR) \
-  case RR: hipLaunchKernelGGL(detect_kernel<RR>, grid, block, 0, s, out, syn, partials, code_dev, b, iters); break;
+  case RR: hipLaunchKernelGGL(detect_kernel<RR>, grid, block, 0, s, out, syn, partials, code_dev, b, iters, geometry_of(ch)); break;
     CODENET_DETECT_CASE(1) CODENET_DETECT_CASE(2) CODENET_DETECT_CASE(3) CODENET_DETECT_CASE(4)
     CODENET_DETECT_CASE(5) CODENET_DETECT_CASE(6) CODENET_DETECT_CASE(7) CODENET_DETECT_CASE(8)
 #undef CODENET_DETECT_CASE
@@ -640,13 +666,13 @@ __global__ __launch_bounds__(256) void finish_kernel(float *__restrict__ out, co
                                                      const DevCode *__restrict__ code, int b,
                                                      float *__restrict__ decoded, int aligned,
                                                      codenet_report *__restrict__ report, int epi,
-                                                     const float *__restrict__ aux) {
+                                                     const float *__restrict__ aux, Geometry geo) {
   __shared__ DevPlan plan;
   decide_body<GENERIC>(partials, n_parts, code, &plan, blockIdx.x == 0 ? report : nullptr);
   __syncthreads();
   const int corrected = plan.verdict == CODENET_CORRECTED ? plan.n_located : 0;
   if (corrected == 0 && decoded == nullptr) return;
-  const int B = code->B, B0 = code->B0, L = code->L, a = code->a, r = code->r, N = code->N;
+  const int B = geo.B, B0 = geo.B0, L = geo.L, a = geo.a, r = geo.r, N = geo.N;
   const int quads = B >> 2;
   const long idx = (long)blockIdx.x * 256 + threadIdx.x;
   if (idx >= (long)b * quads) return;
@@ -706,10 +732,10 @@ hipError_t launch_finish(float *out, const float *syn, const double *partials, i
   dim3 grid((unsigned)((total + 255) / 256)), block(256);
   if (ch.r >= 4)
     hipLaunchKernelGGL(finish_kernel<true>, grid, block, 0, s, out, syn, partials, n_parts, code_dev, b, decoded,
-                       aligned, report, epi, aux);
+                       aligned, report, epi, aux, geometry_of(ch));
   else
     hipLaunchKernelGGL(finish_kernel<false>, grid, block, 0, s, out, syn, partials, n_parts, code_dev, b, decoded,
-                       aligned, report, epi, aux);
+                       aligned, report, epi, aux, geometry_of(ch));
   return hipGetLastError();
 }
 
