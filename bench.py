@@ -193,6 +193,8 @@ class Runner:
         one forward product that locates the row, then `reps` regenerations of it (each rebuilds
         the same row from the same good blocks) between two events."""
         torch, B, WL, L = self.torch, self.B, self.WL, self.layer
+        if self.wl.r < 2:
+            return None                   # r = 1 only detects: nothing is ever located
         n = self.wl.grid[1]
         L.inject([WL.make_fault(WL.PHASE_WEIGHT, 1, j, 10 ** 6) for j in range(n)])
         out = L.forward(self.X[0])

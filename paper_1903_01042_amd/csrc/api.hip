@@ -22,7 +22,6 @@ struct codenet_layer {
   float *syn = nullptr;         // [max r][max_batch][max B]
   double *partials = nullptr;   // [kDetectParts][kMaxEntries]
   double *fault_partials = nullptr;   // [CODENET_MAX_FAULTS][kFaultParts]
-  DevPlan *plan = nullptr;
   // bf16 mode only: k-contiguous bf16 operands of the two products
   __bf16 *Wb = nullptr;         // [Mr][ldWb]   row-major copy of W~ (forward)
   __bf16 *WTb = nullptr;        // [Nc][ldWTb]  transposed copy of W~ (backward)
@@ -35,6 +34,7 @@ struct codenet_layer {
   int KpX = 0, KpD = 0, bpad = 0;   // contraction lengths (multiples of 64): base columns, base rows, batch
   long ldXb = 0, ldDb = 0, ldT = 0; // pitches of Xb, Db and of XTb / DTb
   int fwd_b = 0, bwd_b = 0;     // batch of the cached vectors (0 = none)
+  unsigned long updates = 0;    // number of updates enqueued so far
   bool bf16 = false;
 };
 
@@ -130,7 +130,7 @@ int real_entries(const DevCode &c, int block) {
 void free_layer(codenet_layer *l) {
   if (!l) return;
   (void)hipFree(l->Wt); (void)hipFree(l->Xt); (void)hipFree(l->Dt); (void)hipFree(l->syn);
-  (void)hipFree(l->partials); (void)hipFree(l->fault_partials); (void)hipFree(l->plan);
+  (void)hipFree(l->partials); (void)hipFree(l->fault_partials);
   (void)hipFree(l->code_r_dev); (void)hipFree(l->code_c_dev);
   (void)hipFree(l->Wb); (void)hipFree(l->WTb); (void)hipFree(l->Xb); (void)hipFree(l->Db);
   (void)hipFree(l->XTb); (void)hipFree(l->DTb); (void)hipFree(l->part);
@@ -195,7 +195,6 @@ int codenet_encode(const codenet_desc *d, const float *W_dev, void *stream, code
   alloc((void **)&l->syn, sizeof(float) * (size_t)rmax * mb * bmax);
   alloc((void **)&l->partials, sizeof(double) * (size_t)kDetectParts * kMaxEntries);
   alloc((void **)&l->fault_partials, sizeof(double) * (size_t)CODENET_MAX_FAULTS * kFaultParts);
-  alloc((void **)&l->plan, sizeof(DevPlan));
   alloc((void **)&l->code_r_dev, sizeof(DevCode));
   alloc((void **)&l->code_c_dev, sizeof(DevCode));
   if (l->bf16) {
@@ -340,6 +339,12 @@ int codenet_update(codenet_layer *l, float eta, void *stream) {
     u.Wb = l->Wb; u.ldWb = l->ldWb;
     u.WTb = l->WTb; u.ldWTb = l->ldWTb;
     u.I = l->Nc; u.J = l->Mr; u.K = bp; u.eta = eta;
+    // The matrix and its copies are a little more than the memory-side cache holds; sweeping them
+    // in the same order every step is the worst case for its LRU replacement, so the direction
+    // alternates: what the last update wrote last is read first.
+    const char *alt = getenv("CODENET_ALTERNATE");
+    u.reverse = (alt && alt[0] == '0') ? 0 : (int)(l->updates & 1);
+    ++l->updates;
     CN_HIP(launch_update2(u, s));
     return CODENET_OK;
   }

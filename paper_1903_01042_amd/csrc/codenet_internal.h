@@ -63,6 +63,7 @@ struct Update2Args {
   int I, J, K;
   float eta;
   int tiles_i, tiles_j;
+  int reverse;                   // walk the tiles in the opposite order (alternates from call to call)
 };
 constexpr int kMaxSplits = 8;
 void plan_gemm2(int I, int J, int K, int max_splits, int *tile, int *splits);

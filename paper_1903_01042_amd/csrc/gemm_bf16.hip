@@ -539,7 +539,9 @@ __global__ __launch_bounds__(256, (FM * FN <= 4 ? 2 : 1)) void update2_kernel(Up
 // ---------------------------------------------------------------------------
 struct TileWalk {
   int tiles_i, tiles_j, tjx, span, total, x, step, q;
-  __device__ void init(int ti, int tj) {
+  bool reverse;
+  __device__ void init(int ti, int tj, bool rev = false) {
+    reverse = rev;
     tiles_i = ti; tiles_j = tj;
     tjx = (tj + 7) >> 3;                      // tile rows per XCD
     span = 8 * tjx;                           // tiles in one block of 8 tile columns
@@ -551,7 +553,8 @@ struct TileWalk {
   // next valid tile of this workgroup; false when there is none
   __device__ bool next(int &ti, int &tj) {
     for (q += step; q < total; q += step) {
-      const int blk = q / span, w = q % span;
+      const int qq = reverse ? total - 1 - q : q;
+      const int blk = qq / span, w = qq % span;
       ti = 8 * blk + (w & 7);
       tj = x * tjx + (w >> 3);
       if (ti < tiles_i && tj < tiles_j) return true;
@@ -581,7 +584,7 @@ __global__ __launch_bounds__(512) void update3_kernel(Update2Args g) {
   const int KS = g.K >> 6;                    // slabs per tile (>= 4)
 
   TileWalk walk;
-  walk.init(g.tiles_i, g.tiles_j);
+  walk.init(g.tiles_i, g.tiles_j, g.reverse != 0);
   int ti, tj;
   if (!walk.next(ti, tj)) return;             // uniform: nothing for this workgroup
 

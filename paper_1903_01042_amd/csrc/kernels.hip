@@ -172,7 +172,9 @@ __global__ __launch_bounds__(256) void encode_vector_bf16_kernel(const float *__
                                                                  int aligned, Geometry geo) {
   __shared__ unsigned short tile[64][66];
   const int B = geo.B, B0 = geo.B0, a = geo.a, r = geo.r, N = geo.N;
-  const int rho0 = blockIdx.x * 64, beta0 = blockIdx.y * 64, job = blockIdx.z;
+  // the parity jobs read all a blocks: they are dispatched first so that they do not form the tail
+  const int rho0 = blockIdx.x * 64, beta0 = blockIdx.y * 64;
+  const int job = (int)blockIdx.z < r ? a + (int)blockIdx.z : (int)blockIdx.z - r;
   const int t = threadIdx.x;
   const int c = (t & 15) * 4, rho = rho0 + c;
   auto fetch = [&](const float *src, int i, float (&v)[4]) {
