@@ -190,27 +190,47 @@ __global__ __launch_bounds__(256) void encode_vector_bf16_kernel(const float *__
       }
     }
   };
+  // this thread's four rows: rr = t / 16 + 16 p
+  float v[4][4];
+#pragma unroll
+  for (int p = 0; p < 4; ++p) v[p][0] = v[p][1] = v[p][2] = v[p][3] = 0.f;
+  if (job < a) {
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      const int beta = beta0 + (t >> 4) + 16 * p;
+      if (beta < b && rho < B) fetch(V + (long)beta * N, job, v[p]);
+    }
+  } else {
+    // parity block k = sum_i H[k][i] block_i, i ascending; the loads of four blocks x four rows are
+    // issued together (one block at a time would expose a load latency per block)
+    const int k = job - a;
+    for (int i0 = 0; i0 < a; i0 += 4) {
+      float x[4][4][4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u)
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+          const int beta = beta0 + (t >> 4) + 16 * p;
+          x[u][p][0] = x[u][p][1] = x[u][p][2] = x[u][p][3] = 0.f;
+          if (i0 + u < a && beta < b && rho < B) fetch(V + (long)beta * N, i0 + u, x[u][p]);
+        }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const float h = i0 + u < a ? code->Hf[k][i0 + u] : 0.f;
+#pragma unroll
+        for (int p = 0; p < 4; ++p)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) v[p][e] = i0 + u < a ? fmaf(h, x[u][p][e], v[p][e]) : v[p][e];
+      }
+    }
+  }
 #pragma unroll
   for (int p = 0; p < 4; ++p) {
     const int rr = (t >> 4) + 16 * p, beta = beta0 + rr;
-    float v[4] = {0.f, 0.f, 0.f, 0.f};
-    if (beta < b && rho < B) {
-      const float *src = V + (long)beta * N;
-      if (job < a) {
-        fetch(src, job, v);
-      } else {
-        const int k = job - a;
-        for (int i = 0; i < a; ++i) {
-          float x[4];
-          fetch(src, i, x);
-          const float h = code->Hf[k][i];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] = fmaf(h, x[e], v[e]);
-        }
-      }
-      *reinterpret_cast<float4 *>(Vt + (long)beta * (a + r) * B + (long)job * B + rho) = make_float4(v[0], v[1], v[2], v[3]);
-    }
-    const __bf16 b0 = (__bf16)v[0], b1 = (__bf16)v[1], b2 = (__bf16)v[2], b3 = (__bf16)v[3];
+    if (beta < b && rho < B)
+      *reinterpret_cast<float4 *>(Vt + (long)beta * (a + r) * B + (long)job * B + rho) =
+          make_float4(v[p][0], v[p][1], v[p][2], v[p][3]);
+    const __bf16 b0 = (__bf16)v[p][0], b1 = (__bf16)v[p][1], b2 = (__bf16)v[p][2], b3 = (__bf16)v[p][3];
     const unsigned short u0 = __builtin_bit_cast(unsigned short, b0), u1 = __builtin_bit_cast(unsigned short, b1),
                          u2 = __builtin_bit_cast(unsigned short, b2), u3 = __builtin_bit_cast(unsigned short, b3);
     tile[rr][c] = u0; tile[rr][c + 1] = u1; tile[rr][c + 2] = u2; tile[rr][c + 3] = u3;
@@ -704,24 +724,35 @@ __global__ __launch_bounds__(256) void finish_kernel(float *__restrict__ out, co
     if (epi == CODENET_EPI_MUL) return v * ax[g];
     return v;
   };
-  for (int i = 0; i < a; ++i) {
-    const float4 v = *reinterpret_cast<const float4 *>(row + i * B);   // own writes above are visible to this thread
-    if (aligned && epi == CODENET_EPI_NONE) {
-      const int g = i * B0 + rho;
-      if (g < N) *reinterpret_cast<float4 *>(dst + g) = v;
-      continue;
-    }
-    const float vv[4] = {v.x, v.y, v.z, v.w};
-    if (aligned) {
-      const int g = i * B0 + rho;
-      if (g < N)
-        *reinterpret_cast<float4 *>(dst + g) = make_float4(act(vv[0], g), act(vv[1], g + 1), act(vv[2], g + 2), act(vv[3], g + 3));
-      continue;
-    }
+  // eight blocks at a time: all loads first, then the stores (one block at a time would
+  // expose a load latency per block)
+  for (int i0 = 0; i0 < a; i0 += 8) {
+    float4 blk[8];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const int g = i * B0 + rho + e;
-      if (rho + e < B0 && g < N) dst[g] = act(vv[e], g);
+    for (int u = 0; u < 8; ++u)
+      if (i0 + u < a) blk[u] = *reinterpret_cast<const float4 *>(row + (i0 + u) * B);   // own writes above are visible to this thread
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int i = i0 + u;
+      if (i >= a) break;
+      const float4 v = blk[u];
+      if (aligned && epi == CODENET_EPI_NONE) {
+        const int g = i * B0 + rho;
+        if (g < N) *reinterpret_cast<float4 *>(dst + g) = v;
+        continue;
+      }
+      const float vv[4] = {v.x, v.y, v.z, v.w};
+      if (aligned) {
+        const int g = i * B0 + rho;
+        if (g < N)
+          *reinterpret_cast<float4 *>(dst + g) = make_float4(act(vv[0], g), act(vv[1], g + 1), act(vv[2], g + 2), act(vv[3], g + 3));
+        continue;
+      }
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int g = i * B0 + rho + e;
+        if (rho + e < B0 && g < N) dst[g] = act(vv[e], g);
+      }
     }
   }
 }
