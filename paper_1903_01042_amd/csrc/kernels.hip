@@ -788,7 +788,8 @@ hipError_t launch_finish(float *out, const float *syn, const double *partials, i
 __global__ __launch_bounds__(256) void regen_kernel(RegenArgs g, const DevCode *__restrict__ code,
                                                     const codenet_report *__restrict__ report) {
   __shared__ float coef[CODENET_MAX_L];
-  __shared__ int s_target;
+  __shared__ int src_blk[CODENET_MAX_L];
+  __shared__ int s_target, s_n_src;
   __shared__ unsigned short tile[64][66];
   const int t = threadIdx.x;
   const int slot = blockIdx.z;
@@ -852,9 +853,13 @@ __global__ __launch_bounds__(256) void regen_kernel(RegenArgs g, const DevCode *
         coef[i] = (float)c;
       }
     }
+    int n = 0;
+    for (int i = 0; i < L; ++i)
+      if (coef[i] != 0.f) src_blk[n++] = i;
+    s_n_src = n;
   }
   __syncthreads();
-  const int target = s_target;
+  const int target = s_target, n_src = s_n_src;
   const int B = code->B;
   // tile (r0, c0) of the located block; along the code's axis the block offset is target * B
   const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
@@ -869,11 +874,18 @@ __global__ __launch_bounds__(256) void regen_kernel(RegenArgs g, const DevCode *
     const bool in = r0 + rr < rows && c0 + cc < cols;
     if (in) {
       const float *first = g.W + (long)(g.axis == 0 ? r0 + rr : gr0 + rr) * g.Nc + (g.axis == 0 ? gc0 + cc : c0 + cc);
-      for (int i = 0; i < L; ++i) {
-        const float w = coef[i];
-        if (w == 0.f) continue;
-        const float4 x = *reinterpret_cast<const float4 *>(first + i * blk);
-        v.x = fmaf(w, x.x, v.x); v.y = fmaf(w, x.y, v.y); v.z = fmaf(w, x.z, v.z); v.w = fmaf(w, x.w, v.w);
+      // source blocks (nonzero coefficient) in ascending order, eight loads in flight at a time
+      for (int q0 = 0; q0 < n_src; q0 += 8) {
+        float4 x[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+          if (q0 + u < n_src) x[u] = *reinterpret_cast<const float4 *>(first + src_blk[q0 + u] * blk);
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+          if (q0 + u < n_src) {
+            const float w = coef[src_blk[q0 + u]];
+            v.x = fmaf(w, x[u].x, v.x); v.y = fmaf(w, x[u].y, v.y); v.z = fmaf(w, x[u].z, v.z); v.w = fmaf(w, x[u].w, v.w);
+          }
       }
       *reinterpret_cast<float4 *>(g.W + (long)(gr0 + rr) * g.Nc + gc0 + cc) = v;
     }
@@ -950,11 +962,22 @@ __global__ __launch_bounds__(256) void fault_stats_kernel(FaultBatch fb) {
   const FaultArgs &fa = fb.f[blockIdx.y];
   if (fa.mode != CODENET_NOISE_DENSE_REL) return;
   const long total = (long)fa.n_outer * fa.n_inner;
+  // eight elements of the grid-stride sequence at a time: loads first, then the sum (in order)
   double acc = 0.0;
-  for (long e = (long)blockIdx.x * 256 + threadIdx.x; e < total; e += (long)gridDim.x * 256) {
-    const long o = e / fa.n_inner, in = e % fa.n_inner;
-    const float v = fa.base[o * fa.stride_outer + in];
-    acc += (double)v * (double)v;
+  const long stride = (long)gridDim.x * 256;
+  for (long e0 = (long)blockIdx.x * 256 + threadIdx.x; e0 < total; e0 += 8 * stride) {
+    float v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const long e = e0 + u * stride;
+      v[u] = 0.f;
+      if (e < total) {
+        const long o = e / fa.n_inner, in = e % fa.n_inner;
+        v[u] = fa.base[o * fa.stride_outer + in];
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc += (double)v[u] * (double)v[u];
   }
   __shared__ double red[4];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
