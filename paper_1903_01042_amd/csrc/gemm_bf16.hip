@@ -280,7 +280,7 @@ __global__ __launch_bounds__(256) void gemm2_kernel(Gemm2Args g) {
 
 // ---------------------------------------------------------------------------
 // Product kernel with two wavefronts per SIMD: the same 128 x 128 x 64 slabs and
-// four-stage direct-to-LDS pipeline as gemm2_kernel<2, 2, 4>, but eight
+// direct-to-LDS pipeline as gemm2_kernel<2, 2, 4> (five stages here: all of the LDS), but eight
 // wavefronts of 64 (i) x 32 (j) each.  A wavefront issues in order, so with one
 // wavefront per SIMD its MFMAs stop whenever it waits for LDS or at the barrier;
 // with two, the other one's MFMAs fill those gaps.  The price is 1.5 KB of LDS
@@ -289,11 +289,13 @@ __global__ __launch_bounds__(256) void gemm2_kernel(Gemm2Args g) {
 // Tried and dropped, both slower at 5120 x 512 x 4096: an extra wavefront that touches every
 // line of the slabs ten ahead so that they wait in this XCD's L2 (46 us against 39: the
 // address unit is the busier resource, HBM latency was not the limit), and filling LDS through
-// registers instead of direct-to-LDS loads (47 us).  hipBLASLt's own kernel for this shape
-// (160 x 64 x 128 tiles) takes 32 us.
+// registers instead of direct-to-LDS loads (47 us).  Reading the fragments two k-steps ahead,
+// with the slab barrier moved to mid-slab so that the look-ahead crosses slab boundaries, was
+// slower as well (42 us): the LDS latency is not what the MFMAs wait for.  hipBLASLt's own kernel
+// for this shape (160 x 64 x 128 tiles) takes 32 us.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(512) void gemm3_kernel(Gemm2Args g) {
-  constexpr int NS = 4;
+  constexpr int NS = 5;                       // 5 x 32 KB: all of the LDS; four slabs in flight
   constexpr int STAGE = 256 * 128;            // 128 A rows + 128 B rows of 128 bytes
   extern __shared__ uint4 lds[];
   char *const lds_c = reinterpret_cast<char *>(lds);
@@ -348,7 +350,8 @@ __global__ __launch_bounds__(512) void gemm3_kernel(Gemm2Args g) {
     }
   for (int kt = 0; kt < nk; ++kt) {
     const int later = nk - 1 - kt;
-    if (later >= 2) wait_vm<8>();
+    if (later >= 3) wait_vm<12>();
+    else if (later >= 2) wait_vm<8>();
     else if (later >= 1) wait_vm<4>();
     else wait_vm<0>();
     __builtin_amdgcn_s_barrier();
@@ -1008,7 +1011,7 @@ hipError_t launch_gemm2(Gemm2Args g, int tile, float *workspace, hipStream_t s) 
   {
     const char *env3 = getenv("CODENET_GEMM3");
     if (tile == 1 && g.splits == 1 && !(env3 && env3[0] == '0')) {
-      constexpr int lds = 4 * 256 * 128;
+      constexpr int lds = 5 * 256 * 128;
       static bool attr_done = false;
       e = set_lds(gemm3_kernel, lds, &attr_done);
       if (e != hipSuccess) return e;
