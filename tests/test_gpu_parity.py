@@ -207,6 +207,32 @@ def test_every_error_pattern_on_a_small_grid(m, r, dtype):
     pair.close()
 
 
+def test_largest_parity_count_four_blocks_located_and_regenerated():
+    """The limits of the interface: r = 8 parity blocks, t = 4.  Four erroneous block-rows
+    (systematic and parity) are located and corrected, five are not; four block-rows hit by
+    weight faults are located by the next product and regenerated in one call."""
+    m, r, b = 12, 8, 8
+    P = WL.gaussian_generator(m, r, 12)
+    n_out = n_in = 16 * m
+    pair = Pair(WL.layer_weights(n_out, n_in), P, P, "f32", b)
+    X = WL.normal((b, n_in), 31)
+    rows = [0, 5, 11, m + 3]
+    _, rep, _ = pair.product(FWD, X, [WL.make_fault(FWD, i, 1, 0) for i in rows], check_margins=False)
+    assert rep["verdict"] == CORRECTED and rep["located"] == rows
+    _, rep, _ = pair.product(FWD, X, [WL.make_fault(FWD, i, 1, 1) for i in rows + [7]], check_margins=False)
+    assert rep["verdict"] == UNCORRECTABLE and rep["located"] == []
+    clean = pair.ora.Wt.copy()
+    pair.inject_weights([WL.make_fault(WEIGHT, i, j, 2) for i in rows for j in range(m)])
+    _, rep, res = pair.product(FWD, X, check_margins=False)
+    assert rep["verdict"] == CORRECTED and rep["located"] == rows
+    pair.regenerate(FWD, res)
+    assert rel_fro(pair.ora.Wt, clean) <= 1e-8
+    assert rel_fro(to_np(pair.gpu.export_coded()), clean) <= 1e-4
+    _, rep, _ = pair.product(FWD, X, check_margins=False)
+    assert rep["verdict"] == CLEAN
+    pair.close()
+
+
 # --------------------------------------------------------- multi-step, scaled copies
 @pytest.mark.parametrize("name,block,steps", [("cfg3", 64, 12), ("cfg5", 32, 12), ("cfg4", 32, 8)])
 def test_multi_step_on_a_width_scaled_copy(name, block, steps):
