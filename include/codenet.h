@@ -201,7 +201,9 @@ int codenet_update(codenet_layer *layer, float eta, void *stream);
  * CORRECTED, every stored block of the located block-rows (FWD) or
  * block-columns (BWD) is rebuilt from good blocks of the same grid column
  * (row): the good systematic blocks plus as many good parity blocks as there are
- * located systematic ones.  Any other verdict leaves the matrix untouched.  The
+ * located systematic ones.  Any other verdict, or a located set that does not fit
+ * the code of `phase` (more than r / 2 blocks, an index beyond the grid, a
+ * repeated index), leaves the matrix untouched.  The
  * report is read on the device: the call never synchronises with the host.  In
  * the bf16 mode the bf16 copies of the rebuilt blocks are refreshed as well.
  * The cached vectors [x; x~], [delta; delta~] need no regeneration here: they

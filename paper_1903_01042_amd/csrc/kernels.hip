@@ -795,6 +795,18 @@ __global__ __launch_bounds__(256) void regen_kernel(RegenArgs g, const DevCode *
   const int slot = blockIdx.z;
   if (report->verdict != CODENET_CORRECTED || slot >= report->n_located) return;
   const int a = code->a, r = code->r, L = code->L;
+  // a report that does not fit this code (another phase's, or not a report at all) is ignored:
+  // at most r / 2 distinct block indices below L
+  {
+    const int k = report->n_located;
+    if (k < 1 || k > CODENET_MAX_T || 2 * k > r) return;
+    for (int p = 0; p < k; ++p) {
+      const int i = report->located[p];
+      if (i < 0 || i >= L) return;
+      for (int q = 0; q < p; ++q)
+        if (report->located[q] == i) return;
+    }
+  }
   if (t == 0) {
     const int k = report->n_located;
     bool bad[CODENET_MAX_L];

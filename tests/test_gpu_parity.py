@@ -323,6 +323,14 @@ def test_regeneration_restores_the_stored_code(N_out, N_in, m, n, r, b, dtype, b
             assert rep["verdict"] == CLEAN, rep
         before = pair.gpu.export_coded().clone()
         pair.regenerate(BWD, res)              # verdict CLEAN: nothing to do
+        # a report whose located set does not fit the code is ignored as well
+        from paper_1903_01042_amd import binding as B
+        for located in ([m + n + 2 * r + 5], [0, 0], list(range(r // 2 + 1))):
+            bogus = B.Report(verdict=CORRECTED, n_located=len(located))
+            for q, i in enumerate(located[:4]):
+                bogus.located[q] = i
+            raw = torch.frombuffer(bytearray(bytes(bogus)), dtype=torch.uint8).cuda()
+            pair.gpu.regenerate(FWD, raw)
         torch.cuda.synchronize()
         assert torch.equal(before, pair.gpu.export_coded())
         step += 1
