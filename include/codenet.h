@@ -73,7 +73,8 @@ enum {
 /* Layer description (all host memory, read only during codenet_encode). */
 typedef struct {
   int n_out, n_in;          /* logical shape of W                                              */
-  int m, n;                 /* base node grid (Section "Some Notations")                      */
+  int m, n;                 /* base node grid (Section "Some Notations"); 1 <= m <= n_out,
+                               1 <= n <= n_in, else CODENET_E_SHAPE                         */
   int r_rows, r_cols;       /* parity block-rows / block-columns; the paper uses 2t of each to
                                correct t errors per product (Theorem 1); 0 = uncoded          */
   const double *P_r;        /* m x r_rows, row-major: parity part of G_r = [I | P_r]          */

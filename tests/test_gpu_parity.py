@@ -178,6 +178,47 @@ def test_ragged_shapes(n_out, n_in, m, n, r, b, dtype):
     pair.close()
 
 
+# ------------------------------------------------------------- degenerate grids and sizes
+@pytest.mark.parametrize("n_out,n_in,m,n,r,b,dtype", [
+    (64, 48, 1, 1, 2, 4, "f32"),          # one systematic block per dimension: the code is a repetition-like [1 | P]
+    (5, 6, 4, 4, 2, 2, "f32"),            # blocks of two entries: the last block-row is all padding, the third half
+    (16, 16, 2, 2, 2, 1, "f32"),          # batch of one, as in the paper
+    (260, 260, 2, 2, 2, 300, "bf16"),     # bf16 with a batch above 256 on a grid of two blocks
+])
+def test_degenerate_grids(n_out, n_in, m, n, r, b, dtype):
+    say("degenerate", n_out, n_in, m, n, r, b, dtype)
+    from paper_1903_01042_amd import binding as B
+    P_r, P_c = WL.vandermonde_like(m, r), WL.vandermonde_like(n, r)
+    tau = (1e-3, 1e-2) if dtype == "f32" else (2e-2, 2e-2)
+    pair = Pair(WL.layer_weights(n_out, n_in), P_r, P_c, dtype, b, *tau)
+    pair.check_weights(1e-6)
+    X, D = WL.normal((b, n_in), 41), WL.normal((b, n_out), 42)
+    _, rep, _ = pair.product(FWD, X)
+    assert rep["verdict"] == CLEAN
+    _, rep, _ = pair.product(BWD, D)
+    assert rep["verdict"] == CLEAN
+    pair.update(0.05)
+    pair.check_weights()
+    # a fault on the first block-row (always has real entries) is corrected; one on a block that is
+    # all padding changes nothing
+    _, rep, _ = pair.product(FWD, X, [WL.make_fault(FWD, 0, 0, 1)])
+    assert rep["verdict"] == CORRECTED and rep["located"] == [0]
+    if (m - 1) * -(-n_out // m) >= n_out:       # the last block-row holds no real entry
+        _, rep, _ = pair.product(FWD, X, [WL.make_fault(FWD, m - 1, 0, 2)])
+        assert rep["verdict"] == CLEAN
+        with pytest.raises(B.CodenetError) as e:   # more block-rows than outputs is refused outright
+            B.CodedLayer(pair.dev_tensor(np.zeros((m - 1, n_in))), P_r, P_c, max_batch=b)
+        assert e.value.code == B.E_SHAPE
+    _, rep, _ = pair.product(BWD, D, [WL.make_fault(BWD, 0, n + 1, 3)])
+    assert rep["verdict"] == CORRECTED and rep["located"] == [n + 1]
+    assert rel_fro(to_np(pair.gpu.export_weights()), pair.ora.weights()) < pair.tol
+    # empty calls: no faults is a no-op, a batch of zero is refused
+    pair.gpu.inject([], pair.gpu.forward(pair.dev_tensor(X)))
+    lib, vp = B.load_library(), __import__("ctypes").c_void_p
+    assert lib.codenet_forward(pair.gpu._h, vp(pair.dev_tensor(X).data_ptr()), 0, vp(0), None) in (B.E_BATCH, B.E_NULL)
+    pair.close()
+
+
 # ------------------------------------------------------------ exhaustive campaigns
 @pytest.mark.parametrize("m,r,dtype", [(4, 2, "f32"), (8, 2, "bf16"), (3, 4, "f32")])
 def test_every_error_pattern_on_a_small_grid(m, r, dtype):
