@@ -534,22 +534,26 @@ __global__ __launch_bounds__(256, (FM * FN <= 4 ? 2 : 1)) void update2_kernel(Up
 //    stores, so they never wait for memory.
 // On gfx9 one counter covers loads and stores and stores return out of order:
 // a wavefront that mixes the two can only wait for everything, which is why
-// the roles are split this way.  Tiles are dealt so that the workgroups of one
-// XCD work on an 8 x TJX block of tiles at a time (operand panels of about
-// 1.5 MB stay in that XCD's L2).  Streaming accesses stay ordinary cached ones:
+// the roles are split this way.  Tiles are dealt so that every XCD owns one rectangle of a
+// 2 x 4 partition of the tile grid and needs only the operand panels of that rectangle.  Streaming accesses stay ordinary cached ones:
 // the matrix and its copies largely live in the 256 MB memory-side cache from
 // one step to the next, and non-temporal stores forfeit that (150 us vs 84 us).
 // ---------------------------------------------------------------------------
 struct TileWalk {
-  int tiles_i, tiles_j, tjx, span, total, x, step, q;
+  int tiles_i, tiles_j, tiw, tjh, total, i_base, j_base, step, q;
   bool reverse;
+  // XCD x (workgroup id % 8) owns the rectangle of tiles (x / 4, x % 4) of a 2 x 4 partition and
+  // walks it row by row: the tiw column panels of the rectangle (1.3 MB at 40 x 40 tiles) are in
+  // use all the time and stay in that XCD's L2, the row panels pass through once.
   __device__ void init(int ti, int tj, bool rev = false) {
     reverse = rev;
     tiles_i = ti; tiles_j = tj;
-    tjx = (tj + 7) >> 3;                      // tile rows per XCD
-    span = 8 * tjx;                           // tiles in one block of 8 tile columns
-    total = span * ((ti + 7) >> 3);
-    x = blockIdx.x & 7;
+    tiw = (ti + 3) >> 2;
+    tjh = (tj + 1) >> 1;
+    total = tiw * tjh;
+    const int x = blockIdx.x & 7;
+    i_base = (x & 3) * tiw;
+    j_base = (x >> 2) * tjh;
     step = gridDim.x >> 3;
     q = (int)(blockIdx.x >> 3) - step;
   }
@@ -557,9 +561,8 @@ struct TileWalk {
   __device__ bool next(int &ti, int &tj) {
     for (q += step; q < total; q += step) {
       const int qq = reverse ? total - 1 - q : q;
-      const int blk = qq / span, w = qq % span;
-      ti = 8 * blk + (w & 7);
-      tj = x * tjx + (w >> 3);
+      ti = i_base + qq % tiw;
+      tj = j_base + qq / tiw;
       if (ti < tiles_i && tj < tiles_j) return true;
     }
     return false;
