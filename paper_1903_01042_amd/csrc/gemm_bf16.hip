@@ -537,7 +537,9 @@ __global__ __launch_bounds__(256, (FM * FN <= 4 ? 2 : 1)) void update2_kernel(Up
 // the roles are split this way.  Tiles are dealt so that every XCD owns one rectangle of a
 // 2 x 4 partition of the tile grid and needs only the operand panels of that rectangle.  Streaming accesses stay ordinary cached ones:
 // the matrix and its copies largely live in the 256 MB memory-side cache from
-// one step to the next, and non-temporal stores forfeit that (150 us vs 84 us).
+// one step to the next, and non-temporal stores forfeit that (150 us vs 84 us).  Write-through
+// stores (sc1) keep the operand panels in L2 (operand traffic falls from 95 MB to 43 MB, close
+// to the 31 MB that the partition makes compulsory) but are slower themselves: 100 us.
 // ---------------------------------------------------------------------------
 struct TileWalk {
   int tiles_i, tiles_j, tiw, tjh, total, i_base, j_base, step, q;
