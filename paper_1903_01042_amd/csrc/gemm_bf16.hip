@@ -4,9 +4,10 @@
 // ("shadow" copies of the fp32 coded matrix and of the coded vectors, k padded
 // with zeros to a multiple of 64), fp32 accumulation, fp32 result.
 //
-// What bounds this contraction at the benchmark shape (5120 x 512 x 4096) is not
-// the MFMA rate but how fast operand slabs reach LDS: a 64-deep slab must be in
-// flight for about one HBM latency.  So:
+// At the benchmark shape (5120 x 512 x 4096) the MFMA rate is not the bound: the
+// output is too small for tiles that would take the L2-to-LDS fill off the critical
+// path (160 tiles of 128 x 128 for 256 CUs; the vendor library lands at the same
+// place).  Common to the kernels below:
 //  * slabs go global -> LDS directly (global_load_lds_dwordx4, no VGPR staging),
 //    NS stages deep; a stage is consumed NS-1 iterations after it was requested;
 //  * completion is tracked by hand: s_waitcnt vmcnt(n) leaves the younger
@@ -14,18 +15,17 @@
 //  * fragments are read from LDS with ds_read_b128 issued from inline asm one
 //    k-step ahead of the MFMAs that use them (the compiler would otherwise
 //    drain every outstanding direct-to-LDS load before each LDS read);
-//  * LDS rows are 128 bytes (64 bf16); 16-byte chunk c of row r sits at slot
-//    c ^ (r & 7): fragment reads (32 consecutive rows, one chunk) touch every
-//    bank once; the direct-to-LDS writes are linear per wavefront, and the
-//    swizzle is applied by choosing which global chunk each lane fetches;
-//  * a workgroup (4 wavefronts, 2 x 2) computes a (64 FM) x (64 FN) tile over a
-//    contiguous range of slabs (split-k); with more than one split every split
-//    stores its partial tile to a workspace and a second kernel adds the
-//    partial results in a fixed order (fp32 atomics at L2 were measured to be
-//    several times slower than the whole product, and are order dependent).
+//  * LDS rows are 128 bytes (64 bf16), their 16-byte chunks XOR-swizzled by the
+//    row (swizzle_of_row below) so that fragment reads are free of bank conflicts;
+//    the direct-to-LDS writes are linear per wavefront, and the swizzle is applied
+//    by choosing which global chunk each lane fetches;
 //  * workgroup ids are dealt to the 8 XCDs round-robin by the hardware; the
-//    id -> tile map gives every XCD a contiguous run of tiles so that tiles
-//    sharing an A panel share an L2.
+//    id -> tile maps give every XCD tiles that share operand panels, hence an L2.
+// Kernels: gemm2_kernel (4 wavefronts, templated tile, split-k with an ordered
+// reduction of partial tiles -- fp32 atomics at L2 were several times slower than the
+// whole product and are order dependent), gemm3_kernel (8 wavefronts, the default
+// for the two products), update2_kernel (update, one tile per workgroup),
+// update3_kernel (update, persistent and wave-specialised), shadow_kernel.
 #include "codenet_internal.h"
 
 namespace codenet {
