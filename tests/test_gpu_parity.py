@@ -219,6 +219,34 @@ def test_degenerate_grids(n_out, n_in, m, n, r, b, dtype):
     pair.close()
 
 
+def test_different_parity_counts_for_rows_and_columns():
+    """r_rows = 2 (t = 1 for the forward product), r_cols = 4 (t = 2 for the backward one): each
+    product is held to its own capability."""
+    m, n, b = 4, 3, 12
+    P_r, P_c = WL.vandermonde_like(m, 2), WL.gaussian_generator(n, 4, 21)
+    pair = Pair(WL.layer_weights(96, 90), P_r, P_c, "f32", b)
+    X, D = WL.normal((b, 90), 51), WL.normal((b, 96), 52)
+    _, rep, _ = pair.product(FWD, X, [WL.make_fault(FWD, 2, 0, 0)])
+    assert rep["verdict"] == CORRECTED and rep["located"] == [2]
+    _, rep, _ = pair.product(FWD, X, [WL.make_fault(FWD, 2, 0, 1), WL.make_fault(FWD, 4, 1, 1)])
+    assert rep["verdict"] == UNCORRECTABLE
+    _, rep, res = pair.product(BWD, D, [WL.make_fault(BWD, 0, 1, 2), WL.make_fault(BWD, 1, 5, 2)], check_margins=False)
+    assert rep["verdict"] == CORRECTED and rep["located"] == [1, 5]
+    _, rep, _ = pair.product(BWD, D, [WL.make_fault(BWD, 0, j, 3) for j in (0, 2, 6)], check_margins=False)
+    assert rep["verdict"] == UNCORRECTABLE
+    pair.update(0.03)
+    pair.check_weights()
+    # weight faults in two block-columns: located by the backward product, regenerated along the rows of blocks
+    clean = pair.ora.Wt.copy()
+    pair.inject_weights([WL.make_fault(WEIGHT, i, j, 4) for j in (0, 4) for i in range(m)])
+    _, rep, res = pair.product(BWD, D, check_margins=False)
+    assert rep["verdict"] == CORRECTED and rep["located"] == [0, 4]
+    pair.regenerate(BWD, res)
+    assert rel_fro(pair.ora.Wt, clean) <= 1e-8
+    pair.check_weights(1e-5)
+    pair.close()
+
+
 # ------------------------------------------------------------ exhaustive campaigns
 @pytest.mark.parametrize("m,r,dtype", [(4, 2, "f32"), (8, 2, "bf16"), (3, 4, "f32")])
 def test_every_error_pattern_on_a_small_grid(m, r, dtype):
