@@ -291,7 +291,9 @@ __global__ __launch_bounds__(256) void gemm2_kernel(Gemm2Args g) {
 // address unit is the busier resource, HBM latency was not the limit), and filling LDS through
 // registers instead of direct-to-LDS loads (47 us).  Reading the fragments two k-steps ahead,
 // with the slab barrier moved to mid-slab so that the look-ahead crosses slab boundaries, was
-// slower as well (42 us): the LDS latency is not what the MFMAs wait for.  hipBLASLt's own kernel
+// slower as well (42 us), and so was requesting all four k-steps' fragments right after the
+// barrier (45 us): the LDS latency is not what the MFMAs wait for.  A variant with 160 x 64
+// tiles and five wavefronts (exactly 256 workgroups here) takes the same time as this one.  hipBLASLt's own kernel
 // for this shape (160 x 64 x 128 tiles) takes 32 us.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(512) void gemm3_kernel(Gemm2Args g) {
