@@ -293,8 +293,19 @@ __global__ __launch_bounds__(256) void gemm2_kernel(Gemm2Args g) {
 // with the slab barrier moved to mid-slab so that the look-ahead crosses slab boundaries, was
 // slower as well (42 us), and so was requesting all four k-steps' fragments right after the
 // barrier (45 us): the LDS latency is not what the MFMAs wait for.  A variant with 160 x 64
-// tiles and five wavefronts (exactly 256 workgroups here) takes the same time as this one.  hipBLASLt's own kernel
-// for this shape (160 x 64 x 128 tiles) takes 32 us.
+// tiles and five wavefronts (exactly 256 workgroups here) takes the same time as this one.
+//
+// What the time is made of (ablation builds of a variant with separate loader and MFMA
+// wavefronts, 5120 x 512 x 4096, shader clock 2.05 GHz under this load): launch, barriers and
+// the epilogue's 10.5 MB of stores 7.5 to 11 us; the MFMAs alone 10 to 14 us; the fragment
+// reads alone 6 us; the fill alone 18 us (about 100 GB/s per CU whether the weights come from
+// HBM or, with every tile reading one L2-resident panel, from L2).  On wavefronts that share
+// a SIMD these times add up instead of overlapping: loads + MFMAs take 37, reads + MFMAs 29,
+// all three 42 us, and giving the loads to wavefronts of their own changes nothing (42 us with
+// direct-to-LDS loads, 39 us when the loaders stage through registers), while loaders on two
+// SIMDs and the MFMA wavefronts on the other two do overlap (38 us for MFMAs that alone take
+// 36 us there).  With the sum fixed per tile shape, the shape decides: hipBLASLt's own kernel
+// for this product (160 x 64 x 128 tiles) takes 32 us.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(512) void gemm3_kernel(Gemm2Args g) {
   constexpr int NS = 5;                       // 5 x 32 KB: all of the LDS; four slabs in flight
@@ -394,6 +405,127 @@ __global__ __launch_bounds__(512) void gemm3_kernel(Gemm2Args g) {
         if (j < g.J) g.C[(long)j * g.ldc + i] = acc[a][4 * q + e];
       }
   }
+}
+
+// ---------------------------------------------------------------------------
+// Product kernel with the fill on a SIMD of its own.  Wavefront w of a workgroup runs on SIMD
+// w % 4; on one SIMD the time of the loads, of the fragment reads and of the MFMAs add up (see
+// above), across SIMDs they overlap.  So wavefronts 3 and 7 (SIMD 3) only issue the
+// direct-to-LDS loads and the other six (two on each of SIMDs 0-2) only read fragments and
+// issue MFMAs: a 96 (i) x 128 (j) tile as 3 x 2 wavefronts of 32 x 64, 64-deep slabs of 28 KB,
+// five stages, one barrier per slab for all eight wavefronts.  Three quarters of the MFMA
+// units work, on 216 instead of 160 tiles at 5120 x 512.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(512) void gemm6_kernel(Gemm2Args g) {
+  constexpr int NS = 5;
+  constexpr int A_BYTES = 96 * 128, STAGE = A_BYTES + 128 * 128;
+  extern __shared__ uint4 lds[];
+  char *const lds_c = reinterpret_cast<char *>(lds);
+  const int logical = logical_workgroup(g.tiles_i * g.tiles_j);
+  if (logical < 0) return;
+  const int tj = logical % g.tiles_j, ti = logical / g.tiles_j;
+  const int i0 = ti * 96, j0 = tj * 128;
+  const int nk = g.K >> 6;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, hw = tid >> 6;
+
+  if ((hw & 3) == 3) {
+    // loader lw takes the row groups 2 u + lw of the 28 (12 of A, 16 of B); all of them have
+    // the parity of lw inside their operand, so one swizzle serves the fourteen loads
+    const int lw = hw >> 2;
+    const int lrow = lane >> 3, chunk = (lane & 7) ^ ((4 * lw + (lrow >> 1)) & 7);
+    const __bf16 *src[14];
+#pragma unroll
+    for (int u = 0; u < 14; ++u) {
+      const int grp = 2 * u + lw;
+      if (u < 6) {
+        int row = i0 + 8 * grp + lrow;
+        row = row < g.I ? row : g.I - 1;
+        src[u] = g.A + (long)row * g.lda + chunk * 8;
+      } else {
+        int row = j0 + 8 * (grp - 12) + lrow;
+        row = row < g.J ? row : g.J - 1;
+        src[u] = g.B + (long)row * g.ldb + chunk * 8;
+      }
+    }
+    auto issue = [&](int kt) {
+#if CN_DEVICE_ASM
+      char *stage = lds_c + (kt % NS) * STAGE;
+#pragma unroll
+      for (int u = 0; u < 14; ++u)
+        __builtin_amdgcn_global_load_lds(src[u] + (long)kt * 64, CN_LDS_PTR(stage + (2 * u + lw) * 1024), 16, 0, 0);
+#else
+      (void)kt;
+#endif
+    };
+#pragma unroll
+    for (int s = 0; s < NS - 1; ++s)
+      if (s < nk) issue(s);
+    for (int kt = 0; kt < nk; ++kt) {
+      // slab kt has landed when only the younger slabs' loads are outstanding
+      const int later = nk - 1 - kt;
+      if (later >= 3) wait_vm<42>();
+      else if (later >= 2) wait_vm<28>();
+      else if (later >= 1) wait_vm<14>();
+      else wait_vm<0>();
+      __builtin_amdgcn_s_barrier();
+      // every MFMA wavefront is done with slab kt - 1: its stage takes slab kt + NS - 1
+      if (kt + NS - 1 < nk) issue(kt + NS - 1);
+    }
+    return;
+  }
+
+  const int m = (hw & 3) + 3 * (hw >> 2);     // 0 .. 5
+  const int wi = m % 3, wj = m / 3;           // 3 x 2 wavefronts over (i, j)
+  const int l32 = lane & 31, h = lane >> 5;
+  unsigned offA[4], offB[4];
+#pragma unroll
+  for (int s = 0; s < 4; ++s) {
+    const unsigned slot = (unsigned)(((2 * s + h) ^ swizzle_of_row(l32)) * 16);
+    offA[s] = (unsigned)((wi * 32 + l32) * 128) + slot;
+    offB[s] = (unsigned)(A_BYTES + (wj * 64 + l32) * 128) + slot;
+  }
+  floatx16 acc[2];
+#pragma unroll
+  for (int b = 0; b < 2; ++b)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[b][e] = 0.f;
+
+  for (int kt = 0; kt < nk; ++kt) {
+    __builtin_amdgcn_s_barrier();
+    const unsigned sb = (unsigned)((kt % NS) * STAGE);
+    u32x4 fa[2][1], fb[2][2];
+    read_frags<1>(fa[0], sb + offA[0]);
+    read_frags<2>(fb[0], sb + offB[0]);
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const int cur = s & 1, nxt = cur ^ 1;
+      if (s < 3) {
+        read_frags<1>(fa[nxt], sb + offA[s + 1]);
+        read_frags<2>(fb[nxt], sb + offB[s + 1]);
+        wait_lgkm<3>();
+      } else {
+        wait_lgkm<0>();
+      }
+      pin(fa[cur][0]); pin(fb[cur][0]); pin(fb[cur][1]);
+#pragma unroll
+      for (int b = 0; b < 2; ++b)
+        acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fb[cur][b]),
+                                                         __builtin_bit_cast(bf16x8, fa[cur][0]), acc[b], 0, 0, 0);
+    }
+  }
+  // element 4 q + e of fragment b is (j = 8 q + 4 h + e, i = lane % 32)
+  const int i = i0 + wi * 32 + l32;
+  if (i >= g.I) return;
+#pragma unroll
+  for (int b = 0; b < 2; ++b)
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int j = j0 + (wj * 2 + b) * 32 + 8 * q + 4 * h + e;
+        if (j < g.J) g.C[(long)j * g.ldc + i] = acc[b][4 * q + e];
+      }
 }
 
 // out = sum over splits of the partial results, in split order
@@ -1018,6 +1150,17 @@ hipError_t launch_gemm2(Gemm2Args g, int tile, float *workspace, hipStream_t s) 
   {
     const char *env3 = getenv("CODENET_GEMM3");
     if (tile == 1 && g.splits == 1 && !(env3 && env3[0] == '0')) {
+      if (!(env3 && env3[0] == '3')) {          // CODENET_GEMM3=3: the kernel with mixed roles, for comparison
+        constexpr int lds6 = 5 * (96 + 128) * 128;
+        static bool attr6_done = false;
+        e = set_lds(gemm6_kernel, lds6, &attr6_done);
+        if (e != hipSuccess) return e;
+        g.tiles_i = (g.I + 95) / 96;
+        g.tiles_j = (g.J + 127) / 128;
+        const int total6 = g.tiles_i * g.tiles_j;
+        hipLaunchKernelGGL(gemm6_kernel, dim3((unsigned)(((total6 + 7) / 8) * 8)), dim3(512), lds6, s, g);
+        return hipGetLastError();
+      }
       constexpr int lds = 5 * 256 * 128;
       static bool attr_done = false;
       e = set_lds(gemm3_kernel, lds, &attr_done);
