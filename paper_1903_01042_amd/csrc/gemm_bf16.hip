@@ -4,10 +4,10 @@
 // ("shadow" copies of the fp32 coded matrix and of the coded vectors, k padded
 // with zeros to a multiple of 64), fp32 accumulation, fp32 result.
 //
-// At the benchmark shape (5120 x 512 x 4096) the MFMA rate is not the bound: the
-// output is too small for tiles that would take the L2-to-LDS fill off the critical
-// path (160 tiles of 128 x 128 for 256 CUs; the vendor library lands at the same
-// place).  Common to the kernels below:
+// At the benchmark shape (5120 x 512 x 4096) the MFMA rate is not the bound: per CU the
+// 64 bytes per clock of the global -> LDS fill, the fragment reads and the MFMAs take
+// comparable times, and they only overlap when they run on different SIMDs (see
+// product_kernel).  Common to the kernels below:
 //  * slabs go global -> LDS directly (global_load_lds_dwordx4, no VGPR staging),
 //    NS stages deep; a stage is consumed NS-1 iterations after it was requested;
 //  * completion is tracked by hand: s_waitcnt vmcnt(n) leaves the younger
@@ -23,8 +23,8 @@
 //    id -> tile maps give every XCD tiles that share operand panels, hence an L2.
 // Kernels: gemm2_kernel (4 wavefronts, templated tile, split-k with an ordered
 // reduction of partial tiles -- fp32 atomics at L2 were several times slower than the
-// whole product and are order dependent), gemm3_kernel (8 wavefronts, the default
-// for the two products), update2_kernel (update, one tile per workgroup),
+// whole product and are order dependent), product_kernel (8 wavefronts with separate
+// roles, the default for the two products), update2_kernel (update, one tile per workgroup),
 // update3_kernel (update, persistent and wave-specialised), shadow_kernel.
 #include "codenet_internal.h"
 
@@ -279,144 +279,31 @@ __global__ __launch_bounds__(256) void gemm2_kernel(Gemm2Args g) {
 }
 
 // ---------------------------------------------------------------------------
-// Product kernel with two wavefronts per SIMD: the same 128 x 128 x 64 slabs and
-// direct-to-LDS pipeline as gemm2_kernel<2, 2, 4> (five stages here: all of the LDS), but eight
-// wavefronts of 64 (i) x 32 (j) each.  A wavefront issues in order, so with one
-// wavefront per SIMD its MFMAs stop whenever it waits for LDS or at the barrier;
-// with two, the other one's MFMAs fill those gaps.  The price is 1.5 KB of LDS
-// reads per MFMA instead of 1 KB, still below what the LDS delivers.
+// The product kernel (forward and backward products of the bf16 mode): the fill on a SIMD of
+// its own.  Wavefront w of a workgroup runs on SIMD w % 4.  Wavefronts 3 and 7 (SIMD 3) only
+// issue the direct-to-LDS loads; the other six (two on each of SIMDs 0-2) only read fragments
+// and issue MFMAs: a 96 (i) x 128 (j) tile as 3 x 2 wavefronts of 32 x 64, 64-deep slabs of
+// 28 KB, five stages (four slabs in flight), one barrier per slab for all eight wavefronts.
+// Three quarters of the MFMA units work, on 216 instead of 160 tiles at 5120 x 512.
 //
-// Tried and dropped, both slower at 5120 x 512 x 4096: an extra wavefront that touches every
-// line of the slabs ten ahead so that they wait in this XCD's L2 (46 us against 39: the
-// address unit is the busier resource, HBM latency was not the limit), and filling LDS through
-// registers instead of direct-to-LDS loads (47 us).  Reading the fragments two k-steps ahead,
-// with the slab barrier moved to mid-slab so that the look-ahead crosses slab boundaries, was
-// slower as well (42 us), and so was requesting all four k-steps' fragments right after the
-// barrier (45 us): the LDS latency is not what the MFMAs wait for.  A variant with 160 x 64
-// tiles and five wavefronts (exactly 256 workgroups here) takes the same time as this one.
-//
-// What the time is made of (ablation builds of a variant with separate loader and MFMA
-// wavefronts, 5120 x 512 x 4096, shader clock 2.05 GHz under this load): launch, barriers and
-// the epilogue's 10.5 MB of stores 7.5 to 11 us; the MFMAs alone 10 to 14 us; the fragment
-// reads alone 6 us; the fill alone 18 us (about 100 GB/s per CU whether the weights come from
-// HBM or, with every tile reading one L2-resident panel, from L2).  On wavefronts that share
-// a SIMD these times add up instead of overlapping: loads + MFMAs take 37, reads + MFMAs 29,
-// all three 42 us, and giving the loads to wavefronts of their own changes nothing (42 us with
-// direct-to-LDS loads, 39 us when the loaders stage through registers), while loaders on two
-// SIMDs and the MFMA wavefronts on the other two do overlap (38 us for MFMAs that alone take
-// 36 us there).  With the sum fixed per tile shape, the shape decides: hipBLASLt's own kernel
-// for this product (160 x 64 x 128 tiles) takes 32 us.
+// Why: on wavefronts that share a SIMD the time of the loads, of the fragment reads and of the
+// MFMAs add up instead of overlapping; across SIMDs they overlap.  Measured at
+// 5120 x 512 x 4096 with ablation builds of a 128 x 128 kernel whose four MFMA wavefronts (one
+// per SIMD, 64 x 64 each) and four loader wavefronts are separate (shader clock 2.05 GHz under
+// this load): launch, barriers and the epilogue's 10.5 MB of stores 7.5 to 11 us; MFMAs alone
+// 10 to 14 us; fragment reads alone 6 us; fill alone 18 us, which is the 64 bytes per clock of
+// the CU's vector memory path, whether the weights come from HBM or, with every tile reading
+// one L2-resident panel, from L2.  Loads + MFMAs 37 us, reads + MFMAs 29 us, all three 42 us;
+// the same with the roles mixed in every wavefront (one or two per SIMD: 39 to 42 us), with
+// loaders that stage through registers (39 us), with a sixth wavefront that prefetches into
+// L2 (46 us), with fragments requested one, two or four k-steps ahead (42 to 45 us), and with
+// 160 x 64 tiles on all 256 CUs (41 us).  With the loaders on SIMDs 2 and 3 and the MFMA
+// wavefronts on SIMDs 0 and 1, loads + MFMAs take 38 us where the MFMAs alone take 36: they
+// overlap.  This kernel: 33.6 us (the 128 x 128 kernel with mixed roles: 41.3 us in the same
+// run; 192 x 64 tiles with three MFMA wavefronts of 64 x 64: 36 us; hipBLASLt's kernel for
+// this product, 160 x 64 x 128 tiles: 32 us).
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(512) void gemm3_kernel(Gemm2Args g) {
-  constexpr int NS = 5;                       // 5 x 32 KB: all of the LDS; four slabs in flight
-  constexpr int STAGE = 256 * 128;            // 128 A rows + 128 B rows of 128 bytes
-  extern __shared__ uint4 lds[];
-  char *const lds_c = reinterpret_cast<char *>(lds);
-  const int logical = logical_workgroup(g.tiles_i * g.tiles_j);
-  if (logical < 0) return;
-  const int tj = logical % g.tiles_j, ti = logical / g.tiles_j;
-  const int i0 = ti * 128, j0 = tj * 128;
-  const int nk = g.K >> 6;
-  const int tid = threadIdx.x;
-  const int lane = tid & 63, wave = tid >> 6;
-  const int wi = wave & 1, wj = wave >> 1;    // 2 x 4 wavefronts over (i, j)
-  const int l32 = lane & 31, h = lane >> 5;
-  const int lrow = lane >> 3, chunk = (lane & 7) ^ swizzle_of_row(8 * wave + lrow);
-
-  // loads 0, 1: A rows 8 (8 u + wave) + lane / 8; loads 2, 3: B rows likewise
-  const __bf16 *src[4];
-#pragma unroll
-  for (int u = 0; u < 2; ++u) {
-    int row = i0 + 8 * (8 * u + wave) + lrow;
-    row = row < g.I ? row : g.I - 1;
-    src[u] = g.A + (long)row * g.lda + chunk * 8;
-    row = j0 + 8 * (8 * u + wave) + lrow;
-    row = row < g.J ? row : g.J - 1;
-    src[2 + u] = g.B + (long)row * g.ldb + chunk * 8;
-  }
-  auto issue_one = [&](int kt, int u) {
-#if CN_DEVICE_ASM
-    char *dst = lds_c + (kt % NS) * STAGE + (u < 2 ? 0 : 128 * 128) + (8 * (u & 1) + wave) * 1024;
-    __builtin_amdgcn_global_load_lds(src[u] + (long)kt * 64, CN_LDS_PTR(dst), 16, 0, 0);
-#else
-    (void)kt; (void)u;
-#endif
-  };
-  unsigned offA[4], offB[4];
-#pragma unroll
-  for (int s = 0; s < 4; ++s) {
-    const unsigned slot = (unsigned)(((2 * s + h) ^ swizzle_of_row(l32)) * 16);
-    offA[s] = (unsigned)((wi * 64 + l32) * 128) + slot;
-    offB[s] = (unsigned)(128 * 128 + (wj * 32 + l32) * 128) + slot;
-  }
-  floatx16 acc[2];
-#pragma unroll
-  for (int a = 0; a < 2; ++a)
-#pragma unroll
-    for (int e = 0; e < 16; ++e) acc[a][e] = 0.f;
-
-#pragma unroll
-  for (int s = 0; s < NS - 1; ++s)
-    if (s < nk) {
-#pragma unroll
-      for (int u = 0; u < 4; ++u) issue_one(s, u);
-    }
-  for (int kt = 0; kt < nk; ++kt) {
-    const int later = nk - 1 - kt;
-    if (later >= 3) wait_vm<12>();
-    else if (later >= 2) wait_vm<8>();
-    else if (later >= 1) wait_vm<4>();
-    else wait_vm<0>();
-    __builtin_amdgcn_s_barrier();
-    const bool prefetch = kt + NS - 1 < nk;
-    const unsigned sb = (unsigned)((kt % NS) * STAGE);
-    u32x4 fa[2][2], fb[2][1];
-    read_frags<2>(fa[0], sb + offA[0]);
-    read_frags<1>(fb[0], sb + offB[0]);
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      const int cur = s & 1, nxt = cur ^ 1;
-      if (s < 3) {
-        read_frags<2>(fa[nxt], sb + offA[s + 1]);
-        read_frags<1>(fb[nxt], sb + offB[s + 1]);
-        wait_lgkm<3>();
-      } else {
-        wait_lgkm<0>();
-      }
-      pin(fa[cur][0]); pin(fa[cur][1]); pin(fb[cur][0]);
-      if (prefetch) issue_one(kt + NS - 1, s);
-      __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-      for (int a = 0; a < 2; ++a)
-        acc[a] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fb[cur][0]),
-                                                         __builtin_bit_cast(bf16x8, fa[cur][a]), acc[a], 0, 0, 0);
-    }
-  }
-  // element 4 q + e of fragment a is (j = 8 q + 4 h + e, i = lane % 32)
-#pragma unroll
-  for (int a = 0; a < 2; ++a) {
-    const int i = i0 + (wi * 2 + a) * 32 + l32;
-    if (i >= g.I) continue;
-#pragma unroll
-    for (int q = 0; q < 4; ++q)
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const int j = j0 + wj * 32 + 8 * q + 4 * h + e;
-        if (j < g.J) g.C[(long)j * g.ldc + i] = acc[a][4 * q + e];
-      }
-  }
-}
-
-// ---------------------------------------------------------------------------
-// Product kernel with the fill on a SIMD of its own.  Wavefront w of a workgroup runs on SIMD
-// w % 4; on one SIMD the time of the loads, of the fragment reads and of the MFMAs add up (see
-// above), across SIMDs they overlap.  So wavefronts 3 and 7 (SIMD 3) only issue the
-// direct-to-LDS loads and the other six (two on each of SIMDs 0-2) only read fragments and
-// issue MFMAs: a 96 (i) x 128 (j) tile as 3 x 2 wavefronts of 32 x 64, 64-deep slabs of 28 KB,
-// five stages, one barrier per slab for all eight wavefronts.  Three quarters of the MFMA
-// units work, on 216 instead of 160 tiles at 5120 x 512.
-// ---------------------------------------------------------------------------
-__global__ __launch_bounds__(512) void gemm6_kernel(Gemm2Args g) {
+__global__ __launch_bounds__(512) void product_kernel(Gemm2Args g) {
   constexpr int NS = 5;
   constexpr int A_BYTES = 96 * 128, STAGE = A_BYTES + 128 * 128;
   extern __shared__ uint4 lds[];
@@ -674,6 +561,9 @@ __global__ __launch_bounds__(256, (FM * FN <= 4 ? 2 : 1)) void update2_kernel(Up
 // one step to the next, and non-temporal stores forfeit that (150 us vs 84 us).  Write-through
 // stores (sc1) keep the operand panels in L2 (operand traffic falls from 95 MB to 43 MB, close
 // to the 31 MB that the partition makes compulsory) but are slower themselves: 100 us.
+// Unlike in product_kernel, moving the roles apart by SIMD does not pay here (MMA wavefronts
+// on SIMDs 0 and 1, loaders on 2, storers on 3: 86.5 us against 82.5 us): the MFMAs are the
+// smaller part and the kernel runs at the rate the memory system takes the traffic.
 // ---------------------------------------------------------------------------
 struct TileWalk {
   int tiles_i, tiles_j, tiw, tjh, total, i_base, j_base, step, q;
@@ -1148,27 +1038,17 @@ hipError_t launch_gemm2(Gemm2Args g, int tile, float *workspace, hipStream_t s) 
   }
   hipError_t e;
   {
+    // CODENET_GEMM3=0: the generic kernel below also for this tile, for comparison
     const char *env3 = getenv("CODENET_GEMM3");
     if (tile == 1 && g.splits == 1 && !(env3 && env3[0] == '0')) {
-      if (!(env3 && env3[0] == '3')) {          // CODENET_GEMM3=3: the kernel with mixed roles, for comparison
-        constexpr int lds6 = 5 * (96 + 128) * 128;
-        static bool attr6_done = false;
-        e = set_lds(gemm6_kernel, lds6, &attr6_done);
-        if (e != hipSuccess) return e;
-        g.tiles_i = (g.I + 95) / 96;
-        g.tiles_j = (g.J + 127) / 128;
-        const int total6 = g.tiles_i * g.tiles_j;
-        hipLaunchKernelGGL(gemm6_kernel, dim3((unsigned)(((total6 + 7) / 8) * 8)), dim3(512), lds6, s, g);
-        return hipGetLastError();
-      }
-      constexpr int lds = 5 * 256 * 128;
+      constexpr int lds = 5 * (96 + 128) * 128;
       static bool attr_done = false;
-      e = set_lds(gemm3_kernel, lds, &attr_done);
+      e = set_lds(product_kernel, lds, &attr_done);
       if (e != hipSuccess) return e;
-      g.tiles_i = (g.I + 127) / 128;
+      g.tiles_i = (g.I + 95) / 96;
       g.tiles_j = (g.J + 127) / 128;
       const int total = g.tiles_i * g.tiles_j;
-      hipLaunchKernelGGL(gemm3_kernel, dim3((unsigned)(((total + 7) / 8) * 8)), dim3(512), lds, s, g);
+      hipLaunchKernelGGL(product_kernel, dim3((unsigned)(((total + 7) / 8) * 8)), dim3(512), lds, s, g);
       return hipGetLastError();
     }
   }
