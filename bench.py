@@ -34,7 +34,10 @@ def parse():
     ap.add_argument("--cpu-steps", type=int, default=40, help="oracle layer-steps timed for cpu_baseline (0 = skip)")
     ap.add_argument("--no-faults", action="store_true", help="run the coded path without injecting faults")
     ap.add_argument("--coded-only", action="store_true", help="skip the uncoded baseline and the CPU oracle (profiling runs)")
-    ap.add_argument("--eager", action="store_true", help="launch every call from Python instead of replaying hipGraphs")
+    ap.add_argument("--graph", action="store_true",
+                    help="replay one hipGraph per step instead of launching every call from Python (a kernel node of a "
+                         "graph takes about 3 us longer than the same kernel launched into the stream; the step is not "
+                         "launch bound, so the default is the plain stream)")
     return ap.parse_args()
 
 
@@ -106,7 +109,8 @@ class Runner:
             raise RuntimeError("a codenet call failed in step %d (rc=%d)" % (s, rc))
 
     STAMP_EVERY = 4     # steps whose update kernel is bracketed by two device time stamps
-    EVENT_EVERY = 20    # steps (s % EVENT_EVERY == 10) whose update is launched on its own between two HIP events
+    EVENT_EVERY = 20    # graph replay: steps (s % EVENT_EVERY == 10) whose update is launched on its own between two HIP events
+    EAGER_EVENT_EVERY = 4   # plain stream: steps (s % EAGER_EVENT_EVERY == 2) whose update sits between two HIP events
 
     def update(self, s, stream):
         """The update of step s; on every STAMP_EVERY-th step between two device time stamps."""
@@ -160,19 +164,27 @@ class Runner:
 
         events = {}
 
+        def timed_update(s):
+            ev = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+            ev[0].record()
+            rc = self.lib.codenet_update(self.h, self.eta, stream)
+            ev[1].record()
+            if rc:
+                raise RuntimeError("codenet_update failed (rc=%d)" % rc)
+            if s >= warmup:
+                events[s] = ev
+
         def one(s):
             if eager:
                 self.pre_update(s, stream)
-                self.update(s, stream)
+                if s % self.EAGER_EVENT_EVERY == 2:
+                    timed_update(s)
+                elif self.lib.codenet_update(self.h, self.eta, stream):
+                    raise RuntimeError("codenet_update failed")
                 return
             self.graphs[s].replay()
             if self.split(s):
-                ev = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-                ev[0].record()
-                self.lib.codenet_update(self.h, self.eta, stream)
-                ev[1].record()
-                if s >= warmup:
-                    events[s] = ev
+                timed_update(s)
 
         for s in range(warmup):
             one(s)
@@ -184,7 +196,7 @@ class Runner:
         t1 = time.perf_counter()
         st = self.stamps[warmup:].cpu().numpy()
         st = st[st[:, 0] != 0]
-        upd_ms = float(np.mean(st[:, 1] - st[:, 0])) / self.ticks_per_us.value * 1e-3
+        upd_ms = float(np.mean(st[:, 1] - st[:, 0])) / self.ticks_per_us.value * 1e-3 if len(st) else None
         self.upd_ms_events = float(np.mean([a.elapsed_time(b) for a, b in events.values()])) if events else None
         return (t1 - t0) * 1e3 / steps, upd_ms
 
@@ -304,7 +316,7 @@ def main():
     total = args.steps + args.warmup
 
     coded = Runner(wl, True, not args.no_faults, total)
-    ms_coded, upd_ms = coded.run(args.steps, args.warmup, args.eager)
+    ms_coded, upd_ms = coded.run(args.steps, args.warmup, not args.graph)
     counts = coded.verdict_counts(args.warmup, total)
     if args.coded_only:
         # a plain device-to-device copy of known size (the coded matrix) next to the kernels:
@@ -312,11 +324,11 @@ def main():
         for _ in range(3):
             coded.layer.export_coded()
         torch.cuda.synchronize()
-        print(json.dumps({"ms_per_step": ms_coded, "update_kernel_ms": upd_ms, "verdicts": counts, "workload": wl.name,
+        print(json.dumps({"ms_per_step": ms_coded, "update_kernel_ms": upd_ms if args.graph else coded.upd_ms_events, "verdicts": counts, "workload": wl.name,
                           "calibration_copy_bytes": coded.weight_bytes}))
         return
     uncoded = Runner(wl, False, False, total)
-    ms_uncoded, upd_ms_unc = uncoded.run(args.steps, args.warmup, args.eager)
+    ms_uncoded, upd_ms_unc = uncoded.run(args.steps, args.warmup, not args.graph)
 
     L = coded.layer
     upd_events_ms = coded.update_by_events()
@@ -330,9 +342,8 @@ def main():
     upd_bytes = 2.0 * coded.weight_bytes + elem * coded.b * (L.coded_rows + L.coded_cols)
     if wl.dtype == "bf16":
         upd_bytes += coded.weight_bytes
-    # kernel duration: HIP events around the kernel on the sampled steps of the timed region where it is
-    # launched on its own (eager runs have none: the in-stream time stamps serve there)
-    launch_ms = coded.upd_ms_events if coded.upd_ms_events is not None else upd_ms
+    # kernel duration: HIP events around the kernel, on its stream, on sampled steps of the timed region
+    launch_ms = coded.upd_ms_events
     achieved = upd_bytes / (launch_ms * 1e-3) / 1e9
     out = {
         "metric": "coded layer-steps/s (fwd+bwd+detect/decode+update)",
@@ -344,25 +355,28 @@ def main():
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": wl.name, "layer": "%dx%d" % (wl.widths[1], wl.widths[0]),
                    "grid": "%dx%d+%d" % (m, n, wl.r), "batch": wl.batch, "fault_law": wl.fault_law,
-                   "launch": "eager, one stream" if args.eager else "hipGraph replay, one graph per step, one stream"},
+                   "launch": "hipGraph replay, one graph per step, one stream" if args.graph
+                   else "every call launched into one stream"},
         "tflops": flops_step / (ms_coded * 1e-3) / 1e12,
         "mfma_frac_of_peak_whole_step": flops_step / (ms_coded * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS[wl.dtype],
         "uncoded_ms_per_step": ms_uncoded,
         "coding_overhead": ms_coded / ms_uncoded - 1.0,
         "algorithmic_overhead_floor": floor,
         "verdicts": counts,
-        "update_kernel_ms_uncoded": upd_ms_unc,
+        "update_kernel_ms_uncoded": upd_ms_unc if args.graph else uncoded.upd_ms_events,
         "roofline": {"kernel": "update3_kernel (W~ += eta [d;d~][x;x~]^T, fp32 RMW + bf16 operand copies)"
                      if wl.dtype == "bf16" else "gemm_kernel (update, W~ += eta [d;d~][x;x~]^T)", "bound": "hbm",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(args.workload),
                      "avg_launch_ms": launch_ms,
-                     "avg_launch_ms_by": "HIP events around the kernel on every %d-th step of the timed region, "
-                     "where the step's graph ends before the update and the kernel is launched on its own"
-                     % Runner.EVENT_EVERY,
+                     "avg_launch_ms_by": ("HIP events around the kernel on every %d-th step of the timed region, "
+                                          "where the step's graph ends before the update and the kernel is launched "
+                                          "on its own" % Runner.EVENT_EVERY) if args.graph else
+                     ("HIP events around the kernel, on its stream, on every %d-th step of the timed region"
+                      % Runner.EAGER_EVENT_EVERY),
                      "in_graph_ms": upd_ms,
-                     "in_graph_ms_by": "device time stamps before and after the kernel inside the graph of every "
-                     "%d-th step of the timed region" % Runner.STAMP_EVERY,
+                     "in_graph_ms_by": ("device time stamps before and after the kernel inside the graph of every "
+                                        "%d-th step of the timed region" % Runner.STAMP_EVERY) if args.graph else None,
                      "back_to_back_ms_hip_events": upd_events_ms,
                      "algorithmic_bytes": upd_bytes,
                      "tflops": coded.flops["upd"] / (launch_ms * 1e-3) / 1e12},

@@ -190,8 +190,9 @@ int codenet_encode(const codenet_desc *d, const float *W_dev, void *stream, code
   const char *what = "hipMalloc";
   auto alloc = [&](void **p, size_t bytes) { if (e == hipSuccess) e = hipMalloc(p, bytes ? bytes : 16); };
   alloc((void **)&l->Wt, sizeof(float) * (size_t)l->Mr * l->Nc);
-  alloc((void **)&l->Xt, sizeof(float) * mb * l->Nc);
-  alloc((void **)&l->Dt, sizeof(float) * mb * l->Mr);
+  // fp32 coded vectors [x; x~], [delta; delta~]: operands of the f32 kernels only
+  alloc((void **)&l->Xt, l->bf16 ? 0 : sizeof(float) * mb * l->Nc);
+  alloc((void **)&l->Dt, l->bf16 ? 0 : sizeof(float) * mb * l->Mr);
   alloc((void **)&l->syn, sizeof(float) * (size_t)rmax * mb * bmax);
   alloc((void **)&l->partials, sizeof(double) * (size_t)kDetectParts * kMaxEntries);
   alloc((void **)&l->fault_partials, sizeof(double) * (size_t)CODENET_MAX_FAULTS * kFaultParts);
@@ -273,8 +274,8 @@ int codenet_forward(codenet_layer *l, const float *X_dev, int b, float *S_coded_
   if (l->bf16) {
     int tile = 0, splits = 1;
     plan_gemm2(l->Mr, b, l->KpX, kMaxSplits, &tile, &splits);
-    // coded input: fp32, batch-major bf16 (product operand) and feature-major bf16 [x; x~] (update operand)
-    CN_HIP(launch_encode_vector_bf16(X_dev, l->Xt, l->code_c_dev, l->code_c, b, l->Xb, l->ldXb, l->XTb, l->ldT, s));
+    // coded input: batch-major bf16 x (product operand) and feature-major bf16 [x; x~] (update operand)
+    CN_HIP(launch_encode_vector_bf16(X_dev, l->code_c_dev, l->code_c, b, l->Xb, l->ldXb, l->XTb, l->ldT, s));
     Gemm2Args g2{};
     g2.A = l->Wb; g2.lda = l->ldWb;
     g2.B = l->Xb; g2.ldb = l->ldXb;
@@ -304,7 +305,7 @@ int codenet_backward(codenet_layer *l, const float *D_dev, int b, float *C_coded
   if (l->bf16) {
     int tile = 0, splits = 1;
     plan_gemm2(l->Nc, b, l->KpD, kMaxSplits, &tile, &splits);
-    CN_HIP(launch_encode_vector_bf16(D_dev, l->Dt, l->code_r_dev, l->code_r, b, l->Db, l->ldDb, l->DTb, l->ldT, s));
+    CN_HIP(launch_encode_vector_bf16(D_dev, l->code_r_dev, l->code_r, b, l->Db, l->ldDb, l->DTb, l->ldT, s));
     Gemm2Args g2{};
     g2.A = l->WTb; g2.lda = l->ldWTb;
     g2.B = l->Db; g2.ldb = l->ldDb;

@@ -107,7 +107,7 @@ hipError_t launch_encode_matrix(const float *W, float *Wt, const DevCode *code_r
 // zero (optional): zero_count4 float4 of a buffer to clear in the same pass.
 hipError_t launch_encode_vector(const float *V, float *Vt, const DevCode *code_dev, const DevCode &code_host,
                                 int b, void *Vb, long ldVb, float *zero, long zero_count4, hipStream_t s);
-hipError_t launch_encode_vector_bf16(const float *V, float *Vt, const DevCode *code_dev, const DevCode &code_host,
+hipError_t launch_encode_vector_bf16(const float *V, const DevCode *code_dev, const DevCode &code_host,
                                      int b, void *Vb, long ldVb, void *VTb, long ldVT, hipStream_t s);
 hipError_t launch_detect(const float *out, float *syn, double *partials, int *n_parts,
                          const DevCode *code_dev, const DevCode &code_host, int b, hipStream_t s);

@@ -160,12 +160,13 @@ struct Geometry { int B, B0, a, r, L, N; };
 static inline Geometry geometry_of(const DevCode &c) { return Geometry{c.B, c.B0, c.a, c.r, c.L, c.N}; }
 
 // The same encoding for the bf16 mode, one 64 (batch) x 64 (positions) tile of one
-// output block per workgroup: besides the fp32 coded vector it writes the two bf16
-// copies that the MFMA kernels read, the batch-major one (operand of the product)
-// and, through an LDS transposition, the feature-major one (operand of the update);
+// output block per workgroup.  It writes the two bf16 arrays that the MFMA kernels
+// read (nothing in this mode reads an fp32 coded vector, so none is written): the
+// batch-major systematic part (operand of the product) and, through an LDS
+// transposition, the feature-major coded vector (operand of the update);
 // batch columns b .. Rpad-1 of the latter are written as zeros.  Jobs 0 .. a-1 copy
 // a systematic block, job a + k computes parity block k.
-__global__ __launch_bounds__(256) void encode_vector_bf16_kernel(const float *__restrict__ V, float *__restrict__ Vt,
+__global__ __launch_bounds__(256) void encode_vector_bf16_kernel(const float *__restrict__ V,
                                                                  const DevCode *__restrict__ code, int b,
                                                                  __bf16 *__restrict__ Vb, long ldVb,
                                                                  __bf16 *__restrict__ VTb, long ldVT, int Rpad,
@@ -227,9 +228,6 @@ __global__ __launch_bounds__(256) void encode_vector_bf16_kernel(const float *__
 #pragma unroll
   for (int p = 0; p < 4; ++p) {
     const int rr = (t >> 4) + 16 * p, beta = beta0 + rr;
-    if (beta < b && rho < B)
-      *reinterpret_cast<float4 *>(Vt + (long)beta * (a + r) * B + (long)job * B + rho) =
-          make_float4(v[p][0], v[p][1], v[p][2], v[p][3]);
     const __bf16 b0 = (__bf16)v[p][0], b1 = (__bf16)v[p][1], b2 = (__bf16)v[p][2], b3 = (__bf16)v[p][3];
     const unsigned short u0 = __builtin_bit_cast(unsigned short, b0), u1 = __builtin_bit_cast(unsigned short, b1),
                          u2 = __builtin_bit_cast(unsigned short, b2), u3 = __builtin_bit_cast(unsigned short, b3);
@@ -255,12 +253,12 @@ __global__ __launch_bounds__(256) void encode_vector_bf16_kernel(const float *__
   }
 }
 
-hipError_t launch_encode_vector_bf16(const float *V, float *Vt, const DevCode *code_dev, const DevCode &code_host,
+hipError_t launch_encode_vector_bf16(const float *V, const DevCode *code_dev, const DevCode &code_host,
                                      int b, void *Vb, long ldVb, void *VTb, long ldVT, hipStream_t s) {
   const int Rpad = (b + 63) & ~63;
   dim3 grid((unsigned)((code_host.B + 63) / 64), (unsigned)(Rpad / 64), (unsigned)(code_host.a + code_host.r));
   const int aligned = (code_host.N % 4 == 0) && (code_host.B0 % 4 == 0) && ((reinterpret_cast<uintptr_t>(V) & 15) == 0);
-  hipLaunchKernelGGL(encode_vector_bf16_kernel, grid, dim3(256), 0, s, V, Vt, code_dev, b, (__bf16 *)Vb, ldVb,
+  hipLaunchKernelGGL(encode_vector_bf16_kernel, grid, dim3(256), 0, s, V, code_dev, b, (__bf16 *)Vb, ldVb,
                      (__bf16 *)VTb, ldVT, Rpad, aligned, geometry_of(code_host));
   return hipGetLastError();
 }
