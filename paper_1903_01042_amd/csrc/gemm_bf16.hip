@@ -716,23 +716,29 @@ __global__ __launch_bounds__(512) void update3_kernel(Update2Args g) {
       // end of the tile: the loaders' fp32 tile is in; add eta * acc in place.  Elements
       // 4 q .. 4 q + 3 of fragment (a, b) are j = 8 q + 4 h .. + 3 of column i = lane % 32.
       lds_barrier();
+      // all sixteen reads first: read, add, write one piece at a time is sixteen LDS round trips
+      // in a row (the compiler keeps their order: it cannot tell that the pieces are distinct)
+      f32x4 w[2][2][4];
 #pragma unroll
       for (int a = 0; a < 2; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b) {
-          const int il = (wi * 2 + a) * 32 + l32;
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+          for (int q = 0; q < 4; ++q)
+            w[a][b][q] = *reinterpret_cast<const f32x4 *>(cell((wi * 2 + a) * 32 + l32, (wj * 2 + b) * 32 + 8 * q + 4 * h));
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
 #pragma unroll
           for (int q = 0; q < 4; ++q) {
-            f32x4 *p = reinterpret_cast<f32x4 *>(cell(il, (wj * 2 + b) * 32 + 8 * q + 4 * h));
-            f32x4 w = *p;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-              w[e] += g.eta * acc[a][b][4 * q + e];
+              w[a][b][q][e] += g.eta * acc[a][b][4 * q + e];
               acc[a][b][4 * q + e] = 0.f;
             }
-            *p = w;
+            *reinterpret_cast<f32x4 *>(cell((wi * 2 + a) * 32 + l32, (wj * 2 + b) * 32 + 8 * q + 4 * h)) = w[a][b][q];
           }
-        }
       if (!more) break;
       ti = nti; tj = ntj;
       more = walk.next(nti, ntj);
@@ -743,10 +749,15 @@ __global__ __launch_bounds__(512) void update3_kernel(Update2Args g) {
   }
 
   // Schedule of the other two roles inside a tile period (barriers B0 .. B(KS-1), then
-  // the end-of-tile barrier).  With 8 slabs or more: the storers empty the tile buffer
-  // in four quarters after B0 .. B3 and the loaders refill it in four groups after
-  // B4 .. B7; with fewer slabs the quarters pair up after B0, B1 and the groups after
-  // B2, B3.  No piece is long enough to hold the MMA wavefronts up at the next barrier.
+  // the end-of-tile barrier).  With 8 slabs or more the storers empty the tile buffer in six
+  // pieces after B0 .. B5: the two row quarters as two halves each (they gather their rows
+  // from the transposed tile and take twice a slab of the MMA role: as whole quarters they
+  // made the MMA wavefronts wait 1900 clocks at each of the next barriers), then the two
+  // quarters of the transposed copy; the loaders refill it with two groups after B6 and two
+  // after B7.  (Transposed quarters first and a loader group beside each of the last row
+  // pieces, which the row ranges allow, was slower: a storer piece and a loader group in one
+  // interval stretch it, the MMA wavefronts' own slab included.)  With fewer slabs the
+  // quarters pair up after B0, B1 and the groups after B2, B3.
   const bool wide = KS >= 8;
 
   if (wave < 6) {
@@ -807,13 +818,26 @@ __global__ __launch_bounds__(512) void update3_kernel(Update2Args g) {
     for (int gq = 0; gq < 4; ++gq) request_group(gq, ti, tj);
     bool have = true;
     while (have) {
-      for (int e = wide ? 5 : 3; e > 0; --e) lds_barrier();
+      for (int e = wide ? 7 : 3; e > 0; --e) lds_barrier();
       have = walk.next(ti, tj);
+      // Two copies of the sequence, with and without the requests for the next tile: with the
+      // requests under a condition of their own, the compiler's count of the loads in flight
+      // has to assume the smaller number at every join, and the last group then waits for
+      // vmcnt(0), i.e. for the requests issued a moment ago (a full HBM latency at the
+      // end-of-tile barrier, where the MMA wavefronts wait for this role).
+      if (have) {
 #pragma unroll
-      for (int gq = 0; gq < 4; ++gq) {
-        if (gq > 0 && (wide || gq == 2)) lds_barrier();
-        write_group(gq);
-        if (have) request_group(gq, ti, tj);
+        for (int gq = 0; gq < 4; ++gq) {
+          if (gq == 2) lds_barrier();
+          write_group(gq);
+          request_group(gq, ti, tj);
+        }
+      } else {
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq) {
+          if (gq == 2) lds_barrier();
+          write_group(gq);
+        }
       }
       for (int e = KS - (wide ? 8 : 4); e > 0; --e) lds_barrier();
       lds_barrier();                                      // end of the tile
@@ -837,7 +861,8 @@ __global__ __launch_bounds__(512) void update3_kernel(Update2Args g) {
   // quarters 2, 3: transposed copy; item k is row i = 8 k + v / 16, columns j = 8 (v % 16) .. + 7
   char *const rowB = lds_c + TILE + (v >> 4) * 512;
   int baseB = ((2 * (v & 15)) ^ (v >> 4)) << 4;
-  auto quarter = [&](int qt) {
+  // hsel: -1 the whole quarter, 0 / 1 one half of quarters 0 and 1 (four of their eight row groups)
+  auto quarter = [&](int qt, int hsel = -1) {
     if (DBG & 513) return;
     if ((DBG & 1024) && qt < 2) return;
     if ((DBG & 2048) && qt >= 2) return;
@@ -855,6 +880,7 @@ __global__ __launch_bounds__(512) void update3_kernel(Update2Args g) {
       if (interior) {
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
+          if (hsel >= 0 && half != hsel) continue;
           float c[4][8];
 #pragma unroll
           for (int k4 = 0; k4 < 4; ++k4)
@@ -876,7 +902,7 @@ __global__ __launch_bounds__(512) void update3_kernel(Update2Args g) {
         return;
       }
 #pragma unroll 2
-      for (int k8 = 0; k8 < 8; ++k8) {
+      for (int k8 = (hsel == 1 ? 4 : 0); k8 < (hsel == 0 ? 4 : 8); ++k8) {
         const int k = qt * 8 + k8;
         float c[8];
 #pragma unroll
@@ -937,15 +963,28 @@ __global__ __launch_bounds__(512) void update3_kernel(Update2Args g) {
   };
   bool have_prev = false, more = true;
   while (more) {
-    lds_barrier();
-    if (have_prev) quarter(0);
-    if (wide) lds_barrier();
-    if (have_prev) quarter(1);
-    lds_barrier();
-    if (have_prev) quarter(2);
-    if (wide) lds_barrier();
-    if (have_prev) quarter(3);
-    for (int e = KS - (wide ? 4 : 2); e > 0; --e) lds_barrier();
+    if (wide) {
+      // the row quarters take twice as long as a slab of the MMA role: half a quarter per barrier
+      lds_barrier();
+      if (have_prev) quarter(0, 0);
+      lds_barrier();
+      if (have_prev) quarter(0, 1);
+      lds_barrier();
+      if (have_prev) quarter(1, 0);
+      lds_barrier();
+      if (have_prev) quarter(1, 1);
+      lds_barrier();
+      if (have_prev) quarter(2);
+      lds_barrier();
+      if (have_prev) quarter(3);
+      for (int e = KS - 6; e > 0; --e) lds_barrier();
+    } else {
+      lds_barrier();
+      if (have_prev) { quarter(0); quarter(1); }
+      lds_barrier();
+      if (have_prev) { quarter(2); quarter(3); }
+      for (int e = KS - 2; e > 0; --e) lds_barrier();
+    }
     lds_barrier();                                        // end of the tile
     pti = ti; ptj = tj;
     have_prev = true;

@@ -202,13 +202,14 @@ __global__ __launch_bounds__(256) void encode_vector_bf16_kernel(const float *__
       if (beta < b && rho < B) fetch(V + (long)beta * N, job, v[p]);
     }
   } else {
-    // parity block k = sum_i H[k][i] block_i, i ascending; the loads of four blocks x four rows are
-    // issued together (one block at a time would expose a load latency per block)
+    // parity block k = sum_i H[k][i] block_i, i ascending; the loads of eight blocks x four rows are
+    // issued together (one block at a time would expose a load latency per block; at 8 blocks the
+    // whole job has one)
     const int k = job - a;
-    for (int i0 = 0; i0 < a; i0 += 4) {
-      float x[4][4][4];
+    for (int i0 = 0; i0 < a; i0 += 8) {
+      float x[8][4][4];
 #pragma unroll
-      for (int u = 0; u < 4; ++u)
+      for (int u = 0; u < 8; ++u)
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
           const int beta = beta0 + (t >> 4) + 16 * p;
@@ -216,7 +217,7 @@ __global__ __launch_bounds__(256) void encode_vector_bf16_kernel(const float *__
           if (i0 + u < a && beta < b && rho < B) fetch(V + (long)beta * N, i0 + u, x[u][p]);
         }
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
+      for (int u = 0; u < 8; ++u) {
         const float h = i0 + u < a ? code->Hf[k][i0 + u] : 0.f;
 #pragma unroll
         for (int p = 0; p < 4; ++p)
