@@ -329,6 +329,12 @@ def main():
         return
     uncoded = Runner(wl, False, False, total)
     ms_uncoded, upd_ms_unc = uncoded.run(args.steps, args.warmup, not args.graph)
+    ms_clean = None
+    if not args.no_faults:
+        # the coded path without the injection kernels (scaffolding of the experiment, not of the method)
+        clean = Runner(wl, True, False, total)
+        ms_clean, _ = clean.run(args.steps, args.warmup, not args.graph)
+        clean.layer.destroy()
 
     L = coded.layer
     upd_events_ms = coded.update_by_events()
@@ -361,6 +367,8 @@ def main():
         "mfma_frac_of_peak_whole_step": flops_step / (ms_coded * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS[wl.dtype],
         "uncoded_ms_per_step": ms_uncoded,
         "coding_overhead": ms_coded / ms_uncoded - 1.0,
+        "ms_per_step_without_injection": ms_clean,
+        "coding_overhead_without_injection": (ms_clean / ms_uncoded - 1.0) if ms_clean else None,
         "algorithmic_overhead_floor": floor,
         "verdicts": counts,
         "update_kernel_ms_uncoded": upd_ms_unc if args.graph else uncoded.upd_ms_events,
