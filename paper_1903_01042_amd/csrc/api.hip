@@ -212,7 +212,9 @@ int codenet_encode(const codenet_desc *d, const float *W_dev, void *stream, code
     l->KpD = (int)up64((long)l->code_r.a * l->code_r.B);
     l->ldXb = pitch(l->KpX);
     l->ldDb = pitch(l->KpD);
-    const size_t szWb = 2 * (size_t)l->Mr * l->ldWb, szWTb = 2 * (size_t)l->Nc * l->ldWTb;
+    // the backward product reads rows 0 .. KpD - 1 of the row-major copy: with no parity rows the 64-padding
+    // of the contraction can reach past the matrix, so the copy has that many rows (the extra ones stay zero)
+    const size_t szWb = 2 * (size_t)std::max(l->Mr, l->KpD) * l->ldWb, szWTb = 2 * (size_t)l->Nc * l->ldWTb;
     const size_t szXb = 2 * mb * l->ldXb, szDb = 2 * mb * l->ldDb;
     l->bpad = (int)up64((long)mb);
     l->ldT = pitch(l->bpad);
@@ -308,6 +310,8 @@ int codenet_backward(codenet_layer *l, const float *D_dev, int b, float *C_coded
     CN_HIP(launch_encode_vector_bf16(D_dev, l->code_r_dev, l->code_r, b, l->Db, l->ldDb, l->DTb, l->ldT, s));
     Gemm2Args g2{};
     g2.A = l->WTb; g2.lda = l->ldWTb;
+    const char *tr = getenv("CODENET_BWD_TR");
+    if (tr && tr[0] == '1' && tile == 1 && splits == 1) { g2.A = l->Wb; g2.lda = l->ldWb; g2.a_k_major = 1; }
     g2.B = l->Db; g2.ldb = l->ldDb;
     g2.C = C_coded_dev; g2.ldc = l->Nc;
     g2.I = l->Nc; g2.J = b; g2.K = l->KpD; g2.splits = splits;

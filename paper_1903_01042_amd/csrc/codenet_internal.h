@@ -53,6 +53,7 @@ struct Gemm2Args {
   int I, J, K;
   int tiles_i, tiles_j, splits;
   long split_stride;
+  int a_k_major;                 // A is stored A[k][i], i contiguous (product_kernel only)
 };
 struct Update2Args {
   const __bf16 *XT; long ldx;    // [I = coded columns][batch padded to 64]

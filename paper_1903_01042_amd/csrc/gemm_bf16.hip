@@ -34,6 +34,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 #define CN_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
 
@@ -63,6 +64,20 @@ __device__ __forceinline__ void read_frags(u32x4 (&f)[N], unsigned addr) {
   if constexpr (N > 3) f[3] = lds_read16<12288>(addr);
 }
 
+// Transposing LDS read of gfx950 (16-bit elements): in every group of 16 lanes, lane s points at
+// four consecutive elements, columns 4 (s % 4) .. + 3 of row s / 4 of a 4 x 16 block, and lane n
+// receives column n of that block, rows 0 .. 3 (checked on the device with an index pattern).
+template <int OFF>
+__device__ __forceinline__ u32x2 lds_read_tr8(unsigned addr) {
+  u32x2 v;
+#if CN_DEVICE_ASM
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+#else
+  v = u32x2{addr, 0u};
+#endif
+  return v;
+}
+
 template <int N>
 __device__ __forceinline__ void wait_lgkm() {
 #if CN_DEVICE_ASM
@@ -84,6 +99,11 @@ __device__ __forceinline__ void lds_barrier() {
 }
 // orders the consumers of v after every asm statement issued before this one
 __device__ __forceinline__ void pin(u32x4 &v) {
+#if CN_DEVICE_ASM
+  asm volatile("" : "+v"(v));
+#endif
+}
+__device__ __forceinline__ void pin(u32x2 &v) {
 #if CN_DEVICE_ASM
   asm volatile("" : "+v"(v));
 #endif
@@ -303,6 +323,11 @@ __global__ __launch_bounds__(256) void gemm2_kernel(Gemm2Args g) {
 // run; 192 x 64 tiles with three MFMA wavefronts of 64 x 64: 36 us; hipBLASLt's kernel for
 // this product, 160 x 64 x 128 tiles: 32 us).
 // ---------------------------------------------------------------------------
+// AT: the A operand is stored k-major, A[k][i] with i contiguous (the row-major bf16 copy of the
+// coded matrix seen from the backward product).  Its slab then sits in LDS as 64 rows (k) of
+// 96 elements, filled by the same direct-to-LDS loads, and the MFMA wavefronts fetch their
+// fragments with the transposing LDS read: two 8-byte reads per fragment instead of one of 16.
+template <bool AT>
 __global__ __launch_bounds__(512) void product_kernel(Gemm2Args g) {
   constexpr int NS = 5;
   constexpr int A_BYTES = 96 * 128, STAGE = A_BYTES + 128 * 128;
@@ -326,9 +351,17 @@ __global__ __launch_bounds__(512) void product_kernel(Gemm2Args g) {
     for (int u = 0; u < 14; ++u) {
       const int grp = 2 * u + lw;
       if (u < 6) {
-        int row = i0 + 8 * grp + lrow;
-        row = row < g.I ? row : g.I - 1;
-        src[u] = g.A + (long)row * g.lda + chunk * 8;
+        if (AT) {
+          // load grp fills bytes 1024 grp .. + 1023 of the slab: rows of 192 bytes
+          const int o = 1024 * grp + 16 * lane;
+          int col = i0 + (o % 192) / 2;
+          col = col + 8 <= (int)g.lda ? col : (int)g.lda - 8;    // stay inside the row; such columns are never stored
+          src[u] = g.A + (long)(o / 192) * g.lda + col;
+        } else {
+          int row = i0 + 8 * grp + lrow;
+          row = row < g.I ? row : g.I - 1;
+          src[u] = g.A + (long)row * g.lda + chunk * 8;
+        }
       } else {
         int row = j0 + 8 * (grp - 12) + lrow;
         row = row < g.J ? row : g.J - 1;
@@ -340,7 +373,8 @@ __global__ __launch_bounds__(512) void product_kernel(Gemm2Args g) {
       char *stage = lds_c + (kt % NS) * STAGE;
 #pragma unroll
       for (int u = 0; u < 14; ++u)
-        __builtin_amdgcn_global_load_lds(src[u] + (long)kt * 64, CN_LDS_PTR(stage + (2 * u + lw) * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(src[u] + ((AT && u < 6) ? (long)kt * 64 * g.lda : (long)kt * 64),
+                                         CN_LDS_PTR(stage + (2 * u + lw) * 1024), 16, 0, 0);
 #else
       (void)kt;
 #endif
@@ -372,6 +406,22 @@ __global__ __launch_bounds__(512) void product_kernel(Gemm2Args g) {
     offA[s] = (unsigned)((wi * 32 + l32) * 128) + slot;
     offB[s] = (unsigned)(A_BYTES + (wj * 64 + l32) * 128) + slot;
   }
+  // AT: lane's row of the 4 x 16 block that its group of 16 lanes reads: k = 8 h + (lane % 16) / 4 (+ 4 for the
+  // second read, + 16 per k-step), columns wi * 32 + 16 (lane / 16 % 2) + 4 (lane % 4) .. + 3
+  const unsigned baseAT = (unsigned)((8 * h + ((lane & 15) >> 2)) * 192 + (wi * 32 + 16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2);
+  // The halves of a transposed fragment stay two values until their wait has passed: joined
+  // earlier, the join could be a register move that reads them before they have landed.
+  u32x2 alo[2], ahi[2];
+  auto read_a = [&](int slot, unsigned sb, int s, u32x4 &f) {
+    if constexpr (AT) {
+      const unsigned a = sb + baseAT + (unsigned)(s * 3072);
+      alo[slot] = lds_read_tr8<0>(a);
+      ahi[slot] = lds_read_tr8<768>(a);
+    } else {
+      f = lds_read16<0>(sb + offA[s]);
+    }
+  };
+  constexpr int READS = AT ? 4 : 3;            // LDS reads of one k-step
   floatx16 acc[2];
 #pragma unroll
   for (int b = 0; b < 2; ++b)
@@ -382,19 +432,25 @@ __global__ __launch_bounds__(512) void product_kernel(Gemm2Args g) {
     __builtin_amdgcn_s_barrier();
     const unsigned sb = (unsigned)((kt % NS) * STAGE);
     u32x4 fa[2][1], fb[2][2];
-    read_frags<1>(fa[0], sb + offA[0]);
+    read_a(0, sb, 0, fa[0][0]);
     read_frags<2>(fb[0], sb + offB[0]);
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
       const int cur = s & 1, nxt = cur ^ 1;
       if (s < 3) {
-        read_frags<1>(fa[nxt], sb + offA[s + 1]);
+        read_a(nxt, sb, s + 1, fa[nxt][0]);
         read_frags<2>(fb[nxt], sb + offB[s + 1]);
-        wait_lgkm<3>();
+        wait_lgkm<READS>();
       } else {
         wait_lgkm<0>();
       }
-      pin(fa[cur][0]); pin(fb[cur][0]); pin(fb[cur][1]);
+      if constexpr (AT) {
+        pin(alo[cur]); pin(ahi[cur]);
+        fa[cur][0] = u32x4{alo[cur][0], alo[cur][1], ahi[cur][0], ahi[cur][1]};
+      } else {
+        pin(fa[cur][0]);
+      }
+      pin(fb[cur][0]); pin(fb[cur][1]);
 #pragma unroll
       for (int b = 0; b < 2; ++b)
         acc[b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fb[cur][b]),
@@ -1088,15 +1144,19 @@ hipError_t launch_gemm2(Gemm2Args g, int tile, float *workspace, hipStream_t s) 
     if (tile == 1 && g.splits == 1 && !(env3 && env3[0] == '0')) {
       constexpr int lds = 5 * (96 + 128) * 128;
       static bool attr_done = false;
-      e = set_lds(product_kernel, lds, &attr_done);
+      static bool attr_t_done = false;
+      e = g.a_k_major ? set_lds(product_kernel<true>, lds, &attr_t_done) : set_lds(product_kernel<false>, lds, &attr_done);
       if (e != hipSuccess) return e;
       g.tiles_i = (g.I + 95) / 96;
       g.tiles_j = (g.J + 127) / 128;
       const int total = g.tiles_i * g.tiles_j;
-      hipLaunchKernelGGL(product_kernel, dim3((unsigned)(((total + 7) / 8) * 8)), dim3(512), lds, s, g);
+      const dim3 grid((unsigned)(((total + 7) / 8) * 8));
+      if (g.a_k_major) hipLaunchKernelGGL(product_kernel<true>, grid, dim3(512), lds, s, g);
+      else hipLaunchKernelGGL(product_kernel<false>, grid, dim3(512), lds, s, g);
       return hipGetLastError();
     }
   }
+  if (g.a_k_major) return hipErrorInvalidValue;      // only product_kernel reads a k-major A
 #ifdef CODENET_ABLATION
   const char *dbg_env = getenv("CODENET_GEMM2_DBG");
   const int dbg = dbg_env ? atoi(dbg_env) : 0;
