@@ -244,9 +244,9 @@ class Runner:
         L.detect_decode(B.FWD, L.forward(self.X[1]), report=rep, want_decoded=False)
         after = L.read_report(rep)["verdict"]
         m_sys = self.wl.grid[0]
-        # reads the m good systematic block-rows, writes one block-row (+ its two bf16 copies)
+        # reads the m good systematic block-rows, writes one block-row (+ its bf16 copy)
         row_bytes = 4.0 * L.B_r * L.coded_cols
-        nbytes = row_bytes * (m_sys + 1) + (row_bytes if self.wl.dtype == "bf16" else 0.0)
+        nbytes = row_bytes * (m_sys + 1) + (0.5 * row_bytes if self.wl.dtype == "bf16" else 0.0)
         return {"ms": ms, "algorithmic_bytes": nbytes, "GB/s": nbytes / (ms * 1e-3) / 1e9,
                 "frac_of_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                 "verdict_of_next_product": ["clean", "corrected", "uncorrectable"][after],
@@ -342,12 +342,12 @@ def main():
     m, n = wl.grid
     floor = sum(coded.flops.values()) / sum(uncoded.flops.values()) - 1.0
     # dominant kernel: the update, a read-modify-write of the whole fp32 coded matrix.
-    # algorithmic bytes per launch: read + write W~ (2 * 4 B per element), the bf16 operand copies
-    # of W~ that the two products read (bf16 mode: 2 * 2 B per element), both coded vectors once
+    # algorithmic bytes per launch: read + write W~ (2 * 4 B per element), the bf16 copy of W~ that
+    # the two products read (bf16 mode: 2 B per element), both coded vectors once
     elem = 2.0 if wl.dtype == "bf16" else 4.0
     upd_bytes = 2.0 * coded.weight_bytes + elem * coded.b * (L.coded_rows + L.coded_cols)
     if wl.dtype == "bf16":
-        upd_bytes += coded.weight_bytes
+        upd_bytes += 0.5 * coded.weight_bytes
     # kernel duration: HIP events around the kernel, on its stream, on sampled steps of the timed region
     launch_ms = coded.upd_ms_events
     achieved = upd_bytes / (launch_ms * 1e-3) / 1e9
@@ -372,7 +372,7 @@ def main():
         "algorithmic_overhead_floor": floor,
         "verdicts": counts,
         "update_kernel_ms_uncoded": upd_ms_unc if args.graph else uncoded.upd_ms_events,
-        "roofline": {"kernel": "update3_kernel (W~ += eta [d;d~][x;x~]^T, fp32 RMW + bf16 operand copies)"
+        "roofline": {"kernel": "update3_kernel (W~ += eta [d;d~][x;x~]^T, fp32 RMW + bf16 copy)"
                      if wl.dtype == "bf16" else "gemm_kernel (update, W~ += eta [d;d~][x;x~]^T)", "bound": "hbm",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(args.workload),

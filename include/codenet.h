@@ -206,7 +206,7 @@ int codenet_update(codenet_layer *layer, float eta, void *stream);
  * the code of `phase` (more than r / 2 blocks, an index beyond the grid, a
  * repeated index), leaves the matrix untouched.  The
  * report is read on the device: the call never synchronises with the host.  In
- * the bf16 mode the bf16 copies of the rebuilt blocks are refreshed as well.
+ * the bf16 mode the bf16 copy of the rebuilt blocks is refreshed as well.
  * The cached vectors [x; x~], [delta; delta~] need no regeneration here: they
  * are re-encoded from the caller's inputs on every forward / backward call.
  */

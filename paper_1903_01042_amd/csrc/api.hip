@@ -23,14 +23,13 @@ struct codenet_layer {
   double *partials = nullptr;   // [kDetectParts][kMaxEntries]
   double *fault_partials = nullptr;   // [CODENET_MAX_FAULTS][kFaultParts]
   // bf16 mode only: k-contiguous bf16 operands of the two products
-  __bf16 *Wb = nullptr;         // [Mr][ldWb]   row-major copy of W~ (forward)
-  __bf16 *WTb = nullptr;        // [Nc][ldWTb]  transposed copy of W~ (backward)
+  __bf16 *Wb = nullptr;         // [max(Mr, KpD)][ldWb]  bf16 copy of W~, operand of both products
   __bf16 *Xb = nullptr;         // [max_batch][ldXb]  x, zero beyond the base columns
   __bf16 *Db = nullptr;         // [max_batch][ldDb]  delta, zero beyond the base rows
   __bf16 *XTb = nullptr;        // [Nc][ldT]    feature-major [x; x~] (update)
   __bf16 *DTb = nullptr;        // [Mr][ldT]    feature-major [delta; delta~] (update)
   float *part = nullptr;        // split-k partial results: [kMaxSplits][max_batch][max(Mr, Nc)]
-  long ldWb = 0, ldWTb = 0;
+  long ldWb = 0;
   int KpX = 0, KpD = 0, bpad = 0;   // contraction lengths (multiples of 64): base columns, base rows, batch
   long ldXb = 0, ldDb = 0, ldT = 0; // pitches of Xb, Db and of XTb / DTb
   int fwd_b = 0, bwd_b = 0;     // batch of the cached vectors (0 = none)
@@ -132,7 +131,7 @@ void free_layer(codenet_layer *l) {
   (void)hipFree(l->Wt); (void)hipFree(l->Xt); (void)hipFree(l->Dt); (void)hipFree(l->syn);
   (void)hipFree(l->partials); (void)hipFree(l->fault_partials);
   (void)hipFree(l->code_r_dev); (void)hipFree(l->code_c_dev);
-  (void)hipFree(l->Wb); (void)hipFree(l->WTb); (void)hipFree(l->Xb); (void)hipFree(l->Db);
+  (void)hipFree(l->Wb); (void)hipFree(l->Xb); (void)hipFree(l->Db);
   (void)hipFree(l->XTb); (void)hipFree(l->DTb); (void)hipFree(l->part);
   delete l;
 }
@@ -207,14 +206,13 @@ int codenet_encode(const codenet_desc *d, const float *W_dev, void *stream, code
     const bool skew_on = !(skew_env && skew_env[0] == '0');
     auto pitch = [&](long v) { v = up64(v); return (skew_on && (v * 2) % 2048 == 0) ? v + 64 : v; };
     l->ldWb = pitch(l->Nc);
-    l->ldWTb = pitch(l->Mr);
     l->KpX = (int)up64((long)l->code_c.a * l->code_c.B);
     l->KpD = (int)up64((long)l->code_r.a * l->code_r.B);
     l->ldXb = pitch(l->KpX);
     l->ldDb = pitch(l->KpD);
     // the backward product reads rows 0 .. KpD - 1 of the row-major copy: with no parity rows the 64-padding
     // of the contraction can reach past the matrix, so the copy has that many rows (the extra ones stay zero)
-    const size_t szWb = 2 * (size_t)std::max(l->Mr, l->KpD) * l->ldWb, szWTb = 2 * (size_t)l->Nc * l->ldWTb;
+    const size_t szWb = 2 * (size_t)std::max(l->Mr, l->KpD) * l->ldWb;
     const size_t szXb = 2 * mb * l->ldXb, szDb = 2 * mb * l->ldDb;
     l->bpad = (int)up64((long)mb);
     l->ldT = pitch(l->bpad);
@@ -222,13 +220,11 @@ int codenet_encode(const codenet_desc *d, const float *W_dev, void *stream, code
     alloc((void **)&l->DTb, 2 * (size_t)l->Mr * l->ldT);
     alloc((void **)&l->part, sizeof(float) * (size_t)kMaxSplits * mb * std::max(l->Mr, l->Nc));
     alloc((void **)&l->Wb, szWb);
-    alloc((void **)&l->WTb, szWTb);
     alloc((void **)&l->Xb, szXb);
     alloc((void **)&l->Db, szDb);
     // pitch padding and the tails beyond the base blocks stay zero for the layer's life
     what = "clearing the bf16 operands";
     if (e == hipSuccess) e = hipMemsetAsync(l->Wb, 0, szWb, s);
-    if (e == hipSuccess) e = hipMemsetAsync(l->WTb, 0, szWTb, s);
     if (e == hipSuccess) e = hipMemsetAsync(l->Xb, 0, szXb, s);
     if (e == hipSuccess) e = hipMemsetAsync(l->Db, 0, szDb, s);
   }
@@ -243,7 +239,7 @@ int codenet_encode(const codenet_desc *d, const float *W_dev, void *stream, code
   }
   if (e == hipSuccess && l->bf16) {
     what = "bf16 copies of the coded matrix";
-    e = launch_shadow(l->Wt, l->Mr, l->Nc, l->Wb, l->ldWb, l->WTb, l->ldWTb, s);
+    e = launch_shadow(l->Wt, l->Mr, l->Nc, l->Wb, l->ldWb, s);
   }
   // the host copies of the code tables must outlive the asynchronous copies above
   if (e == hipSuccess) {
@@ -309,9 +305,8 @@ int codenet_backward(codenet_layer *l, const float *D_dev, int b, float *C_coded
     plan_gemm2(l->Nc, b, l->KpD, kMaxSplits, &tile, &splits);
     CN_HIP(launch_encode_vector_bf16(D_dev, l->code_r_dev, l->code_r, b, l->Db, l->ldDb, l->DTb, l->ldT, s));
     Gemm2Args g2{};
-    g2.A = l->WTb; g2.lda = l->ldWTb;
-    const char *tr = getenv("CODENET_BWD_TR");
-    if (tr && tr[0] == '1' && tile == 1 && splits == 1) { g2.A = l->Wb; g2.lda = l->ldWb; g2.a_k_major = 1; }
+    // A[i][k] = W~[k][i]: the row-major copy, read k-major (transposing LDS reads in the kernel)
+    g2.A = l->Wb; g2.lda = l->ldWb; g2.a_k_major = 1;
     g2.B = l->Db; g2.ldb = l->ldDb;
     g2.C = C_coded_dev; g2.ldc = l->Nc;
     g2.I = l->Nc; g2.J = b; g2.K = l->KpD; g2.splits = splits;
@@ -342,7 +337,6 @@ int codenet_update(codenet_layer *l, float eta, void *stream) {
     u.DT = l->DTb; u.ldd = l->ldT;
     u.W = l->Wt; u.ldw = l->Nc;
     u.Wb = l->Wb; u.ldWb = l->ldWb;
-    u.WTb = l->WTb; u.ldWTb = l->ldWTb;
     u.I = l->Nc; u.J = l->Mr; u.K = bp; u.eta = eta;
     // The matrix and its copies are a little more than the memory-side cache holds; sweeping them
     // in the same order every step is the worst case for its LRU replacement, so the direction
@@ -453,7 +447,7 @@ int codenet_inject(codenet_layer *l, const codenet_fault *faults, int n_faults, 
     CN_HIP(launch_faults(fb, s, pass == 0));
   }
   if (phase == CODENET_WEIGHT && l->bf16)
-    CN_HIP(launch_shadow(l->Wt, l->Mr, l->Nc, l->Wb, l->ldWb, l->WTb, l->ldWTb, s));
+    CN_HIP(launch_shadow(l->Wt, l->Mr, l->Nc, l->Wb, l->ldWb, s));
   return CODENET_OK;
 }
 
@@ -463,7 +457,6 @@ int codenet_regenerate(codenet_layer *l, int phase, const codenet_report *report
   RegenArgs g{};
   g.W = l->Wt; g.Mr = l->Mr; g.Nc = l->Nc;
   g.Wb = l->bf16 ? l->Wb : nullptr; g.ldWb = l->ldWb;
-  g.WTb = l->bf16 ? l->WTb : nullptr; g.ldWTb = l->ldWTb;
   g.axis = phase == CODENET_FWD ? 0 : 1;
   // the forward output is checked by the code along the rows, so its located nodes are block-rows
   const bool rows = phase == CODENET_FWD;

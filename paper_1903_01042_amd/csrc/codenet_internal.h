@@ -59,8 +59,7 @@ struct Update2Args {
   const __bf16 *XT; long ldx;    // [I = coded columns][batch padded to 64]
   const __bf16 *DT; long ldd;    // [J = coded rows][batch padded to 64]
   float *W; long ldw;            // fp32 coded matrix [J][I]
-  __bf16 *Wb; long ldWb;         // its bf16 copy, row-major
-  __bf16 *WTb; long ldWTb;       // its bf16 copy, transposed
+  __bf16 *Wb; long ldWb;         // its bf16 copy (row-major)
   int I, J, K;
   float eta;
   int tiles_i, tiles_j;
@@ -70,14 +69,12 @@ constexpr int kMaxSplits = 8;
 void plan_gemm2(int I, int J, int K, int max_splits, int *tile, int *splits);
 hipError_t launch_gemm2(Gemm2Args g, int tile, float *workspace, hipStream_t s);
 hipError_t launch_update2(Update2Args g, hipStream_t s);
-hipError_t launch_shadow(const float *Wt, int Mr, int Nc, void *Wb, long ldWb, void *WTb, long ldWTb,
-                         hipStream_t s);
+hipError_t launch_shadow(const float *Wt, int Mr, int Nc, void *Wb, long ldWb, hipStream_t s);
 
 // Regeneration of located blocks: axis 0 = block-rows (code along the rows), 1 = block-columns
 struct RegenArgs {
   float *W; int Mr, Nc;          // fp32 coded matrix [Mr][Nc]
-  __bf16 *Wb; long ldWb;         // bf16 copies (null in the f32 mode)
-  __bf16 *WTb; long ldWTb;
+  __bf16 *Wb; long ldWb;         // bf16 copy (null in the f32 mode)
   int axis;
 };
 hipError_t launch_regen(RegenArgs g, const DevCode *code_dev, const DevCode &code_host, const codenet_report *report,

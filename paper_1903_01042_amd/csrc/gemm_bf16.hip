@@ -489,8 +489,8 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float4 *__re
 //   W~[j][i] += eta * sum_k delta~[j][k] x~[i][k]      (j coded row, i coded column, k batch)
 // Operands are the feature-major bf16 copies of the cached coded vectors.  The
 // epilogue reads-modifies-writes the fp32 matrix with fully coalesced dword
-// accesses and refreshes both bf16 copies of it: the row-major one and the
-// transposed one are staged through LDS so that they leave as 16-byte stores.
+// accesses and refreshes its bf16 copy, staged through LDS so that it leaves as
+// 16-byte stores.
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ unsigned pack2_bf16(float lo, float hi) {
   const __bf16 a = (__bf16)lo, b = (__bf16)hi;
@@ -500,9 +500,7 @@ __device__ __forceinline__ unsigned pack2_bf16(float lo, float hi) {
 template <int FM, int FN, int NS, int DBG = 0>
 __global__ __launch_bounds__(256, (FM * FN <= 4 ? 2 : 1)) void update2_kernel(Update2Args g) {
   constexpr int TI = 64 * FM, TJ = 64 * FN;
-  constexpr int PT = TJ * 2 + 16;       // pitch of the transposed staging tile [i][j], bytes
-  constexpr int PR = TI * 2 + 16;       // pitch of the row-major staging tile [j][i], bytes
-  constexpr int ST = TI * PT;           // the row-major tile follows the transposed one
+  constexpr int PR = TI * 2 + 16;       // pitch of the staging tile [j][i], bytes
   extern __shared__ uint4 lds[];
   char *const lds_c = reinterpret_cast<char *>(lds);
   const int logical = logical_workgroup(g.tiles_i * g.tiles_j);
@@ -555,35 +553,23 @@ __global__ __launch_bounds__(256, (FM * FN <= 4 ? 2 : 1)) void update2_kernel(Up
         if (in && !(DBG & 2)) g.W[(long)j * g.ldw + i] = w;
         acc[a][b][x] = w;
       }
-      // 2. stage the bf16 value of w twice: transposed [i][j] and row-major [j][i]
+      // 2. stage the bf16 value of w, row-major [j][i]
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int jl = (wj * FN + b) * 32 + 8 * q + 4 * h;
-        uint2 pk;
-        pk.x = pack2_bf16(acc[a][b][4 * q], acc[a][b][4 * q + 1]);
-        pk.y = pack2_bf16(acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]);
-        *reinterpret_cast<uint2 *>(lds_c + il * PT + jl * 2) = pk;
-        *reinterpret_cast<unsigned short *>(lds_c + ST + (jl + 0) * PR + il * 2) = (unsigned short)(pk.x & 0xffffu);
-        *reinterpret_cast<unsigned short *>(lds_c + ST + (jl + 1) * PR + il * 2) = (unsigned short)(pk.x >> 16);
-        *reinterpret_cast<unsigned short *>(lds_c + ST + (jl + 2) * PR + il * 2) = (unsigned short)(pk.y & 0xffffu);
-        *reinterpret_cast<unsigned short *>(lds_c + ST + (jl + 3) * PR + il * 2) = (unsigned short)(pk.y >> 16);
+      for (int x = 0; x < 16; ++x) {
+        const int jl = (wj * FN + b) * 32 + 8 * (x >> 2) + 4 * h + (x & 3);
+        const __bf16 v = (__bf16)acc[a][b][x];
+        *reinterpret_cast<unsigned short *>(lds_c + jl * PR + il * 2) = __builtin_bit_cast(unsigned short, v);
       }
     }
   __syncthreads();
   if (DBG & 4) return;
-  // 3. both bf16 copies leave as rows of 16-byte chunks (the pitches are multiples
-  //    of 64 elements: whole chunks fit, and entries beyond the matrix are zeros)
-  for (int id = tid; id < TI * (TJ / 8); id += 256) {
-    const int row = id / (TJ / 8), cj = id % (TJ / 8);
-    const int i = i0 + row, j = j0 + cj * 8;
-    if (i < g.I && j < g.ldWTb)
-      *reinterpret_cast<uint4 *>(g.WTb + (long)i * g.ldWTb + j) = *reinterpret_cast<const uint4 *>(lds_c + row * PT + cj * 16);
-  }
+  // 3. the copy leaves as rows of 16-byte chunks (the pitch is a multiple of 64
+  //    elements: whole chunks fit, and entries beyond the matrix are zeros)
   for (int id = tid; id < TJ * (TI / 8); id += 256) {
     const int row = id / (TI / 8), ci = id % (TI / 8);
     const int j = j0 + row, i = i0 + ci * 8;
     if (j < g.J && i < g.ldWb)
-      *reinterpret_cast<uint4 *>(g.Wb + (long)j * g.ldWb + i) = *reinterpret_cast<const uint4 *>(lds_c + ST + row * PR + ci * 16);
+      *reinterpret_cast<uint4 *>(g.Wb + (long)j * g.ldWb + i) = *reinterpret_cast<const uint4 *>(lds_c + row * PR + ci * 16);
   }
 }
 
@@ -658,7 +644,7 @@ struct TileWalk {
 };
 
 // DBG (ablation builds): 1 loaders and storers idle, 2 MMA role idles, 4 no stores at all,
-// 8 no transposed-copy stores, 16 no row-major-copy stores, 32 no fp32 stores
+// 16 no stores of the bf16 copy, 32 no fp32 stores
 template <int DBG = 0>
 __global__ __launch_bounds__(512) void update3_kernel(Update2Args g) {
   constexpr int STAGE = 256 * 128;            // bytes: 128 A rows + 128 B rows of 128 bytes
@@ -811,15 +797,13 @@ __global__ __launch_bounds__(512) void update3_kernel(Update2Args g) {
   }
 
   // Schedule of the other two roles inside a tile period (barriers B0 .. B(KS-1), then
-  // the end-of-tile barrier).  With 8 slabs or more the storers empty the tile buffer in six
-  // pieces after B0 .. B5: the two row quarters as two halves each (they gather their rows
-  // from the transposed tile and take twice a slab of the MMA role: as whole quarters they
-  // made the MMA wavefronts wait 1900 clocks at each of the next barriers), then the two
-  // quarters of the transposed copy; the loaders refill it with two groups after B6 and two
-  // after B7.  (Transposed quarters first and a loader group beside each of the last row
-  // pieces, which the row ranges allow, was slower: a storer piece and a loader group in one
-  // interval stretch it, the MMA wavefronts' own slab included.)  With fewer slabs the
-  // quarters pair up after B0, B1 and the groups after B2, B3.
+  // the end-of-tile barrier).  With 8 slabs or more the storers empty the tile buffer in four
+  // pieces after B0 .. B3, half a row quarter each (they gather their rows from the
+  // transposed tile and push 24 KB of stores per piece; as whole quarters they took twice a
+  // slab of the MMA role, which then waited 1900 clocks at each of the next barriers -- seen
+  // in time stamps that one MMA wavefront took at every barrier), and the loaders refill it
+  // with one group after each of B4 .. B7.  With fewer slabs the quarters follow B0 and B1
+  // and the groups pair up after B2 and B3.
   const bool wide = KS >= 8;
 
   if (wave < 6) {
@@ -880,7 +864,7 @@ __global__ __launch_bounds__(512) void update3_kernel(Update2Args g) {
     for (int gq = 0; gq < 4; ++gq) request_group(gq, ti, tj);
     bool have = true;
     while (have) {
-      for (int e = wide ? 7 : 3; e > 0; --e) lds_barrier();
+      for (int e = wide ? 5 : 3; e > 0; --e) lds_barrier();
       have = walk.next(ti, tj);
       // Two copies of the sequence, with and without the requests for the next tile: with the
       // requests under a condition of their own, the compiler's count of the loads in flight
@@ -890,14 +874,14 @@ __global__ __launch_bounds__(512) void update3_kernel(Update2Args g) {
       if (have) {
 #pragma unroll
         for (int gq = 0; gq < 4; ++gq) {
-          if (gq == 2) lds_barrier();
+          if (gq > 0 && (wide || gq == 2)) lds_barrier();
           write_group(gq);
           request_group(gq, ti, tj);
         }
       } else {
 #pragma unroll
         for (int gq = 0; gq < 4; ++gq) {
-          if (gq == 2) lds_barrier();
+          if (gq > 0 && (wide || gq == 2)) lds_barrier();
           write_group(gq);
         }
       }
@@ -920,18 +904,13 @@ __global__ __launch_bounds__(512) void update3_kernel(Update2Args g) {
     rowA[e] = lds_c + TILE + il * 512 + (((v >> 4) & 3) << 2);
     feA[e] = ((((il ^ (il >> 5)) & 31) ^ (v >> 6)) << 4);
   }
-  // quarters 2, 3: transposed copy; item k is row i = 8 k + v / 16, columns j = 8 (v % 16) .. + 7
-  char *const rowB = lds_c + TILE + (v >> 4) * 512;
-  int baseB = ((2 * (v & 15)) ^ (v >> 4)) << 4;
-  // hsel: -1 the whole quarter, 0 / 1 one half of quarters 0 and 1 (four of their eight row groups)
+  // qt: rows 64 qt .. 64 qt + 63 of the tile; hsel: -1 all of them, 0 / 1 one half (four of the eight row groups)
   auto quarter = [&](int qt, int hsel = -1) {
     if (DBG & 513) return;
-    if ((DBG & 1024) && qt < 2) return;
-    if ((DBG & 2048) && qt >= 2) return;
     // a tile that lies inside the matrix takes the branch-free path: all LDS reads of the
     // quarter first, then the stores; an edge tile masks every access
     const bool interior = (pti + 1) * 128 <= g.I && (ptj + 1) * 128 <= g.J;
-    if (qt < 2) {
+    {
 #if CN_DEVICE_ASM
 #pragma unroll
       for (int e = 0; e < 8; ++e) asm volatile("" : "+v"(feA[e]));
@@ -982,51 +961,12 @@ __global__ __launch_bounds__(512) void update3_kernel(Update2Args g) {
         if (j < g.J && i < g.ldWb && (!(DBG & 20) || pk.x == 0x12345u))
           *reinterpret_cast<uint4 *>(pb + (long)(8 * k) * g.ldWb) = pk;
       }
-    } else {
-#if CN_DEVICE_ASM
-      asm volatile("" : "+v"(baseB));
-#endif
-      const int i0 = pti * 128 + (v >> 4), j = ptj * 128 + (v & 15) * 8;
-      __bf16 *const pt = g.WTb + (long)i0 * g.ldWTb + j;
-      // f(8 k + r) = 8 (k % 4) ^ r ^ k / 4 for r < 8
-      if (interior) {
-        f32x4 c[8][2];
-#pragma unroll
-        for (int k8 = 0; k8 < 8; ++k8) {
-          const int k = (qt - 2) * 8 + k8;
-          const int ck = ((8 * (k & 3)) ^ (k >> 2)) << 4;
-          c[k8][0] = *reinterpret_cast<const f32x4 *>(rowB + 4096 * k + (baseB ^ ck));
-          c[k8][1] = *reinterpret_cast<const f32x4 *>(rowB + 4096 * k + (baseB ^ ck ^ 16));
-        }
-#pragma unroll
-        for (int k8 = 0; k8 < 8; ++k8) {
-          const int k = (qt - 2) * 8 + k8;
-          const u32x4 pk = {pack2_bf16(c[k8][0][0], c[k8][0][1]), pack2_bf16(c[k8][0][2], c[k8][0][3]),
-                            pack2_bf16(c[k8][1][0], c[k8][1][1]), pack2_bf16(c[k8][1][2], c[k8][1][3])};
-          if (!(DBG & 12) || pk[0] == 0x12345u) *reinterpret_cast<u32x4 *>(pt + (long)(8 * k) * g.ldWTb) = pk;
-        }
-        return;
-      }
-#pragma unroll 2
-      for (int k8 = 0; k8 < 8; ++k8) {
-        const int k = (qt - 2) * 8 + k8;
-        const int ck = ((8 * (k & 3)) ^ (k >> 2)) << 4;
-        f32x4 c0 = *reinterpret_cast<const f32x4 *>(rowB + 4096 * k + (baseB ^ ck));
-        f32x4 c1 = *reinterpret_cast<const f32x4 *>(rowB + 4096 * k + (baseB ^ ck ^ 16));
-        if (j >= g.J) c0 = f32x4{0.f, 0.f, 0.f, 0.f};       // J is a multiple of 4
-        if (j + 4 >= g.J) c1 = f32x4{0.f, 0.f, 0.f, 0.f};
-        uint4 pk;
-        pk.x = pack2_bf16(c0[0], c0[1]); pk.y = pack2_bf16(c0[2], c0[3]);
-        pk.z = pack2_bf16(c1[0], c1[1]); pk.w = pack2_bf16(c1[2], c1[3]);
-        if (i0 + 8 * k < g.I && j < g.ldWTb && (!(DBG & 12) || pk.x == 0x12345u))
-          *reinterpret_cast<uint4 *>(pt + (long)(8 * k) * g.ldWTb) = pk;
-      }
     }
   };
   bool have_prev = false, more = true;
   while (more) {
     if (wide) {
-      // the row quarters take twice as long as a slab of the MMA role: half a quarter per barrier
+      // a whole quarter takes twice as long as a slab of the MMA role: half a quarter per barrier
       lds_barrier();
       if (have_prev) quarter(0, 0);
       lds_barrier();
@@ -1035,16 +975,12 @@ __global__ __launch_bounds__(512) void update3_kernel(Update2Args g) {
       if (have_prev) quarter(1, 0);
       lds_barrier();
       if (have_prev) quarter(1, 1);
-      lds_barrier();
-      if (have_prev) quarter(2);
-      lds_barrier();
-      if (have_prev) quarter(3);
-      for (int e = KS - 6; e > 0; --e) lds_barrier();
+      for (int e = KS - 4; e > 0; --e) lds_barrier();
     } else {
       lds_barrier();
-      if (have_prev) { quarter(0); quarter(1); }
+      if (have_prev) quarter(0);
       lds_barrier();
-      if (have_prev) { quarter(2); quarter(3); }
+      if (have_prev) quarter(1);
       for (int e = KS - 2; e > 0; --e) lds_barrier();
     }
     lds_barrier();                                        // end of the tile
@@ -1053,7 +989,7 @@ __global__ __launch_bounds__(512) void update3_kernel(Update2Args g) {
     more = walk.next(ti, tj);
   }
   lds_barrier();
-  quarter(0); quarter(1); quarter(2); quarter(3);
+  quarter(0); quarter(1);
 }
 
 namespace {
@@ -1086,9 +1022,9 @@ hipError_t launch2(Gemm2Args g, hipStream_t s) {
 template <int FM, int FN, int NS, int DBG = 0>
 hipError_t launch_upd2(Update2Args g, hipStream_t s) {
   constexpr int TI = 64 * FM, TJ = 64 * FN;
-  constexpr int stage = NS * (TI + TJ) * 128, st = TI * (TJ * 2 + 16) + TJ * (TI * 2 + 16);
+  constexpr int stage = NS * (TI + TJ) * 128, st = TJ * (TI * 2 + 16);
   constexpr int lds = stage > st ? stage : st;
-  static_assert(lds <= 160 * 1024, "staging tiles do not fit in LDS");
+  static_assert(lds <= 160 * 1024, "the staging tile does not fit in LDS");
   g.tiles_i = (g.I + TI - 1) / TI;
   g.tiles_j = (g.J + TJ - 1) / TJ;
   const int nt = g.tiles_i * g.tiles_j;
@@ -1127,6 +1063,8 @@ void plan_gemm2(int I, int J, int K, int max_splits, int *tile, int *splits) {
 hipError_t launch_gemm2(Gemm2Args g, int tile, float *workspace, hipStream_t s) {
   if ((g.K & 63) || (g.lda & 7) || (g.ldb & 7) || (g.ldc & 3) || (g.I & 3) || g.splits < 1 || g.I < 1 || g.J < 1)
     return hipErrorInvalidValue;
+  // only product_kernel reads a k-major A: the tuning switches below do not apply to such a product
+  if (g.a_k_major) { tile = 1; g.splits = 1; }
   const int ti = 64 * kTiles2[tile].fm, tj = 64 * kTiles2[tile].fn;
   g.tiles_i = (g.I + ti - 1) / ti;
   g.tiles_j = (g.J + tj - 1) / tj;
@@ -1141,7 +1079,7 @@ hipError_t launch_gemm2(Gemm2Args g, int tile, float *workspace, hipStream_t s) 
   {
     // CODENET_GEMM3=0: the generic kernel below also for this tile, for comparison
     const char *env3 = getenv("CODENET_GEMM3");
-    if (tile == 1 && g.splits == 1 && !(env3 && env3[0] == '0')) {
+    if (g.a_k_major || (tile == 1 && g.splits == 1 && !(env3 && env3[0] == '0'))) {
       constexpr int lds = 5 * (96 + 128) * 128;
       static bool attr_done = false;
       static bool attr_t_done = false;
@@ -1156,7 +1094,6 @@ hipError_t launch_gemm2(Gemm2Args g, int tile, float *workspace, hipStream_t s) 
       return hipGetLastError();
     }
   }
-  if (g.a_k_major) return hipErrorInvalidValue;      // only product_kernel reads a k-major A
 #ifdef CODENET_ABLATION
   const char *dbg_env = getenv("CODENET_GEMM2_DBG");
   const int dbg = dbg_env ? atoi(dbg_env) : 0;
@@ -1214,16 +1151,11 @@ hipError_t launch_update3(Update2Args g, hipStream_t s) {
     case 3: return launch_upd3<3>(g, s);
     case 4: return launch_upd3<4>(g, s);
     case 6: return launch_upd3<6>(g, s);
-    case 8: return launch_upd3<8>(g, s);
     case 16: return launch_upd3<16>(g, s);
-    case 24: return launch_upd3<24>(g, s);
     case 32: return launch_upd3<32>(g, s);
-    case 68: return launch_upd3<68>(g, s);
-    case 132: return launch_upd3<132>(g, s);
-    case 388: return launch_upd3<388>(g, s);
-    case 644: return launch_upd3<644>(g, s);
-    case 1156: return launch_upd3<1156>(g, s);
-    case 2180: return launch_upd3<2180>(g, s);
+    case 128: return launch_upd3<128>(g, s);
+    case 256: return launch_upd3<256>(g, s);
+    case 512: return launch_upd3<512>(g, s);
     default: break;
   }
 #endif
@@ -1231,7 +1163,7 @@ hipError_t launch_update3(Update2Args g, hipStream_t s) {
 }
 
 hipError_t launch_update2(Update2Args g, hipStream_t s) {
-  if ((g.K & 63) || (g.ldx & 7) || (g.ldd & 7) || (g.ldWb & 63) || (g.ldWTb & 63) || g.I < 1 || g.J < 1)
+  if ((g.K & 63) || (g.ldx & 7) || (g.ldd & 7) || (g.ldWb & 63) || g.I < 1 || g.J < 1)
     return hipErrorInvalidValue;
   const char *env3 = getenv("CODENET_UPD3");
   if (g.K >= 256 && (g.I & 3) == 0 && (g.J & 3) == 0 && !(env3 && env3[0] == '0')) return launch_update3(g, s);
@@ -1256,50 +1188,30 @@ hipError_t launch_update2(Update2Args g, hipStream_t s) {
 }
 
 // ---------------------------------------------------------------------------
-// Shadow refresh: bf16 copies of the fp32 coded matrix, row-major (forward
-// product) and transposed (backward product), 64 x 64 tiles through LDS.
+// Shadow refresh: the bf16 copy of the fp32 coded matrix (row-major; the forward product
+// reads it as it is, the backward product through transposing LDS reads).
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void shadow_kernel(const float *__restrict__ Wt, int Mr, int Nc,
-                                                     __bf16 *__restrict__ Wb, long ldWb,
-                                                     __bf16 *__restrict__ WTb, long ldWTb) {
-  __shared__ unsigned short tile[64][66];
+                                                     __bf16 *__restrict__ Wb, long ldWb) {
+  // 64 x 64 tiles: thread t handles float4 (t & 15) of rows (t >> 4) + 16 p
   const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
   const int t = threadIdx.x;
-  // 64 rows x 16 float4: thread t handles float4 (t & 15) of rows (t >> 4) + 16 p
 #pragma unroll
   for (int p = 0; p < 4; ++p) {
-    const int r = (t >> 4) + 16 * p, c = (t & 15) * 4;
-    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (r0 + r < Mr && c0 + c < Nc) v = *reinterpret_cast<const float4 *>(Wt + (long)(r0 + r) * Nc + c0 + c);
-    const __bf16 b0 = (__bf16)v.x, b1 = (__bf16)v.y, b2 = (__bf16)v.z, b3 = (__bf16)v.w;
-    const unsigned short u0 = __builtin_bit_cast(unsigned short, b0), u1 = __builtin_bit_cast(unsigned short, b1),
-                         u2 = __builtin_bit_cast(unsigned short, b2), u3 = __builtin_bit_cast(unsigned short, b3);
-    tile[r][c] = u0; tile[r][c + 1] = u1; tile[r][c + 2] = u2; tile[r][c + 3] = u3;
-    if (r0 + r < Mr && c0 + c < Nc) {
+    const int r = r0 + (t >> 4) + 16 * p, c = c0 + (t & 15) * 4;
+    if (r < Mr && c < Nc) {
+      const float4 v = *reinterpret_cast<const float4 *>(Wt + (long)r * Nc + c);
       uint2 pk;
-      pk.x = (unsigned)u0 | ((unsigned)u1 << 16);
-      pk.y = (unsigned)u2 | ((unsigned)u3 << 16);
-      *reinterpret_cast<uint2 *>(Wb + (long)(r0 + r) * ldWb + c0 + c) = pk;
-    }
-  }
-  __syncthreads();
-  // transposed: thread t writes 4 consecutive rows (t & 15) * 4 .. of column (t >> 4) + 16 p
-#pragma unroll
-  for (int p = 0; p < 4; ++p) {
-    const int c = (t >> 4) + 16 * p, r = (t & 15) * 4;
-    if (c0 + c < Nc && r0 + r < Mr) {
-      uint2 pk;
-      pk.x = (unsigned)tile[r][c] | ((unsigned)tile[r + 1][c] << 16);
-      pk.y = (unsigned)tile[r + 2][c] | ((unsigned)tile[r + 3][c] << 16);
-      *reinterpret_cast<uint2 *>(WTb + (long)(c0 + c) * ldWTb + r0 + r) = pk;
+      pk.x = pack2_bf16(v.x, v.y);
+      pk.y = pack2_bf16(v.z, v.w);
+      *reinterpret_cast<uint2 *>(Wb + (long)r * ldWb + c) = pk;
     }
   }
 }
 
-hipError_t launch_shadow(const float *Wt, int Mr, int Nc, void *Wb, long ldWb, void *WTb, long ldWTb,
-                         hipStream_t s) {
+hipError_t launch_shadow(const float *Wt, int Mr, int Nc, void *Wb, long ldWb, hipStream_t s) {
   dim3 grid((unsigned)((Nc + 63) / 64), (unsigned)((Mr + 63) / 64));
-  hipLaunchKernelGGL(shadow_kernel, grid, dim3(256), 0, s, Wt, Mr, Nc, (__bf16 *)Wb, ldWb, (__bf16 *)WTb, ldWTb);
+  hipLaunchKernelGGL(shadow_kernel, grid, dim3(256), 0, s, Wt, Mr, Nc, (__bf16 *)Wb, ldWb);
   return hipGetLastError();
 }
 

@@ -782,14 +782,13 @@ hipError_t launch_finish(float *out, const float *syn, const double *partials, i
 // thread, a few hundred flops) from the report that the decision left on the
 // device: no host round trip, and nothing happens unless the verdict is
 // CORRECTED.  One workgroup rebuilds a 64 x 64 tile of one located block:
-// fp32 matrix, row-major bf16 copy and, through LDS, transposed bf16 copy.
+// fp32 matrix and its bf16 copy.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void regen_kernel(RegenArgs g, const DevCode *__restrict__ code,
                                                     const codenet_report *__restrict__ report) {
   __shared__ float coef[CODENET_MAX_L];
   __shared__ int src_blk[CODENET_MAX_L];
   __shared__ int s_target, s_n_src;
-  __shared__ unsigned short tile[64][66];
   const int t = threadIdx.x;
   const int slot = blockIdx.z;
   if (report->verdict != CODENET_CORRECTED || slot >= report->n_located) return;
@@ -900,31 +899,14 @@ __global__ __launch_bounds__(256) void regen_kernel(RegenArgs g, const DevCode *
       }
       *reinterpret_cast<float4 *>(g.W + (long)(gr0 + rr) * g.Nc + gc0 + cc) = v;
     }
-    if (g.Wb != nullptr) {
+    if (g.Wb != nullptr && in) {
       const __bf16 b0 = (__bf16)v.x, b1 = (__bf16)v.y, b2 = (__bf16)v.z, b3 = (__bf16)v.w;
       const unsigned short u0 = __builtin_bit_cast(unsigned short, b0), u1 = __builtin_bit_cast(unsigned short, b1),
                            u2 = __builtin_bit_cast(unsigned short, b2), u3 = __builtin_bit_cast(unsigned short, b3);
-      tile[rr][cc] = u0; tile[rr][cc + 1] = u1; tile[rr][cc + 2] = u2; tile[rr][cc + 3] = u3;
-      if (in) {
-        uint2 pk;
-        pk.x = (unsigned)u0 | ((unsigned)u1 << 16);
-        pk.y = (unsigned)u2 | ((unsigned)u3 << 16);
-        *reinterpret_cast<uint2 *>(g.Wb + (long)(gr0 + rr) * g.ldWb + gc0 + cc) = pk;
-      }
-    }
-  }
-  if (g.Wb == nullptr) return;
-  __syncthreads();
-  // transposed copy: thread t writes rows 4 (t % 16) .. + 3 of column t / 16 + 16 p
-  // (the matrix has a multiple of 4 rows and the block pitch is one too)
-#pragma unroll
-  for (int p = 0; p < 4; ++p) {
-    const int cc = (t >> 4) + 16 * p, rr = (t & 15) * 4;
-    if (c0 + cc < cols && r0 + rr < rows) {
       uint2 pk;
-      pk.x = (unsigned)tile[rr][cc] | ((unsigned)tile[rr + 1][cc] << 16);
-      pk.y = (unsigned)tile[rr + 2][cc] | ((unsigned)tile[rr + 3][cc] << 16);
-      *reinterpret_cast<uint2 *>(g.WTb + (long)(gc0 + cc) * g.ldWTb + gr0 + rr) = pk;
+      pk.x = (unsigned)u0 | ((unsigned)u1 << 16);
+      pk.y = (unsigned)u2 | ((unsigned)u3 << 16);
+      *reinterpret_cast<uint2 *>(g.Wb + (long)(gr0 + rr) * g.ldWb + gc0 + cc) = pk;
     }
   }
 }

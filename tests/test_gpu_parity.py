@@ -378,7 +378,7 @@ def test_weight_fault_shows_up_in_the_next_products():
     (96, 80, 4, 4, 2, 8, "f32", [(FWD, [1])]),                 # a systematic block-row
     (96, 80, 4, 4, 2, 8, "f32", [(FWD, [5])]),                 # a parity block-row
     (96, 80, 4, 4, 2, 8, "f32", [(BWD, [2])]),                 # a systematic block-column
-    (300, 200, 5, 4, 2, 33, "bf16", [(FWD, [0]), (BWD, [4])]),   # ragged, bf16 copies refreshed, both axes in turn
+    (300, 200, 5, 4, 2, 33, "bf16", [(FWD, [0]), (BWD, [4])]),   # ragged, bf16 copy refreshed, both axes in turn
     (130, 70, 3, 3, 4, 5, "f32", [(FWD, [0, 2])]),             # two systematic block-rows (t = 2)
     (130, 70, 3, 3, 4, 5, "f32", [(BWD, [1, 5])]),             # a systematic and a parity block-column
     (1024, 1024, 8, 8, 2, 64, "bf16", [(FWD, [3]), (BWD, [9])]),   # several 64 x 64 tiles per block
@@ -412,7 +412,7 @@ def test_regeneration_restores_the_stored_code(N_out, N_in, m, n, r, b, dtype, b
         assert rel_fro(pair.ora.Wt, clean) <= 1e-9
         err = pair.check_weights(1e-5)
         assert rel_fro(to_np(pair.gpu.export_coded()), clean) <= 1e-5
-        # the copies that the bf16 products read were refreshed too: both products are clean again
+        # the copy that the bf16 products read was refreshed too: both products are clean again
         for ph in (FWD, BWD):
             V = WL.normal((b, N_in if ph == FWD else N_out), seed=200 + step + ph)
             _, rep, res = pair.product(ph, V)
