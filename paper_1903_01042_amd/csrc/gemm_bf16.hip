@@ -577,7 +577,7 @@ __global__ __launch_bounds__(256, (FM * FN <= 4 ? 2 : 1)) void update2_kernel(Up
 // Coded update, persistent and wave-specialised (batch of at least 256).
 //
 // update2_kernel spends 40 us in its contraction and 54 us streaming the fp32
-// matrix and its bf16 copies, one after the other.  Here a workgroup of 8
+// matrix and its bf16 copy, one after the other.  Here a workgroup of 8
 // wavefronts stays resident and walks over 128 x 128 tiles, with three roles
 // that meet only at the per-slab workgroup barriers (every wavefront executes
 // the same number of s_barrier: one per slab, one at the end of a tile):
@@ -590,28 +590,29 @@ __global__ __launch_bounds__(256, (FM * FN <= 4 ? 2 : 1)) void update2_kernel(Up
 //    the last slabs of the tile, once the storers have released the buffer; no other
 //    wavefront ever waits on HBM;
 //  * wavefronts 6-7 (storers) work one tile behind: during the first slabs they gather
-//    rows of the matrix from the (transposed) LDS tile and store them and the
-//    row-major bf16 copy, then they store the transposed copy; every store
-//    instruction writes whole 64-byte segments (the L2 request rate, not its
-//    bandwidth, is what this kernel runs into).  They only ever issue stores, so
-//    they never wait for memory.
+//    rows of the matrix from the (transposed) LDS tile and store them and their bf16
+//    copy; every store instruction writes whole 64-byte segments (the L2 request
+//    rate, not its bandwidth, is what this kernel runs into).  They only ever issue
+//    stores, so they never wait for memory.
 // Which piece follows which barrier is described at the roles' code below.
 // On gfx9 one counter covers loads and stores and stores return out of order:
 // a wavefront that mixes the two can only wait for everything, which is why
 // the roles are split this way.  Tiles are dealt so that every XCD owns one rectangle of a
 // 2 x 4 partition of the tile grid and needs only the operand panels of that rectangle.
-// Streaming accesses stay ordinary cached ones: the matrix and its copies largely live in
+// Streaming accesses stay ordinary cached ones: the matrix and its copy largely live in
 // the 256 MB memory-side cache from one step to the next, and non-temporal stores forfeit
 // that (150 us vs 84 us); non-temporal loads of the fp32 tile change nothing.  Write-through
 // stores (sc1) keep the operand panels in L2 (operand traffic falls from 95 MB to 43 MB, close
 // to the 31 MB that the partition makes compulsory) but are slower themselves: 100 us.
-// The roles' times mostly add up (MMA role alone 42 us, the streaming roles alone 58 us, all
-// 79 us; without the transposed copy 72, without the row-major copy 70, without the fp32
-// stores 64, without the fp32 loads 67 us): the kernel moves 408 MB at 5.2 TB/s, and a plain
-// pass over the same matrix (shadow_kernel) reaches 5.8.
 // Unlike in product_kernel, moving the roles apart by SIMD does not pay here (MMA wavefronts
 // on SIMDs 0 and 1, loaders on 2, storers on 3: 86.5 us against 82.5 us): the MFMAs are the
 // smaller part and the kernel runs at the rate the memory system takes the traffic.
+// The roles' times mostly add up.  Measured while the kernel still wrote a second, transposed
+// bf16 copy for the backward product: MMA role alone 42 us, the streaming roles alone 58 us,
+// all 79 us; without the transposed copy 72, without the row-major copy 70, without the fp32
+// stores 64, without the fp32 loads 67 us.  That is why the transposed copy went (the backward
+// product now reads the row-major one through transposing LDS reads): 70 us in the step for
+// 357 MB of traffic, 5.1 TB/s; a plain pass over the same matrix (shadow_kernel) reaches 5.8.
 // ---------------------------------------------------------------------------
 struct TileWalk {
   int tiles_i, tiles_j, tiw, tjh, total, i_base, j_base, step, q;
@@ -895,7 +896,8 @@ __global__ __launch_bounds__(512) void update3_kernel(Update2Args g) {
   // -------------------------------------------------------------------- storers
   const int v = tid - 384;                    // 0 .. 127
   int pti = 0, ptj = 0;                       // tile being stored (one behind the MMA role)
-  // quarters 0, 1: fp32 matrix and row-major copy; item k is row j = 8 k + v / 16, columns i = 8 (v % 16) .. + 7
+  // quarters 0, 1 (rows 0 .. 63 and 64 .. 127 of the tile): fp32 matrix and its bf16 copy;
+  // item k is row j = 8 k + v / 16, columns i = 8 (v % 16) .. + 7
   char *rowA[8];
   int feA[8];
 #pragma unroll
