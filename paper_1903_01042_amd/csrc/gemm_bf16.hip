@@ -652,13 +652,13 @@ __global__ __launch_bounds__(512) void update3_kernel(Update2Args g) {
   constexpr int TILE = 3 * STAGE;             // fp32 tile of the matrix, 64 KB: 160 KB in all
   extern __shared__ uint4 lds[];
   char *const lds_c = reinterpret_cast<char *>(lds);
-  // The fp32 tile is kept transposed, [i][j] with 512-byte rows, because an MMA lane
-  // owns four consecutive j of one i.  The 16-byte piece j / 4 of row i sits at
-  // piece (j / 4) ^ f(i), f(i) = (i ^ i / 32) % 32: the MMA lanes (32 consecutive i),
-  // the loaders (i = 4 c + e over 32 c) and the column readers (i = 8 c + e over 16 c)
-  // all spread over the banks with at most two-way conflicts.
-  auto cell = [&](int il, int jl) -> char * {
-    return lds_c + TILE + il * 512 + ((((jl >> 2) ^ il ^ (il >> 5)) & 31) << 4) + ((jl & 3) << 2);
+  // The fp32 tile sits in LDS as the matrix does in memory, [j][i] with 512-byte rows: the
+  // loaders and the storers move whole rows, and an MMA lane owns four consecutive i of one j
+  // (the A-side fragment is the first MFMA operand here).  The 16-byte piece i / 4 of row j
+  // sits at piece (i / 4) ^ (j % 32): the MMA lanes (32 consecutive j, one piece) spread over
+  // all banks, a row's pieces stay a permutation of the row.
+  auto cell = [&](int jl, int il) -> char * {
+    return lds_c + TILE + jl * 512 + ((((il >> 2) ^ jl) & 31) << 4) + ((il & 3) << 2);
   };
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
@@ -757,13 +757,13 @@ __global__ __launch_bounds__(512) void update3_kernel(Update2Args g) {
                 if (prefetch) issue_one(pk, pstage, s * 2 + (m >> 1));
                 __builtin_amdgcn_sched_barrier(0);
               }
-              acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fb[cur][b]),
-                                                                  __builtin_bit_cast(bf16x8, fa[cur][a]), acc[a][b], 0, 0, 0);
+              acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, fa[cur][a]),
+                                                                  __builtin_bit_cast(bf16x8, fb[cur][b]), acc[a][b], 0, 0, 0);
             }
         }
       }
       // end of the tile: the loaders' fp32 tile is in; add eta * acc in place.  Elements
-      // 4 q .. 4 q + 3 of fragment (a, b) are j = 8 q + 4 h .. + 3 of column i = lane % 32.
+      // 4 q .. 4 q + 3 of fragment (a, b) are i = 8 q + 4 h .. + 3 of row j = lane % 32.
       lds_barrier();
       // all sixteen reads first: read, add, write one piece at a time is sixteen LDS round trips
       // in a row (the compiler keeps their order: it cannot tell that the pieces are distinct)
@@ -774,7 +774,7 @@ __global__ __launch_bounds__(512) void update3_kernel(Update2Args g) {
         for (int b = 0; b < 2; ++b)
 #pragma unroll
           for (int q = 0; q < 4; ++q)
-            w[a][b][q] = *reinterpret_cast<const f32x4 *>(cell((wi * 2 + a) * 32 + l32, (wj * 2 + b) * 32 + 8 * q + 4 * h));
+            w[a][b][q] = *reinterpret_cast<const f32x4 *>(cell((wj * 2 + b) * 32 + l32, (wi * 2 + a) * 32 + 8 * q + 4 * h));
 #pragma unroll
       for (int a = 0; a < 2; ++a)
 #pragma unroll
@@ -786,7 +786,7 @@ __global__ __launch_bounds__(512) void update3_kernel(Update2Args g) {
               w[a][b][q][e] += g.eta * acc[a][b][4 * q + e];
               acc[a][b][4 * q + e] = 0.f;
             }
-            *reinterpret_cast<f32x4 *>(cell((wi * 2 + a) * 32 + l32, (wj * 2 + b) * 32 + 8 * q + 4 * h)) = w[a][b][q];
+            *reinterpret_cast<f32x4 *>(cell((wj * 2 + b) * 32 + l32, (wi * 2 + a) * 32 + 8 * q + 4 * h)) = w[a][b][q];
           }
       if (!more) break;
       ti = nti; tj = ntj;
@@ -816,14 +816,9 @@ __global__ __launch_bounds__(512) void update3_kernel(Update2Args g) {
     f32x4 old[32];                            // native vectors: an array of HIP's float4 struct ends up in scratch here
     if (DBG & 128)
       for (int n = 0; n < 32; ++n) old[n] = f32x4{0.f, 0.f, 0.f, 0.f};
-    char *rowbase[4];
-    int fe[4];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      const int il = 4 * (v & 31) + e;
-      rowbase[e] = lds_c + TILE + il * 512 + ((v >> 5) << 2);
-      fe[e] = (il ^ (il >> 5)) & 31;
-    }
+    // item n goes to row 4 n + v / 32, piece (v % 32) ^ (row % 32) = ((v % 32) ^ (v / 32)) ^ (4 n % 32)
+    char *const wbase = lds_c + TILE + (v >> 5) * 512;
+    int wpiece = (((v & 31) ^ (v >> 5)) << 4);
     auto request_group = [&](int gq, int rti, int rtj) {
       if (DBG & 129) return;
       if ((rti + 1) * 128 <= g.I && (rtj + 1) * 128 <= g.J) {
@@ -849,17 +844,14 @@ __global__ __launch_bounds__(512) void update3_kernel(Update2Args g) {
     auto write_group = [&](int gq) {
       if (DBG & 257) return;
 #if CN_DEVICE_ASM
-      // recompute the 32 addresses of a group here: hoisted out of the tile loop they cost 128 registers
-#pragma unroll
-      for (int e = 0; e < 4; ++e) asm volatile("" : "+v"(fe[e]));
+      // recompute the addresses of a group here: hoisted out of the tile loop they cost 32 registers
+      asm volatile("" : "+v"(wpiece));
 #endif
 #pragma unroll
-      for (int n8 = 0; n8 < 8; ++n8)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int n = gq * 8 + n8;
-          *reinterpret_cast<float *>(rowbase[e] + ((n ^ fe[e]) << 4)) = old[n][e];
-        }
+      for (int n8 = 0; n8 < 8; ++n8) {
+        const int n = gq * 8 + n8;
+        *reinterpret_cast<f32x4 *>(wbase + 2048 * n + (wpiece ^ (((4 * n) & 31) << 4))) = old[n];
+      }
     };
 #pragma unroll
     for (int gq = 0; gq < 4; ++gq) request_group(gq, ti, tj);
@@ -898,14 +890,9 @@ __global__ __launch_bounds__(512) void update3_kernel(Update2Args g) {
   int pti = 0, ptj = 0;                       // tile being stored (one behind the MMA role)
   // quarters 0, 1 (rows 0 .. 63 and 64 .. 127 of the tile): fp32 matrix and its bf16 copy;
   // item k is row j = 8 k + v / 16, columns i = 8 (v % 16) .. + 7
-  char *rowA[8];
-  int feA[8];
-#pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    const int il = 8 * (v & 15) + e;
-    rowA[e] = lds_c + TILE + il * 512 + (((v >> 4) & 3) << 2);
-    feA[e] = ((((il ^ (il >> 5)) & 31) ^ (v >> 6)) << 4);
-  }
+  // its two pieces are 2 (v % 16) and 2 (v % 16) + 1, at (piece ^ row % 32) = ((2 (v % 16)) ^ (v / 16)) ^ (8 k % 32) (^ 1)
+  const char *const rbase = lds_c + TILE + (v >> 4) * 512;
+  int rpiece = (((2 * (v & 15)) ^ (v >> 4)) << 4);
   // qt: rows 64 qt .. 64 qt + 63 of the tile; hsel: -1 all of them, 0 / 1 one half (four of the eight row groups)
   auto quarter = [&](int qt, int hsel = -1) {
     if (DBG & 513) return;
@@ -914,9 +901,10 @@ __global__ __launch_bounds__(512) void update3_kernel(Update2Args g) {
     const bool interior = (pti + 1) * 128 <= g.I && (ptj + 1) * 128 <= g.J;
     {
 #if CN_DEVICE_ASM
-#pragma unroll
-      for (int e = 0; e < 8; ++e) asm volatile("" : "+v"(feA[e]));
+      asm volatile("" : "+v"(rpiece));
 #endif
+      // byte offset of item k's first piece from rbase; the second piece is that offset ^ 16
+      auto piece0 = [&](int k) -> int { return 4096 * k + (rpiece ^ (((8 * k) & 31) << 4)); };
       const int j0 = ptj * 128 + (v >> 4), i = pti * 128 + (v & 15) * 8;
       float *const pw = g.W + (long)j0 * g.ldw + i;
       __bf16 *const pb = g.Wb + (long)j0 * g.ldWb + i;
@@ -924,16 +912,17 @@ __global__ __launch_bounds__(512) void update3_kernel(Update2Args g) {
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
           if (hsel >= 0 && half != hsel) continue;
-          float c[4][8];
+          f32x4 c[4][2];
 #pragma unroll
-          for (int k4 = 0; k4 < 4; ++k4)
-#pragma unroll
-            for (int e = 0; e < 8; ++e)
-              c[k4][e] = *reinterpret_cast<const float *>(rowA[e] + (feA[e] ^ (32 * (qt * 8 + half * 4 + k4))));
+          for (int k4 = 0; k4 < 4; ++k4) {
+            const int o = piece0(qt * 8 + half * 4 + k4);
+            c[k4][0] = *reinterpret_cast<const f32x4 *>(rbase + o);
+            c[k4][1] = *reinterpret_cast<const f32x4 *>(rbase + (o ^ 16));
+          }
 #pragma unroll
           for (int k4 = 0; k4 < 4; ++k4) {
             const int k = qt * 8 + half * 4 + k4;
-            const f32x4 w0 = {c[k4][0], c[k4][1], c[k4][2], c[k4][3]}, w1 = {c[k4][4], c[k4][5], c[k4][6], c[k4][7]};
+            const f32x4 w0 = c[k4][0], w1 = c[k4][1];
             const u32x4 pk = {pack2_bf16(w0[0], w0[1]), pack2_bf16(w0[2], w0[3]), pack2_bf16(w1[0], w1[1]), pack2_bf16(w1[2], w1[3])};
             if (!(DBG & 36)) {
               *reinterpret_cast<f32x4 *>(pw + (long)(8 * k) * g.ldw) = w0;
@@ -947,10 +936,10 @@ __global__ __launch_bounds__(512) void update3_kernel(Update2Args g) {
 #pragma unroll 2
       for (int k8 = (hsel == 1 ? 4 : 0); k8 < (hsel == 0 ? 4 : 8); ++k8) {
         const int k = qt * 8 + k8;
-        float c[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) c[e] = *reinterpret_cast<const float *>(rowA[e] + (feA[e] ^ (32 * k)));
-        float4 w0 = make_float4(c[0], c[1], c[2], c[3]), w1 = make_float4(c[4], c[5], c[6], c[7]);
+        const int o = piece0(k);
+        const f32x4 c0 = *reinterpret_cast<const f32x4 *>(rbase + o);
+        const f32x4 c1 = *reinterpret_cast<const f32x4 *>(rbase + (o ^ 16));
+        float4 w0 = make_float4(c0[0], c0[1], c0[2], c0[3]), w1 = make_float4(c1[0], c1[1], c1[2], c1[3]);
         const int j = j0 + 8 * k;
         const bool in0 = j < g.J && i < g.I, in1 = j < g.J && i + 4 < g.I;
         if (!in0) w0 = make_float4(0.f, 0.f, 0.f, 0.f);
