@@ -192,6 +192,9 @@ int codenet_encode(const codenet_desc *d, const float *W_dev, void *stream, code
   // fp32 coded vectors [x; x~], [delta; delta~]: operands of the f32 kernels only
   alloc((void **)&l->Xt, l->bf16 ? 0 : sizeof(float) * mb * l->Nc);
   alloc((void **)&l->Dt, l->bf16 ? 0 : sizeof(float) * mb * l->Mr);
+  // split-k workspace of the f32 products: thin batches only (their tiles do not fill the chip)
+  if (!l->bf16 && mb <= 256)
+    alloc((void **)&l->part, sizeof(float) * (size_t)kMaxSplits * mb * std::max(l->Mr, l->Nc));
   alloc((void **)&l->syn, sizeof(float) * (size_t)rmax * mb * bmax);
   alloc((void **)&l->partials, sizeof(double) * (size_t)kDetectParts * kMaxEntries);
   alloc((void **)&l->fault_partials, sizeof(double) * (size_t)CODENET_MAX_FAULTS * kFaultParts);
@@ -290,6 +293,7 @@ int codenet_forward(codenet_layer *l, const float *X_dev, int b, float *S_coded_
   g.C = S_coded_dev; g.ldc = l->Mr;
   g.I = l->Mr; g.J = b; g.K = l->code_c.a * l->code_c.B;
   g.alpha = 1.f;
+  g.workspace = l->part; g.max_splits = kMaxSplits;
   CN_HIP(launch_gemm(kFwd, l->bf16, g, s));
   l->fwd_b = b;
   return CODENET_OK;
@@ -321,6 +325,7 @@ int codenet_backward(codenet_layer *l, const float *D_dev, int b, float *C_coded
   g.C = C_coded_dev; g.ldc = l->Nc;
   g.I = l->Nc; g.J = b; g.K = l->code_r.a * l->code_r.B;
   g.alpha = 1.f;
+  g.workspace = l->part; g.max_splits = kMaxSplits;
   CN_HIP(launch_gemm(kBwd, l->bf16, g, s));
   l->bwd_b = b;
   return CODENET_OK;

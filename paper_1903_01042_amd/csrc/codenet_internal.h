@@ -37,7 +37,13 @@ struct GemmArgs {
   int I, J, K;
   float alpha;                  // accumulate variant: C += alpha * A B^T
   int tiles_i, tiles_j;
+  // split-k (products of thin batches): with a workspace of max_splits x J x ldc floats the launcher
+  // may cut the contraction in pieces whose partial results are then added in split order
+  float *workspace; int max_splits;
+  int splits; long split_stride;   // set by the launcher
 };
+// out[idx] = sum over s < splits of part[s * stride + idx], in split order (count a multiple of 4)
+hipError_t launch_reduce_partials(const float *part, long stride, int splits, float *out, long count, hipStream_t s);
 
 enum GemmLayout { kFwd = 0, kBwd = 1, kUpd = 2 };
 // fwd: A k-contiguous, B k-contiguous, C = A B^T

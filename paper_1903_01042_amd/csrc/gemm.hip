@@ -132,11 +132,12 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
   // Workgroup -> tile.  Consecutive workgroup ids go to different XCDs (8 of
   // them, one L2 each); give each XCD a contiguous run of tiles so that tiles
   // sharing an operand panel share an L2.
-  const int nt = g.tiles_i * g.tiles_j;
+  const int nt = g.tiles_i * g.tiles_j * g.splits;
   const int per = (nt + 7) >> 3;
   const int logical = (int)(blockIdx.x & 7) * per + (int)(blockIdx.x >> 3);
   if (logical >= nt) return;
-  const int tj = logical % g.tiles_j, ti = logical / g.tiles_j;
+  const int split = logical % g.splits, tile = logical / g.splits;
+  const int tj = tile % g.tiles_j, ti = tile / g.tiles_j;
   const int i0 = ti * TI, j0 = tj * TJ;
 
   const int tid = threadIdx.x;
@@ -155,15 +156,17 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.f;
 
-  const int nk = (g.K + KT - 1) / KT;
-  la.load(g.A, g.lda, i0, g.I, 0, g.K, tid);
-  lb.load(g.B, g.ldb, j0, g.J, 0, g.K, tid);
+  // this workgroup's share of the slabs (all of them unless the contraction is split)
+  const int nk_all = (g.K + KT - 1) / KT;
+  const int kb = (int)((long)split * nk_all / g.splits), nk = (int)((long)(split + 1) * nk_all / g.splits);
+  la.load(g.A, g.lda, i0, g.I, kb * KT, g.K, tid);
+  lb.load(g.B, g.ldb, j0, g.J, kb * KT, g.K, tid);
   la.store(lds, tid);
   lb.store(lds + TI * 8, tid);
   __syncthreads();
 
-  for (int kt = 0; kt < nk; ++kt) {
-    const int cur = kt & 1;
+  for (int kt = kb; kt < nk; ++kt) {
+    const int cur = (kt - kb) & 1;
     if (kt + 1 < nk) {
       la.load(g.A, g.lda, i0, g.I, (kt + 1) * KT, g.K, tid);
       lb.load(g.B, g.ldb, j0, g.J, (kt + 1) * KT, g.K, tid);
@@ -210,7 +213,54 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
   }
 
   // Accumulator element 4 g + e of a 32 x 32 tile is (i = 8 g + 4 h + e, j = lane % 32):
-  // four consecutive i per lane, stored as one float4 of C[j][i..i+3].
+  // four consecutive i per lane.
+  if (ACCUM) {
+    // Read-modify-write of C through an LDS copy of the tile, so that every global access is a
+    // whole row segment (a wavefront instruction moves 1 KB of one or a few rows).  Straight from
+    // the accumulators, a lane's float4 is a 16-byte piece of its own row: 64 rows per
+    // instruction, every 128-byte line requested eight times -- the 18432 x 18432 update of a
+    // batch of 64 spent 1.07 ms on 170 M such requests.
+    constexpr int PITCH = TI + 4;                          // floats; 16-byte aligned rows, skewed banks
+    float *tile = reinterpret_cast<float *>(lds);          // the operand stages are free (barrier above)
+#pragma unroll
+    for (int a = 0; a < FM; ++a)
+#pragma unroll
+      for (int b = 0; b < FN; ++b) {
+        const int jl = (wj * FN + b) * 32 + l32;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int il = (wi * FM + a) * 32 + 8 * q + 4 * h;
+          *reinterpret_cast<float4 *>(tile + jl * PITCH + il) =
+              make_float4(acc[a][b][4 * q], acc[a][b][4 * q + 1], acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]);
+        }
+      }
+    __syncthreads();
+    constexpr int QPR = TI / 4;                            // float4 per tile row
+    constexpr int PASSES = TJ * QPR / 256;
+    constexpr int CH = PASSES < 8 ? PASSES : 8;            // accesses in flight per thread
+    static_assert(TJ * QPR % 256 == 0 && PASSES % CH == 0, "tile rows divide among the threads");
+    for (int p0 = 0; p0 < PASSES; p0 += CH) {
+      float4 o[CH], v[CH];
+#pragma unroll
+      for (int u = 0; u < CH; ++u) {
+        const int idx = tid + 256 * (p0 + u);
+        const int jl = idx / QPR, il = (idx % QPR) * 4;
+        const bool in = j0 + jl < g.J && i0 + il < g.I;
+        o[u] = in ? *reinterpret_cast<const float4 *>(g.C + (long)(j0 + jl) * g.ldc + i0 + il) : make_float4(0.f, 0.f, 0.f, 0.f);
+        v[u] = *reinterpret_cast<const float4 *>(tile + jl * PITCH + il);
+      }
+#pragma unroll
+      for (int u = 0; u < CH; ++u) {
+        const int idx = tid + 256 * (p0 + u);
+        const int jl = idx / QPR, il = (idx % QPR) * 4;
+        if (j0 + jl < g.J && i0 + il < g.I)
+          *reinterpret_cast<float4 *>(g.C + (long)(j0 + jl) * g.ldc + i0 + il) =
+              make_float4(o[u].x + g.alpha * v[u].x, o[u].y + g.alpha * v[u].y, o[u].z + g.alpha * v[u].z,
+                          o[u].w + g.alpha * v[u].w);
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int a = 0; a < FM; ++a)
 #pragma unroll
@@ -221,15 +271,8 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
       for (int q = 0; q < 4; ++q) {
         const int i = i0 + (wi * FM + a) * 32 + 8 * q + 4 * h;
         if (i >= g.I) continue;
-        float4 *dst = reinterpret_cast<float4 *>(g.C + (long)j * g.ldc + i);
-        float4 v = make_float4(acc[a][b][4 * q], acc[a][b][4 * q + 1], acc[a][b][4 * q + 2],
-                               acc[a][b][4 * q + 3]);
-        if (ACCUM) {
-          const float4 o = *dst;
-          v = make_float4(o.x + g.alpha * v.x, o.y + g.alpha * v.y, o.z + g.alpha * v.z,
-                          o.w + g.alpha * v.w);
-        }
-        *dst = v;
+        *reinterpret_cast<float4 *>(g.C + (long)split * g.split_stride + (long)j * g.ldc + i) =
+            make_float4(acc[a][b][4 * q], acc[a][b][4 * q + 1], acc[a][b][4 * q + 2], acc[a][b][4 * q + 3]);
       }
     }
 }
@@ -239,10 +282,14 @@ namespace {
 struct TileChoice { int fm, fn; double eff; };
 const TileChoice kTiles[] = {{4, 2, 1.00}, {2, 2, 0.95}, {2, 1, 0.80}, {1, 2, 0.80}, {1, 1, 0.60}};
 
-int pick_tile(const GemmArgs &g) {
+int pick_tile(const GemmArgs &g, bool accum) {
   // Cheapest estimated time: rounds of resident workgroups x tile area / tile efficiency.
   const char *env = getenv("CODENET_GEMM_TILE");
   if (env && env[0] >= '0' && env[0] <= '4') return env[0] - '0';
+  // A short contraction into a large C (the update of a thin batch) is a read-modify-write of C:
+  // 128 x 128 tiles, two workgroups per CU, so that one's contraction hides the other's memory
+  // latency (18432 x 18432, batch 64: 733 us against 922 us with 256 x 128 and 813 us with 64 x 64).
+  if (accum && g.K <= 256 && g.I >= 1024 && g.J >= 1024) return 1;
   int best = 0;
   double best_cost = 1e300;
   for (int t = 0; t < 5; ++t) {
@@ -260,10 +307,30 @@ int pick_tile(const GemmArgs &g) {
 template <bool BF16, int FM, int FN, bool AKC, bool BKC, bool ACCUM>
 hipError_t launch_one(GemmArgs g, hipStream_t s) {
   constexpr int TI = 64 * FM, TJ = 64 * FN;
-  constexpr int lds = 2 * (TI + TJ) * 128;
+  constexpr int stages = 2 * (TI + TJ) * 128, ctile = ACCUM ? TJ * (TI + 4) * 4 : 0;
+  constexpr int lds = stages > ctile ? stages : ctile;
+  static_assert(lds <= 160 * 1024, "the tile of C does not fit in LDS");
   g.tiles_i = (g.I + TI - 1) / TI;
   g.tiles_j = (g.J + TJ - 1) / TJ;
-  const int nt = g.tiles_i * g.tiles_j;
+  // Split-k for products whose tiles do not fill the chip while the contraction is long (thin
+  // batches: the kernel then streams the matrix, and a workgroup keeps only one 128-byte slab per
+  // row in flight): enough pieces for about eight workgroups per CU, at least 16 slabs each.
+  float *final_out = g.C;
+  g.splits = 1;
+  g.split_stride = 0;
+  constexpr int KT = BF16 ? 64 : 32;
+  const int tiles = g.tiles_i * g.tiles_j, slabs = (g.K + KT - 1) / KT;
+  if (!ACCUM && g.workspace != nullptr && tiles < 512 && slabs >= 64) {
+    int sp = (2048 + tiles - 1) / tiles;
+    if (sp > slabs / 16) sp = slabs / 16;
+    if (sp > g.max_splits) sp = g.max_splits;
+    if (sp > 1) {
+      g.splits = sp;
+      g.split_stride = (long)g.J * g.ldc;
+      g.C = g.workspace;
+    }
+  }
+  const int nt = tiles * g.splits;
   const int grid = ((nt + 7) / 8) * 8;
   auto kern = gemm_kernel<BF16, FM, FN, AKC, BKC, ACCUM>;
   static bool attr_done = false;
@@ -274,12 +341,14 @@ hipError_t launch_one(GemmArgs g, hipStream_t s) {
     attr_done = true;
   }
   hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, s, g);
-  return hipGetLastError();
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || g.splits == 1) return e;
+  return launch_reduce_partials(g.workspace, g.split_stride, g.splits, final_out, g.split_stride, s);
 }
 
 template <bool BF16, bool AKC, bool BKC, bool ACCUM>
 hipError_t launch_layout(const GemmArgs &g, hipStream_t s) {
-  switch (pick_tile(g)) {
+  switch (pick_tile(g, ACCUM)) {
     case 0: return launch_one<BF16, 4, 2, AKC, BKC, ACCUM>(g, s);
     case 1: return launch_one<BF16, 2, 2, AKC, BKC, ACCUM>(g, s);
     case 2: return launch_one<BF16, 2, 1, AKC, BKC, ACCUM>(g, s);

@@ -1114,10 +1114,14 @@ hipError_t launch_gemm2(Gemm2Args g, int tile, float *workspace, hipStream_t s) 
     default: e = launch2<2, 4, 3>(g, s); break;
   }
   if (e != hipSuccess || g.splits == 1) return e;
-  const long count4 = g.split_stride / 4;
+  return launch_reduce_partials(workspace, g.split_stride, g.splits, final_out, g.split_stride, s);
+}
+
+hipError_t launch_reduce_partials(const float *part, long stride, int splits, float *out, long count, hipStream_t s) {
+  if ((stride & 3) || (count & 3) || splits < 1) return hipErrorInvalidValue;
+  const long count4 = count / 4;
   hipLaunchKernelGGL(reduce_partials_kernel, dim3((unsigned)((count4 + 255) / 256)), dim3(256), 0, s,
-                     reinterpret_cast<const float4 *>(workspace), count4, g.splits,
-                     reinterpret_cast<float4 *>(final_out), count4);
+                     reinterpret_cast<const float4 *>(part), stride / 4, splits, reinterpret_cast<float4 *>(out), count4);
   return hipGetLastError();
 }
 
