@@ -30,7 +30,8 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg3", "cfg5"])
+    ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg3", "cfg4", "cfg5"],
+                    help="cfg4: one layer (the first) of that 8-layer workload")
     ap.add_argument("--cpu-steps", type=int, default=40, help="oracle layer-steps timed for cpu_baseline (0 = skip)")
     ap.add_argument("--no-faults", action="store_true", help="run the coded path without injecting faults")
     ap.add_argument("--coded-only", action="store_true", help="skip the uncoded baseline and the CPU oracle (profiling runs)")
