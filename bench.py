@@ -28,8 +28,8 @@ MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=1000)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg3", "cfg4", "cfg5"],
                     help="cfg4: one layer (the first) of that 8-layer workload")
     ap.add_argument("--cpu-steps", type=int, default=40, help="oracle layer-steps timed for cpu_baseline (0 = skip)")
