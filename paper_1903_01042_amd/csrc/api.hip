@@ -17,18 +17,18 @@ struct codenet_layer {
   DevCode *code_r_dev = nullptr, *code_c_dev = nullptr;
   int Mr = 0, Nc = 0;           // coded sizes
   float *Wt = nullptr;          // [Mr][Nc]
-  float *Xt = nullptr;          // [max_batch][Nc]   cached [x; x~]
-  float *Dt = nullptr;          // [max_batch][Mr]   cached [delta; delta~]
+  float *Xt = nullptr;          // [max_batch][Nc]   cached [x; x~]          (f32 mode only)
+  float *Dt = nullptr;          // [max_batch][Mr]   cached [delta; delta~]  (f32 mode only)
   float *syn = nullptr;         // [max r][max_batch][max B]
   double *partials = nullptr;   // [kDetectParts][kMaxEntries]
   double *fault_partials = nullptr;   // [CODENET_MAX_FAULTS][kFaultParts]
-  // bf16 mode only: k-contiguous bf16 operands of the two products
+  // bf16 mode only: bf16 operands of the products and of the update
   __bf16 *Wb = nullptr;         // [max(Mr, KpD)][ldWb]  bf16 copy of W~, operand of both products
   __bf16 *Xb = nullptr;         // [max_batch][ldXb]  x, zero beyond the base columns
   __bf16 *Db = nullptr;         // [max_batch][ldDb]  delta, zero beyond the base rows
   __bf16 *XTb = nullptr;        // [Nc][ldT]    feature-major [x; x~] (update)
   __bf16 *DTb = nullptr;        // [Mr][ldT]    feature-major [delta; delta~] (update)
-  float *part = nullptr;        // split-k partial results: [kMaxSplits][max_batch][max(Mr, Nc)]
+  float *part = nullptr;        // split-k partial results: [kMaxSplits][max_batch][max(Mr, Nc)] (bf16 mode; f32 mode at thin batches)
   long ldWb = 0;
   int KpX = 0, KpD = 0, bpad = 0;   // contraction lengths (multiples of 64): base columns, base rows, batch
   long ldXb = 0, ldDb = 0, ldT = 0; // pitches of Xb, Db and of XTb / DTb
