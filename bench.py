@@ -111,7 +111,8 @@ class Runner:
 
     STAMP_EVERY = 4     # steps whose update kernel is bracketed by two device time stamps
     EVENT_EVERY = 20    # graph replay: steps (s % EVENT_EVERY == 10) whose update is launched on its own between two HIP events
-    EAGER_EVENT_EVERY = 4   # plain stream: steps (s % EAGER_EVENT_EVERY == 2) whose update sits between two HIP events
+    EAGER_EVENT_EVERY = 16  # plain stream: steps (s % EAGER_EVENT_EVERY == 2) whose update sits between two HIP events
+                            # (a pair of records costs the stream several us: see roofline.empty_event_pair_ms)
 
     def update(self, s, stream):
         """The update of step s; on every STAMP_EVERY-th step between two device time stamps."""
@@ -190,6 +191,13 @@ class Runner:
         for s in range(warmup):
             one(s)
         torch.cuda.synchronize()
+        # what a pair of event records reads with nothing between them (their own cost on this stream)
+        pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(20)]
+        for a, b in pairs:
+            a.record()
+            b.record()
+        torch.cuda.synchronize()
+        self.event_pair_ms = float(np.median([a.elapsed_time(b) for a, b in pairs]))
         t0 = time.perf_counter()
         for s in range(steps):
             one(warmup + s)
@@ -378,6 +386,7 @@ def main():
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(args.workload),
                      "avg_launch_ms": launch_ms,
+                     "empty_event_pair_ms": coded.event_pair_ms,
                      "avg_launch_ms_by": ("HIP events around the kernel on every %d-th step of the timed region, "
                                           "where the step's graph ends before the update and the kernel is launched "
                                           "on its own" % Runner.EVENT_EVERY) if args.graph else
