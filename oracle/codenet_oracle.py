@@ -22,7 +22,9 @@ Pins (tests/test_oracle_*.py): the paper's worked example for m = n = 2, t = 1
 update and regeneration), H G^T = 0, brute-force MDS / spark enumeration,
 element-wise triple-loop evaluation of the Kronecker encoding, decoded output
 equal to the textbook product, T coded updates equal to encode(T plain
-updates), and exhaustive enumeration of error supports on tiny grids.
+updates), exhaustive enumeration of error supports on tiny grids, and for the
+verification steps of Error Model 2: agreement reproduces the plain check, any
+planted difference in any evaluator gives DISAGREE with the output untouched.
 Parity unpinned by the paper (fixed by this build's readings, documented in
 the design notes): the relative thresholds tau_detect / tau_resid, the noise
 law of the fault injector and its counter hash, zero padding.
@@ -31,7 +33,7 @@ import itertools
 
 import numpy as np
 
-CLEAN, CORRECTED, UNCORRECTABLE = 0, 1, 2
+CLEAN, CORRECTED, UNCORRECTABLE, DISAGREE = 0, 1, 2, 3
 PHASE_FWD, PHASE_BWD, PHASE_WEIGHT = 0, 1, 2
 MODE_DENSE_REL, MODE_SPARSE_ABS = 0, 1
 
@@ -251,6 +253,70 @@ def detect_decode(out, P, B, tau_detect, tau_resid):
 
 
 # --------------------------------------------------------------------------
+# Verification steps of Error Model 2 (decentralized implementation:
+# "Errors in Error-Detection" and "Errors in decoding")
+# --------------------------------------------------------------------------
+def verified_detect_decode(out, P, B, tau_detect, tau_resid, evaluators=2,
+                           check_faults=(), list_faults=()):
+    """The check of one coded output when the checking itself is error-prone.
+
+    Every one of `evaluators` evaluators works out the r consistency checks
+    (H (x) I) out and the list of erroneous nodes for itself.
+    Verification step 1: the evaluations of the checks are exchanged and
+    compared; verification step 2: the lists of erroneous nodes (with the
+    verdict they come with) are exchanged and compared.  The comparisons are
+    exact and are themselves taken to be error-free.  Any disagreement gives
+    the verdict DISAGREE and leaves `out` untouched (the paper then restores
+    the network from the last checkpoint); full agreement gives exactly what
+    detect_decode gives.
+
+    Planted errors, for tests of the two steps:
+      check_faults: (evaluator, k, scale) -- that evaluator's check k becomes
+                    (1 + scale) * check + scale;
+      list_faults:  (evaluator,) -- that evaluator's first erroneous node is
+                    replaced by the next block (a CORRECTED verdict), or its
+                    verdict flips between CLEAN and UNCORRECTABLE.
+    """
+    out = np.array(out, dtype=np.float64)
+    H = parity_check(P)
+    r, L = H.shape
+    b = out.shape[1]
+    blocks = np.stack([out[i * B:(i + 1) * B].reshape(-1) for i in range(L)])
+    disagree = dict(verdict=DISAGREE, located=[], out=out.copy(),
+                    syn_rel=np.zeros(r), resid_rel=0.0)
+    # step 1: every evaluator's evaluation of the r checks
+    evaluations = []
+    for v in range(evaluators):
+        syn = H @ blocks
+        for who, k, scale in check_faults:
+            if who == v:
+                syn[k] = (1.0 + scale) * syn[k] + scale
+        evaluations.append(syn)
+    for syn in evaluations[1:]:
+        if not np.array_equal(syn, evaluations[0]):
+            return disagree
+    # step 2: every evaluator's verdict and list of erroneous nodes
+    lists = []
+    result = None
+    for v in range(evaluators):
+        res = detect_decode(out, P, B, tau_detect, tau_resid)
+        verdict, located = res["verdict"], list(res["located"])
+        for (who,) in list_faults:
+            if who == v:
+                if verdict == CORRECTED:
+                    located[0] = (located[0] + 1) % L
+                else:
+                    verdict = UNCORRECTABLE if verdict == CLEAN else CLEAN
+        lists.append((verdict, tuple(located)))
+        if v == 0:
+            result = res
+    for entry in lists[1:]:
+        if entry != lists[0]:
+            return disagree
+    return result
+
+
+# --------------------------------------------------------------------------
 # Coded update (O3 with the three block rules; the corner is one more block
 # updated by the same rule when it is stored)
 # --------------------------------------------------------------------------
@@ -457,6 +523,14 @@ class CodedLayer:
         else:
             res = detect_decode(coded_out, self.P_c, self.Bc, self.tau_detect, self.tau_resid)
             res["decoded"] = unpad_blocks(res["out"][: self.n * self.Bc], self.N_in, self.n, self.Bc)
+        return res
+
+    def verified_detect_decode(self, phase, coded_out, evaluators=2, check_faults=(), list_faults=()):
+        P, B, N, a = ((self.P_r, self.Br, self.N_out, self.m) if phase == PHASE_FWD
+                      else (self.P_c, self.Bc, self.N_in, self.n))
+        res = verified_detect_decode(coded_out, P, B, self.tau_detect, self.tau_resid,
+                                     evaluators, check_faults, list_faults)
+        res["decoded"] = unpad_blocks(res["out"][: a * B], N, a, B)
         return res
 
     def regenerate(self, phase, located):

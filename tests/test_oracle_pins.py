@@ -526,3 +526,54 @@ def test_weight_fault_laws():
     nz = np.count_nonzero(d)
     assert np.count_nonzero(d[:200, 200:400]) == nz and 100 < nz < 320       # 0.005 * 40000 = 200
     assert np.abs(d).max() < 5.0
+
+
+# ------------------------------------------------- verification steps (Error Model 2)
+def _coded_output(a, r, B, b, seed):
+    P = WL.vandermonde_like(a, r, nodes="spread")
+    g = np.random.default_rng(seed)
+    base = g.standard_normal((a * B, b))
+    return P, O.encode_vector(base, P, B)
+
+
+@pytest.mark.parametrize("n_err,verdict", [(0, O.CLEAN), (1, O.CORRECTED), (2, O.UNCORRECTABLE)])
+def test_verification_with_agreement_is_the_plain_check(n_err, verdict):
+    """Decentralized implementation, "Errors in Error-Detection" / "Errors in decoding" under
+    Error Model 2: if all evaluators agree the algorithm moves forward -- same verdict, same
+    located nodes and same repaired output as the check without verification."""
+    a, r, B, b = 4, 2, 6, 3
+    P, out = _coded_output(a, r, B, b, 5)
+    for i in range(n_err):
+        out[(1 + 2 * i) * B:(2 + 2 * i) * B] += rng.standard_normal((B, b))
+    plain = O.detect_decode(out, P, B, 1e-9, 1e-6)
+    ver = O.verified_detect_decode(out, P, B, 1e-9, 1e-6, evaluators=5)
+    assert plain["verdict"] == verdict == ver["verdict"]
+    assert plain["located"] == ver["located"]
+    assert np.array_equal(plain["out"], ver["out"])
+
+
+@pytest.mark.parametrize("n_err", [0, 1, 2])
+@pytest.mark.parametrize("who", [0, 1, 3])
+def test_any_disagreement_stops_the_step_and_leaves_the_output(n_err, who):
+    """The same passages: a difference in one evaluator's consistency checks (step 1) or in its
+    list of erroneous nodes (step 2) is a disagreement, whatever the state of the product and
+    whichever evaluator it is; nothing is corrected then (the network is restored instead)."""
+    a, r, B, b = 4, 2, 6, 3
+    P, out = _coded_output(a, r, B, b, 6)
+    for i in range(n_err):
+        out[(2 * i) * B:(1 + 2 * i) * B] += rng.standard_normal((B, b))
+    for kw in (dict(check_faults=[(who, 1, 0.25)]), dict(list_faults=[(who,)])):
+        ver = O.verified_detect_decode(out, P, B, 1e-9, 1e-6, evaluators=4, **kw)
+        assert ver["verdict"] == O.DISAGREE and ver["located"] == []
+        assert np.array_equal(ver["out"], out)
+
+
+def test_the_same_error_in_every_evaluator_is_not_a_disagreement():
+    """Comparing evaluations only finds errors that differ between evaluators: identical
+    corruption of every evaluation passes step 1 (the lists, taken from the output itself in
+    this model, agree as well)."""
+    a, r, B, b = 3, 2, 4, 2
+    P, out = _coded_output(a, r, B, b, 7)
+    ver = O.verified_detect_decode(out, P, B, 1e-9, 1e-6, evaluators=3,
+                                   check_faults=[(v, 0, 0.5) for v in range(3)])
+    assert ver["verdict"] == O.CLEAN
