@@ -47,7 +47,7 @@ class Runner:
 
     RING = 8
 
-    def __init__(self, wl, coded, faults_on, total_steps):
+    def __init__(self, wl, coded, faults_on, total_steps, verified=False):
         import torch
         from paper_1903_01042_amd import binding as B
         from paper_1903_01042_amd import workloads as WL
@@ -58,6 +58,7 @@ class Runner:
         m, n = wl.grid
         self.b = wl.batch
         self.coded = coded
+        self.verified = verified   # checks with the verification steps of Error Model 2
         W = torch.from_numpy(WL.layer_weights(n_out, n_in)).to(dev)
         if coded:
             P_r, P_c = wl.generators()
@@ -93,19 +94,23 @@ class Runner:
         """forward, faults, check, backward, faults, check of step s (everything but the update)."""
         lib, h, b = self.lib, self.h, self.b
         k = s % self.RING
+        if self.verified:
+            def check(phase, coded_out, decoded, report):
+                return lib.codenet_detect_decode_verified(h, phase, coded_out, b, decoded, report, 0, None, stream)
+        else:
+            def check(phase, coded_out, decoded, report):
+                return lib.codenet_detect_decode(h, phase, coded_out, b, decoded, report, stream)
         rc = lib.codenet_forward(h, self.pX[k], b, self.pSt, stream)
         if self.coded:
             (ff, nf), (fb, nb) = self.faults[s]
             if nf:
                 rc |= lib.codenet_inject(h, ff, nf, self.pSt, b, stream)
-            rc |= lib.codenet_detect_decode(h, 0, self.pSt, b, self.pS,
-                                            ctypes.c_void_p(self.reports[s, 0].data_ptr()), stream)
+            rc |= check(0, self.pSt, self.pS, ctypes.c_void_p(self.reports[s, 0].data_ptr()))
         rc |= lib.codenet_backward(h, self.pD[k], b, self.pCt, stream)
         if self.coded:
             if nb:
                 rc |= lib.codenet_inject(h, fb, nb, self.pCt, b, stream)
-            rc |= lib.codenet_detect_decode(h, 1, self.pCt, b, self.pC,
-                                            ctypes.c_void_p(self.reports[s, 1].data_ptr()), stream)
+            rc |= check(1, self.pCt, self.pC, ctypes.c_void_p(self.reports[s, 1].data_ptr()))
         if rc:
             raise RuntimeError("a codenet call failed in step %d (rc=%d)" % (s, rc))
 
@@ -268,7 +273,8 @@ class Runner:
         for s in range(raw.shape[0]):
             for p in range(2):
                 v = B.Report.from_buffer_copy(raw[s, p].tobytes()).verdict
-                counts[["clean", "corrected", "uncorrectable"][v]] += 1
+                name = ["clean", "corrected", "uncorrectable", "disagree"][v]   # the last from verified checks only
+                counts[name] = counts.get(name, 0) + 1
         return counts
 
 
@@ -344,6 +350,11 @@ def main():
         clean = Runner(wl, True, False, total)
         ms_clean, _ = clean.run(args.steps, args.warmup, not args.graph)
         clean.layer.destroy()
+    # the coded step with both verification steps of Error Model 2 in every check
+    ver = Runner(wl, True, not args.no_faults, total, verified=True)
+    ms_verified, _ = ver.run(args.steps, args.warmup, not args.graph)
+    counts_verified = ver.verdict_counts(args.warmup, total)
+    ver.layer.destroy()
 
     L = coded.layer
     upd_events_ms = coded.update_by_events()
@@ -378,6 +389,8 @@ def main():
         "coding_overhead": ms_coded / ms_uncoded - 1.0,
         "ms_per_step_without_injection": ms_clean,
         "coding_overhead_without_injection": (ms_clean / ms_uncoded - 1.0) if ms_clean else None,
+        "ms_per_step_verified_checks": ms_verified,
+        "verified_checks_agree": counts_verified == counts,
         "algorithmic_overhead_floor": floor,
         "verdicts": counts,
         "update_kernel_ms_uncoded": upd_ms_unc if args.graph else uncoded.upd_ms_events,

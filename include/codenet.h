@@ -53,8 +53,11 @@ extern "C" {
 typedef struct codenet_layer codenet_layer;   /* opaque */
 
 typedef enum { CODENET_F32 = 0, CODENET_BF16_F32ACC = 1 } codenet_dtype;
-typedef enum { CODENET_FWD = 0, CODENET_BWD = 1, CODENET_WEIGHT = 2 } codenet_phase;
-typedef enum { CODENET_CLEAN = 0, CODENET_CORRECTED = 1, CODENET_UNCORRECTABLE = 2 } codenet_verdict;
+typedef enum { CODENET_FWD = 0, CODENET_BWD = 1, CODENET_WEIGHT = 2, CODENET_CHECK = 3 } codenet_phase;
+typedef enum { CODENET_CLEAN = 0, CODENET_CORRECTED = 1, CODENET_UNCORRECTABLE = 2,
+               CODENET_DISAGREE = 3 /* codenet_detect_decode_verified only */ } codenet_verdict;
+/* what a CODENET_CHECK fault hits (its `bi`) */
+typedef enum { CODENET_CHECK_EVALUATION = 0, CODENET_CHECK_LIST = 1 } codenet_check_target;
 typedef enum { CODENET_NOISE_DENSE_REL = 0, CODENET_NOISE_SPARSE_ABS = 1 } codenet_noise_mode;
 
 enum {
@@ -97,7 +100,7 @@ typedef struct {
 
 /* One soft error (Error Model 2: additive continuous noise on a node's output). */
 typedef struct {
-  int phase;                /* codenet_phase: product whose output is hit, or WEIGHT (update stage) */
+  int phase;                /* codenet_phase: product whose output is hit, WEIGHT (update stage) or CHECK */
   int bi, bj;               /* node (block-row, block-column) in the coded grid                  */
   int mode;                 /* codenet_noise_mode                                                 */
   uint64_t seed, step;      /* noise is a pure function of (seed, step, phase, bi, bj, element)   */
@@ -146,6 +149,14 @@ int codenet_backward(codenet_layer *layer, const float *D_dev, int b, float *C_c
  * DENSE_REL: every real element gets sign * U[lo, hi) * rms(clean target block);
  * SPARSE_ABS: a fraction `density` of the elements gets U[lo, hi).
  * faults_host: n_faults <= CODENET_MAX_FAULTS entries, host memory.
+ * CHECK (errors in the error detection or in the decoding themselves, Error Model 2;
+ * n_faults must be 1, coded_out_dev and b are ignored): nothing is enqueued; the fault is
+ * kept and planted into the next codenet_detect_decode_verified call on this layer, then
+ * forgotten.  bi = CODENET_CHECK_EVALUATION: one record of evaluation `bj % 2` of the
+ * consistency checks (the partial squared norm of the first check kept by workgroup
+ * `seed % workgroups`) becomes (1 + hi) * record + hi.  bi = CODENET_CHECK_LIST: evaluator
+ * `bj % evaluators` of the decision gets a wrong list (first located node replaced by the
+ * next block) or, with nothing located, a flipped verdict (CLEAN <-> UNCORRECTABLE).
  */
 int codenet_inject(codenet_layer *layer, const codenet_fault *faults_host, int n_faults,
                    float *coded_out_dev, int b, void *stream);
@@ -182,6 +193,28 @@ typedef enum { CODENET_EPI_NONE = 0, CODENET_EPI_RELU = 1, CODENET_EPI_MASK_POS 
 int codenet_detect_decode_act(codenet_layer *layer, int phase, float *coded_out_dev, int b,
                               float *decoded_dev, codenet_report *report_dev, int epilogue,
                               const float *aux_dev, void *stream);
+
+/*
+ * The same check with the two verification steps that the decentralized
+ * implementation adds under Error Model 2 ("Errors in Error-Detection" and
+ * "Errors in decoding": the nodes exchange and compare their evaluations of the
+ * 2t consistency checks, and later their lists of erroneous nodes; any
+ * disagreement means that the checking itself went wrong and the network is
+ * restored from the last checkpoint).  On one GPU: (1) the consistency checks are
+ * evaluated twice, the second time with every partial result computed on another
+ * compute unit, and the two sets of partial results are compared bit for bit;
+ * (2) every workgroup of the correcting kernel takes the decision (verdict and
+ * list of erroneous nodes) for itself and the decisions are compared.  Agreement:
+ * exactly the results of codenet_detect_decode_act.  Disagreement: verdict
+ * CODENET_DISAGREE, n_located 0; after a disagreement in step 1 nothing has been
+ * corrected, after one in step 2 the contents of coded_out_dev and decoded_dev
+ * are unspecified (an evaluator may have acted on its wrong decision) -- either
+ * way the caller restores its checkpoint.  report_dev is required.  With r = 0
+ * there is nothing to verify and the call equals codenet_detect_decode_act.
+ */
+int codenet_detect_decode_verified(codenet_layer *layer, int phase, float *coded_out_dev, int b,
+                                   float *decoded_dev, codenet_report *report_dev, int epilogue,
+                                   const float *aux_dev, void *stream);
 
 /*
  * Update stage (the three block rules, plus the same rule on the corner):

@@ -14,14 +14,16 @@ LIB_PATH = os.path.join(_HERE, "libcodenet.so")
 
 MAX_T, MAX_R, MAX_L, MAX_FAULTS = 4, 8, 40, 64
 F32, BF16_F32ACC = 0, 1
-FWD, BWD, WEIGHT = 0, 1, 2
-CLEAN, CORRECTED, UNCORRECTABLE = 0, 1, 2
+FWD, BWD, WEIGHT, CHECK = 0, 1, 2, 3
+CLEAN, CORRECTED, UNCORRECTABLE, DISAGREE = 0, 1, 2, 3
+CHECK_EVALUATION, CHECK_LIST = 0, 1
 DENSE_REL, SPARSE_ABS = 0, 1
 EPI_NONE, EPI_RELU, EPI_MASK_POS, EPI_MUL = 0, 1, 2, 3
 E_NULL, E_SHAPE, E_BATCH, E_ORDER, E_CODE, E_FAULT, E_HIP, E_DTYPE, E_ALLOC = range(-1, -10, -1)
 
 EXPORTS = ["codenet_encode", "codenet_layer_geometry", "codenet_forward", "codenet_backward",
-           "codenet_inject", "codenet_detect_decode", "codenet_detect_decode_act", "codenet_update", "codenet_regenerate", "codenet_export_coded",
+           "codenet_inject", "codenet_detect_decode", "codenet_detect_decode_act",
+           "codenet_detect_decode_verified", "codenet_update", "codenet_regenerate", "codenet_export_coded",
            "codenet_export_weights", "codenet_destroy", "codenet_timestamp", "codenet_strerror"]
 
 
@@ -70,6 +72,7 @@ def load_library(path=LIB_PATH):
     lib.codenet_inject.argtypes = [vp, ctypes.POINTER(Fault), ci, vp, ci, vp]
     lib.codenet_detect_decode.argtypes = [vp, ci, vp, ci, vp, vp, vp]
     lib.codenet_detect_decode_act.argtypes = [vp, ci, vp, ci, vp, vp, ci, vp, vp]
+    lib.codenet_detect_decode_verified.argtypes = [vp, ci, vp, ci, vp, vp, ci, vp, vp]
     lib.codenet_update.argtypes = [vp, cf, vp]
     lib.codenet_regenerate.argtypes = [vp, ci, vp, vp]
     lib.codenet_export_coded.argtypes = [vp, vp, vp]
@@ -185,7 +188,9 @@ class CodedLayer:
             return
         phase = int(faults[0]["phase"])
         b = 0
-        if phase != WEIGHT:
+        if phase == CHECK:
+            coded_out = None
+        elif phase != WEIGHT:
             width = self.coded_rows if phase == FWD else self.coded_cols
             b = int(coded_out.shape[0])
             _dev_f32(coded_out, (b, width), "coded_out")
@@ -193,9 +198,11 @@ class CodedLayer:
         _check(load_library().codenet_inject(self._h, arr, len(faults), _ptr(coded_out), b, _stream()),
                "codenet_inject")
 
-    def detect_decode(self, phase, coded_out, decoded=None, report=None, want_decoded=True, epilogue=0, aux=None):
+    def detect_decode(self, phase, coded_out, decoded=None, report=None, want_decoded=True, epilogue=0, aux=None,
+                      verified=False):
         """report: optional uint8 CUDA (or pinned) tensor of REPORT_BYTES bytes.
-        epilogue / aux: EPI_* elementwise step applied to the decoded output (aux shaped like it)."""
+        epilogue / aux: EPI_* elementwise step applied to the decoded output (aux shaped like it).
+        verified: the check with the verification steps of Error Model 2 (needs a report)."""
         import torch
         width, n_logical = (self.coded_rows, self.n_out) if phase == FWD else (self.coded_cols, self.n_in)
         b = int(coded_out.shape[0])
@@ -208,6 +215,12 @@ class CodedLayer:
             raise ValueError("report must be a uint8 tensor of at least %d bytes" % REPORT_BYTES)
         if aux is not None:
             _dev_f32(aux, (b, n_logical), "aux")
+        if verified:
+            _check(load_library().codenet_detect_decode_verified(self._h, int(phase), _ptr(coded_out), b,
+                                                                 _ptr(decoded), _ptr(report), int(epilogue),
+                                                                 _ptr(aux), _stream()),
+                   "codenet_detect_decode_verified")
+            return decoded
         if epilogue:
             _check(load_library().codenet_detect_decode_act(self._h, int(phase), _ptr(coded_out), b, _ptr(decoded),
                                                             _ptr(report), int(epilogue), _ptr(aux), _stream()),

@@ -22,6 +22,12 @@ struct codenet_layer {
   float *syn = nullptr;         // [max r][max_batch][max B]
   double *partials = nullptr;   // [kDetectParts][kMaxEntries]
   double *fault_partials = nullptr;   // [CODENET_MAX_FAULTS][kFaultParts]
+  double *partials_b = nullptr; // records of the second evaluation of the checks (verified check), as partials
+  unsigned long long *votes = nullptr;  // one decision word per workgroup of the finishing kernel (verified check)
+  // pending CODENET_CHECK fault, planted into the next verified check: target -1 = none
+  int check_target = -1, check_who = 0;
+  unsigned long long check_seed = 0;
+  double check_scale = 0.0;
   // bf16 mode only: bf16 operands of the products and of the update
   __bf16 *Wb = nullptr;         // [max(Mr, KpD)][ldWb]  bf16 copy of W~, operand of both products
   __bf16 *Xb = nullptr;         // [max_batch][ldXb]  x, zero beyond the base columns
@@ -130,6 +136,7 @@ void free_layer(codenet_layer *l) {
   if (!l) return;
   (void)hipFree(l->Wt); (void)hipFree(l->Xt); (void)hipFree(l->Dt); (void)hipFree(l->syn);
   (void)hipFree(l->partials); (void)hipFree(l->fault_partials);
+  (void)hipFree(l->partials_b); (void)hipFree(l->votes);
   (void)hipFree(l->code_r_dev); (void)hipFree(l->code_c_dev);
   (void)hipFree(l->Wb); (void)hipFree(l->Xb); (void)hipFree(l->Db);
   (void)hipFree(l->XTb); (void)hipFree(l->DTb); (void)hipFree(l->part);
@@ -198,6 +205,8 @@ int codenet_encode(const codenet_desc *d, const float *W_dev, void *stream, code
   alloc((void **)&l->syn, sizeof(float) * (size_t)rmax * mb * bmax);
   alloc((void **)&l->partials, sizeof(double) * (size_t)kDetectParts * kMaxEntries);
   alloc((void **)&l->fault_partials, sizeof(double) * (size_t)CODENET_MAX_FAULTS * kFaultParts);
+  alloc((void **)&l->partials_b, sizeof(double) * (size_t)kDetectParts * kMaxEntries);
+  alloc((void **)&l->votes, sizeof(unsigned long long) * ((mb * (size_t)(bmax / 4) + 255) / 256 + 1));
   alloc((void **)&l->code_r_dev, sizeof(DevCode));
   alloc((void **)&l->code_c_dev, sizeof(DevCode));
   if (l->bf16) {
@@ -368,8 +377,25 @@ int codenet_detect_decode(codenet_layer *l, int phase, float *coded_out_dev, int
                                    stream);
 }
 
+namespace {
+int check_call(codenet_layer *l, int phase, float *coded_out_dev, int b, float *decoded_dev, codenet_report *report_dev,
+               int epilogue, const float *aux_dev, bool verified, void *stream);
+}
+
 int codenet_detect_decode_act(codenet_layer *l, int phase, float *coded_out_dev, int b, float *decoded_dev,
                               codenet_report *report_dev, int epilogue, const float *aux_dev, void *stream) {
+  return check_call(l, phase, coded_out_dev, b, decoded_dev, report_dev, epilogue, aux_dev, false, stream);
+}
+
+int codenet_detect_decode_verified(codenet_layer *l, int phase, float *coded_out_dev, int b, float *decoded_dev,
+                                   codenet_report *report_dev, int epilogue, const float *aux_dev, void *stream) {
+  if (!report_dev) return CODENET_E_NULL;
+  return check_call(l, phase, coded_out_dev, b, decoded_dev, report_dev, epilogue, aux_dev, true, stream);
+}
+
+namespace {
+int check_call(codenet_layer *l, int phase, float *coded_out_dev, int b, float *decoded_dev, codenet_report *report_dev,
+               int epilogue, const float *aux_dev, bool verified, void *stream) {
   if (!l || !coded_out_dev) return CODENET_E_NULL;
   if (epilogue < CODENET_EPI_NONE || epilogue > CODENET_EPI_MUL) return CODENET_E_DTYPE;
   if (epilogue != CODENET_EPI_NONE && !decoded_dev) return CODENET_E_NULL;
@@ -381,13 +407,27 @@ int codenet_detect_decode_act(codenet_layer *l, int phase, float *coded_out_dev,
   const DevCode *cd = phase == CODENET_FWD ? l->code_r_dev : l->code_c_dev;
   int n_parts = 0;
   if (ch.r > 0) {
-    CN_HIP(launch_detect(coded_out_dev, l->syn, l->partials, &n_parts, cd, ch, b, s));
+    CN_HIP(launch_detect(coded_out_dev, l->syn, l->partials, &n_parts, cd, ch, b, false, s));
+  }
+  if (verified && ch.r > 0) {
+    CN_HIP(launch_detect(coded_out_dev, nullptr, l->partials_b, &n_parts, cd, ch, b, true, s));
+    VerifyArgs ver{l->partials_b, l->votes, -1};
+    if (l->check_target == CODENET_CHECK_EVALUATION)
+      CN_HIP(launch_record_fault(l->check_who % 2 ? l->partials_b : l->partials, (int)(l->check_seed % (unsigned)n_parts),
+                                 l->check_scale, s));
+    else if (l->check_target == CODENET_CHECK_LIST)
+      ver.faulty_evaluator = (int)(l->check_who % finish_workgroups(ch, b, true));
+    l->check_target = -1;
+    CN_HIP(launch_finish(coded_out_dev, l->syn, l->partials, n_parts, cd, ch, b, decoded_dev, report_dev, epilogue,
+                         aux_dev, &ver, s));
+    return CODENET_OK;
   }
   // with r = 0 there is nothing to check: zero records make the decision CLEAN
   CN_HIP(launch_finish(coded_out_dev, l->syn, l->partials, n_parts, cd, ch, b, decoded_dev, report_dev, epilogue,
-                       aux_dev, s));
+                       aux_dev, nullptr, s));
   return CODENET_OK;
 }
+}  // namespace
 
 int codenet_inject(codenet_layer *l, const codenet_fault *faults, int n_faults, float *coded_out_dev, int b,
                    void *stream) {
@@ -396,6 +436,16 @@ int codenet_inject(codenet_layer *l, const codenet_fault *faults, int n_faults, 
   if (!faults) return CODENET_E_NULL;
   if (n_faults < 0 || n_faults > CODENET_MAX_FAULTS) return CODENET_E_SHAPE;
   const int phase = faults[0].phase;
+  if (phase == CODENET_CHECK) {
+    const codenet_fault &ft = faults[0];
+    if (n_faults != 1) return CODENET_E_SHAPE;
+    if ((ft.bi != CODENET_CHECK_EVALUATION && ft.bi != CODENET_CHECK_LIST) || ft.bj < 0) return CODENET_E_FAULT;
+    l->check_target = ft.bi;
+    l->check_who = ft.bj;
+    l->check_seed = ft.seed;
+    l->check_scale = (double)ft.hi;
+    return CODENET_OK;
+  }
   if (phase != CODENET_FWD && phase != CODENET_BWD && phase != CODENET_WEIGHT) return CODENET_E_DTYPE;
   if (phase != CODENET_WEIGHT) {
     if (!coded_out_dev) return CODENET_E_NULL;

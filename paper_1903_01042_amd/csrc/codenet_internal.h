@@ -113,12 +113,25 @@ hipError_t launch_encode_vector(const float *V, float *Vt, const DevCode *code_d
                                 int b, void *Vb, long ldVb, float *zero, long zero_count4, hipStream_t s);
 hipError_t launch_encode_vector_bf16(const float *V, const DevCode *code_dev, const DevCode &code_host,
                                      int b, void *Vb, long ldVb, void *VTb, long ldVT, hipStream_t s);
+// pass 1 of a check.  second_evaluation: the same records computed by other workgroups (another
+// compute unit for every record); syn may then be null (the syndromes are not written again)
 hipError_t launch_detect(const float *out, float *syn, double *partials, int *n_parts,
-                         const DevCode *code_dev, const DevCode &code_host, int b, hipStream_t s);
-// passes 2 + 3 of a check: decision (every workgroup, from the pass-1 records), correction, decoded output
+                         const DevCode *code_dev, const DevCode &code_host, int b, bool second_evaluation,
+                         hipStream_t s);
+// Verification steps of Error Model 2 (null = none)
+struct VerifyArgs {
+  const double *partials_b;      // pass-1 records of the second evaluation
+  unsigned long long *votes;     // one word per workgroup of the finishing kernel: its verdict and located nodes
+  int faulty_evaluator;          // workgroup whose decision gets a planted error; -1 = none
+};
+long finish_workgroups(const DevCode &code_host, int b, bool verified);
+hipError_t launch_record_fault(double *partials, int part, double scale, hipStream_t s);
+// passes 2 + 3 of a check: decision (every workgroup, from the pass-1 records), correction, decoded output;
+// with ver, the comparison of the two evaluations and of the workgroups' decisions as well
 hipError_t launch_finish(float *out, const float *syn, const double *partials, int n_parts,
                          const DevCode *code_dev, const DevCode &code_host, int b, float *decoded,
-                         codenet_report *report, int epilogue, const float *aux, hipStream_t s);
+                         codenet_report *report, int epilogue, const float *aux, const VerifyArgs *ver,
+                         hipStream_t s);
 hipError_t launch_faults(const FaultBatch &fb, hipStream_t s, bool stats_pass);
 hipError_t launch_export_weights(const float *Wt, float *W, const DevCode &cr, const DevCode &cc,
                                  int Nc, int n_out, int n_in, hipStream_t s);

@@ -566,7 +566,12 @@ template <int R>
 __global__ __launch_bounds__(256) void detect_kernel(const float *__restrict__ out, float *__restrict__ syn,
                                                      double *__restrict__ partials,
                                                      const DevCode *__restrict__ code, int b, int iters,
-                                                     Geometry geo) {
+                                                     int shift, Geometry geo) {
+  // A second, independent evaluation of the same checks (verification step 1) runs with
+  // shift > 0: workgroup w does the work and fills the record of workgroup w + shift, so that
+  // every record is computed on another compute unit, in the same order of operations.
+  unsigned wg = blockIdx.x + (unsigned)shift;
+  if (wg >= gridDim.x) wg -= gridDim.x;
   const int B = geo.B, L = geo.L;
   const int quads = B >> 2;
   const long npos = (long)b * quads;
@@ -579,7 +584,7 @@ __global__ __launch_bounds__(256) void detect_kernel(const float *__restrict__ o
   for (int e = 0; e < NG; ++e) gram[e] = 0.f;
 
   for (int it = 0; it < iters; ++it) {
-    const long idx = ((long)it * gridDim.x + blockIdx.x) * 256 + threadIdx.x;
+    const long idx = ((long)it * gridDim.x + wg) * 256 + threadIdx.x;
     if (idx >= npos) break;
     const int beta = (int)(idx / quads), rho = (int)(idx % quads) * 4;
     const float *row = out + (long)beta * L * B + rho;
@@ -603,7 +608,7 @@ __global__ __launch_bounds__(256) void detect_kernel(const float *__restrict__ o
     int e = 0;
 #pragma unroll
     for (int k = 0; k < R; ++k) {
-      *reinterpret_cast<float4 *>(syn + ((long)k * b + beta) * B + rho) = sy[k];
+      if (syn) *reinterpret_cast<float4 *>(syn + ((long)k * b + beta) * B + rho) = sy[k];
 #pragma unroll
       for (int k2 = k; k2 < R; ++k2, ++e)
         gram[e] += sy[k].x * sy[k2].x + sy[k].y * sy[k2].y + sy[k].z * sy[k2].z + sy[k].w * sy[k2].w;
@@ -645,14 +650,14 @@ __global__ __launch_bounds__(256) void detect_kernel(const float *__restrict__ o
       for (int q = 0; q < 16; ++q) acc += red2[t][q];
       const int k = c0 + t;
       const int e = k < NG ? CODENET_MAX_L + k : k - NG;
-      partials[(long)e * kDetectParts + blockIdx.x] = acc;
+      partials[(long)e * kDetectParts + wg] = acc;
     }
     __syncthreads();
   }
 }
 
 hipError_t launch_detect(const float *out, float *syn, double *partials, int *n_parts, const DevCode *code_dev,
-                         const DevCode &ch, int b, hipStream_t s) {
+                         const DevCode &ch, int b, bool second_evaluation, hipStream_t s) {
   const long npos = (long)b * (ch.B >> 2);
   long wgs = (npos + 255) / 256;
   int iters = 1;
@@ -661,10 +666,12 @@ hipError_t launch_detect(const float *out, float *syn, double *partials, int *n_
     wgs = (npos + 256L * iters - 1) / (256L * iters);
   }
   *n_parts = (int)wgs;
+  // an odd shift near half the grid: another compute unit in another XCD
+  const int shift = second_evaluation && wgs > 1 ? (int)(((wgs / 2) | 1) % wgs) : 0;
   dim3 grid((unsigned)wgs), block(256);
   switch (ch.r) {
 #define CODENET_DETECT_CASE(RR) \
-  case RR: hipLaunchKernelGGL(detect_kernel<RR>, grid, block, 0, s, out, syn, partials, code_dev, b, iters, geometry_of(ch)); break;
+  case RR: hipLaunchKernelGGL(detect_kernel<RR>, grid, block, 0, s, out, syn, partials, code_dev, b, iters, shift, geometry_of(ch)); break;
     CODENET_DETECT_CASE(1) CODENET_DETECT_CASE(2) CODENET_DETECT_CASE(3) CODENET_DETECT_CASE(4)
     CODENET_DETECT_CASE(5) CODENET_DETECT_CASE(6) CODENET_DETECT_CASE(7) CODENET_DETECT_CASE(8)
 #undef CODENET_DETECT_CASE
@@ -681,19 +688,57 @@ hipError_t launch_detect(const float *out, float *syn, double *partials, int *n_
 // the accepted support and emits the decoded (systematic, unpadded) output.
 // Workgroup 0 writes the report.
 // ---------------------------------------------------------------------------
-template <bool GENERIC>
+// With VERIFY the two verification steps of Error Model 2 ride along.  Step 1: the pass-1
+// records of a second evaluation of the checks are compared, bit for bit, with the ones the
+// decision was taken from (every workgroup compares all of them); a difference makes the
+// verdict DISAGREE and nothing is corrected.  Step 2: every workgroup is one evaluator of the
+// decision and leaves its verdict and list of erroneous nodes as one word in votes[]; a
+// single-workgroup kernel (verify_kernel) compares the words afterwards.
+template <bool GENERIC, bool VERIFY>
 __global__ __launch_bounds__(256) void finish_kernel(float *__restrict__ out, const float *__restrict__ syn,
                                                      const double *__restrict__ partials, int n_parts,
                                                      const DevCode *__restrict__ code, int b,
                                                      float *__restrict__ decoded, int aligned,
                                                      codenet_report *__restrict__ report, int epi,
-                                                     const float *__restrict__ aux, Geometry geo) {
+                                                     const float *__restrict__ aux, VerifyArgs ver, Geometry geo) {
   __shared__ DevPlan plan;
   decide_body<GENERIC>(partials, n_parts, code, &plan, blockIdx.x == 0 ? report : nullptr);
   __syncthreads();
+  const int B = geo.B, B0 = geo.B0, L = geo.L, a = geo.a, r = geo.r, N = geo.N;
+  if constexpr (VERIFY) {
+    const int n_live = L + r * (r + 1) / 2;
+    int differ = 0;
+    for (int k = 0; k < n_live; ++k) {
+      const long e = k < L ? k : CODENET_MAX_L + (k - L);
+      for (int q = threadIdx.x; q < n_parts; q += 256)
+        differ |= __double_as_longlong(partials[e * kDetectParts + q]) !=
+                  __double_as_longlong(ver.partials_b[e * kDetectParts + q]);
+    }
+    differ = __syncthreads_or(differ);
+    if (threadIdx.x == 0) {
+      if (differ) {
+        plan.verdict = CODENET_DISAGREE;
+        plan.n_located = 0;
+        for (int p = 0; p < CODENET_MAX_T; ++p) plan.located[p] = -1;
+        if (blockIdx.x == 0 && report) {
+          report->verdict = CODENET_DISAGREE;
+          report->n_located = 0;
+          for (int p = 0; p < CODENET_MAX_T; ++p) report->located[p] = -1;
+        }
+      } else if ((int)blockIdx.x == ver.faulty_evaluator) {
+        // planted error in this evaluator's decision (tests of step 2)
+        if (plan.verdict == CODENET_CORRECTED) plan.located[0] = (plan.located[0] + 1) % L;
+        else plan.verdict = plan.verdict == CODENET_CLEAN ? CODENET_UNCORRECTABLE : CODENET_CLEAN;
+      }
+      unsigned long long word = (unsigned long long)plan.verdict | ((unsigned long long)plan.n_located << 8);
+      for (int p = 0; p < CODENET_MAX_T; ++p)
+        word |= (unsigned long long)((plan.located[p] + 1) & 0xff) << (16 + 8 * p);
+      ver.votes[blockIdx.x] = word;
+    }
+    __syncthreads();
+  }
   const int corrected = plan.verdict == CODENET_CORRECTED ? plan.n_located : 0;
   if (corrected == 0 && decoded == nullptr) return;
-  const int B = geo.B, B0 = geo.B0, L = geo.L, a = geo.a, r = geo.r, N = geo.N;
   const int quads = B >> 2;
   const long idx = (long)blockIdx.x * 256 + threadIdx.x;
   if (idx >= (long)b * quads) return;
@@ -756,19 +801,59 @@ __global__ __launch_bounds__(256) void finish_kernel(float *__restrict__ out, co
   }
 }
 
+// Verification step 2: do all evaluators' words agree?  One workgroup; the report's verdict
+// becomes DISAGREE if not.
+__global__ __launch_bounds__(256) void verify_kernel(const unsigned long long *__restrict__ votes, int n,
+                                                     codenet_report *__restrict__ report) {
+  const unsigned long long first = votes[0];
+  int differ = 0;
+  for (int q = threadIdx.x; q < n; q += 256) differ |= votes[q] != first;
+  differ = __syncthreads_or(differ);
+  if (differ && threadIdx.x == 0) {
+    report->verdict = CODENET_DISAGREE;
+    report->n_located = 0;
+    for (int p = 0; p < CODENET_MAX_T; ++p) report->located[p] = -1;
+  }
+}
+
+// Planted error in one evaluation of the checks (tests of verification step 1): one pass-1
+// record of the first check's squared norm becomes (1 + scale) * record + scale.
+__global__ void record_fault_kernel(double *record, double scale) { *record = (1.0 + scale) * *record + scale; }
+
+hipError_t launch_record_fault(double *partials, int part, double scale, hipStream_t s) {
+  hipLaunchKernelGGL(record_fault_kernel, dim3(1), dim3(1), 0, s, partials + (long)CODENET_MAX_L * kDetectParts + part,
+                     scale);
+  return hipGetLastError();
+}
+
+// workgroups of the finishing kernel; a verified check has at least two (two evaluators of the
+// decision even when one workgroup covers the whole output)
+long finish_workgroups(const DevCode &ch, int b, bool verified) {
+  const long wgs = ((long)b * (ch.B >> 2) + 255) / 256;
+  return verified && wgs < 2 ? 2 : wgs;
+}
+
 hipError_t launch_finish(float *out, const float *syn, const double *partials, int n_parts, const DevCode *code_dev,
                          const DevCode &ch, int b, float *decoded, codenet_report *report, int epi, const float *aux,
-                         hipStream_t s) {
-  const long total = (long)b * (ch.B >> 2);
+                         const VerifyArgs *ver, hipStream_t s) {
   const int aligned = (ch.N % 4 == 0) && (ch.B0 % 4 == 0) && ((reinterpret_cast<uintptr_t>(decoded) & 15) == 0);
-  dim3 grid((unsigned)((total + 255) / 256)), block(256);
-  if (ch.r >= 4)
-    hipLaunchKernelGGL(finish_kernel<true>, grid, block, 0, s, out, syn, partials, n_parts, code_dev, b, decoded,
-                       aligned, report, epi, aux, geometry_of(ch));
-  else
-    hipLaunchKernelGGL(finish_kernel<false>, grid, block, 0, s, out, syn, partials, n_parts, code_dev, b, decoded,
-                       aligned, report, epi, aux, geometry_of(ch));
-  return hipGetLastError();
+  dim3 grid((unsigned)finish_workgroups(ch, b, ver != nullptr)), block(256);
+  const VerifyArgs none{};
+#define CODENET_FINISH(GEN, VER)                                                                                    \
+  hipLaunchKernelGGL((finish_kernel<GEN, VER>), grid, block, 0, s, out, syn, partials, n_parts, code_dev, b, decoded, \
+                     aligned, report, epi, aux, ver ? *ver : none, geometry_of(ch))
+  if (ver) {
+    if (ch.r >= 4) CODENET_FINISH(true, true); else CODENET_FINISH(false, true);
+  } else {
+    if (ch.r >= 4) CODENET_FINISH(true, false); else CODENET_FINISH(false, false);
+  }
+#undef CODENET_FINISH
+  hipError_t e = hipGetLastError();
+  if (e == hipSuccess && ver) {
+    hipLaunchKernelGGL(verify_kernel, dim3(1), dim3(256), 0, s, ver->votes, (int)grid.x, report);
+    e = hipGetLastError();
+  }
+  return e;
 }
 
 // ---------------------------------------------------------------------------

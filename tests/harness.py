@@ -48,9 +48,12 @@ class Pair:
         assert err <= (tol or self.tol), "coded weights differ: rel %.3e" % err
         return err
 
-    def product(self, phase, V, faults=(), check_margins=True, epilogue=0, aux=None):
+    def product(self, phase, V, faults=(), check_margins=True, epilogue=0, aux=None, verified=False,
+                check_fault=None):
         """One coded product + injection + check on both sides; V is batch-major [b][N].
-        epilogue / aux (batch-major numpy): the elementwise step fused into the GPU's check."""
+        epilogue / aux (batch-major numpy): the elementwise step fused into the GPU's check.
+        verified: the check with the verification steps of Error Model 2; check_fault =
+        dict(target=CHECK_EVALUATION | CHECK_LIST, who, seed, hi) plants an error in the checking."""
         B = self.B
         Vd = self.dev_tensor(V)
         if phase == B.FWD:
@@ -67,10 +70,21 @@ class Pair:
             out_o = self.ora.inject(faults, out_o)
             err = rel_fro(to_np(out_g).T, out_o)
             assert err <= self.tol, "injected output differs: rel %.3e" % err
+        if check_fault is not None:
+            self.gpu.inject([dict(phase=B.CHECK, bi=check_fault["target"], bj=check_fault["who"],
+                                  seed=check_fault.get("seed", 0), step=0, lo=0.0, hi=check_fault["hi"])])
         dec_g = self.gpu.detect_decode(phase, out_g, report=self.report, epilogue=epilogue,
-                                       aux=None if aux is None else self.dev_tensor(aux))
+                                       aux=None if aux is None else self.dev_tensor(aux), verified=verified)
         rep = self.gpu.read_report(self.report)
-        res = self.ora.detect_decode(phase, out_o)
+        if verified:
+            kw = {}
+            if check_fault is not None and check_fault["target"] == B.CHECK_EVALUATION:
+                kw = dict(check_faults=[(check_fault["who"] % 2, 0, check_fault["hi"])])
+            elif check_fault is not None:
+                kw = dict(evaluators=check_fault["who"] + 2, list_faults=[(check_fault["who"],)])
+            res = self.ora.verified_detect_decode(phase, out_o, **kw)
+        else:
+            res = self.ora.detect_decode(phase, out_o)
         if epilogue == B.EPI_RELU:
             res["decoded"] = O.relu(res["decoded"])
         elif epilogue == B.EPI_MASK_POS:
@@ -80,6 +94,11 @@ class Pair:
         self.log.append((phase, [(f["bi"], f["bj"]) for f in faults], rep["verdict"], rep["located"]))
         assert rep["verdict"] == res["verdict"], (rep, res["verdict"], res["located"], res["syn_rel"], res["resid_rel"])
         assert rep["located"] == res["located"], (rep, res["located"])
+        if rep["verdict"] == B.DISAGREE:
+            if check_fault["target"] == B.CHECK_EVALUATION:   # found before anything was corrected
+                err = rel_fro(to_np(out_g).T, res["out"])
+                assert err <= self.tol, "output changed before a disagreement in step 1: rel %.3e" % err
+            return dec_g, rep, res
         if check_margins and (self.ora.r_r if phase == B.FWD else self.ora.r_c) > 0:
             self._margins(rep, res, self.ora.r_r if phase == B.FWD else self.ora.r_c)
         if rep["verdict"] != B.UNCORRECTABLE:

@@ -489,6 +489,62 @@ def test_activation_fused_into_the_check(n_out, n_in, m, n, r, b, dtype):
     pair.close()
 
 
+# ------------------------------------------- verification steps of Error Model 2
+@pytest.mark.parametrize("n_out,n_in,m,n,r,b,dtype", [
+    (256, 192, 4, 3, 2, 16, "f32"),       # 4 workgroups in the check
+    (1024, 1024, 8, 8, 2, 128, "bf16"),   # 16 workgroups
+    (320, 256, 4, 4, 4, 9, "f32"),        # t = 2 (generic decision); one workgroup of work, two evaluators
+    (100, 52, 3, 5, 2, 7, "f32"),         # ragged blocks
+])
+def test_verified_check_agrees_or_reports_the_disagreement(n_out, n_in, m, n, r, b, dtype):
+    """Without planted errors the verified check gives exactly the plain one (clean, corrected,
+    uncorrectable; with a fused activation); an error planted in either evaluation of the checks or
+    in any evaluator's list gives DISAGREE on both sides, and the next check is back to normal."""
+    from paper_1903_01042_amd import binding as B
+    if r <= 2:
+        P_r, P_c = WL.vandermonde_like(m, r), WL.vandermonde_like(n, r)
+    else:   # a random generator: some nearly dependent column pairs, so no margin is asked below
+        P_r, P_c = WL.gaussian_generator(m, r, 8), WL.gaussian_generator(n, r, 9)
+    tau = (1e-3, 1e-2) if dtype == "f32" else (2e-2, 2e-2)
+    pair = Pair(WL.layer_weights(n_out, n_in), P_r, P_c, dtype, b, *tau)
+    X, D = WL.normal((b, n_in), 31), WL.normal((b, n_out), 32)
+    t = r // 2
+    mg = dict(check_margins=(r <= 2))
+    one_f, one_b = [WL.make_fault(FWD, 1, 0, 5)], [WL.make_fault(BWD, 0, n, 5)]
+    many_f = [WL.make_fault(FWD, i, 0, 6) for i in range(t + 1)]
+    for faults_f, faults_b, want in (((), (), CLEAN), (one_f, one_b, CORRECTED), (many_f, (), UNCORRECTABLE)):
+        _, rep, _ = pair.product(FWD, X, faults_f, verified=True, epilogue=B.EPI_RELU, **mg)
+        assert rep["verdict"] == want
+        if want != UNCORRECTABLE:
+            _, rep, _ = pair.product(BWD, D, faults_b, verified=True, **mg)
+            assert rep["verdict"] == want
+    for faults_f in ((), one_f, many_f):
+        for fault in (dict(target=B.CHECK_EVALUATION, who=0, seed=1, hi=0.5),
+                      dict(target=B.CHECK_EVALUATION, who=1, seed=2, hi=1e-6),
+                      dict(target=B.CHECK_LIST, who=0, hi=0.0),
+                      dict(target=B.CHECK_LIST, who=3, hi=0.0)):
+            _, rep, _ = pair.product(FWD, X, faults_f, verified=True, check_fault=fault, **mg)
+            assert rep["verdict"] == B.DISAGREE and rep["n_located"] == 0, (faults_f, fault, rep)
+            # the planted error is used up: the same product checks normally again
+            _, rep, _ = pair.product(FWD, X, faults_f, verified=True, **mg)
+            assert rep["verdict"] != B.DISAGREE
+    # a pending CHECK fault waits for the next verified call; plain calls ignore it
+    pair.gpu.inject([dict(phase=B.CHECK, bi=B.CHECK_LIST, bj=0, seed=0, step=0, lo=0.0, hi=0.0)])
+    _, rep, _ = pair.product(FWD, X)
+    assert rep["verdict"] == CLEAN
+    out = pair.gpu.forward(pair.dev_tensor(X))
+    pair.gpu.detect_decode(FWD, out, report=pair.report, verified=True)
+    assert pair.gpu.read_report(pair.report)["verdict"] == B.DISAGREE
+    lib, vp = B.load_library(), __import__("ctypes").c_void_p
+    assert lib.codenet_detect_decode_verified(pair.gpu._h, B.FWD, vp(out.data_ptr()), b, None, None, 0, None,
+                                              None) == B.E_NULL
+    bad = B.pack_faults([dict(phase=B.CHECK, bi=2, bj=0, seed=0, step=0, lo=0.0, hi=0.0)])
+    assert lib.codenet_inject(pair.gpu._h, bad, 1, None, 0, None) == B.E_FAULT
+    two = B.pack_faults([dict(phase=B.CHECK, bi=0, bj=0, seed=0, step=0, lo=0.0, hi=0.1)] * 2)
+    assert lib.codenet_inject(pair.gpu._h, two, 2, None, 0, None) == B.E_SHAPE
+    pair.close()
+
+
 # ------------------------------------------------------------------ API error paths
 def test_api_errors_on_the_gpu():
     import torch
