@@ -590,7 +590,7 @@ __global__ __launch_bounds__(256, (FM * FN <= 4 ? 2 : 1)) void update2_kernel(Up
 //    the last slabs of the tile, once the storers have released the buffer; no other
 //    wavefront ever waits on HBM;
 //  * wavefronts 6-7 (storers) work one tile behind: during the first slabs they gather
-//    rows of the matrix from the (transposed) LDS tile and store them and their bf16
+//    rows of the matrix from the LDS tile and store them and their bf16
 //    copy; every store instruction writes whole 64-byte segments (the L2 request
 //    rate, not its bandwidth, is what this kernel runs into).  They only ever issue
 //    stores, so they never wait for memory.
@@ -799,8 +799,8 @@ __global__ __launch_bounds__(512) void update3_kernel(Update2Args g) {
 
   // Schedule of the other two roles inside a tile period (barriers B0 .. B(KS-1), then
   // the end-of-tile barrier).  With 8 slabs or more the storers empty the tile buffer in four
-  // pieces after B0 .. B3, half a row quarter each (they gather their rows from the
-  // transposed tile and push 24 KB of stores per piece; as whole quarters they took twice a
+  // pieces after B0 .. B3, half a row quarter each (they read their rows from the
+  // tile and push 24 KB of stores per piece; as whole quarters they took twice a
   // slab of the MMA role, which then waited 1900 clocks at each of the next barriers -- seen
   // in time stamps that one MMA wavefront took at every barrier), and the loaders refill it
   // with one group after each of B4 .. B7.  With fewer slabs the quarters follow B0 and B1

@@ -166,11 +166,12 @@ static inline Geometry geometry_of(const DevCode &c) { return Geometry{c.B, c.B0
 // transposition, the feature-major coded vector (operand of the update);
 // batch columns b .. Rpad-1 of the latter are written as zeros.  Jobs 0 .. a-1 copy
 // a systematic block, job a + k computes parity block k.
+template <bool ALIGNED>
 __global__ __launch_bounds__(256) void encode_vector_bf16_kernel(const float *__restrict__ V,
                                                                  const DevCode *__restrict__ code, int b,
                                                                  __bf16 *__restrict__ Vb, long ldVb,
                                                                  __bf16 *__restrict__ VTb, long ldVT, int Rpad,
-                                                                 int aligned, Geometry geo) {
+                                                                 Geometry geo) {
   __shared__ unsigned short tile[64][66];
   const int B = geo.B, B0 = geo.B0, a = geo.a, r = geo.r, N = geo.N;
   // the parity jobs read all a blocks: they are dispatched first so that they do not form the tail
@@ -178,51 +179,54 @@ __global__ __launch_bounds__(256) void encode_vector_bf16_kernel(const float *__
   const int job = (int)blockIdx.z < r ? a + (int)blockIdx.z : (int)blockIdx.z - r;
   const int t = threadIdx.x;
   const int c = (t & 15) * 4, rho = rho0 + c;
-  auto fetch = [&](const float *src, int i, float (&v)[4]) {
-    if (aligned) {        // N and B0 multiples of 4, V 16-byte aligned: whole quads are real or padding
+  // Four entries rho .. rho + 3 of block i of one batch row.  The loads are unconditional, from an
+  // address moved into the array where the entry is padding or the row is beyond the batch, and the
+  // value is dropped afterwards: a load under a condition would sit in a branch of its own and wait
+  // for its data there, one memory latency per load instead of one per batch of loads.
+  // ALIGNED: N and B0 multiples of 4, V 16-byte aligned -- whole quads are real or padding.
+  auto fetch = [&](int beta, int i, float (&v)[4]) {
+    const bool row_ok = beta < b && rho < B;
+    const float *src = V + (long)(beta < b ? beta : b - 1) * N;
+    if constexpr (ALIGNED) {
       const int g = i * B0 + rho;
-      const float4 q = (rho < B0 && g < N) ? *reinterpret_cast<const float4 *>(src + g) : make_float4(0.f, 0.f, 0.f, 0.f);
-      v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+      const bool ok = row_ok && rho < B0 && g < N;
+      const float4 q = *reinterpret_cast<const float4 *>(src + (ok ? g : 0));
+      v[0] = ok ? q.x : 0.f; v[1] = ok ? q.y : 0.f; v[2] = ok ? q.z : 0.f; v[3] = ok ? q.w : 0.f;
     } else {
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         const int g = i * B0 + rho + e;
-        v[e] = (rho + e < B0 && g < N) ? src[g] : 0.f;
+        const bool ok = row_ok && rho + e < B0 && g < N;
+        const float q = src[ok ? g : 0];
+        v[e] = ok ? q : 0.f;
       }
     }
   };
   // this thread's four rows: rr = t / 16 + 16 p
   float v[4][4];
-#pragma unroll
-  for (int p = 0; p < 4; ++p) v[p][0] = v[p][1] = v[p][2] = v[p][3] = 0.f;
   if (job < a) {
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
-      const int beta = beta0 + (t >> 4) + 16 * p;
-      if (beta < b && rho < B) fetch(V + (long)beta * N, job, v[p]);
-    }
+    for (int p = 0; p < 4; ++p) fetch(beta0 + (t >> 4) + 16 * p, job, v[p]);
   } else {
-    // parity block k = sum_i H[k][i] block_i, i ascending; the loads of eight blocks x four rows are
-    // issued together (one block at a time would expose a load latency per block; at 8 blocks the
-    // whole job has one)
+    // parity block k = sum_i H[k][i] block_i, i ascending; eight blocks x four rows of loads in flight
+    // at a time (beyond the last block: block a - 1 again, with weight zero)
+#pragma unroll
+    for (int p = 0; p < 4; ++p) v[p][0] = v[p][1] = v[p][2] = v[p][3] = 0.f;
     const int k = job - a;
     for (int i0 = 0; i0 < a; i0 += 8) {
       float x[8][4][4];
 #pragma unroll
       for (int u = 0; u < 8; ++u)
 #pragma unroll
-        for (int p = 0; p < 4; ++p) {
-          const int beta = beta0 + (t >> 4) + 16 * p;
-          x[u][p][0] = x[u][p][1] = x[u][p][2] = x[u][p][3] = 0.f;
-          if (i0 + u < a && beta < b && rho < B) fetch(V + (long)beta * N, i0 + u, x[u][p]);
-        }
+        for (int p = 0; p < 4; ++p) fetch(beta0 + (t >> 4) + 16 * p, i0 + u < a ? i0 + u : a - 1, x[u][p]);
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
-        const float h = i0 + u < a ? code->Hf[k][i0 + u] : 0.f;
+        const bool live = i0 + u < a;
+        const float h = code->Hf[k][live ? i0 + u : a - 1];
 #pragma unroll
         for (int p = 0; p < 4; ++p)
 #pragma unroll
-          for (int e = 0; e < 4; ++e) v[p][e] = i0 + u < a ? fmaf(h, x[u][p][e], v[p][e]) : v[p][e];
+          for (int e = 0; e < 4; ++e) v[p][e] = live ? fmaf(h, x[u][p][e], v[p][e]) : v[p][e];
       }
     }
   }
@@ -259,8 +263,12 @@ hipError_t launch_encode_vector_bf16(const float *V, const DevCode *code_dev, co
   const int Rpad = (b + 63) & ~63;
   dim3 grid((unsigned)((code_host.B + 63) / 64), (unsigned)(Rpad / 64), (unsigned)(code_host.a + code_host.r));
   const int aligned = (code_host.N % 4 == 0) && (code_host.B0 % 4 == 0) && ((reinterpret_cast<uintptr_t>(V) & 15) == 0);
-  hipLaunchKernelGGL(encode_vector_bf16_kernel, grid, dim3(256), 0, s, V, code_dev, b, (__bf16 *)Vb, ldVb,
-                     (__bf16 *)VTb, ldVT, Rpad, aligned, geometry_of(code_host));
+  if (aligned)
+    hipLaunchKernelGGL(encode_vector_bf16_kernel<true>, grid, dim3(256), 0, s, V, code_dev, b, (__bf16 *)Vb, ldVb,
+                       (__bf16 *)VTb, ldVT, Rpad, geometry_of(code_host));
+  else
+    hipLaunchKernelGGL(encode_vector_bf16_kernel<false>, grid, dim3(256), 0, s, V, code_dev, b, (__bf16 *)Vb, ldVb,
+                       (__bf16 *)VTb, ldVT, Rpad, geometry_of(code_host));
   return hipGetLastError();
 }
 
@@ -362,8 +370,10 @@ __device__ double support_residual2(const double (*H)[CODENET_MAX_L], int r, con
 
 // Executed by all 256 threads of one workgroup.  GENERIC = supports of two or more
 // blocks may be needed (r >= 4); without it the kernel needs no private scratch.
+// Always inlined: with several kernels using it the compiler would otherwise emit a call,
+// which costs the finishing kernel about 2 us.
 template <bool GENERIC>
-__device__ void decide_body(const double *partials, int n_parts, const DevCode *__restrict__ code,
+__device__ __forceinline__ void decide_body(const double *partials, int n_parts, const DevCode *__restrict__ code,
                             DevPlan *__restrict__ plan, codenet_report *__restrict__ report) {
   __shared__ double tot[kMaxEntries];
   __shared__ double G[CODENET_MAX_R][CODENET_MAX_R];
@@ -562,7 +572,7 @@ __device__ void decide_body(const double *partials, int n_parts, const DevCode *
 // positions, then float64 across lanes, wavefronts and workgroups in a fixed
 // order (no atomics), so the decision is reproducible.
 // ---------------------------------------------------------------------------
-template <int R>
+template <int R, int CH>
 __global__ __launch_bounds__(256) void detect_kernel(const float *__restrict__ out, float *__restrict__ syn,
                                                      double *__restrict__ partials,
                                                      const DevCode *__restrict__ code, int b, int iters,
@@ -591,20 +601,36 @@ __global__ __launch_bounds__(256) void detect_kernel(const float *__restrict__ o
     float4 sy[R];
 #pragma unroll
     for (int k = 0; k < R; ++k) sy[k] = make_float4(0.f, 0.f, 0.f, 0.f);
+    // CH blocks at a time, all their loads issued before the first is used.  A load guarded
+    // by "i < L" would sit in a branch of its own and wait for its data there (one memory
+    // latency per block); instead every load is unconditional, from a clamped block index,
+    // and a block beyond the code contributes through a zero weight (H is zero there).
 #pragma unroll
-    for (int i = 0; i < CODENET_MAX_L; ++i)
-      if (i < L) {
-        const float4 v = *reinterpret_cast<const float4 *>(row + i * B);
-        sq[i] += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+    for (int i0 = 0; i0 < CODENET_MAX_L; i0 += CH) {
+      if (i0 >= L) break;
+      float4 v[CH];
+#pragma unroll
+      for (int u = 0; u < CH; ++u) {
+        const int i = i0 + u < L ? i0 + u : L - 1;
+        v[u] = *reinterpret_cast<const float4 *>(row + i * B);
+      }
+#pragma unroll
+      for (int u = 0; u < CH; ++u) {
+        constexpr int last = CODENET_MAX_L - 1;
+        const int i = i0 + u < last ? i0 + u : last;   // compile-time after unrolling
+        const bool live = i0 + u < L;
+        const float4 x = v[u];
+        sq[i] += live ? x.x * x.x + x.y * x.y + x.z * x.z + x.w * x.w : 0.f;
 #pragma unroll
         for (int k = 0; k < R; ++k) {
-          const float hk = code->Hf[k][i];
-          sy[k].x = fmaf(hk, v.x, sy[k].x);
-          sy[k].y = fmaf(hk, v.y, sy[k].y);
-          sy[k].z = fmaf(hk, v.z, sy[k].z);
-          sy[k].w = fmaf(hk, v.w, sy[k].w);
+          const float hk = code->Hf[k][i];            // zero for i >= L
+          sy[k].x = fmaf(hk, x.x, sy[k].x);
+          sy[k].y = fmaf(hk, x.y, sy[k].y);
+          sy[k].z = fmaf(hk, x.z, sy[k].z);
+          sy[k].w = fmaf(hk, x.w, sy[k].w);
         }
       }
+    }
     int e = 0;
 #pragma unroll
     for (int k = 0; k < R; ++k) {
@@ -669,9 +695,18 @@ hipError_t launch_detect(const float *out, float *syn, double *partials, int *n_
   // an odd shift near half the grid: another compute unit in another XCD
   const int shift = second_evaluation && wgs > 1 ? (int)(((wgs / 2) | 1) % wgs) : 0;
   dim3 grid((unsigned)wgs), block(256);
+  // blocks loaded at a time: the whole codeword when it has at most 16 blocks
+  const bool wide = ch.L > 8 && ch.L <= 16;
   switch (ch.r) {
-#define CODENET_DETECT_CASE(RR) \
-  case RR: hipLaunchKernelGGL(detect_kernel<RR>, grid, block, 0, s, out, syn, partials, code_dev, b, iters, shift, geometry_of(ch)); break;
+#define CODENET_DETECT_CASE(RR)                                                                                     \
+  case RR:                                                                                                          \
+    if (wide)                                                                                                       \
+      hipLaunchKernelGGL((detect_kernel<RR, 16>), grid, block, 0, s, out, syn, partials, code_dev, b, iters, shift,  \
+                         geometry_of(ch));                                                                          \
+    else                                                                                                            \
+      hipLaunchKernelGGL((detect_kernel<RR, 8>), grid, block, 0, s, out, syn, partials, code_dev, b, iters, shift,   \
+                         geometry_of(ch));                                                                          \
+    break;
     CODENET_DETECT_CASE(1) CODENET_DETECT_CASE(2) CODENET_DETECT_CASE(3) CODENET_DETECT_CASE(4)
     CODENET_DETECT_CASE(5) CODENET_DETECT_CASE(6) CODENET_DETECT_CASE(7) CODENET_DETECT_CASE(8)
 #undef CODENET_DETECT_CASE
@@ -746,14 +781,15 @@ __global__ __launch_bounds__(256) void finish_kernel(float *__restrict__ out, co
   float *row = out + (long)beta * L * B + rho;
 
   for (int p = 0; p < corrected; ++p) {
+    // the located block and the r syndromes of this position: loads issued together
+    const int i = plan.located[p];
+    float4 v = *reinterpret_cast<float4 *>(row + i * B);
     float4 e = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int c = 0; c < r; ++c) {
       const float4 s = *reinterpret_cast<const float4 *>(syn + ((long)c * b + beta) * B + rho);
       const float w = plan.coef[p][c];
       e.x = fmaf(w, s.x, e.x); e.y = fmaf(w, s.y, e.y); e.z = fmaf(w, s.z, e.z); e.w = fmaf(w, s.w, e.w);
     }
-    const int i = plan.located[p];
-    float4 v = *reinterpret_cast<float4 *>(row + i * B);
     v.x -= e.x; v.y -= e.y; v.z -= e.z; v.w -= e.w;
     *reinterpret_cast<float4 *>(row + i * B) = v;
   }
