@@ -998,30 +998,53 @@ __global__ __launch_bounds__(256) void regen_kernel(RegenArgs g, const DevCode *
   const long blk = g.axis == 0 ? (long)B * g.Nc : (long)B;      // distance between consecutive blocks of a line
   const int gr0 = g.axis == 0 ? target * B + r0 : r0;           // row / column of the tile in the coded matrix
   const int gc0 = g.axis == 0 ? c0 : target * B + c0;
+  // This thread's four rows rr = t / 16 + 16 p, columns cc .. cc + 3.  Source blocks (nonzero
+  // coefficient) in ascending order, eight at a time for all four rows: 32 loads in flight, all
+  // unconditional (rows / columns beyond the tile and sources beyond the last are clamped and
+  // enter with weight zero or are not stored) -- a guarded load would wait for its data in a
+  // branch of its own.
+  const int cc = (t & 15) * 4;
+  const int ccl = c0 + cc < cols ? c0 + cc : cols - 4;
+  const float *first[4];
+  bool in[4];
+  float4 v[4];
 #pragma unroll
   for (int p = 0; p < 4; ++p) {
-    const int rr = (t >> 4) + 16 * p, cc = (t & 15) * 4;
-    float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-    const bool in = r0 + rr < rows && c0 + cc < cols;
-    if (in) {
-      const float *first = g.W + (long)(g.axis == 0 ? r0 + rr : gr0 + rr) * g.Nc + (g.axis == 0 ? gc0 + cc : c0 + cc);
-      // source blocks (nonzero coefficient) in ascending order, eight loads in flight at a time
-      for (int q0 = 0; q0 < n_src; q0 += 8) {
-        float4 x[8];
+    const int rr = (t >> 4) + 16 * p;
+    in[p] = r0 + rr < rows && c0 + cc < cols;
+    const int rrl = r0 + rr < rows ? r0 + rr : rows - 1;
+    first[p] = g.W + (long)rrl * g.Nc + ccl;     // the same position in block 0 of the line; block sb is sb * blk further
+    v[p] = make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+  for (int q0 = 0; q0 < n_src; q0 += 8) {
+    float4 x[4][8];
+    long off[8];
+    float w[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u)
-          if (q0 + u < n_src) x[u] = *reinterpret_cast<const float4 *>(first + src_blk[q0 + u] * blk);
-#pragma unroll
-        for (int u = 0; u < 8; ++u)
-          if (q0 + u < n_src) {
-            const float w = coef[src_blk[q0 + u]];
-            v.x = fmaf(w, x[u].x, v.x); v.y = fmaf(w, x[u].y, v.y); v.z = fmaf(w, x[u].z, v.z); v.w = fmaf(w, x[u].w, v.w);
-          }
-      }
-      *reinterpret_cast<float4 *>(g.W + (long)(gr0 + rr) * g.Nc + gc0 + cc) = v;
+    for (int u = 0; u < 8; ++u) {
+      const int sb = src_blk[q0 + u < n_src ? q0 + u : n_src - 1];
+      off[u] = sb * blk;
+      w[u] = q0 + u < n_src ? coef[sb] : 0.f;
     }
-    if (g.Wb != nullptr && in) {
-      const __bf16 b0 = (__bf16)v.x, b1 = (__bf16)v.y, b2 = (__bf16)v.z, b3 = (__bf16)v.w;
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+#pragma unroll
+      for (int p = 0; p < 4; ++p) x[p][u] = *reinterpret_cast<const float4 *>(first[p] + off[u]);
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+#pragma unroll
+      for (int p = 0; p < 4; ++p) {
+        v[p].x = fmaf(w[u], x[p][u].x, v[p].x); v[p].y = fmaf(w[u], x[p][u].y, v[p].y);
+        v[p].z = fmaf(w[u], x[p][u].z, v[p].z); v[p].w = fmaf(w[u], x[p][u].w, v[p].w);
+      }
+  }
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    if (!in[p]) continue;
+    const int rr = (t >> 4) + 16 * p;
+    *reinterpret_cast<float4 *>(g.W + (long)(gr0 + rr) * g.Nc + gc0 + cc) = v[p];
+    if (g.Wb != nullptr) {
+      const __bf16 b0 = (__bf16)v[p].x, b1 = (__bf16)v[p].y, b2 = (__bf16)v[p].z, b3 = (__bf16)v[p].w;
       const unsigned short u0 = __builtin_bit_cast(unsigned short, b0), u1 = __builtin_bit_cast(unsigned short, b1),
                            u2 = __builtin_bit_cast(unsigned short, b2), u3 = __builtin_bit_cast(unsigned short, b3);
       uint2 pk;
@@ -1077,18 +1100,26 @@ __global__ __launch_bounds__(256) void fault_stats_kernel(FaultBatch fb) {
   if (fa.mode != CODENET_NOISE_DENSE_REL) return;
   const long total = (long)fa.n_outer * fa.n_inner;
   // eight elements of the grid-stride sequence at a time: loads first, then the sum (in order)
+  const bool small = total <= 0x7fffffffL;     // 32-bit index arithmetic (a 64-bit division is ~100 instructions)
   double acc = 0.0;
   const long stride = (long)gridDim.x * 256;
   for (long e0 = (long)blockIdx.x * 256 + threadIdx.x; e0 < total; e0 += 8 * stride) {
+    // unconditional loads (index clamped, value dropped beyond the end): guarded ones would each
+    // wait for their data in a branch of their own
     float v[8];
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
       const long e = e0 + u * stride;
-      v[u] = 0.f;
-      if (e < total) {
-        const long o = e / fa.n_inner, in = e % fa.n_inner;
-        v[u] = fa.base[o * fa.stride_outer + in];
+      const long ec = e < total ? e : total - 1;
+      long o, in;
+      if (small) {
+        const unsigned q = (unsigned)ec / (unsigned)fa.n_inner;
+        o = q; in = (unsigned)ec - q * (unsigned)fa.n_inner;
+      } else {
+        o = ec / fa.n_inner; in = ec % fa.n_inner;
       }
+      const float x = fa.base[o * fa.stride_outer + in];
+      v[u] = e < total ? x : 0.f;
     }
 #pragma unroll
     for (int u = 0; u < 8; ++u) acc += (double)v[u] * (double)v[u];
@@ -1106,19 +1137,37 @@ __global__ __launch_bounds__(256) void fault_apply_kernel(FaultBatch fb) {
   const FaultArgs &fa = fb.f[blockIdx.y];
   const long total = (long)fa.n_outer * fa.n_inner;
   const long e = (long)blockIdx.x * 256 + threadIdx.x;
+  // rms of the clean block from the kFaultParts partial sums of squares: one load per thread,
+  // then a fixed-order tree (16 sums of 8, one sum of 16)
   __shared__ float s_scale;
+  __shared__ double s_part[kFaultParts];
+  __shared__ double s_sum[16];
+  static_assert(kFaultParts == 128, "the tree below adds 16 x 8 partial sums");
+  const bool dense = fa.mode == CODENET_NOISE_DENSE_REL;
+  if (threadIdx.x < kFaultParts) s_part[threadIdx.x] = dense ? fa.partials[threadIdx.x] : 0.0;
+  __syncthreads();
+  if (threadIdx.x < 16) {
+    double a = 0.0;
+#pragma unroll
+    for (int q = 0; q < 8; ++q) a += s_part[8 * threadIdx.x + q];
+    s_sum[threadIdx.x] = a;
+  }
+  __syncthreads();
   if (threadIdx.x == 0) {
-    float scale = 1.f;
-    if (fa.mode == CODENET_NOISE_DENSE_REL) {
-      double ss = 0.0;
-      for (int p = 0; p < kFaultParts; ++p) ss += fa.partials[p];
-      scale = (float)sqrt(ss / (double)total);
-    }
-    s_scale = scale;
+    double ss = 0.0;
+#pragma unroll
+    for (int q = 0; q < 16; ++q) ss += s_sum[q];
+    s_scale = dense ? (float)sqrt(ss / (double)total) : 1.f;
   }
   __syncthreads();
   if (e >= total) return;
-  const long o = e / fa.n_inner, in = e % fa.n_inner;
+  long o, in;
+  if (total <= 0x7fffffffL) {
+    const unsigned q = (unsigned)e / (unsigned)fa.n_inner;
+    o = q; in = (unsigned)e - q * (unsigned)fa.n_inner;
+  } else {
+    o = e / fa.n_inner; in = e % fa.n_inner;
+  }
   const unsigned long long idx = (unsigned long long)o * fa.idx_outer + (unsigned long long)in * fa.idx_inner;
   const unsigned long long z = mix64(fa.key + idx);
   const float u = (float)((z >> 32) & 0xFFFFFFull) * (1.0f / 16777216.0f);
