@@ -67,18 +67,24 @@ hipError_t launch_export_weights(const float *Wt, float *W, const DevCode &cr, c
   return hipGetLastError();
 }
 
+// Block geometry by value: kernels that take it need no dependent load from the code table
+// before they can form their first address.
+struct Geometry { int B, B0, a, r, L, N; };
+static inline Geometry geometry_of(const DevCode &c) { return Geometry{c.B, c.B0, c.a, c.r, c.L, c.N}; }
+
 // ---------------------------------------------------------------------------
 // Additional encoding step (step 4 of the feedforward and backpropagation
 // stages): [v; v~] = (G^T (x) I) v for every batch row.  Input is the caller's
 // dense [b][N]; output is the block-padded [b][(a + r) B] that the products and
 // the update read.  One thread per (batch row, 4 positions inside a block).
 // ---------------------------------------------------------------------------
+template <bool ALIGNED>
 __global__ __launch_bounds__(256) void encode_vector_kernel(const float *__restrict__ V, float *__restrict__ Vt,
                                                             const DevCode *__restrict__ code, int b,
                                                             __bf16 *__restrict__ Vb, long ldVb,
                                                             float4 *__restrict__ zero, long zero_count4,
-                                                            int aligned) {
-  const int B = code->B, B0 = code->B0, a = code->a, r = code->r, N = code->N;
+                                                            Geometry geo) {
+  const int B = geo.B, B0 = geo.B0, a = geo.a, r = geo.r, N = geo.N;
   const int quads = B >> 2;
   const long idx = (long)blockIdx.x * 256 + threadIdx.x;
   const int job = blockIdx.y;            // 0 .. a-1: copy systematic block `job`; a: the r parity blocks
@@ -88,20 +94,30 @@ __global__ __launch_bounds__(256) void encode_vector_kernel(const float *__restr
   const int beta = (int)(idx / quads), rho = (int)(idx % quads) * 4;
   const float *src = V + (long)beta * N;
   float *dst = Vt + (long)beta * (a + r) * B;
-  if (job < a) {
-    const int i = job;
-    float v[4];
-    if (aligned) {        // N and B0 multiples of 4, V 16-byte aligned: whole quads are real or padding
+  // Entries rho .. rho + 3 of block i.  Unconditional loads (the address moves to the start of the
+  // row where the entry is padding, and the value is dropped): a guarded load would wait for its
+  // data in a branch of its own.  ALIGNED: N and B0 multiples of 4, V 16-byte aligned -- whole
+  // quads are real or padding.
+  auto fetch = [&](int i, float (&v)[4]) {
+    if constexpr (ALIGNED) {
       const int g = i * B0 + rho;
-      const float4 q = g < N ? *reinterpret_cast<const float4 *>(src + g) : make_float4(0.f, 0.f, 0.f, 0.f);
-      v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+      const bool ok = g < N;
+      const float4 q = *reinterpret_cast<const float4 *>(src + (ok ? g : 0));
+      v[0] = ok ? q.x : 0.f; v[1] = ok ? q.y : 0.f; v[2] = ok ? q.z : 0.f; v[3] = ok ? q.w : 0.f;
     } else {
 #pragma unroll
       for (int e = 0; e < 4; ++e) {
         const int g = i * B0 + rho + e;
-        v[e] = (rho + e < B0 && g < N) ? src[g] : 0.f;
+        const bool ok = rho + e < B0 && g < N;
+        const float q = src[ok ? g : 0];
+        v[e] = ok ? q : 0.f;
       }
     }
+  };
+  if (job < a) {
+    const int i = job;
+    float v[4];
+    fetch(i, v);
     *reinterpret_cast<float4 *>(dst + i * B + rho) = make_float4(v[0], v[1], v[2], v[3]);
     if (Vb != nullptr) {
       const __bf16 b0 = (__bf16)v[0], b1 = (__bf16)v[1], b2 = (__bf16)v[2], b3 = (__bf16)v[3];
@@ -113,30 +129,27 @@ __global__ __launch_bounds__(256) void encode_vector_kernel(const float *__restr
     return;
   }
   if (r == 0) return;
+  // parity block k = sum_i H[k][i] block_i, i ascending, eight blocks' loads in flight at a time
+  // (beyond the last block: block a - 1 again, with weight zero)
   float par[CODENET_MAX_R][4];
 #pragma unroll
   for (int k = 0; k < CODENET_MAX_R; ++k) par[k][0] = par[k][1] = par[k][2] = par[k][3] = 0.f;
-#pragma unroll 4
-  for (int i = 0; i < a; ++i) {
-    float v[4];
-    if (aligned) {
-      const int g = i * B0 + rho;
-      const float4 q = g < N ? *reinterpret_cast<const float4 *>(src + g) : make_float4(0.f, 0.f, 0.f, 0.f);
-      v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
-    } else {
+  for (int i0 = 0; i0 < a; i0 += 8) {
+    float v[8][4];
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const int g = i * B0 + rho + e;
-        v[e] = (rho + e < B0 && g < N) ? src[g] : 0.f;
-      }
+    for (int u = 0; u < 8; ++u) fetch(i0 + u < a ? i0 + u : a - 1, v[u]);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const bool live = i0 + u < a;
+      const int i = live ? i0 + u : a - 1;
+#pragma unroll
+      for (int k = 0; k < CODENET_MAX_R; ++k)
+        if (k < r) {
+          const float p = code->Hf[k][i];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) par[k][e] = live ? fmaf(p, v[u][e], par[k][e]) : par[k][e];
+        }
     }
-#pragma unroll
-    for (int k = 0; k < CODENET_MAX_R; ++k)
-      if (k < r) {
-        const float p = code->Hf[k][i];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) par[k][e] = fmaf(p, v[e], par[k][e]);
-      }
   }
 #pragma unroll
   for (int k = 0; k < CODENET_MAX_R; ++k)
@@ -144,20 +157,21 @@ __global__ __launch_bounds__(256) void encode_vector_kernel(const float *__restr
       *reinterpret_cast<float4 *>(dst + (a + k) * B + rho) = make_float4(par[k][0], par[k][1], par[k][2], par[k][3]);
 }
 
+
 hipError_t launch_encode_vector(const float *V, float *Vt, const DevCode *code_dev, const DevCode &code_host,
                                 int b, void *Vb, long ldVb, float *zero, long zero_count4, hipStream_t s) {
   const long total = (long)b * (code_host.B >> 2);
   dim3 grid((unsigned)((total + 255) / 256), (unsigned)(code_host.a + 1));
   const int aligned = (code_host.N % 4 == 0) && (code_host.B0 % 4 == 0) && ((reinterpret_cast<uintptr_t>(V) & 15) == 0);
-  hipLaunchKernelGGL(encode_vector_kernel, grid, dim3(256), 0, s, V, Vt, code_dev, b, (__bf16 *)Vb, ldVb,
-                     reinterpret_cast<float4 *>(zero), zero_count4, aligned);
+  if (aligned)
+    hipLaunchKernelGGL(encode_vector_kernel<true>, grid, dim3(256), 0, s, V, Vt, code_dev, b, (__bf16 *)Vb, ldVb,
+                       reinterpret_cast<float4 *>(zero), zero_count4, geometry_of(code_host));
+  else
+    hipLaunchKernelGGL(encode_vector_kernel<false>, grid, dim3(256), 0, s, V, Vt, code_dev, b, (__bf16 *)Vb, ldVb,
+                       reinterpret_cast<float4 *>(zero), zero_count4, geometry_of(code_host));
   return hipGetLastError();
 }
 
-// Block geometry by value: kernels that take it need no dependent load from the code table
-// before they can form their first address.
-struct Geometry { int B, B0, a, r, L, N; };
-static inline Geometry geometry_of(const DevCode &c) { return Geometry{c.B, c.B0, c.a, c.r, c.L, c.N}; }
 
 // The same encoding for the bf16 mode, one 64 (batch) x 64 (positions) tile of one
 // output block per workgroup.  It writes the two bf16 arrays that the MFMA kernels
@@ -926,21 +940,25 @@ __global__ __launch_bounds__(256) void regen_kernel(RegenArgs g, const DevCode *
         if (report->located[q] == i) return;
     }
   }
+  // work arrays of the one thread that derives the coefficients: in LDS, because dynamically
+  // indexed private arrays live in scratch memory, where every dependent access is a memory latency
+  __shared__ bool bad[CODENET_MAX_L];
+  __shared__ int As[CODENET_MAX_T], Q[CODENET_MAX_T];
+  __shared__ double M[CODENET_MAX_T][2 * CODENET_MAX_T];
+  __shared__ double cs[CODENET_MAX_T][CODENET_MAX_L];
   if (t == 0) {
     const int k = report->n_located;
-    bool bad[CODENET_MAX_L];
     for (int i = 0; i < L; ++i) bad[i] = false;
-    int As[CODENET_MAX_T], ks = 0;
+    int ks = 0;
     for (int p = 0; p < k; ++p) {
       const int i = report->located[p];
       bad[i] = true;
       if (i < a) As[ks++] = i;
     }
-    int Q[CODENET_MAX_T], nq = 0;
+    int nq = 0;
     for (int q = 0; q < r && nq < ks; ++q)
       if (!bad[a + q]) Q[nq++] = q;
     // M[x][y] = P[As[y]][Q[x]] = H[Q[x]][As[y]]; Gauss-Jordan with partial pivoting -> Minv
-    double M[CODENET_MAX_T][2 * CODENET_MAX_T];
     for (int x = 0; x < ks; ++x)
       for (int y = 0; y < ks; ++y) {
         M[x][y] = code->H[Q[x]][As[y]];
@@ -960,7 +978,6 @@ __global__ __launch_bounds__(256) void regen_kernel(RegenArgs g, const DevCode *
         }
     }
     // located systematic block As[y] = sum_x Minv[y][x] (parity_Q[x] - sum_{good i'} P[i'][Q[x]] block_i')
-    double cs[CODENET_MAX_T][CODENET_MAX_L];
     for (int y = 0; y < ks; ++y) {
       for (int i = 0; i < L; ++i) cs[y][i] = 0.0;
       for (int x = 0; x < ks; ++x) {
