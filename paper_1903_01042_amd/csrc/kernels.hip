@@ -755,13 +755,28 @@ __global__ __launch_bounds__(256) void finish_kernel(float *__restrict__ out, co
   __syncthreads();
   const int B = geo.B, B0 = geo.B0, L = geo.L, a = geo.a, r = geo.r, N = geo.N;
   if constexpr (VERIFY) {
+    // eight live entries at a time, this thread's two records of each from both evaluations: 32
+    // unconditional loads in flight (indices beyond the end are clamped: those records are compared
+    // again, which changes nothing)
     const int n_live = L + r * (r + 1) / 2;
+    static_assert(kDetectParts <= 512, "a thread compares records t and t + 256");
     int differ = 0;
-    for (int k = 0; k < n_live; ++k) {
-      const long e = k < L ? k : CODENET_MAX_L + (k - L);
-      for (int q = threadIdx.x; q < n_parts; q += 256)
-        differ |= __double_as_longlong(partials[e * kDetectParts + q]) !=
-                  __double_as_longlong(ver.partials_b[e * kDetectParts + q]);
+    for (int k0 = 0; k0 < n_live; k0 += 8) {
+      long long xa[8][2], xb[8][2];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int k = k0 + u < n_live ? k0 + u : n_live - 1;
+        const long e = k < L ? k : CODENET_MAX_L + (k - L);
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+          const int q = (int)threadIdx.x + 256 * h;
+          const long at = e * kDetectParts + (q < n_parts ? q : 0);
+          xa[u][h] = __double_as_longlong(partials[at]);
+          xb[u][h] = __double_as_longlong(ver.partials_b[at]);
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) differ |= (xa[u][0] != xb[u][0]) | (xa[u][1] != xb[u][1]);
     }
     differ = __syncthreads_or(differ);
     if (threadIdx.x == 0) {
