@@ -872,7 +872,17 @@ __global__ __launch_bounds__(256) void verify_kernel(const unsigned long long *_
                                                      codenet_report *__restrict__ report) {
   const unsigned long long first = votes[0];
   int differ = 0;
-  for (int q = threadIdx.x; q < n; q += 256) differ |= votes[q] != first;
+  // four words per thread and trip, loaded together (beyond the end: the last word again)
+  for (int q0 = 0; q0 < n; q0 += 1024) {
+    unsigned long long w[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int q = q0 + 256 * u + (int)threadIdx.x;
+      w[u] = votes[q < n ? q : n - 1];
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) differ |= w[u] != first;
+  }
   differ = __syncthreads_or(differ);
   if (differ && threadIdx.x == 0) {
     report->verdict = CODENET_DISAGREE;
