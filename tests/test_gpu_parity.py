@@ -329,6 +329,29 @@ def test_largest_parity_count_four_blocks_located_and_regenerated():
     pair.close()
 
 
+def test_longest_codeword():
+    """The longest codeword the interface takes, m + r = n + r = 40 blocks, in both dimensions (the
+    kernels walk the blocks in chunks of 8 and 16: last chunk full, indices clamped at the end):
+    clean products, one corrected block at either end of the codeword, two with t = 2, update."""
+    m, n, b = 38, 36, 5
+    P_r, P_c = WL.vandermonde_like(m, 2), WL.gaussian_generator(n, 4, 21)
+    n_out, n_in = 4 * m, 8 * n - 3            # the last block-column is ragged
+    pair = Pair(WL.layer_weights(n_out, n_in), P_r, P_c, "f32", b)
+    assert pair.gpu.coded_rows == 40 * pair.gpu.B_r and pair.gpu.coded_cols == 40 * pair.gpu.B_c
+    pair.check_weights(1e-6)
+    X, D = WL.normal((b, n_in), 51), WL.normal((b, n_out), 52)
+    for step, (rows, cols) in enumerate((((), ()), ((0,), (0, 39)), ((39,), (17, 35)), ((38,), (36,)))):
+        _, rep, _ = pair.product(FWD, X, [WL.make_fault(FWD, i, 0, step) for i in rows], check_margins=False)
+        assert rep["verdict"] == (CORRECTED if rows else CLEAN) and rep["located"] == list(rows)
+        _, rep, _ = pair.product(BWD, D, [WL.make_fault(BWD, 0, j, step) for j in cols], check_margins=False)
+        assert rep["verdict"] == (CORRECTED if cols else CLEAN) and rep["located"] == list(cols)
+        pair.update(0.05)
+        pair.check_weights()
+    _, rep, _ = pair.product(FWD, X, [WL.make_fault(FWD, 3, 0, 9), WL.make_fault(FWD, 30, 0, 9)], check_margins=False)
+    assert rep["verdict"] == UNCORRECTABLE
+    pair.close()
+
+
 # --------------------------------------------------------- multi-step, scaled copies
 @pytest.mark.parametrize("name,block,steps", [("cfg3", 64, 12), ("cfg5", 32, 12), ("cfg4", 32, 8)])
 def test_multi_step_on_a_width_scaled_copy(name, block, steps):
