@@ -34,7 +34,9 @@
  *    coded inputs [x; x~] (from codenet_forward) and [delta; delta~] (from
  *    codenet_backward) that codenet_update consumes, and all scratch memory,
  *    all allocated by codenet_encode and released by codenet_destroy.
- *  - Calls on one layer must not overlap in time (they share scratch memory).
+ *  - Calls on one layer must not overlap in time (they share scratch memory), and are made
+ *    with the device current that was current in codenet_encode (the layer's memory lives
+ *    there).  Different layers may be driven from different host threads.
  */
 #ifndef CODENET_H
 #define CODENET_H
@@ -172,7 +174,7 @@ int codenet_inject(codenet_layer *layer, const codenet_fault *faults_host, int n
  * coded_out_dev untouched (the caller rolls back; not an API error).
  * phase: CODENET_FWD or CODENET_BWD.  decoded_dev: [b][n_out] (FWD) or
  * [b][n_in] (BWD), receives the systematic part without padding; may be NULL.
- * report_dev: written by the GPU; may be NULL.
+ * report_dev: written by the GPU; may be NULL.  decoded_dev must not overlap coded_out_dev.
  */
 int codenet_detect_decode(codenet_layer *layer, int phase, float *coded_out_dev, int b,
                           float *decoded_dev, codenet_report *report_dev, void *stream);

@@ -2,9 +2,25 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <atomic>
 #include "codenet.h"
 
 namespace codenet {
+
+// A kernel that needs more than 64 KB of LDS has to be told so once per device; one of these per
+// kernel remembers on which devices that has happened (a bit per device ordinal).
+struct LdsOnce { std::atomic<unsigned long long> devices{0}; };
+template <typename K>
+inline hipError_t allow_lds(K kern, int lds_bytes, LdsOnce *once) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const unsigned long long bit = 1ull << (dev & 63);
+  if (once->devices.load(std::memory_order_acquire) & bit) return hipSuccess;
+  e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+  if (e == hipSuccess) once->devices.fetch_or(bit, std::memory_order_release);
+  return e;
+}
 
 constexpr int kDetectParts = 512;      // most per-workgroup partial records of one check
 constexpr int kFaultParts = 128;       // partial sums of squares per fault

@@ -333,15 +333,11 @@ hipError_t launch_one(GemmArgs g, hipStream_t s) {
   const int nt = tiles * g.splits;
   const int grid = ((nt + 7) / 8) * 8;
   auto kern = gemm_kernel<BF16, FM, FN, AKC, BKC, ACCUM>;
-  static bool attr_done = false;
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  static LdsOnce attr_done;
+  hipError_t e = allow_lds(kern, lds, &attr_done);
+  if (e != hipSuccess) return e;
   hipLaunchKernelGGL(kern, dim3(grid), dim3(256), lds, s, g);
-  hipError_t e = hipGetLastError();
+  e = hipGetLastError();
   if (e != hipSuccess || g.splits == 1) return e;
   return launch_reduce_partials(g.workspace, g.split_stride, g.splits, final_out, g.split_stride, s);
 }

@@ -989,22 +989,13 @@ struct Tile2 { int fm, fn, ns; };
 const Tile2 kTiles2[] = {{4, 2, 3}, {2, 2, 4}, {2, 2, 2}, {4, 4, 2}, {2, 4, 3}};
 constexpr int kNumTiles2 = 5;
 
-template <typename K>
-hipError_t set_lds(K kern, int lds, bool *done) {
-  if (*done) return hipSuccess;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-  if (e == hipSuccess) *done = true;
-  return e;
-}
-
 template <int FM, int FN, int NS, int DBG = 0>
 hipError_t launch2(Gemm2Args g, hipStream_t s) {
   constexpr int lds = NS * (64 * FM + 64 * FN) * 128;
   const int nt = g.tiles_i * g.tiles_j * g.splits;
   const int grid = ((nt + 7) / 8) * 8;
-  static bool attr_done = false;
-  hipError_t e = set_lds(gemm2_kernel<FM, FN, NS, DBG>, lds, &attr_done);
+  static LdsOnce attr_done;
+  hipError_t e = allow_lds(gemm2_kernel<FM, FN, NS, DBG>, lds, &attr_done);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((gemm2_kernel<FM, FN, NS, DBG>), dim3(grid), dim3(256), lds, s, g);
   return hipGetLastError();
@@ -1020,8 +1011,8 @@ hipError_t launch_upd2(Update2Args g, hipStream_t s) {
   g.tiles_j = (g.J + TJ - 1) / TJ;
   const int nt = g.tiles_i * g.tiles_j;
   const int grid = ((nt + 7) / 8) * 8;
-  static bool attr_done = false;
-  hipError_t e = set_lds(update2_kernel<FM, FN, NS, DBG>, lds, &attr_done);
+  static LdsOnce attr_done;
+  hipError_t e = allow_lds(update2_kernel<FM, FN, NS, DBG>, lds, &attr_done);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL((update2_kernel<FM, FN, NS, DBG>), dim3(grid), dim3(256), lds, s, g);
   return hipGetLastError();
@@ -1072,9 +1063,9 @@ hipError_t launch_gemm2(Gemm2Args g, int tile, float *workspace, hipStream_t s) 
     const char *env3 = getenv("CODENET_GEMM3");
     if (g.a_k_major || (tile == 1 && g.splits == 1 && !(env3 && env3[0] == '0'))) {
       constexpr int lds = 5 * (96 + 128) * 128;
-      static bool attr_done = false;
-      static bool attr_t_done = false;
-      e = g.a_k_major ? set_lds(product_kernel<true>, lds, &attr_t_done) : set_lds(product_kernel<false>, lds, &attr_done);
+      static LdsOnce attr_done;
+      static LdsOnce attr_t_done;
+      e = g.a_k_major ? allow_lds(product_kernel<true>, lds, &attr_t_done) : allow_lds(product_kernel<false>, lds, &attr_done);
       if (e != hipSuccess) return e;
       g.tiles_i = (g.I + 95) / 96;
       g.tiles_j = (g.J + 127) / 128;
@@ -1130,8 +1121,8 @@ hipError_t launch_upd3(Update2Args g, hipStream_t s) {
   constexpr int lds = 3 * 256 * 128 + 128 * 128 * 4;   // 160 KB
   g.tiles_i = (g.I + 127) / 128;
   g.tiles_j = (g.J + 127) / 128;
-  static bool attr_done = false;
-  hipError_t e = set_lds(update3_kernel<DBG>, lds, &attr_done);
+  static LdsOnce attr_done;
+  hipError_t e = allow_lds(update3_kernel<DBG>, lds, &attr_done);
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(update3_kernel<DBG>, dim3(256), dim3(512), lds, s, g);
   return hipGetLastError();
