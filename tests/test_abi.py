@@ -41,6 +41,14 @@ def test_struct_layouts_match_the_header():
     for name, val in (("CODENET_MAX_T", B.MAX_T), ("CODENET_MAX_R", B.MAX_R), ("CODENET_MAX_L", B.MAX_L),
                       ("CODENET_MAX_FAULTS", B.MAX_FAULTS)):
         assert re.search(r"#define\s+%s\s+%d\b" % (name, val), text), name
+    # enumerators the binding restates
+    for name, val in (("CODENET_CLEAN", B.CLEAN), ("CODENET_CORRECTED", B.CORRECTED),
+                      ("CODENET_UNCORRECTABLE", B.UNCORRECTABLE), ("CODENET_DISAGREE", B.DISAGREE),
+                      ("CODENET_FWD", B.FWD), ("CODENET_BWD", B.BWD), ("CODENET_WEIGHT", B.WEIGHT),
+                      ("CODENET_CHECK", B.CHECK), ("CODENET_CHECK_EVALUATION", B.CHECK_EVALUATION),
+                      ("CODENET_CHECK_LIST", B.CHECK_LIST), ("CODENET_EPI_MUL", B.EPI_MUL),
+                      ("CODENET_E_ALLOC", B.E_ALLOC)):
+        assert re.search(r"\b%s\s*=\s*%d\b" % (name, val), text), name
 
 
 def test_argument_errors_without_a_gpu(lib):
