@@ -173,26 +173,29 @@ hipError_t launch_encode_vector(const float *V, float *Vt, const DevCode *code_d
 }
 
 
-// The same encoding for the bf16 mode, one 64 (batch) x 64 (positions) tile of one
-// output block per workgroup.  It writes the two bf16 arrays that the MFMA kernels
+// The same encoding for the bf16 mode, one 64 (batch) x TP (positions) tile of one
+// output block per workgroup (TP = 32: 1280 workgroups at 4096 x 512 were measured at 6.8 us,
+// 640 of 64 x 64 at 7.7, 2560 of 64 x 16 at 8.6).  It writes the two bf16 arrays that the MFMA kernels
 // read (nothing in this mode reads an fp32 coded vector, so none is written): the
 // batch-major systematic part (operand of the product) and, through an LDS
 // transposition, the feature-major coded vector (operand of the update);
 // batch columns b .. Rpad-1 of the latter are written as zeros.  Jobs 0 .. a-1 copy
 // a systematic block, job a + k computes parity block k.
-template <bool ALIGNED>
+template <bool ALIGNED, int TP>
 __global__ __launch_bounds__(256) void encode_vector_bf16_kernel(const float *__restrict__ V,
                                                                  const DevCode *__restrict__ code, int b,
                                                                  __bf16 *__restrict__ Vb, long ldVb,
                                                                  __bf16 *__restrict__ VTb, long ldVT, int Rpad,
                                                                  Geometry geo) {
-  __shared__ unsigned short tile[64][66];
+  constexpr int PER_ROW = TP / 4, ROWS = 256 / PER_ROW, P = 64 / ROWS;   // threads per batch row, rows per pass, passes
+  static_assert(TP == 16 || TP == 32 || TP == 64, "tile width in positions");
+  __shared__ unsigned short tile[64][TP + 2];
   const int B = geo.B, B0 = geo.B0, a = geo.a, r = geo.r, N = geo.N;
   // the parity jobs read all a blocks: they are dispatched first so that they do not form the tail
-  const int rho0 = blockIdx.x * 64, beta0 = blockIdx.y * 64;
+  const int rho0 = blockIdx.x * TP, beta0 = blockIdx.y * 64;
   const int job = (int)blockIdx.z < r ? a + (int)blockIdx.z : (int)blockIdx.z - r;
   const int t = threadIdx.x;
-  const int c = (t & 15) * 4, rho = rho0 + c;
+  const int c = (t % PER_ROW) * 4, rho = rho0 + c;
   // Four entries rho .. rho + 3 of block i of one batch row.  The loads are unconditional, from an
   // address moved into the array where the entry is padding or the row is beyond the batch, and the
   // value is dropped afterwards: a load under a condition would sit in a branch of its own and wait
@@ -217,36 +220,36 @@ __global__ __launch_bounds__(256) void encode_vector_bf16_kernel(const float *__
     }
   };
   // this thread's four rows: rr = t / 16 + 16 p
-  float v[4][4];
+  float v[P][4];
   if (job < a) {
 #pragma unroll
-    for (int p = 0; p < 4; ++p) fetch(beta0 + (t >> 4) + 16 * p, job, v[p]);
+    for (int p = 0; p < P; ++p) fetch(beta0 + t / PER_ROW + ROWS * p, job, v[p]);
   } else {
     // parity block k = sum_i H[k][i] block_i, i ascending; eight blocks x four rows of loads in flight
     // at a time (beyond the last block: block a - 1 again, with weight zero)
 #pragma unroll
-    for (int p = 0; p < 4; ++p) v[p][0] = v[p][1] = v[p][2] = v[p][3] = 0.f;
+    for (int p = 0; p < P; ++p) v[p][0] = v[p][1] = v[p][2] = v[p][3] = 0.f;
     const int k = job - a;
     for (int i0 = 0; i0 < a; i0 += 8) {
-      float x[8][4][4];
+      float x[8][P][4];
 #pragma unroll
       for (int u = 0; u < 8; ++u)
 #pragma unroll
-        for (int p = 0; p < 4; ++p) fetch(beta0 + (t >> 4) + 16 * p, i0 + u < a ? i0 + u : a - 1, x[u][p]);
+        for (int p = 0; p < P; ++p) fetch(beta0 + t / PER_ROW + ROWS * p, i0 + u < a ? i0 + u : a - 1, x[u][p]);
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
         const bool live = i0 + u < a;
         const float h = code->Hf[k][live ? i0 + u : a - 1];
 #pragma unroll
-        for (int p = 0; p < 4; ++p)
+        for (int p = 0; p < P; ++p)
 #pragma unroll
           for (int e = 0; e < 4; ++e) v[p][e] = live ? fmaf(h, x[u][p][e], v[p][e]) : v[p][e];
       }
     }
   }
 #pragma unroll
-  for (int p = 0; p < 4; ++p) {
-    const int rr = (t >> 4) + 16 * p, beta = beta0 + rr;
+  for (int p = 0; p < P; ++p) {
+    const int rr = t / PER_ROW + ROWS * p, beta = beta0 + rr;
     const __bf16 b0 = (__bf16)v[p][0], b1 = (__bf16)v[p][1], b2 = (__bf16)v[p][2], b3 = (__bf16)v[p][3];
     const unsigned short u0 = __builtin_bit_cast(unsigned short, b0), u1 = __builtin_bit_cast(unsigned short, b1),
                          u2 = __builtin_bit_cast(unsigned short, b2), u3 = __builtin_bit_cast(unsigned short, b3);
@@ -261,7 +264,7 @@ __global__ __launch_bounds__(256) void encode_vector_bf16_kernel(const float *__
   __syncthreads();
   // feature-major: thread t writes batch rows 4 (t % 16) .. + 3 of positions t / 16 + 16 p
 #pragma unroll
-  for (int p = 0; p < 4; ++p) {
+  for (int p = 0; p < P; ++p) {
     const int cc = (t >> 4) + 16 * p, rr = (t & 15) * 4;
     if (rho0 + cc < B && beta0 + rr < Rpad) {
       uint2 pk;
@@ -275,14 +278,21 @@ __global__ __launch_bounds__(256) void encode_vector_bf16_kernel(const float *__
 hipError_t launch_encode_vector_bf16(const float *V, const DevCode *code_dev, const DevCode &code_host,
                                      int b, void *Vb, long ldVb, void *VTb, long ldVT, hipStream_t s) {
   const int Rpad = (b + 63) & ~63;
-  dim3 grid((unsigned)((code_host.B + 63) / 64), (unsigned)(Rpad / 64), (unsigned)(code_host.a + code_host.r));
   const int aligned = (code_host.N % 4 == 0) && (code_host.B0 % 4 == 0) && ((reinterpret_cast<uintptr_t>(V) & 15) == 0);
-  if (aligned)
-    hipLaunchKernelGGL(encode_vector_bf16_kernel<true>, grid, dim3(256), 0, s, V, code_dev, b, (__bf16 *)Vb, ldVb,
-                       (__bf16 *)VTb, ldVT, Rpad, geometry_of(code_host));
-  else
-    hipLaunchKernelGGL(encode_vector_bf16_kernel<false>, grid, dim3(256), 0, s, V, code_dev, b, (__bf16 *)Vb, ldVb,
-                       (__bf16 *)VTb, ldVT, Rpad, geometry_of(code_host));
+  // tile width in positions (CODENET_ENCODE_TP: 16, 32 or 64, for tuning runs)
+  const char *env = getenv("CODENET_ENCODE_TP");
+  const int tp = env ? atoi(env) : 32;
+#define CODENET_ENCODE(AL, TPV)                                                                                       \
+  hipLaunchKernelGGL((encode_vector_bf16_kernel<AL, TPV>),                                                             \
+                     dim3((unsigned)((code_host.B + TPV - 1) / TPV), (unsigned)(Rpad / 64),                            \
+                          (unsigned)(code_host.a + code_host.r)),                                                      \
+                     dim3(256), 0, s, V, code_dev, b, (__bf16 *)Vb, ldVb, (__bf16 *)VTb, ldVT, Rpad, geometry_of(code_host))
+  if (aligned) {
+    if (tp == 16) CODENET_ENCODE(true, 16); else if (tp == 64) CODENET_ENCODE(true, 64); else CODENET_ENCODE(true, 32);
+  } else {
+    if (tp == 16) CODENET_ENCODE(false, 16); else if (tp == 64) CODENET_ENCODE(false, 64); else CODENET_ENCODE(false, 32);
+  }
+#undef CODENET_ENCODE
   return hipGetLastError();
 }
 
