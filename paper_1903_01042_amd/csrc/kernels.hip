@@ -954,6 +954,7 @@ hipError_t launch_finish(float *out, const float *syn, const double *partials, i
 // CORRECTED.  One workgroup rebuilds a 64 x 64 tile of one located block:
 // fp32 matrix and its bf16 copy.
 // ---------------------------------------------------------------------------
+template <int TR>      // tile height: TR rows x 64 columns per workgroup
 __global__ __launch_bounds__(256) void regen_kernel(RegenArgs g, const DevCode *__restrict__ code,
                                                     const codenet_report *__restrict__ report) {
   __shared__ float coef[CODENET_MAX_L];
@@ -1045,7 +1046,9 @@ __global__ __launch_bounds__(256) void regen_kernel(RegenArgs g, const DevCode *
   const int target = s_target, n_src = s_n_src;
   const int B = code->B;
   // tile (r0, c0) of the located block; along the code's axis the block offset is target * B
-  const int r0 = blockIdx.y * 64, c0 = blockIdx.x * 64;
+  constexpr int P = TR / 16;
+  static_assert(TR == 16 || TR == 32 || TR == 64, "tile height");
+  const int r0 = blockIdx.y * TR, c0 = blockIdx.x * 64;
   const int rows = g.axis == 0 ? B : g.Mr, cols = g.axis == 0 ? g.Nc : B;
   const long blk = g.axis == 0 ? (long)B * g.Nc : (long)B;      // distance between consecutive blocks of a line
   const int gr0 = g.axis == 0 ? target * B + r0 : r0;           // row / column of the tile in the coded matrix
@@ -1057,11 +1060,11 @@ __global__ __launch_bounds__(256) void regen_kernel(RegenArgs g, const DevCode *
   // branch of its own.
   const int cc = (t & 15) * 4;
   const int ccl = c0 + cc < cols ? c0 + cc : cols - 4;
-  const float *first[4];
-  bool in[4];
-  float4 v[4];
+  const float *first[P];
+  bool in[P];
+  float4 v[P];
 #pragma unroll
-  for (int p = 0; p < 4; ++p) {
+  for (int p = 0; p < P; ++p) {
     const int rr = (t >> 4) + 16 * p;
     in[p] = r0 + rr < rows && c0 + cc < cols;
     const int rrl = r0 + rr < rows ? r0 + rr : rows - 1;
@@ -1069,7 +1072,7 @@ __global__ __launch_bounds__(256) void regen_kernel(RegenArgs g, const DevCode *
     v[p] = make_float4(0.f, 0.f, 0.f, 0.f);
   }
   for (int q0 = 0; q0 < n_src; q0 += 8) {
-    float4 x[4][8];
+    float4 x[P][8];
     long off[8];
     float w[8];
 #pragma unroll
@@ -1081,17 +1084,17 @@ __global__ __launch_bounds__(256) void regen_kernel(RegenArgs g, const DevCode *
 #pragma unroll
     for (int u = 0; u < 8; ++u)
 #pragma unroll
-      for (int p = 0; p < 4; ++p) x[p][u] = *reinterpret_cast<const float4 *>(first[p] + off[u]);
+      for (int p = 0; p < P; ++p) x[p][u] = *reinterpret_cast<const float4 *>(first[p] + off[u]);
 #pragma unroll
     for (int u = 0; u < 8; ++u)
 #pragma unroll
-      for (int p = 0; p < 4; ++p) {
+      for (int p = 0; p < P; ++p) {
         v[p].x = fmaf(w[u], x[p][u].x, v[p].x); v[p].y = fmaf(w[u], x[p][u].y, v[p].y);
         v[p].z = fmaf(w[u], x[p][u].z, v[p].z); v[p].w = fmaf(w[u], x[p][u].w, v[p].w);
       }
   }
 #pragma unroll
-  for (int p = 0; p < 4; ++p) {
+  for (int p = 0; p < P; ++p) {
     if (!in[p]) continue;
     const int rr = (t >> 4) + 16 * p;
     *reinterpret_cast<float4 *>(g.W + (long)(gr0 + rr) * g.Nc + gc0 + cc) = v[p];
@@ -1112,8 +1115,13 @@ hipError_t launch_regen(RegenArgs g, const DevCode *code_dev, const DevCode &ch,
   const int tcap = ch.r / 2 < CODENET_MAX_T ? ch.r / 2 : CODENET_MAX_T;
   if (tcap < 1) return hipSuccess;
   const int rows = g.axis == 0 ? ch.B : g.Mr, cols = g.axis == 0 ? g.Nc : ch.B;
-  dim3 grid((unsigned)((cols + 63) / 64), (unsigned)((rows + 63) / 64), (unsigned)tcap);
-  hipLaunchKernelGGL(regen_kernel, grid, dim3(256), 0, s, g, code_dev, report);
+  // tile height (CODENET_REGEN_TR: 16, 32 or 64, for tuning runs)
+  const char *env = getenv("CODENET_REGEN_TR");
+  const int tr = env ? atoi(env) : 32;      // 20.3 us at cfg3 against 20.9 (64) and 21.2 (16)
+  const unsigned gx = (unsigned)((cols + 63) / 64);
+  if (tr == 16) hipLaunchKernelGGL(regen_kernel<16>, dim3(gx, (unsigned)((rows + 15) / 16), (unsigned)tcap), dim3(256), 0, s, g, code_dev, report);
+  else if (tr == 32) hipLaunchKernelGGL(regen_kernel<32>, dim3(gx, (unsigned)((rows + 31) / 32), (unsigned)tcap), dim3(256), 0, s, g, code_dev, report);
+  else hipLaunchKernelGGL(regen_kernel<64>, dim3(gx, (unsigned)((rows + 63) / 64), (unsigned)tcap), dim3(256), 0, s, g, code_dev, report);
   return hipGetLastError();
 }
 
