@@ -23,3 +23,35 @@ def test_traffic_figure_comes_from_the_committed_counter_summary():
     text = open(os.path.join(ROOT, "profiles", "cfg3_update_kernel_hbm_traffic.txt")).read()
     assert "rocprofv3 --pmc FETCH_SIZE" in text and "rocprofv3 --pmc WRITE_SIZE" in text
     assert bench.measured_traffic("no-such-workload") is None
+
+
+import json
+
+import pytest
+
+
+@pytest.mark.gpu
+def test_the_bench_line_keeps_its_contract():
+    """One JSON line on stdout with the fields the driver reads, the roofline of the dominant kernel
+    and the oracle's CPU baseline (short run: 30 timed steps, 2 oracle steps)."""
+    p = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--steps", "30", "--warmup", "5",
+                        "--cpu-steps", "2"], capture_output=True, text=True, timeout=600, cwd=ROOT)
+    assert p.returncode == 0, p.stderr[-2000:]
+    lines = [l for l in p.stdout.splitlines() if l.strip()]
+    assert len(lines) == 1, lines
+    d = json.loads(lines[0])
+    for key in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
+                "vs_baseline", "dtype", "data", "config", "roofline", "cpu_baseline"):
+        assert key in d, key
+    assert d["n_gpus"] == 1 and d["steps"] == 30 and d["warmup"] == 5 and d["higher_is_better"] is True
+    assert d["unit"] == "coded layer-steps/s" and d["vs_baseline"] is None and d["data"] == "synthetic"
+    assert abs(d["value"] * d["ms_per_step"] - 1000.0) < 1e-6 * 1000.0
+    assert d["config"]["workload"].startswith("cfg3") and "model" not in d["config"]
+    r = d["roofline"]
+    assert r["bound"] == "hbm" and r["unit"] == "GB/s" and r["peak"] == 8000.0
+    assert abs(r["frac"] - r["achieved"] / r["peak"]) < 1e-9 and 0.05 < r["frac"] < 1.0
+    assert abs(r["achieved"] - r["algorithmic_bytes"] / (r["avg_launch_ms"] * 1e-3) / 1e9) < 1e-6 * r["achieved"]
+    assert r["traffic"] is None or r["traffic"] > r["algorithmic_bytes"] * 0.9
+    c = d["cpu_baseline"]
+    assert c["kind"] == "oracle" and c["cores"] >= 1 and c["value"] > 0 and c["unit"] == d["unit"] and c["sample"]
+    assert sum(d["verdicts"].values()) == 60 and d["verified_checks_agree"] is True
