@@ -592,9 +592,10 @@ __device__ __forceinline__ void decide_body(const double *partials, int n_parts,
 // the coded output is read once.  (Letting the last workgroup to finish take the
 // decision in the same kernel was tried: the device-scope fence it needs writes
 // back the L2 of every XCD and cost 25 us; a second tiny kernel costs 3-10 us.)
-// Per-thread float32 sums over a few
-// positions, then float64 across lanes, wavefronts and workgroups in a fixed
-// order (no atomics), so the decision is reproducible.
+// Per-thread float32 sums over a few positions, then float64 across lanes,
+// wavefronts and workgroups in a fixed order (no atomics), so the decision is
+// reproducible -- and two evaluations of it are bit-identical, which the verified
+// check relies on.
 // ---------------------------------------------------------------------------
 template <int R, int CH>
 __global__ __launch_bounds__(256) void detect_kernel(const float *__restrict__ out, float *__restrict__ syn,
