@@ -181,11 +181,21 @@ class Runner:
             if s >= warmup:
                 events[s] = ev
 
+        def stamped_update(s):
+            rc = self.lib.codenet_timestamp(ctypes.c_void_p(self.stamps[s, 0].data_ptr()), stream,
+                                            ctypes.byref(self.ticks_per_us))
+            rc |= self.lib.codenet_update(self.h, self.eta, stream)
+            rc |= self.lib.codenet_timestamp(ctypes.c_void_p(self.stamps[s, 1].data_ptr()), stream, None)
+            if rc:
+                raise RuntimeError("codenet_update failed (rc=%d)" % rc)
+
         def one(s):
             if eager:
                 self.pre_update(s, stream)
                 if s % self.EAGER_EVENT_EVERY == 2:
                     timed_update(s)
+                elif s % self.EAGER_EVENT_EVERY == 10:
+                    stamped_update(s)       # a second clock on other steps: the GPU's own, read by two tiny kernels
                 elif self.lib.codenet_update(self.h, self.eta, stream):
                     raise RuntimeError("codenet_update failed")
                 return
@@ -405,9 +415,14 @@ def main():
                                           "on its own" % Runner.EVENT_EVERY) if args.graph else
                      ("HIP events around the kernel, on its stream, on every %d-th step of the timed region"
                       % Runner.EAGER_EVENT_EVERY),
-                     "in_graph_ms": upd_ms,
+                     "in_graph_ms": upd_ms if args.graph else None,
                      "in_graph_ms_by": ("device time stamps before and after the kernel inside the graph of every "
                                         "%d-th step of the timed region" % Runner.STAMP_EVERY) if args.graph else None,
+                     "device_stamp_ms": upd_ms,
+                     "device_stamp_ms_by": "codenet_timestamp kernels (the GPU's 100 MHz wall clock) before and after the "
+                                           "update on %s of the timed region: the kernel plus one kernel boundary"
+                                           % ("every %d-th step" % (Runner.STAMP_EVERY if args.graph
+                                                                     else Runner.EAGER_EVENT_EVERY)),
                      "back_to_back_ms_hip_events": upd_events_ms,
                      "algorithmic_bytes": upd_bytes,
                      "tflops": coded.flops["upd"] / (launch_ms * 1e-3) / 1e12},
