@@ -352,6 +352,42 @@ def test_longest_codeword():
     pair.close()
 
 
+@pytest.mark.parametrize("seed", [7, 2026])
+def test_random_ragged_layers_agree_with_the_oracle(seed):
+    """Seeded random layers -- grids up to 11 x 11, r in {1, 2, 4}, nothing dividing anything, batches
+    from 1 to 260, both dtypes -- two steps each with up to t + 1 faulty blocks per product, plain and
+    verified checks, regeneration after every forward check, update: verdicts, located sets, outputs
+    and coded weights as the oracle's every time."""
+    g = np.random.default_rng(seed)
+    for case in range(25):
+        m, n = int(g.integers(1, 12)), int(g.integers(1, 12))
+        r = int(g.choice([1, 2, 2, 2, 4]))
+        n_out = max(int(m * g.integers(1, 40) + g.integers(0, m)), m)
+        n_in = max(int(n * g.integers(1, 40) + g.integers(0, n)), n)
+        b = int(g.choice([1, 3, 8, 17, 64, 130, 260]))
+        dtype = "bf16" if g.random() < 0.4 else "f32"
+        if r <= 2:
+            P_r, P_c = WL.vandermonde_like(m, r), WL.vandermonde_like(n, r)
+        else:
+            P_r, P_c = WL.gaussian_generator(m, r, 100 + case), WL.gaussian_generator(n, r, 200 + case)
+        tau = (1e-3, 1e-2) if dtype == "f32" else (2e-2, 2e-2)
+        say("random layer", seed, case, n_out, n_in, m, n, r, b, dtype)
+        pair = Pair(WL.layer_weights(n_out, n_in), P_r, P_c, dtype, b, *tau)
+        X, D = WL.normal((b, n_in), 300 + case), WL.normal((b, n_out), 400 + case)
+        t = r // 2
+        for step in range(2):
+            rows = sorted(g.choice(m + r, size=min(int(g.integers(0, t + 2)), m + r), replace=False).tolist())
+            faults = [WL.make_fault(FWD, i, int(g.integers(0, n)), step) for i in rows]
+            _, _, res = pair.product(FWD, X, faults, check_margins=False, verified=bool(g.integers(0, 2)))
+            pair.regenerate(FWD, res)
+            cols = sorted(g.choice(n + r, size=min(int(g.integers(0, t + 2)), n + r), replace=False).tolist())
+            faults = [WL.make_fault(BWD, int(g.integers(0, m)), j, step) for j in cols]
+            pair.product(BWD, D, faults, check_margins=False)
+            pair.update(0.05)
+            pair.check_weights()
+        pair.close()
+
+
 # --------------------------------------------------------- multi-step, scaled copies
 @pytest.mark.parametrize("name,block,steps", [("cfg3", 64, 12), ("cfg5", 32, 12), ("cfg4", 32, 8)])
 def test_multi_step_on_a_width_scaled_copy(name, block, steps):
