@@ -402,6 +402,9 @@ def main():
         "ms_per_step_verified_checks": ms_verified,
         "verified_checks_agree": counts_verified == counts,
         "algorithmic_overhead_floor": floor,
+        # what the checks, encodings and injection cost beyond the redundant rows themselves
+        "excess_over_floor": (ms_coded / ms_uncoded) / (1.0 + floor) - 1.0,
+        "excess_over_floor_without_injection": ((ms_clean / ms_uncoded) / (1.0 + floor) - 1.0) if ms_clean else None,
         "verdicts": counts,
         "update_kernel_ms_uncoded": upd_ms_unc if args.graph else uncoded.upd_ms_events,
         "roofline": {"kernel": "update3_kernel (W~ += eta [d;d~][x;x~]^T, fp32 RMW + bf16 copy)"
