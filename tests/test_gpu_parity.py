@@ -8,7 +8,7 @@ import numpy as np
 import pytest
 
 from paper_1903_01042_amd import workloads as WL
-from harness import MlpPair, Pair, rel_fro, to_np
+from harness import TOL, MlpPair, Pair, rel_fro, to_np
 
 pytestmark = pytest.mark.gpu
 
@@ -135,6 +135,77 @@ def test_full_size_layer_step(name):
     _, rep, _ = pair.product(FWD, wl.inputs(2))
     assert rep["verdict"] == CLEAN
     pair.close()
+
+
+@pytest.mark.parametrize("name,steps,drift_every", [("cfg3", 48, 16), ("cfg5", 51, 50)])
+def test_full_size_multi_step_invariants(name, steps, drift_every):
+    """Many steps at the benchmark size under the workload's own fault law, as bench.py drives them
+    (the oracle cannot follow every step at this size; a width-scaled copy is followed step by step
+    elsewhere).  What must hold at any size: (i) the number of faulty blocks planted decides the
+    verdict (none: CLEAN; at most t: CORRECTED with exactly those blocks located; more:
+    UNCORRECTABLE, output untouched); (ii) an accepted output checks CLEAN when checked again;
+    (iii) every `drift_every` steps the stored matrix is still a codeword: it equals the oracle's
+    encoding of its own systematic part; (iv) at the end the systematic part equals the plain
+    float64 update W + eta sum_s Delta_s X_s^T (cfg3; the product of the method, O-upd)."""
+    import torch
+    from oracle import codenet_oracle as O
+    from paper_1903_01042_amd import binding as B
+    wl = WL.WORKLOADS[name]
+    n_in, n_out = wl.widths[0], wl.widths[1]
+    m, n = wl.grid
+    t = wl.r // 2
+    P_r, P_c = wl.generators()
+    W0 = WL.layer_weights(n_out, n_in)
+    dev = torch.device("cuda:0")
+    lay = B.CodedLayer(torch.from_numpy(W0).to(dev), P_r, P_c, dtype=B.BF16_F32ACC if wl.dtype == "bf16" else B.F32,
+                       max_batch=wl.batch, tau_detect=wl.tau_detect, tau_resid=wl.tau_resid)
+    tol = TOL[wl.dtype]
+    rep, rep2 = lay.new_report(), lay.new_report()
+    ref = W0.astype(np.float64) if name == "cfg3" else None
+    seen = set()
+
+    def checked_product(phase, V, faults):
+        out = lay.forward(V) if phase == FWD else lay.backward(V)
+        lay.inject(faults, out)
+        before = out.clone()
+        lay.detect_decode(phase, out, report=rep, want_decoded=False)
+        got = lay.read_report(rep)
+        hit = sorted({f["bi"] if phase == FWD else f["bj"] for f in faults})
+        want = CLEAN if not hit else (CORRECTED if len(hit) <= t else UNCORRECTABLE)
+        assert got["verdict"] == want, (phase, hit, got)
+        seen.add(want)
+        if want == CORRECTED:
+            assert got["located"] == hit, (hit, got)
+        if want == UNCORRECTABLE:
+            assert got["located"] == [] and torch.equal(out, before)
+        else:
+            lay.detect_decode(phase, out, report=rep2, want_decoded=False)
+            assert lay.read_report(rep2)["verdict"] == CLEAN
+        return got
+
+    for step in range(steps):
+        say(name, "full size step", step)
+        X, D = wl.inputs(step), wl.deltas(step)
+        Xd, Dd = torch.from_numpy(X).to(dev), torch.from_numpy(D).to(dev)
+        checked_product(FWD, Xd, wl.product_faults(FWD, step))
+        checked_product(BWD, Dd, wl.product_faults(BWD, step))
+        lay.update(wl.eta)
+        if ref is not None:
+            ref += wl.eta * (D.astype(np.float64).T @ X.astype(np.float64))
+        if (step + 1) % drift_every == 0:
+            Wc = to_np(lay.export_coded()).astype(np.float64)
+            sys_part = Wc[: m * lay.B_r, : n * lay.B_c]
+            again = O.encode(sys_part, P_r, P_c, lay.B_r, lay.B_c)
+            drift = rel_fro(Wc, again)
+            say(name, "drift after", step + 1, "steps: %.3e" % drift)
+            assert drift <= tol, drift
+            del Wc, again
+    assert len(seen) >= 2, seen            # the fault law produces more than one kind of step
+    if ref is not None:
+        err = rel_fro(to_np(lay.export_weights()), ref)
+        say(name, "weights after", steps, "steps against the plain float64 update: %.3e" % err)
+        assert err <= tol, err
+    lay.destroy()
 
 
 # ------------------------------------------------------------- ragged / odd shapes
