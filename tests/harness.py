@@ -151,8 +151,14 @@ class Pair:
 class MlpPair:
     EPI_RELU, EPI_MASK_POS = 1, 2
 
-    def __init__(self, wl, max_layers=None):
+    def __init__(self, wl, max_layers=None, roll_forward=False):
+        """roll_forward: the stored blocks of every located node are regenerated after a CORRECTED
+        check, and the workload's update-stage (weight) faults are planted after every update."""
         self.wl = wl
+        self.roll_forward = roll_forward
+        self.regenerated = 0
+        self.restored = 0
+        self.ckpt = {}
         widths = wl.widths if max_layers is None else wl.widths[: max_layers + 1]
         self.layers = []
         for l in range(len(widths) - 1):
@@ -168,7 +174,18 @@ class MlpPair:
         self.counts[rep["verdict"]] += 1
         if rep["verdict"] == O.UNCORRECTABLE:
             dec, rep, res = pair.product(phase, V, (), epilogue=epilogue, aux=aux)   # roll back = recompute the product
-            assert rep["verdict"] == O.CLEAN
+            if rep["verdict"] == O.UNCORRECTABLE and self.roll_forward and l in self.ckpt:
+                # more persistent (weight) faults than the code corrects: the paper restores the last
+                # checkpoint -- here the layer as it was after its last update, encoded afresh
+                pair = self.restore(l)
+                dec, rep, res = pair.product(phase, V, (), epilogue=epilogue, aux=aux)
+            if not self.roll_forward:
+                assert rep["verdict"] == O.CLEAN
+            else:        # a single persistent fault may still be there: it is located now
+                assert rep["verdict"] != O.UNCORRECTABLE
+        if self.roll_forward and rep["verdict"] == O.CORRECTED:
+            pair.regenerate(phase, res)
+            self.regenerated += 1
         return to_np(dec).astype(np.float32), res["decoded"].T.astype(np.float32)
 
     def step(self, step, labels=None):
@@ -204,7 +221,20 @@ class MlpPair:
                 delta = c_g.astype(np.float32)
         for l in range(L):
             self.layers[l].update(wl.eta)
+        if self.roll_forward and wl.weight_faults:
+            for l in range(L):       # errors of the update stage: seen by the next step's products
+                self.ckpt[l] = self.layers[l].ora.weights().copy()      # checkpoint: the state the update should leave
+                self.layers[l].inject_weights(wl.update_faults(step, l))
         return loss
+
+    def restore(self, l):
+        """Both sides of layer l re-created from the checkpointed weights."""
+        old = self.layers[l]
+        P_r, P_c = self.wl.generators(l)
+        old.close()
+        self.layers[l] = Pair(self.ckpt[l], P_r, P_c, self.wl.dtype, self.wl.batch, self.wl.tau_detect, self.wl.tau_resid)
+        self.restored += 1
+        return self.layers[l]
 
     def close(self):
         for p in self.layers:

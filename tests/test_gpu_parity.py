@@ -96,6 +96,28 @@ def test_cfg2_mlp_full_size():
     mlp.close()
 
 
+def test_cfg4_style_mlp_rolls_forward_through_update_stage_faults():
+    """A width-scaled copy of cfg4 (MLP with an 8 x 8 grid + 2 parity rows / columns per layer, ReLU)
+    with its three kinds of faults -- forward outputs, backward outputs and stored blocks after the
+    update: every located node is regenerated and training goes on; where more stored blocks are hit
+    than the code corrects, the layer is restored from its checkpoint (the state after its last update)
+    as the paper prescribes; every product of every step as the oracle's, weights at the end."""
+    import dataclasses
+    wl = dataclasses.replace(WL.WORKLOADS["cfg4"].scaled(32, batch=48), fault_p=0.003)
+    mlp = MlpPair(wl, max_layers=4, roll_forward=True)
+    planted = 0
+    for step in range(10):
+        say("cfg4-style step", step)
+        mlp.step(step)
+        planted += sum(len(wl.update_faults(step, l)) for l in range(4))
+    for l, pair in enumerate(mlp.layers):
+        say("cfg4-style layer", l, "coded weights rel err", pair.check_weights())
+    say("cfg4-style verdict counts", mlp.counts, "regenerations", mlp.regenerated, "restores", mlp.restored,
+        "weight faults planted", planted)
+    assert planted > 0 and mlp.regenerated > 0 and mlp.counts[1] > 0 and mlp.restored >= 1
+    mlp.close()
+
+
 # ------------------------------------------------- full-size single layers, one step
 @pytest.mark.parametrize("name", ["cfg3", "cfg4", "cfg5"])
 def test_full_size_layer_step(name):
