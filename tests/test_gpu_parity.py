@@ -159,8 +159,8 @@ def test_full_size_layer_step(name):
     pair.close()
 
 
-@pytest.mark.parametrize("name,steps,drift_every", [("cfg3", 48, 16), ("cfg5", 51, 50)])
-def test_full_size_multi_step_invariants(name, steps, drift_every):
+@pytest.mark.parametrize("name,steps,drift_every,probe_every", [("cfg3", 48, 16, 6), ("cfg5", 51, 50, 25)])
+def test_full_size_multi_step_invariants(name, steps, drift_every, probe_every):
     """Many steps at the benchmark size under the workload's own fault law, as bench.py drives them
     (the oracle cannot follow every step at this size; a width-scaled copy is followed step by step
     elsewhere).  What must hold at any size: (i) the number of faulty blocks planted decides the
@@ -168,7 +168,10 @@ def test_full_size_multi_step_invariants(name, steps, drift_every):
     UNCORRECTABLE, output untouched); (ii) an accepted output checks CLEAN when checked again;
     (iii) every `drift_every` steps the stored matrix is still a codeword: it equals the oracle's
     encoding of its own systematic part; (iv) at the end the systematic part equals the plain
-    float64 update W + eta sum_s Delta_s X_s^T (cfg3; the product of the method, O-upd)."""
+    float64 update W + eta sum_s Delta_s X_s^T (cfg3; the product of the method, O-upd); (v) every
+    `probe_every` steps both coded products pass a float64 Freivalds probe against the stored
+    matrix of that step: out^T z = W~ (V^T z) for a random z over the batch (library-independent
+    float64 arithmetic in torch)."""
     import torch
     from oracle import codenet_oracle as O
     from paper_1903_01042_amd import binding as B
@@ -186,8 +189,21 @@ def test_full_size_multi_step_invariants(name, steps, drift_every):
     ref = W0.astype(np.float64) if name == "cfg3" else None
     seen = set()
 
-    def checked_product(phase, V, faults):
+    def probe(phase, V, out, Wc64, step):
+        z = torch.from_numpy(np.random.default_rng(9000 + step).standard_normal(wl.batch)).to(dev)
+        lhs = out.double().T @ z
+        if phase == FWD:
+            rhs = Wc64[:, : n * lay.B_c] @ (V.double().T @ z)
+        else:
+            rhs = Wc64[: m * lay.B_r, :].T @ (V.double().T @ z)
+        err = float(torch.linalg.norm(lhs - rhs) / torch.linalg.norm(rhs))
+        assert err <= tol, (name, phase, step, err)
+        return err
+
+    def checked_product(phase, V, faults, Wc64=None, step=0):
         out = lay.forward(V) if phase == FWD else lay.backward(V)
+        if Wc64 is not None:
+            say(name, "Freivalds probe, phase", phase, "step", step, "%.2e" % probe(phase, V, out, Wc64, step))
         lay.inject(faults, out)
         before = out.clone()
         lay.detect_decode(phase, out, report=rep, want_decoded=False)
@@ -209,8 +225,10 @@ def test_full_size_multi_step_invariants(name, steps, drift_every):
         say(name, "full size step", step)
         X, D = wl.inputs(step), wl.deltas(step)
         Xd, Dd = torch.from_numpy(X).to(dev), torch.from_numpy(D).to(dev)
-        checked_product(FWD, Xd, wl.product_faults(FWD, step))
-        checked_product(BWD, Dd, wl.product_faults(BWD, step))
+        Wc64 = lay.export_coded().double() if step % probe_every == 0 else None
+        checked_product(FWD, Xd, wl.product_faults(FWD, step), Wc64, step)
+        checked_product(BWD, Dd, wl.product_faults(BWD, step), Wc64, step)
+        del Wc64
         lay.update(wl.eta)
         if ref is not None:
             ref += wl.eta * (D.astype(np.float64).T @ X.astype(np.float64))
