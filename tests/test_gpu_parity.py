@@ -248,6 +248,100 @@ def test_full_size_multi_step_invariants(name, steps, drift_every, probe_every):
     lay.destroy()
 
 
+def test_cfg4_full_size_mlp_invariants():
+    """The 8-layer width-8192 MLP of cfg4 at its real size (8 x 8 grid + 2 per layer, batch 1024,
+    float32), two training steps driven through the library alone: forward chain with the ReLU fused
+    into the check, squared-error head, backward chain with g(x) (.) c fused into the check, update of
+    every layer, faults in forward and backward outputs and one stored block hit after the first
+    update.  Checked at this size: float64 Freivalds probes of every product of the first step, the
+    verdict that the number of planted blocks dictates, the decoded activations as the elementwise
+    step of the corrected systematic part (bit for bit), the hit block-row located by the next
+    step's forward product and regenerated, and the stored code of two layers against the oracle's
+    re-encoding at the end."""
+    import dataclasses
+    import torch
+    from oracle import codenet_oracle as O
+    from paper_1903_01042_amd import binding as B
+    wl = dataclasses.replace(WL.WORKLOADS["cfg4"], fault_p=0.004)
+    L = len(wl.widths) - 1
+    N, b = wl.widths[0], wl.batch
+    m, n = wl.grid
+    t = wl.r // 2
+    dev = torch.device("cuda:0")
+    layers = []
+    for l in range(L):
+        say("cfg4 full size: encoding layer", l)
+        P_r, P_c = wl.generators(l)
+        layers.append(B.CodedLayer(torch.from_numpy(WL.layer_weights(N, N, l)).to(dev), P_r, P_c, dtype=B.F32,
+                                   max_batch=b, tau_detect=wl.tau_detect, tau_resid=wl.tau_resid))
+    rep = layers[0].new_report()
+    tol = TOL["f32"]
+    counts = {CLEAN: 0, CORRECTED: 0, UNCORRECTABLE: 0}
+
+    def product(l, phase, V, faults, step, epilogue, aux, also_hit=()):
+        lay = layers[l]
+        out = lay.forward(V) if phase == FWD else lay.backward(V)
+        if step == 0:
+            Wc = lay.export_coded().double()
+            z = torch.from_numpy(np.random.default_rng(9100 + 2 * l + phase).standard_normal(b)).to(dev)
+            rhs = (Wc[:, : n * lay.B_c] @ (V.double().T @ z)) if phase == FWD else (Wc[: m * lay.B_r, :].T @ (V.double().T @ z))
+            err = float(torch.linalg.norm(out.double().T @ z - rhs) / torch.linalg.norm(rhs))
+            assert err <= tol, (l, phase, err)
+            del Wc
+        lay.inject(faults, out)
+        dec = lay.detect_decode(phase, out, report=rep, epilogue=epilogue, aux=aux)
+        got = lay.read_report(rep)
+        hit = sorted({f["bi"] if phase == FWD else f["bj"] for f in faults} | set(also_hit))
+        want = CLEAN if not hit else (CORRECTED if len(hit) <= t else UNCORRECTABLE)
+        assert got["verdict"] == want and (want != CORRECTED or got["located"] == hit), (l, phase, hit, got)
+        counts[want] += 1
+        if want == UNCORRECTABLE:                 # transient faults: the product is computed again;
+            out = lay.forward(V) if phase == FWD else lay.backward(V)       # a hit stored block is still there
+            dec = lay.detect_decode(phase, out, report=rep, epilogue=epilogue, aux=aux)
+            got = lay.read_report(rep)
+            want = CORRECTED if also_hit else CLEAN
+            assert got["verdict"] == want and (want != CORRECTED or got["located"] == sorted(also_hit)), got
+        if want == CORRECTED:
+            lay.regenerate(phase, rep)
+        sys_part = out[:, :N]
+        if epilogue == B.EPI_RELU:
+            sys_part = torch.relu(sys_part)
+        elif epilogue == B.EPI_MASK_POS:
+            sys_part = torch.where(aux > 0, sys_part, torch.zeros_like(sys_part))
+        assert torch.equal(dec, sys_part), (l, phase)
+        return dec
+
+    for step in range(2):
+        acts = [torch.from_numpy(wl.inputs(step)).to(dev)]
+        for l in range(L):
+            say("cfg4 full size step", step, "forward layer", l)
+            extra = (3,) if (step == 1 and l == 5) else ()       # the stored block hit after the first update
+            acts.append(product(l, FWD, acts[-1], wl.product_faults(FWD, step, l), step,
+                                B.EPI_RELU if l < L - 1 else B.EPI_NONE, None, extra))
+        Y = torch.from_numpy(WL.normal((b, N), WL.SEED_DELTAS + step)).to(dev)
+        delta = (Y - acts[-1]) / b                                  # squared-error head
+        for l in range(L - 1, -1, -1):
+            say("cfg4 full size step", step, "backward layer", l)
+            c = product(l, BWD, delta, wl.product_faults(BWD, step, l), step,
+                        B.EPI_MASK_POS if l > 0 else B.EPI_NONE, acts[l] if l > 0 else None)
+            if l > 0:
+                delta = c
+        for lay in layers:
+            lay.update(wl.eta)
+        if step == 0:
+            layers[5].inject([WL.make_fault(WEIGHT, 3, 2, 0)])
+    say("cfg4 full size verdicts", counts)
+    assert counts[CORRECTED] >= 1 and counts[CLEAN] >= 1
+    for l in (0, 5):
+        P_r, P_c = wl.generators(l)
+        Wc = to_np(layers[l].export_coded()).astype(np.float64)
+        drift = rel_fro(Wc, O.encode(Wc[: m * layers[l].B_r, : n * layers[l].B_c], P_r, P_c, layers[l].B_r, layers[l].B_c))
+        say("cfg4 full size layer", l, "drift %.3e" % drift)
+        assert drift <= tol
+    for lay in layers:
+        lay.destroy()
+
+
 # ------------------------------------------------------------- ragged / odd shapes
 @pytest.mark.parametrize("n_out,n_in,m,n,r,b,dtype", [
     (10, 1024, 4, 4, 1, 128, "f32"),      # cfg2's last layer: 10 outputs on 4 block-rows
