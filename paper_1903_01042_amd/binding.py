@@ -137,7 +137,7 @@ def pack_faults(faults):
 class CodedLayer:
     """Owns one `codenet_layer*`.  Methods are the C calls with tensors for pointers."""
 
-    def __init__(self, W, P_r, P_c, dtype=F32, max_batch=1, tau_detect=1e-3, tau_resid=1e-2):
+    def __init__(self, W, P_r, P_c, dtype=F32, max_batch=1, tau_detect=1e-3, tau_resid=2e-3):
         import torch
         self._h = ctypes.c_void_p(0)
         lib = load_library()

@@ -135,7 +135,7 @@ class Workload:
     fault_p: float = 0.0
     weight_faults: bool = False
     tau_detect: float = 1e-3
-    tau_resid: float = 1e-2
+    tau_resid: float = 2e-3
     drift_every: int = 0
     notes: str = ""
 

@@ -61,6 +61,55 @@ def test_paper_example_grid_every_single_block_error():
     pair.close()
 
 
+def test_hand_computed_residuals_and_ties_on_the_gpu():
+    """The check fed with outputs written by hand (the cases worked out in the oracle's pins): the
+    relative residual of the best support as a number -- sqrt(1/65) with two erroneous blocks at
+    one position, accepted or rejected around it, sqrt(1/90) at two positions -- and exact ties,
+    which go to the first support in lexicographic order on both sides."""
+    import torch
+    from oracle import codenet_oracle as O
+    from paper_1903_01042_amd import binding as B
+    P_r, P_c = WL.paper_example_generators()         # H_r columns (1,1), (1,-1), (-1,0), (0,-1); H_c columns (1,1), (1,2), ...
+    dev = torch.device("cuda:0")
+
+    def run(n_out, n_in, phase, blocks, tau_resid, want_verdict, want_located, want_resid, want_blocks):
+        lay = B.CodedLayer(torch.zeros((n_out, n_in), device=dev), P_r, P_c, max_batch=1, tau_detect=1e-3,
+                           tau_resid=tau_resid)
+        Bp = lay.B_r if phase == FWD else lay.B_c
+        out = np.zeros((1, 4 * Bp), dtype=np.float32)
+        for i, vals in enumerate(blocks):
+            out[0, i * Bp: i * Bp + len(vals)] = vals
+        out_d = torch.from_numpy(out).to(dev)
+        rep = lay.new_report()
+        dec = lay.detect_decode(phase, out_d, report=rep)
+        got = lay.read_report(rep)
+        res = O.detect_decode(out.astype(np.float64).T, P_r if phase == FWD else P_c, Bp, 1e-3, tau_resid)
+        say("hand case", blocks, "->", got["verdict"], got["located"], got["resid_rel"])
+        assert got["verdict"] == res["verdict"] == want_verdict
+        assert got["located"] == res["located"] == want_located
+        assert abs(got["resid_rel"] - want_resid) <= 2e-6 and abs(res["resid_rel"] - want_resid) <= 1e-12
+        fixed = to_np(out_d)[0]
+        for i, vals in enumerate(want_blocks):
+            assert np.allclose(fixed[i * Bp: i * Bp + len(vals)], vals, atol=1e-6), (i, fixed)
+            assert np.allclose(res["out"][i * Bp: i * Bp + len(vals), 0], vals, atol=1e-12)
+        n_dec = n_out if phase == FWD else n_in
+        assert np.allclose(to_np(dec)[0], np.concatenate(want_blocks[:2])[:n_dec], atol=1e-6)
+        lay.destroy()
+
+    s65, s90 = np.sqrt(1.0 / 65.0), np.sqrt(1.0 / 90.0)
+    run(2, 2, BWD, [[1], [1], [0], [0]], 0.2, CORRECTED, [1], s65, [[1], [-0.6], [0], [0]])
+    run(2, 2, BWD, [[1], [1], [0], [0]], 0.12, UNCORRECTABLE, [], s65, [[1], [1], [0], [0]])
+    run(2, 4, BWD, [[1, 0], [1, 1], [0, 0], [0, 0]], 0.2, CORRECTED, [1], s90, [[1, 0], [-0.6, 0], [0, 0], [0, 0]])
+    run(2, 2, BWD, [[0], [2], [0], [0]], 1e-6, CORRECTED, [1], 0.0, [[0], [0], [0], [0]])
+    # ties: supports {0} and {2}, then {1} and {3}, then all four
+    run(6, 2, FWD, [[0, 0, 0], [0, 0, 0], [-1, -1, -1], [0, 0, -1]], 0.6, CORRECTED, [0], 0.5,
+        [[-0.5, -0.5, -1.0], [0, 0, 0], [-1, -1, -1], [0, 0, -1]])
+    run(6, 2, FWD, [[0, 0, 0], [0, 0, 0], [0, 0, -1], [-1, -1, 1]], 0.6, CORRECTED, [1], 0.5,
+        [[0, 0, 0], [0.5, 0.5, -1.0], [0, 0, -1], [-1, -1, 1]])
+    run(4, 2, FWD, [[0, 0], [0, 0], [-1, 0], [0, -1]], 0.8, CORRECTED, [0], np.sqrt(0.5),
+        [[-0.5, -0.5], [0, 0], [-1, 0], [0, -1]])
+
+
 # ------------------------------------------------------------------- cfg1, full size
 def test_cfg1_full():
     wl = WL.WORKLOADS["cfg1"]
@@ -80,36 +129,61 @@ def test_cfg1_full():
 # ------------------------------------------------------------------- cfg2, full size
 def test_cfg2_mlp_full_size():
     """784-1024-1024-10 MLP, 4x4 grid + 1 parity row/col per layer (detect only),
-    ReLU, softmax-CE on random labels, Bernoulli(0.05) faults per node and product:
-    every product of every step against the oracle, weights of all layers at the end."""
+    ReLU, softmax-CE on random labels, Bernoulli(0.05) faults per node and product, all 100 steps
+    of the workload: every product of every step against the oracle (which is handed the GPU's
+    activations before each product), weights of all layers every 25 steps."""
     wl = WL.WORKLOADS["cfg2"]
     mlp = MlpPair(wl)
     losses = []
-    for step in range(12):
+    for step in range(wl.steps):
         say("cfg2 step", step)
         losses.append(mlp.step(step))
-    for l, pair in enumerate(mlp.layers):
-        say("cfg2 layer", l, "coded weights rel err", pair.check_weights())
+        if (step + 1) % 25 == 0:
+            for l, pair in enumerate(mlp.layers):
+                say("cfg2 layer", l, "after", step + 1, "steps: coded weights rel err", pair.check_weights())
     say("cfg2 verdict counts", mlp.counts, "loss", losses[0], "->", losses[-1])
     assert mlp.counts[2] > 0 and mlp.counts[1] == 0        # r = 1: faults are detected, never located
     assert all(np.isfinite(losses))
     mlp.close()
 
 
+def test_cfg2_mlp_against_an_oracle_on_its_own_trajectory():
+    """The same 100 steps with the oracle never seeing a GPU value after the first input: it runs
+    feedforward, loss head, backpropagation and update on its own activations in float64, and every
+    product, every decoded activation, every backpropagated error and the weights of all layers
+    are compared along the way (bounds five times the per-product ones: the difference is the
+    float32 rounding accumulated over the run)."""
+    wl = WL.WORKLOADS["cfg2"]
+    mlp = MlpPair(wl, independent=True)
+    for step in range(wl.steps):
+        say("cfg2 independent step", step)
+        loss = mlp.step(step)
+        assert abs(loss - mlp.loss_ora) <= 1e-4 * max(1.0, abs(mlp.loss_ora)), (step, loss, mlp.loss_ora)
+        if (step + 1) % 25 == 0:
+            for l, pair in enumerate(mlp.layers):
+                say("cfg2 independent layer", l, "after", step + 1, "steps: coded weights rel err", pair.check_weights())
+    say("cfg2 independent: verdict counts", mlp.counts, "mask decisions taken from the GPU", mlp.snapped,
+        "loss gpu", loss, "oracle", mlp.loss_ora)
+    assert mlp.snapped <= 64
+    mlp.close()
+
+
 def test_cfg4_style_mlp_rolls_forward_through_update_stage_faults():
-    """A width-scaled copy of cfg4 (MLP with an 8 x 8 grid + 2 parity rows / columns per layer, ReLU)
-    with its three kinds of faults -- forward outputs, backward outputs and stored blocks after the
+    """A width-scaled copy of cfg4 (all 8 layers, 8 x 8 grid + 2 parity rows / columns per layer, ReLU,
+    the workload's 20 steps) with its three kinds of faults -- forward outputs, backward outputs and stored blocks after the
     update: every located node is regenerated and training goes on; where more stored blocks are hit
     than the code corrects, the layer is restored from its checkpoint (the state after its last update)
     as the paper prescribes; every product of every step as the oracle's, weights at the end."""
     import dataclasses
     wl = dataclasses.replace(WL.WORKLOADS["cfg4"].scaled(32, batch=48), fault_p=0.003)
-    mlp = MlpPair(wl, max_layers=4, roll_forward=True)
+    L = len(wl.widths) - 1
+    assert L == 8
+    mlp = MlpPair(wl, roll_forward=True)
     planted = 0
-    for step in range(10):
+    for step in range(wl.steps):
         say("cfg4-style step", step)
         mlp.step(step)
-        planted += sum(len(wl.update_faults(step, l)) for l in range(4))
+        planted += sum(len(wl.update_faults(step, l)) for l in range(L))
     for l, pair in enumerate(mlp.layers):
         say("cfg4-style layer", l, "coded weights rel err", pair.check_weights())
     say("cfg4-style verdict counts", mlp.counts, "regenerations", mlp.regenerated, "restores", mlp.restored,
@@ -159,7 +233,7 @@ def test_full_size_layer_step(name):
     pair.close()
 
 
-@pytest.mark.parametrize("name,steps,drift_every,probe_every", [("cfg3", 48, 16, 6), ("cfg5", 51, 50, 25)])
+@pytest.mark.parametrize("name,steps,drift_every,probe_every", [("cfg3", 50, 25, 10), ("cfg5", 200, 50, 50)])
 def test_full_size_multi_step_invariants(name, steps, drift_every, probe_every):
     """Many steps at the benchmark size under the workload's own fault law, as bench.py drives them
     (the oracle cannot follow every step at this size; a width-scaled copy is followed step by step
@@ -250,7 +324,7 @@ def test_full_size_multi_step_invariants(name, steps, drift_every, probe_every):
 
 def test_cfg4_full_size_mlp_invariants():
     """The 8-layer width-8192 MLP of cfg4 at its real size (8 x 8 grid + 2 per layer, batch 1024,
-    float32), two training steps driven through the library alone: forward chain with the ReLU fused
+    float32), the workload's 20 training steps driven through the library alone: forward chain with the ReLU fused
     into the check, squared-error head, backward chain with g(x) (.) c fused into the check, update of
     every layer, faults in forward and backward outputs and one stored block hit after the first
     update.  Checked at this size: float64 Freivalds probes of every product of the first step, the
@@ -311,7 +385,7 @@ def test_cfg4_full_size_mlp_invariants():
         assert torch.equal(dec, sys_part), (l, phase)
         return dec
 
-    for step in range(2):
+    for step in range(wl.steps):
         acts = [torch.from_numpy(wl.inputs(step)).to(dev)]
         for l in range(L):
             say("cfg4 full size step", step, "forward layer", l)
@@ -356,7 +430,7 @@ def test_ragged_shapes(n_out, n_in, m, n, r, b, dtype):
     say("ragged", n_out, n_in, m, n, r, b, dtype)
     P_r = WL.vandermonde_like(m, r) if r in (0, 2) else WL.gaussian_generator(m, r, 3)
     P_c = WL.vandermonde_like(n, r) if r in (0, 2) else WL.gaussian_generator(n, r, 4)
-    tau = (1e-3, 1e-2) if dtype == "f32" else (2e-2, 2e-2)
+    tau = (1e-3, 2e-3) if dtype == "f32" else (2e-2, 2e-2)
     pair = Pair(WL.layer_weights(n_out, n_in), P_r, P_c, dtype, b, *tau)
     pair.check_weights(1e-6)
     X, D = WL.normal((b, n_in), 11), WL.normal((b, n_out), 12)
@@ -421,7 +495,7 @@ def test_degenerate_grids(n_out, n_in, m, n, r, b, dtype):
     say("degenerate", n_out, n_in, m, n, r, b, dtype)
     from paper_1903_01042_amd import binding as B
     P_r, P_c = WL.vandermonde_like(m, r), WL.vandermonde_like(n, r)
-    tau = (1e-3, 1e-2) if dtype == "f32" else (2e-2, 2e-2)
+    tau = (1e-3, 2e-3) if dtype == "f32" else (2e-2, 2e-2)
     pair = Pair(WL.layer_weights(n_out, n_in), P_r, P_c, dtype, b, *tau)
     pair.check_weights(1e-6)
     X, D = WL.normal((b, n_in), 41), WL.normal((b, n_out), 42)
@@ -462,16 +536,16 @@ def test_different_parity_counts_for_rows_and_columns():
     assert rep["verdict"] == CORRECTED and rep["located"] == [2]
     _, rep, _ = pair.product(FWD, X, [WL.make_fault(FWD, 2, 0, 1), WL.make_fault(FWD, 4, 1, 1)])
     assert rep["verdict"] == UNCORRECTABLE
-    _, rep, res = pair.product(BWD, D, [WL.make_fault(BWD, 0, 1, 2), WL.make_fault(BWD, 1, 5, 2)], check_margins=False)
+    _, rep, res = pair.product(BWD, D, [WL.make_fault(BWD, 0, 1, 2), WL.make_fault(BWD, 1, 5, 2)])
     assert rep["verdict"] == CORRECTED and rep["located"] == [1, 5]
-    _, rep, _ = pair.product(BWD, D, [WL.make_fault(BWD, 0, j, 3) for j in (0, 2, 6)], check_margins=False)
+    _, rep, _ = pair.product(BWD, D, [WL.make_fault(BWD, 0, j, 3) for j in (0, 2, 6)])
     assert rep["verdict"] == UNCORRECTABLE
     pair.update(0.03)
     pair.check_weights()
     # weight faults in two block-columns: located by the backward product, regenerated along the rows of blocks
     clean = pair.ora.Wt.copy()
     pair.inject_weights([WL.make_fault(WEIGHT, i, j, 4) for j in (0, 4) for i in range(m)])
-    _, rep, res = pair.product(BWD, D, check_margins=False)
+    _, rep, res = pair.product(BWD, D)
     assert rep["verdict"] == CORRECTED and rep["located"] == [0, 4]
     pair.regenerate(BWD, res)
     assert rel_fro(pair.ora.Wt, clean) <= 1e-8
@@ -487,7 +561,7 @@ def test_every_error_pattern_on_a_small_grid(m, r, dtype):
     t, L = r // 2, m + r
     P = WL.vandermonde_like(m, r) if r <= 2 else WL.gaussian_generator(m, r, 8)
     n_out = n_in = 64 * m
-    tau = (1e-3, 1e-2) if dtype == "f32" else (2e-2, 2e-2)
+    tau = (1e-3, 2e-3) if dtype == "f32" else (2e-2, 2e-2)
     pair = Pair(WL.layer_weights(n_out, n_in), P, P, dtype, 24, *tau)
     X = WL.normal((24, n_in), 5)
     D = WL.normal((24, n_out), 6)
@@ -496,13 +570,12 @@ def test_every_error_pattern_on_a_small_grid(m, r, dtype):
         for A in itertools.combinations(range(L), k):
             say("campaign", m, r, dtype, "support", A)
             faults = [WL.make_fault(FWD, i, (i + k) % m, step=count) for i in A]
-            # a random r = 4 generator has some nearly dependent column pairs: no 5x margin asked there
-            _, rep, _ = pair.product(FWD, X, faults, check_margins=(r <= 2))
+            _, rep, _ = pair.product(FWD, X, faults)
             assert rep["verdict"] == (CORRECTED if k <= t else UNCORRECTABLE)
             assert rep["located"] == (list(A) if k <= t else [])
             if k == 1:
                 faults = [WL.make_fault(BWD, (A[0] + 1) % m, A[0], step=count)]
-                _, rep, _ = pair.product(BWD, D, faults, check_margins=(r <= 2))
+                _, rep, _ = pair.product(BWD, D, faults)
                 assert rep["verdict"] == CORRECTED and rep["located"] == list(A)
             count += 1
     pair.close()
@@ -518,18 +591,18 @@ def test_largest_parity_count_four_blocks_located_and_regenerated():
     pair = Pair(WL.layer_weights(n_out, n_in), P, P, "f32", b)
     X = WL.normal((b, n_in), 31)
     rows = [0, 5, 11, m + 3]
-    _, rep, _ = pair.product(FWD, X, [WL.make_fault(FWD, i, 1, 0) for i in rows], check_margins=False)
+    _, rep, _ = pair.product(FWD, X, [WL.make_fault(FWD, i, 1, 0) for i in rows])
     assert rep["verdict"] == CORRECTED and rep["located"] == rows
-    _, rep, _ = pair.product(FWD, X, [WL.make_fault(FWD, i, 1, 1) for i in rows + [7]], check_margins=False)
+    _, rep, _ = pair.product(FWD, X, [WL.make_fault(FWD, i, 1, 1) for i in rows + [7]])
     assert rep["verdict"] == UNCORRECTABLE and rep["located"] == []
     clean = pair.ora.Wt.copy()
     pair.inject_weights([WL.make_fault(WEIGHT, i, j, 2) for i in rows for j in range(m)])
-    _, rep, res = pair.product(FWD, X, check_margins=False)
+    _, rep, res = pair.product(FWD, X)
     assert rep["verdict"] == CORRECTED and rep["located"] == rows
     pair.regenerate(FWD, res)
     assert rel_fro(pair.ora.Wt, clean) <= 1e-8
     assert rel_fro(to_np(pair.gpu.export_coded()), clean) <= 1e-4
-    _, rep, _ = pair.product(FWD, X, check_margins=False)
+    _, rep, _ = pair.product(FWD, X)
     assert rep["verdict"] == CLEAN
     pair.close()
 
@@ -546,13 +619,13 @@ def test_longest_codeword():
     pair.check_weights(1e-6)
     X, D = WL.normal((b, n_in), 51), WL.normal((b, n_out), 52)
     for step, (rows, cols) in enumerate((((), ()), ((0,), (0, 39)), ((39,), (17, 35)), ((38,), (36,)))):
-        _, rep, _ = pair.product(FWD, X, [WL.make_fault(FWD, i, 0, step) for i in rows], check_margins=False)
+        _, rep, _ = pair.product(FWD, X, [WL.make_fault(FWD, i, 0, step) for i in rows])
         assert rep["verdict"] == (CORRECTED if rows else CLEAN) and rep["located"] == list(rows)
-        _, rep, _ = pair.product(BWD, D, [WL.make_fault(BWD, 0, j, step) for j in cols], check_margins=False)
+        _, rep, _ = pair.product(BWD, D, [WL.make_fault(BWD, 0, j, step) for j in cols])
         assert rep["verdict"] == (CORRECTED if cols else CLEAN) and rep["located"] == list(cols)
         pair.update(0.05)
         pair.check_weights()
-    _, rep, _ = pair.product(FWD, X, [WL.make_fault(FWD, 3, 0, 9), WL.make_fault(FWD, 30, 0, 9)], check_margins=False)
+    _, rep, _ = pair.product(FWD, X, [WL.make_fault(FWD, 3, 0, 9), WL.make_fault(FWD, 30, 0, 9)])
     assert rep["verdict"] == UNCORRECTABLE
     pair.close()
 
@@ -562,7 +635,9 @@ def test_random_ragged_layers_agree_with_the_oracle(seed):
     """Seeded random layers -- grids up to 11 x 11, r in {1, 2, 4}, nothing dividing anything, batches
     from 1 to 260, both dtypes -- two steps each with up to t + 1 faulty blocks per product, plain and
     verified checks, regeneration after every forward check, update: verdicts, located sets, outputs
-    and coded weights as the oracle's every time."""
+    and coded weights as the oracle's every time.  Grids and generators here are drawn, not chosen for
+    the separation of their columns: every thresholded quantity is asked to clear its threshold by a
+    factor 2 instead of the 5 that the workloads' own codes are held to."""
     g = np.random.default_rng(seed)
     for case in range(25):
         m, n = int(g.integers(1, 12)), int(g.integers(1, 12))
@@ -575,7 +650,7 @@ def test_random_ragged_layers_agree_with_the_oracle(seed):
             P_r, P_c = WL.vandermonde_like(m, r), WL.vandermonde_like(n, r)
         else:
             P_r, P_c = WL.gaussian_generator(m, r, 100 + case), WL.gaussian_generator(n, r, 200 + case)
-        tau = (1e-3, 1e-2) if dtype == "f32" else (2e-2, 2e-2)
+        tau = (1e-3, 2e-3) if dtype == "f32" else (2e-2, 2e-2)
         say("random layer", seed, case, n_out, n_in, m, n, r, b, dtype)
         pair = Pair(WL.layer_weights(n_out, n_in), P_r, P_c, dtype, b, *tau)
         X, D = WL.normal((b, n_in), 300 + case), WL.normal((b, n_out), 400 + case)
@@ -583,32 +658,45 @@ def test_random_ragged_layers_agree_with_the_oracle(seed):
         for step in range(2):
             rows = sorted(g.choice(m + r, size=min(int(g.integers(0, t + 2)), m + r), replace=False).tolist())
             faults = [WL.make_fault(FWD, i, int(g.integers(0, n)), step) for i in rows]
-            _, _, res = pair.product(FWD, X, faults, check_margins=False, verified=bool(g.integers(0, 2)))
+            _, _, res = pair.product(FWD, X, faults, check_margins=2.0, verified=bool(g.integers(0, 2)))
             pair.regenerate(FWD, res)
             cols = sorted(g.choice(n + r, size=min(int(g.integers(0, t + 2)), n + r), replace=False).tolist())
             faults = [WL.make_fault(BWD, int(g.integers(0, m)), j, step) for j in cols]
-            pair.product(BWD, D, faults, check_margins=False)
+            pair.product(BWD, D, faults, check_margins=2.0)
             pair.update(0.05)
             pair.check_weights()
         pair.close()
 
 
 # --------------------------------------------------------- multi-step, scaled copies
-@pytest.mark.parametrize("name,block,steps", [("cfg3", 64, 12), ("cfg5", 32, 12), ("cfg4", 32, 8)])
-def test_multi_step_on_a_width_scaled_copy(name, block, steps):
-    """Same grid, parity count, dtype, thresholds and fault law as the full
-    workload with blocks of `block`: the oracle follows every step."""
-    wl = WL.WORKLOADS[name].scaled(block, batch=min(WL.WORKLOADS[name].batch, 96))
+@pytest.mark.parametrize("name,block", [("cfg3", 64), ("cfg5", 32), ("cfg4", 32)])
+def test_multi_step_on_a_width_scaled_copy(name, block):
+    """Same grid, parity count, dtype, thresholds, fault law and number of steps (50 / 200 / 20) as
+    the full workload with blocks of `block`: the oracle follows every step; where the workload
+    asks for a drift check (cfg5: every 50 steps) the stored matrix is also compared with the
+    oracle's encoding of its own systematic part."""
+    from oracle import codenet_oracle as O
+    full = WL.WORKLOADS[name]
+    wl = full.scaled(block, batch=min(full.batch, 96))
+    assert wl.steps == full.steps
     P_r, P_c = wl.generators()
     n_in, n_out = wl.widths[0], wl.widths[1]
+    m, n = wl.grid
     pair = Pair(WL.layer_weights(n_out, n_in), P_r, P_c, wl.dtype, wl.batch, wl.tau_detect, wl.tau_resid)
     verdicts = []
-    for step in range(steps):
+    for step in range(wl.steps):
         say(name, "scaled step", step)
         rf, rb = layer_step(pair, wl, step, n_out=n_out, n_in=n_in)
         verdicts += [rf["verdict"], rb["verdict"]]
         pair.check_weights()
+        if wl.drift_every and (step + 1) % wl.drift_every == 0:
+            Wc = to_np(pair.gpu.export_coded())
+            again = O.encode(Wc[: m * pair.gpu.B_r, : n * pair.gpu.B_c], P_r, P_c, pair.gpu.B_r, pair.gpu.B_c)
+            drift = rel_fro(Wc, again)
+            say(name, "scaled copy: drift after", step + 1, "steps %.3e" % drift)
+            assert drift <= pair.tol
     say(name, "verdicts", verdicts)
+    assert len(set(verdicts)) >= 2
     pair.close()
 
 
@@ -632,6 +720,8 @@ def test_weight_fault_shows_up_in_the_next_products():
     # the paper's sparse law on a parity-column block: only the backward product sees it
     pair.inject_weights([WL.make_fault(WEIGHT, 0, 5, step=1, lo=-5.0, hi=5.0, mode=WL.MODE_SPARSE_ABS, density=0.005)])
     pair.check_weights()
+    # (no margin asked here: the sparse law's few small hits on a parity-column block are a fault that the
+    # threshold margin was not designed around -- the verdict and located set must still be the oracle's)
     _, rep, _ = pair.product(BWD, D, check_margins=False)
     assert rep["verdict"] == UNCORRECTABLE        # columns 1 and 5 are now both erroneous, t = 1
     pair.close()
@@ -655,7 +745,7 @@ def test_regeneration_restores_the_stored_code(N_out, N_in, m, n, r, b, dtype, b
     import torch
     P_r = WL.vandermonde_like(m, r) if r <= 2 else WL.gaussian_generator(m, r, seed=5)
     P_c = WL.vandermonde_like(n, r) if r <= 2 else WL.gaussian_generator(n, r, seed=6)
-    tau = (2e-2, 2e-2) if dtype == "bf16" else (1e-3, 1e-2)
+    tau = (2e-2, 2e-2) if dtype == "bf16" else (1e-3, 2e-3)
     pair = Pair(WL.layer_weights(N_out, N_in), P_r, P_c, dtype, b, *tau)
     clean = pair.ora.Wt.copy()
     step = 0
@@ -730,7 +820,7 @@ def test_activation_fused_into_the_check(n_out, n_in, m, n, r, b, dtype):
     before the elementwise step."""
     from paper_1903_01042_amd import binding as B
     P_r, P_c = WL.vandermonde_like(m, r), WL.vandermonde_like(n, r)
-    tau = (1e-3, 1e-2) if dtype == "f32" else (2e-2, 2e-2)
+    tau = (1e-3, 2e-3) if dtype == "f32" else (2e-2, 2e-2)
     pair = Pair(WL.layer_weights(n_out, n_in), P_r, P_c, dtype, b, *tau)
     X, D = WL.normal((b, n_in), 21), WL.normal((b, n_out), 22)
     for faults_f, faults_b in (((), ()), ([WL.make_fault(FWD, 1, 0, 3)], [WL.make_fault(BWD, 0, n, 3)])):
@@ -767,30 +857,29 @@ def test_verified_check_agrees_or_reports_the_disagreement(n_out, n_in, m, n, r,
     from paper_1903_01042_amd import binding as B
     if r <= 2:
         P_r, P_c = WL.vandermonde_like(m, r), WL.vandermonde_like(n, r)
-    else:   # a random generator: some nearly dependent column pairs, so no margin is asked below
+    else:
         P_r, P_c = WL.gaussian_generator(m, r, 8), WL.gaussian_generator(n, r, 9)
-    tau = (1e-3, 1e-2) if dtype == "f32" else (2e-2, 2e-2)
+    tau = (1e-3, 2e-3) if dtype == "f32" else (2e-2, 2e-2)
     pair = Pair(WL.layer_weights(n_out, n_in), P_r, P_c, dtype, b, *tau)
     X, D = WL.normal((b, n_in), 31), WL.normal((b, n_out), 32)
     t = r // 2
-    mg = dict(check_margins=(r <= 2))
     one_f, one_b = [WL.make_fault(FWD, 1, 0, 5)], [WL.make_fault(BWD, 0, n, 5)]
     many_f = [WL.make_fault(FWD, i, 0, 6) for i in range(t + 1)]
     for faults_f, faults_b, want in (((), (), CLEAN), (one_f, one_b, CORRECTED), (many_f, (), UNCORRECTABLE)):
-        _, rep, _ = pair.product(FWD, X, faults_f, verified=True, epilogue=B.EPI_RELU, **mg)
+        _, rep, _ = pair.product(FWD, X, faults_f, verified=True, epilogue=B.EPI_RELU)
         assert rep["verdict"] == want
         if want != UNCORRECTABLE:
-            _, rep, _ = pair.product(BWD, D, faults_b, verified=True, **mg)
+            _, rep, _ = pair.product(BWD, D, faults_b, verified=True)
             assert rep["verdict"] == want
     for faults_f in ((), one_f, many_f):
         for fault in (dict(target=B.CHECK_EVALUATION, who=0, seed=1, hi=0.5),
                       dict(target=B.CHECK_EVALUATION, who=1, seed=2, hi=1e-6),
                       dict(target=B.CHECK_LIST, who=0, hi=0.0),
                       dict(target=B.CHECK_LIST, who=3, hi=0.0)):
-            _, rep, _ = pair.product(FWD, X, faults_f, verified=True, check_fault=fault, **mg)
+            _, rep, _ = pair.product(FWD, X, faults_f, verified=True, check_fault=fault)
             assert rep["verdict"] == B.DISAGREE and rep["n_located"] == 0, (faults_f, fault, rep)
             # the planted error is used up: the same product checks normally again
-            _, rep, _ = pair.product(FWD, X, faults_f, verified=True, **mg)
+            _, rep, _ = pair.product(FWD, X, faults_f, verified=True)
             assert rep["verdict"] != B.DISAGREE
     # a pending CHECK fault waits for the next verified call; plain calls ignore it
     pair.gpu.inject([dict(phase=B.CHECK, bi=B.CHECK_LIST, bj=0, seed=0, step=0, lo=0.0, hi=0.0)])

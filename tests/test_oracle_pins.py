@@ -282,6 +282,71 @@ def test_relative_syndrome_of_a_hand_computed_case():
     assert np.allclose(O.syndromes(out, P, 1), [[5.0, 11.0]])
 
 
+def test_relative_residual_of_hand_computed_cases():
+    """Decoding algorithm of the appendix, least-squares reading.  H = [1 1 -1 0; 1 2 0 -1] (the
+    worked example's column code): columns h0 = (1,1), h1 = (1,2), h2 = (-1,0), h3 = (0,-1).
+
+    Two erroneous blocks, one position: out = (1, 1, 0, 0) gives the syndrome s = (2, 3), |s|^2 = 13.
+    Residual^2 of the one-block support {i} is |s|^2 - (h_i . s)^2 / |h_i|^2:
+      {0}: 13 - 25/2 = 1/2     {1}: 13 - 64/5 = 1/5     {2}: 13 - 4 = 9     {3}: 13 - 9 = 4
+    so the best support is {1} with relative residual sqrt((1/5)/13) = sqrt(1/65), its error estimate
+    is (h1 . s)/|h1|^2 = 8/5, and the repaired block is 1 - 8/5 = -3/5.  Beyond the threshold the same
+    number is reported with the verdict UNCORRECTABLE and the output untouched.
+
+    Two positions (B = 2): block 0 = (1, 0), block 1 = (1, 1) give s(0) = (2, 3), s(1) = (1, 2) = h1.
+    {1}: 1/5 + 0 of 13 + 5 = 18, relative residual sqrt(1/90); {0}: 1/2 + (5 - 9/2) = 1 of 18.
+    One erroneous block, out = (0, 2, 0, 0): s = 2 h1, residual exactly 0."""
+    P = np.array([[1.0, 1.0], [1.0, 2.0]])
+    out = np.array([[1.0], [1.0], [0.0], [0.0]])
+    res = O.detect_decode(out, P, 1, 1e-3, 0.2)
+    assert res["verdict"] == O.CORRECTED and res["located"] == [1]
+    assert abs(res["resid_rel"] - np.sqrt(1.0 / 65.0)) < 1e-15
+    assert np.allclose(res["out"].ravel(), [1.0, -0.6, 0.0, 0.0], atol=1e-15)
+    res = O.detect_decode(out, P, 1, 1e-3, 0.12)          # sqrt(1/65) = 0.12403...: just above the threshold
+    assert res["verdict"] == O.UNCORRECTABLE and res["located"] == []
+    assert abs(res["resid_rel"] - np.sqrt(1.0 / 65.0)) < 1e-15
+    assert np.array_equal(res["out"], out)
+    out2 = np.array([[1.0], [0.0], [1.0], [1.0], [0.0], [0.0], [0.0], [0.0]])
+    res = O.detect_decode(out2, P, 2, 1e-3, 0.2)
+    assert res["verdict"] == O.CORRECTED and res["located"] == [1]
+    assert abs(res["resid_rel"] - np.sqrt(1.0 / 90.0)) < 1e-15
+    assert np.allclose(res["out"].ravel(), [1.0, 0.0, -0.6, 0.0, 0, 0, 0, 0], atol=1e-15)
+    res = O.detect_decode(np.array([[0.0], [2.0], [0.0], [0.0]]), P, 1, 1e-3, 1e-9)
+    assert res["verdict"] == O.CORRECTED and res["located"] == [1] and res["resid_rel"] == 0.0
+    assert np.array_equal(res["out"], np.zeros((4, 1)))
+
+
+def test_equal_residuals_go_to_the_first_support_in_lexicographic_order():
+    """This build's tie rule (the paper's true support is unique, so it needs none).
+    H = [1 1 -1 0; 1 -1 0 -1]: h0 = (1,1), h1 = (1,-1), h2 = (-1,0), h3 = (0,-1), three positions.
+    Syndromes (1,0), (1,0), (1,1) (written into the parity blocks): |s|^2 sums to 4;
+      {0}: 1/2 + 1/2 + 0 = 1     {2}: 0 + 0 + 1 = 1     {1}: 1/2 + 1/2 + 2 = 3     {3}: 1 + 1 + 1 = 3
+    -- {0} and {2} tie at relative residual 1/2 and {0} is taken.  A change of 1e-9 in the last
+    syndrome towards h2 hands the decision to {2}: it is the residual that decides, the order only
+    breaks the tie.  Mirrored syndromes (0,1), (0,1), (1,-1) tie {1} and {3}: {1} is taken; syndromes
+    (1,0), (0,1) tie all four supports at 1/sqrt(2): {0} is taken."""
+    P = np.array([[1.0, 1.0], [1.0, -1.0]])
+
+    def coded(s0, s1):           # out with zero systematic blocks: syndrome_k = -parity block k
+        B = len(s0)
+        out = np.zeros((4 * B, 1))
+        out[2 * B:3 * B, 0] = -np.asarray(s0, dtype=np.float64)
+        out[3 * B:4 * B, 0] = -np.asarray(s1, dtype=np.float64)
+        return out
+
+    res = O.detect_decode(coded([1, 1, 1], [0, 0, 1]), P, 3, 1e-3, 0.6)
+    assert res["verdict"] == O.CORRECTED and res["located"] == [0] and res["resid_rel"] == 0.5
+    res = O.detect_decode(coded([1, 1, 1], [0, 0, 1 - 1e-9]), P, 3, 1e-3, 0.6)
+    assert res["located"] == [2] and res["resid_rel"] < 0.5
+    res = O.detect_decode(coded([1, 1, 1], [0, 0, 1 + 1e-9]), P, 3, 1e-3, 0.6)
+    assert res["located"] == [0] and res["resid_rel"] < 0.5
+    res = O.detect_decode(coded([0, 0, 1], [1, 1, -1]), P, 3, 1e-3, 0.6)
+    assert res["verdict"] == O.CORRECTED and res["located"] == [1] and res["resid_rel"] == 0.5
+    res = O.detect_decode(coded([1, 0], [0, 1]), P, 2, 1e-3, 0.8)
+    assert res["verdict"] == O.CORRECTED and res["located"] == [0]
+    assert abs(res["resid_rel"] - np.sqrt(0.5)) < 1e-15
+
+
 def test_single_parity_block_only_detects():
     """r = 1 gives t = 0 (Theorem 1 needs 2t parity blocks to correct t): an
     error is detected, nothing is located."""
@@ -474,6 +539,25 @@ def test_counter_hash_matches_published_splitmix64_outputs():
     assert outs == [6457827717110365317, 3203168211198807973]
     arr = O._mix64(np.array([0, 1234567], dtype=np.uint64))
     assert [int(v) for v in arr] == [0xE220A8397B1DCDAF, 6457827717110365317]
+
+
+def test_fault_key_is_this_builds_own_specification():
+    """Parity unpinned: the paper only asks for independent continuous noise per erroneous element
+    (Error Model 2); how (seed, step, phase, bi, bj) select a noise stream is this build's choice
+    and nothing in the paper can confirm it.  The specification, stated here once: three chained
+    applications of the SplitMix64 output function (pinned above), the node packed as
+    phase * 2^40 + bi * 2^20 + bj.  What a noise stream selector must do is checked: the same
+    tuple gives the same key, and tuples that differ in any one coordinate give different keys
+    (no two of 3 x 3 x 3 x 41 x 41 tuples collide), so no two faults of a run share their noise."""
+    assert O.fault_key(5000, 3, 1, 2, 7) == O.fault_key(5000, 3, 1, 2, 7)
+    assert O.fault_key(5000, 3, 1, 2, 7) == O._mix64(O._mix64(O._mix64(5000) ^ 3) ^ ((1 << 40) | (2 << 20) | 7))
+    keys = {O.fault_key(seed, step, phase, bi, bj)
+            for seed in (0, 5000, 5007) for step in (0, 1, 199) for phase in (0, 1, 2)
+            for bi in range(41) for bj in range(41)}
+    assert len(keys) == 3 * 3 * 3 * 41 * 41
+    # consecutive elements of two different faults do not overlap either: the streams are key + idx
+    a, b = O.fault_key(5000, 0, 0, 0, 0), O.fault_key(5000, 0, 0, 0, 1)
+    assert abs(a - b) > 1 << 32
 
 
 def test_fault_draws_are_deterministic_and_well_distributed():
