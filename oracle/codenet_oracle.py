@@ -332,18 +332,24 @@ def update(Wt, Dt, Xt, eta, m, n, Br, Bc, store_corner=True):
     return Wn
 
 
-def regenerate_blocks(Wt, bad, P, B, axis=0):
+def regenerate_blocks(Wt, bad, P, B, axis=0, sources=None):
     """Regeneration: rebuild every stored block of the block-rows (axis 0) or
-    block-columns (axis 1) listed in `bad` from the other blocks of the same
-    grid column (row).  Any a good blocks of a line determine it (MDS); this is
-    the least-squares solve over all the good ones, which is the same thing
-    when they are consistent."""
+    block-columns (axis 1) listed in `bad` from other blocks of the same grid
+    column (row).  The paper accesses "any" a blocks of the line that are known
+    to be correct (a = number of systematic blocks; any a of them determine the
+    line, MDS).  `sources` names the blocks that are accessed; by default all
+    good ones are, solved in the least-squares sense, which is the same thing
+    whenever the accessed blocks are consistent.  (They are not when a block
+    that passes for good carries an undetected error of its own: the rebuilt
+    block then depends on which blocks were accessed, and the error shows at
+    the next product that uses it.)"""
     if axis == 1:
-        return regenerate_blocks(Wt.T, bad, P, B, 0).T
+        return regenerate_blocks(Wt.T, bad, P, B, 0, sources).T
     G = generator(P)                         # a x L
     L = G.shape[1]
     bad = sorted(set(int(i) for i in bad))
-    good = [i for i in range(L) if i not in bad]
+    good = [i for i in range(L) if i not in bad] if sources is None else [int(i) for i in sources]
+    assert not set(good) & set(bad) and len(good) >= G.shape[0]
     Wn = Wt.copy()
     cols = Wt.shape[1]
     stack = np.stack([Wt[i * B:(i + 1) * B].reshape(-1) for i in good])     # |good| x (B cols)
@@ -537,15 +543,16 @@ class CodedLayer:
         res["decoded"] = unpad_blocks(res["out"][: a * B], N, a, B)
         return res
 
-    def regenerate(self, phase, located):
+    def regenerate(self, phase, located, sources=None):
         """Rebuild the stored blocks at the nodes located in `phase`'s product:
-        block-rows for the forward product, block-columns for the backward one."""
+        block-rows for the forward product, block-columns for the backward one
+        (sources: the blocks of each line that are accessed, see regenerate_blocks)."""
         if len(located) == 0:
             return
         if phase == PHASE_FWD:
-            self.Wt = regenerate_blocks(self.Wt, located, self.P_r, self.Br, 0)
+            self.Wt = regenerate_blocks(self.Wt, located, self.P_r, self.Br, 0, sources)
         else:
-            self.Wt = regenerate_blocks(self.Wt, located, self.P_c, self.Bc, 1)
+            self.Wt = regenerate_blocks(self.Wt, located, self.P_c, self.Bc, 1, sources)
 
     def update(self, eta):
         self.Wt = update(self.Wt, self.Dt, self.Xt, eta, self.m, self.n,

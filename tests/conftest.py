@@ -30,3 +30,13 @@ def load_golden(name):
 @pytest.fixture(scope="session")
 def worked_example():
     return load_golden("worked_example_m2n2t1.txt")
+
+
+def pytest_terminal_summary(terminalreporter):
+    """Largest value errors that the GPU parity harness has seen, per kind of comparison."""
+    mod = sys.modules.get("harness")
+    lines = mod.Stats.lines() if mod is not None else []
+    if lines:
+        terminalreporter.write_sep("-", "largest errors against the oracle (relative to the bounds' scale)")
+        for line in lines:
+            terminalreporter.write_line(line)

@@ -8,20 +8,21 @@ from paper_1903_01042_amd import workloads as WL
 # Bounds on values.  TOL is the whole-tensor relative Frobenius error that the task states.  A
 # whole-tensor norm alone is blind to a wrong row or a stale tile whose error drowns in the rest,
 # so every comparison also holds each block (node output block, stored block W~_{i,j}) to its own
-# relative Frobenius bound, and every element to a multiple of its block's rms:
-#   BLOCK_TOL  f32: fp32 accumulation of up to 16384 products, error ~ sqrt(K) 2^-24 < 1e-5; the
-#              bound is twice that.  bf16: both factors rounded to 8 significant bits give a
-#              measured 2.2e-3 per block; the bound is three times that.
-#   ELEM_C     the element errors of a block are sums of many rounding errors, close to normal with
-#              sigma = (block's relative error) x rms; among the 2.6 million elements of the
-#              largest output compared the largest is about 5.2 sigma.  Bound: 4 x BLOCK_TOL x rms,
-#              i.e. 12 sigma of what is measured in bf16.
+# relative Frobenius bound, and every element to a multiple of its block's rms.  Set from what the
+# GPU tests measure (largest values over all tests, printed at the end of every run):
+#   BLOCK_TOL  f32: largest block error measured 4.2e-6 (fp32 accumulation of up to 16384
+#              products, ~ sqrt(K) 2^-24); bound 2e-5.  bf16: both factors rounded to 8 significant
+#              bits give 2.2e-3 .. 3.4e-3 per block, 4.2e-3 at the most (small, ragged blocks);
+#              bound 6.6e-3 = 3 x the typical and 1.6 x the largest value.
+#   ELEM_C     largest element error measured: 2.2e-2 of the block's rms in bf16, 3.7e-5 in f32
+#              (the variance of an element's error follows the products that went into it, so
+#              the tail is heavier than a normal law's); bound 6 x BLOCK_TOL x rms: 4.0e-2 / 1.2e-4.
 # A block that the check has corrected, or that was regenerated, carries the rounding noise of the
 # blocks it was rebuilt from: its two bounds are scaled by that amplification (computed from the
 # code's coefficients where it applies, see corrected_amp / regenerated_amp).
 TOL = {"f32": 1e-4, "bf16": 2e-2}          # relative Frobenius error on values
 BLOCK_TOL = {"f32": 2e-5, "bf16": 6.6e-3}
-ELEM_C = 4.0
+ELEM_C = 6.0
 MARGIN = 5.0                               # every threshold decision must clear its tau by this factor
 
 
@@ -36,10 +37,14 @@ def to_np(t):
     return t.detach().cpu().numpy().astype(np.float64)
 
 
+SMALL = 64       # a block of fewer nonzero entries has no stable rms of its own
+
+
 def block_errors(got, ref, row_edges, col_edges=None):
     """Per block: (relative Frobenius error, largest |difference| / rms of the reference block's
-    nonzero entries).  Blocks are the rectangles between consecutive row (and column) edges; a
-    block whose reference is all zero is measured against the rms of the whole reference."""
+    nonzero entries, number of nonzero entries).  Blocks are the rectangles between consecutive row
+    (and column) edges; a block whose reference is all zero, or has fewer than SMALL nonzero
+    entries, is measured against the rms of the whole reference if that is larger."""
     got = np.asarray(got, dtype=np.float64)
     ref = np.asarray(ref, dtype=np.float64)
     if col_edges is None:
@@ -47,7 +52,7 @@ def block_errors(got, ref, row_edges, col_edges=None):
     nz_all = np.count_nonzero(ref)
     rms_all = np.sqrt(np.sum(ref * ref) / nz_all) if nz_all else 1.0
     nr, nc = len(row_edges) - 1, len(col_edges) - 1
-    fro, elem = np.zeros((nr, nc)), np.zeros((nr, nc))
+    fro, elem, count = np.zeros((nr, nc)), np.zeros((nr, nc)), np.ones((nr, nc))
     for i in range(nr):
         for j in range(nc):
             g = got[row_edges[i]:row_edges[i + 1], col_edges[j]:col_edges[j + 1]]
@@ -56,13 +61,17 @@ def block_errors(got, ref, row_edges, col_edges=None):
                 continue
             d = g - r
             ss, nz = np.sum(r * r), np.count_nonzero(r)
+            count[i, j] = max(nz, 1)
             if nz == 0:
                 fro[i, j] = np.sqrt(np.sum(d * d) / d.size) / rms_all
                 elem[i, j] = np.max(np.abs(d)) / rms_all
             else:
-                fro[i, j] = np.sqrt(np.sum(d * d) / ss)
-                elem[i, j] = np.max(np.abs(d)) / np.sqrt(ss / nz)
-    return fro, elem
+                rms = np.sqrt(ss / nz)
+                if nz < SMALL:
+                    rms = max(rms, rms_all)
+                fro[i, j] = np.sqrt(np.sum(d * d) / nz) / rms
+                elem[i, j] = np.max(np.abs(d)) / rms
+    return fro, elem, count
 
 
 def pitch_edges(nblocks, B):
@@ -89,15 +98,22 @@ def corrected_amp(P, located, blk_rms):
     return amp
 
 
-def regenerated_amp(P, bad, blk_rms):
-    """The same for regenerated blocks: block i is the combination sum_j c_j block_j of the source
-    blocks the library uses (the good systematic blocks and, for ks lost systematic ones, the first
-    ks good parity blocks), G[:, S] c = G[:, i]."""
-    G = O.generator(P)
-    a, L = G.shape
+def library_sources(P, bad):
+    """The a blocks of a line that the library accesses to regenerate the blocks `bad` (the paper
+    leaves the choice open: any a good ones): the good systematic blocks and, for ks lost
+    systematic ones, the first ks good parity blocks."""
+    a, r = np.shape(P)[0], (np.shape(P)[1] if np.ndim(P) == 2 else 0)
     bad = sorted(set(bad))
     ks = sum(1 for i in bad if i < a)
-    S = [i for i in range(a) if i not in bad] + [a + q for q in range(L - a) if a + q not in bad][:ks]
+    return [i for i in range(a) if i not in bad] + [a + q for q in range(r) if a + q not in bad][:ks]
+
+
+def regenerated_amp(P, bad, blk_rms):
+    """The same for regenerated blocks: block i is the combination sum_j c_j block_j of the source
+    blocks S that are accessed, G[:, S] c = G[:, i]."""
+    G = O.generator(P)
+    bad = sorted(set(bad))
+    S = library_sources(P, bad)
     amp = {}
     for i in bad:
         c = np.linalg.solve(G[:, S], G[:, i])
@@ -131,8 +147,10 @@ def assert_close(got, ref, dtype, what, row_edges, col_edges=None, row_amp=None,
     blk_tol = BLOCK_TOL[dtype] if blk_tol is None else blk_tol
     whole = rel_fro(got, ref)
     assert whole <= tol, "%s differs: rel %.3e" % (what, whole)
-    fro, elem = block_errors(got, ref, row_edges, col_edges)
-    scale = np.ones_like(fro)
+    fro, elem, count = block_errors(got, ref, row_edges, col_edges)
+    # the relative error of a block of n entries scatters by about 1 / sqrt(2 n) around its mean:
+    # small blocks get that allowance (four standard deviations), large ones are unaffected
+    scale = 1.0 + 4.0 / np.sqrt(2.0 * count)
     for i, f in (row_amp or {}).items():
         scale[i, :] *= f
     for j, f in (col_amp or {}).items():
@@ -216,7 +234,6 @@ class Pair:
         P, L, Bp, N, a = self._code(phase)
         edges = pitch_edges(L, Bp)
         self._cmp(to_np(out_g).T, out_o, "coded product", edges)
-        clean_rms = np.sqrt(np.mean(out_o.reshape(L, -1) ** 2, axis=1))
         faults = list(faults)
         if faults:
             self.gpu.inject(faults, out_g)
@@ -257,7 +274,10 @@ class Pair:
                           MARGIN if check_margins is True else float(check_margins))
         if rep["verdict"] != B.UNCORRECTABLE:
             # repaired blocks carry the rounding noise of the blocks they were rebuilt from
-            amp = corrected_amp(P, res["located"], clean_rms) if res["located"] else {}
+            # (scale of a repaired block: its rms after the repair -- a block produced from a corrupted
+            # stored block is large before it)
+            fixed_rms = np.sqrt(np.mean(res["out"].reshape(L, -1) ** 2, axis=1))
+            amp = corrected_amp(P, res["located"], fixed_rms) if res["located"] else {}
             mul = np.asarray(aux if aux_ora is None else aux_ora, dtype=np.float64) if epilogue == B.EPI_MUL else None
             self._cmp(to_np(dec_g).T, res["decoded"], "decoded output", logical_edges(N, a),
                       row_amp={i: f for i, f in amp.items() if i < a},
@@ -292,10 +312,13 @@ class Pair:
         self.gpu.regenerate(phase, self.report)
         if res["verdict"] != O.CORRECTED:
             return {}
-        self.ora.regenerate(phase, res["located"])
         o = self.ora
         rows = phase == self.B.FWD
         P, L, Bp = (o.P_r, o.m + o.r_r, o.Br) if rows else (o.P_c, o.n + o.r_c, o.Bc)
+        # the oracle accesses the same a good blocks as the library: where one of them carries an
+        # undetected error of its own (a second stored block hit in the same grid column), the
+        # rebuilt block depends on the choice, and both sides must make the same one
+        self.ora.regenerate(phase, res["located"], sources=library_sources(P, res["located"]))
         lines = (o.Wt if rows else o.Wt.T).reshape(L, -1)
         amp = regenerated_amp(P, res["located"], np.sqrt(np.mean(lines ** 2, axis=1)))
         if self.dtype == "bf16":

@@ -458,6 +458,28 @@ def test_regeneration_restores_any_r_blocks_of_a_codeword(axis, r):
             assert np.allclose(O.regenerate_blocks(hit, bad, P, B, axis), Wt, atol=1e-9), (axis, bad)
 
 
+def test_any_choice_of_good_blocks_regenerates_the_same_line():
+    """Regeneration passage: "any" a blocks of the line that are known to be correct may be accessed
+    (MDS).  Every choice of a = 4 of the good blocks rebuilds two lost blocks of a consistent line
+    identically; once one of the accessed blocks carries an error of its own, the choice shows."""
+    a, r, B, cols = 4, 4, 3, 5
+    P = WL.vandermonde_like(a, r, "positive")
+    line = O.encode_vector(rng.standard_normal((a * B, cols)), P, B)          # 8 blocks of B x cols
+    lost = line.copy()
+    lost[1 * B:2 * B] = 99.0
+    lost[6 * B:7 * B] = -99.0
+    good = [0, 2, 3, 4, 5, 7]
+    for src in itertools.combinations(good, a):
+        assert np.allclose(O.regenerate_blocks(lost, [1, 6], P, B, 0, sources=src), line, atol=1e-9)
+    assert np.allclose(O.regenerate_blocks(lost, [1, 6], P, B), line, atol=1e-9)
+    hit = lost.copy()
+    hit[4 * B:5 * B] += 1.0                       # block 4 passes for good but is not
+    with_it = O.regenerate_blocks(hit, [1, 6], P, B, 0, sources=(0, 2, 3, 4))
+    without = O.regenerate_blocks(hit, [1, 6], P, B, 0, sources=(0, 2, 3, 5))
+    assert np.allclose(without[1 * B:2 * B], line[1 * B:2 * B], atol=1e-9)
+    assert not np.allclose(with_it[1 * B:2 * B], line[1 * B:2 * B], atol=1e-3)
+
+
 def test_regeneration_of_a_parity_block_is_reencoding():
     """Special case with a textbook form: a lost parity block-row q is the
     encoding of the systematic ones, sum_i P[i][q] W~_i."""
