@@ -207,6 +207,26 @@ class Pair:
     def _cmp(self, got, ref, what, row_edges, **kw):
         return assert_close(got, ref, self.dtype, what, row_edges, blk_tol=BLOCK_TOL[self.dtype] * self.blk_scale, **kw)
 
+    def _weight_amp(self, phase):
+        """Bound scaling of a product's output blocks that stems from regenerated lines of the stored
+        matrix (bf16 mode, see w_row_amp): output block i of the forward product sums the blocks
+        W~_{i,j} x_j over the base columns j, the backward one W~_{i,j}^T delta_i over the base rows i;
+        a term's noise is scaled by its block's factor."""
+        o = self.ora
+        f = lambda d, k: d.get(k, 1.0)
+        amp = {}
+        if phase == self.B.FWD:
+            for i in range(o.m + o.r_r):
+                v = np.sqrt(np.mean([(f(self.w_row_amp, i) * f(self.w_col_amp, j)) ** 2 for j in range(o.n)]))
+                if v > 1.0:
+                    amp[i] = float(v)
+        else:
+            for j in range(o.n + o.r_c):
+                v = np.sqrt(np.mean([(f(self.w_row_amp, i) * f(self.w_col_amp, j)) ** 2 for i in range(o.m)]))
+                if v > 1.0:
+                    amp[j] = float(v)
+        return amp
+
     def _code(self, phase):
         """(P, number of blocks, block pitch, logical length, systematic blocks) of the phase's codeword."""
         o = self.ora
@@ -233,12 +253,13 @@ class Pair:
             out_o = self.ora.backward(Vo)
         P, L, Bp, N, a = self._code(phase)
         edges = pitch_edges(L, Bp)
-        self._cmp(to_np(out_g).T, out_o, "coded product", edges)
+        wamp = self._weight_amp(phase)
+        self._cmp(to_np(out_g).T, out_o, "coded product", edges, row_amp=wamp)
         faults = list(faults)
         if faults:
             self.gpu.inject(faults, out_g)
             out_o = self.ora.inject(faults, out_o)
-            self._cmp(to_np(out_g).T, out_o, "injected output", edges)
+            self._cmp(to_np(out_g).T, out_o, "injected output", edges, row_amp=wamp)
         if check_fault is not None:
             self.gpu.inject([dict(phase=B.CHECK, bi=check_fault["target"], bj=check_fault["who"],
                                   seed=check_fault.get("seed", 0), step=0, lo=0.0, hi=check_fault["hi"])])
@@ -265,7 +286,7 @@ class Pair:
         assert rep["located"] == res["located"], (rep, res["located"])
         if rep["verdict"] == B.DISAGREE:
             if check_fault["target"] == B.CHECK_EVALUATION:   # found before anything was corrected
-                self._cmp(to_np(out_g).T, res["out"], "output before a disagreement", edges)
+                self._cmp(to_np(out_g).T, res["out"], "output before a disagreement", edges, row_amp=wamp)
             return dec_g, rep, res
         if check_margins and (self.ora.r_r if phase == B.FWD else self.ora.r_c) > 0:
             # check_margins: True = the factor MARGIN; a number = that factor (seeded random grids and
@@ -277,14 +298,18 @@ class Pair:
             # (scale of a repaired block: its rms after the repair -- a block produced from a corrupted
             # stored block is large before it)
             fixed_rms = np.sqrt(np.mean(res["out"].reshape(L, -1) ** 2, axis=1))
-            amp = corrected_amp(P, res["located"], fixed_rms) if res["located"] else {}
+            noise_rms = fixed_rms * np.array([wamp.get(i, 1.0) for i in range(L)])
+            amp = dict(wamp)
+            if res["located"]:
+                for i, f in corrected_amp(P, res["located"], noise_rms).items():
+                    amp[i] = f * wamp.get(i, 1.0)
             mul = np.asarray(aux if aux_ora is None else aux_ora, dtype=np.float64) if epilogue == B.EPI_MUL else None
             self._cmp(to_np(dec_g).T, res["decoded"], "decoded output", logical_edges(N, a),
                       row_amp={i: f for i, f in amp.items() if i < a},
                       elem_scale=1.0 if mul is None else max(1.0, float(np.max(np.abs(mul)) / np.sqrt(np.mean(mul ** 2)))))
             self._cmp(to_np(out_g).T, res["out"], "corrected coded output", edges, row_amp=amp)
         else:
-            self._cmp(to_np(out_g).T, res["out"], "output left as it was", edges)
+            self._cmp(to_np(out_g).T, res["out"], "output left as it was", edges, row_amp=wamp)
         return dec_g, rep, res
 
     def _margins(self, rep, res, r, MARGIN):
