@@ -34,7 +34,7 @@ struct codenet_layer {
   __bf16 *Db = nullptr;         // [max_batch][ldDb]  delta, zero beyond the base rows
   __bf16 *XTb = nullptr;        // [Nc][ldT]    feature-major [x; x~] (update)
   __bf16 *DTb = nullptr;        // [Mr][ldT]    feature-major [delta; delta~] (update)
-  float *part = nullptr;        // split-k partial results: [kMaxSplits][max_batch][max(Mr, Nc)] (bf16 mode; f32 mode at thin batches)
+  float *part = nullptr;        // split-k partial results of the f32 products at thin batches: [kMaxSplits][max_batch][max(Mr, Nc)]
   long ldWb = 0;
   int KpX = 0, KpD = 0, bpad = 0;   // contraction lengths (multiples of 64): base columns, base rows, batch
   long ldXb = 0, ldDb = 0, ldT = 0; // pitches of Xb, Db and of XTb / DTb
@@ -90,25 +90,69 @@ bool next_subset(std::vector<int> &s, int n) {
   return true;
 }
 
-// G = [I | P] is MDS iff every square minor of P is non-zero.  Orders are
-// checked smallest first until a budget of minors is spent (tiny codes are
-// checked completely).
+// |det| of the k x k minor of P on (rows, cols), relative to the product of the Euclidean norms of its
+// columns (Hadamard's bound): 1 for orthogonal columns, 0 for dependent ones, whatever the scale of P.
+double relative_minor(const double *P, int r, const std::vector<int> &rows, const std::vector<int> &cols) {
+  const int k = (int)rows.size();
+  std::vector<double> sub((size_t)k * k);
+  double bound = 1.0;
+  for (int y = 0; y < k; ++y) {
+    double n2 = 0.0;
+    for (int x = 0; x < k; ++x) {
+      const double v = P[rows[x] * r + cols[y]];
+      sub[x * k + y] = v;
+      n2 += v * v;
+    }
+    bound *= std::sqrt(n2);
+  }
+  return bound > 0.0 ? std::fabs(det_small(sub, k)) / bound : 0.0;
+}
+
+double binomial(int n, int k) {
+  double c = 1.0;
+  for (int q = 1; q <= k; ++q) c = c * (n - k + q) / q;
+  return c;
+}
+
+// G = [I | P] is MDS iff every square minor of P is non-zero (taken as: above 1e-9 of Hadamard's
+// bound).  All minors of all orders are checked while there are at most 4e6 of them; a longer code
+// gets every order checked on a share of that budget: completely where the order has few enough
+// minors, otherwise on minors drawn by a fixed linear congruential sequence -- such a generator
+// is verified by sampling only.
 bool generator_is_mds(const double *P, int a, int r) {
   const double tol = 1e-9;
-  long budget = 4000000;
-  for (int k = 1; k <= std::min(a, r); ++k) {
+  const double budget = 4e6;
+  const int orders = std::min(a, r);
+  double total = 0.0;
+  for (int k = 1; k <= orders; ++k) total += binomial(a, k) * binomial(r, k);
+  const double share = total <= budget ? budget : budget / orders;
+  unsigned long long lcg = 0x2545F4914F6CDD1Dull;
+  for (int k = 1; k <= orders; ++k) {
     std::vector<int> rows(k), cols(k);
-    for (int q = 0; q < k; ++q) rows[q] = q;
-    do {
-      for (int q = 0; q < k; ++q) cols[q] = q;
+    if (binomial(a, k) * binomial(r, k) <= share) {
+      for (int q = 0; q < k; ++q) rows[q] = q;
       do {
-        std::vector<double> sub(k * k);
-        for (int x = 0; x < k; ++x)
-          for (int y = 0; y < k; ++y) sub[x * k + y] = P[rows[x] * r + cols[y]];
-        if (!(std::fabs(det_small(sub, k)) > tol)) return false;
-        if (--budget <= 0) return true;
-      } while (next_subset(cols, r));
-    } while (next_subset(rows, a));
+        for (int q = 0; q < k; ++q) cols[q] = q;
+        do {
+          if (!(relative_minor(P, r, rows, cols) > tol)) return false;
+        } while (next_subset(cols, r));
+      } while (next_subset(rows, a));
+      continue;
+    }
+    auto draw = [&](std::vector<int> &set, int n) {      // k distinct indices below n, ascending
+      std::vector<char> used((size_t)n, 0);
+      for (int got = 0; got < k;) {
+        lcg = lcg * 6364136223846793005ull + 1442695040888963407ull;
+        const int v = (int)((lcg >> 33) % (unsigned long long)n);
+        if (!used[v]) { used[v] = 1; ++got; }
+      }
+      for (int v = 0, q = 0; v < n; ++v) if (used[v]) set[q++] = v;
+    };
+    for (long trial = 0; trial < (long)share; ++trial) {
+      draw(rows, a);
+      draw(cols, r);
+      if (!(relative_minor(P, r, rows, cols) > tol)) return false;
+    }
   }
   return true;
 }
@@ -214,9 +258,7 @@ int codenet_encode(const codenet_desc *d, const float *W_dev, void *stream, code
     // A row pitch that is a multiple of 2 KB puts the same 128-byte column of every row of an
     // operand tile on one L2 channel, and all workgroups of an XCD walk those columns together:
     // such pitches get one more line (64 elements), so that consecutive rows change channel.
-    const char *skew_env = getenv("CODENET_SKEW");
-    const bool skew_on = !(skew_env && skew_env[0] == '0');
-    auto pitch = [&](long v) { v = up64(v); return (skew_on && (v * 2) % 2048 == 0) ? v + 64 : v; };
+    auto pitch = [&](long v) { v = up64(v); return (v * 2) % 2048 == 0 ? v + 64 : v; };
     l->ldWb = pitch(l->Nc);
     l->KpX = (int)up64((long)l->code_c.a * l->code_c.B);
     l->KpD = (int)up64((long)l->code_r.a * l->code_r.B);
@@ -230,7 +272,6 @@ int codenet_encode(const codenet_desc *d, const float *W_dev, void *stream, code
     l->ldT = pitch(l->bpad);
     alloc((void **)&l->XTb, 2 * (size_t)l->Nc * l->ldT);
     alloc((void **)&l->DTb, 2 * (size_t)l->Mr * l->ldT);
-    alloc((void **)&l->part, sizeof(float) * (size_t)kMaxSplits * mb * std::max(l->Mr, l->Nc));
     alloc((void **)&l->Wb, szWb);
     alloc((void **)&l->Xb, szXb);
     alloc((void **)&l->Db, szDb);
@@ -282,16 +323,14 @@ int codenet_forward(codenet_layer *l, const float *X_dev, int b, float *S_coded_
   hipStream_t s = (hipStream_t)stream;
   l->fwd_b = 0;
   if (l->bf16) {
-    int tile = 0, splits = 1;
-    plan_gemm2(l->Mr, b, l->KpX, kMaxSplits, &tile, &splits);
     // coded input: batch-major bf16 x (product operand) and feature-major bf16 [x; x~] (update operand)
     CN_HIP(launch_encode_vector_bf16(X_dev, l->code_c_dev, l->code_c, b, l->Xb, l->ldXb, l->XTb, l->ldT, s));
     Gemm2Args g2{};
     g2.A = l->Wb; g2.lda = l->ldWb;
     g2.B = l->Xb; g2.ldb = l->ldXb;
     g2.C = S_coded_dev; g2.ldc = l->Mr;
-    g2.I = l->Mr; g2.J = b; g2.K = l->KpX; g2.splits = splits;
-    CN_HIP(launch_gemm2(g2, tile, l->part, s));
+    g2.I = l->Mr; g2.J = b; g2.K = l->KpX;
+    CN_HIP(launch_product(g2, s));
     l->fwd_b = b;
     return CODENET_OK;
   }
@@ -303,7 +342,7 @@ int codenet_forward(codenet_layer *l, const float *X_dev, int b, float *S_coded_
   g.I = l->Mr; g.J = b; g.K = l->code_c.a * l->code_c.B;
   g.alpha = 1.f;
   g.workspace = l->part; g.max_splits = kMaxSplits;
-  CN_HIP(launch_gemm(kFwd, l->bf16, g, s));
+  CN_HIP(launch_gemm(kFwd, g, s));
   l->fwd_b = b;
   return CODENET_OK;
 }
@@ -314,16 +353,14 @@ int codenet_backward(codenet_layer *l, const float *D_dev, int b, float *C_coded
   hipStream_t s = (hipStream_t)stream;
   l->bwd_b = 0;
   if (l->bf16) {
-    int tile = 0, splits = 1;
-    plan_gemm2(l->Nc, b, l->KpD, kMaxSplits, &tile, &splits);
     CN_HIP(launch_encode_vector_bf16(D_dev, l->code_r_dev, l->code_r, b, l->Db, l->ldDb, l->DTb, l->ldT, s));
     Gemm2Args g2{};
     // A[i][k] = W~[k][i]: the row-major copy, read k-major (transposing LDS reads in the kernel)
     g2.A = l->Wb; g2.lda = l->ldWb; g2.a_k_major = 1;
     g2.B = l->Db; g2.ldb = l->ldDb;
     g2.C = C_coded_dev; g2.ldc = l->Nc;
-    g2.I = l->Nc; g2.J = b; g2.K = l->KpD; g2.splits = splits;
-    CN_HIP(launch_gemm2(g2, tile, l->part, s));
+    g2.I = l->Nc; g2.J = b; g2.K = l->KpD;
+    CN_HIP(launch_product(g2, s));
     l->bwd_b = b;
     return CODENET_OK;
   }
@@ -335,7 +372,7 @@ int codenet_backward(codenet_layer *l, const float *D_dev, int b, float *C_coded
   g.I = l->Nc; g.J = b; g.K = l->code_r.a * l->code_r.B;
   g.alpha = 1.f;
   g.workspace = l->part; g.max_splits = kMaxSplits;
-  CN_HIP(launch_gemm(kBwd, l->bf16, g, s));
+  CN_HIP(launch_gemm(kBwd, g, s));
   l->bwd_b = b;
   return CODENET_OK;
 }
@@ -355,8 +392,7 @@ int codenet_update(codenet_layer *l, float eta, void *stream) {
     // The matrix and its copies are a little more than the memory-side cache holds; sweeping them
     // in the same order every step is the worst case for its LRU replacement, so the direction
     // alternates: what the last update wrote last is read first.
-    const char *alt = getenv("CODENET_ALTERNATE");
-    u.reverse = (alt && alt[0] == '0') ? 0 : (int)(l->updates & 1);
+    u.reverse = (int)(l->updates & 1);
     ++l->updates;
     CN_HIP(launch_update2(u, s));
     return CODENET_OK;
@@ -367,7 +403,7 @@ int codenet_update(codenet_layer *l, float eta, void *stream) {
   g.C = l->Wt; g.ldc = l->Nc;
   g.I = l->Nc; g.J = l->Mr; g.K = l->fwd_b;
   g.alpha = eta;
-  CN_HIP(launch_gemm(kUpd, false, g, s));
+  CN_HIP(launch_gemm(kUpd, g, s));
   return CODENET_OK;
 }
 

@@ -62,10 +62,10 @@ struct GemmArgs {
 hipError_t launch_reduce_partials(const float *part, long stride, int splits, float *out, long count, hipStream_t s);
 
 enum GemmLayout { kFwd = 0, kBwd = 1, kUpd = 2 };
-// fwd: A k-contiguous, B k-contiguous, C = A B^T
-// bwd: A k-strided   , B k-contiguous, C = A B^T
-// upd: A k-strided   , B k-strided   , C += alpha A B^T
-hipError_t launch_gemm(GemmLayout layout, bool bf16, const GemmArgs &args, hipStream_t stream);
+// float32 operands: fwd: A k-contiguous, B k-contiguous, C = A B^T
+//                   bwd: A k-strided   , B k-contiguous, C = A B^T
+//                   upd: A k-strided   , B k-strided   , C += alpha A B^T
+hipError_t launch_gemm(GemmLayout layout, const GemmArgs &args, hipStream_t stream);
 
 // bf16 operands, k contiguous and zero padded to a multiple of 64; C[j][i] fp32
 struct Gemm2Args {
@@ -73,9 +73,8 @@ struct Gemm2Args {
   const __bf16 *B; long ldb;
   float *C; long ldc;
   int I, J, K;
-  int tiles_i, tiles_j, splits;
-  long split_stride;
-  int a_k_major;                 // A is stored A[k][i], i contiguous (product_kernel only)
+  int tiles_i, tiles_j;          // set by the launcher
+  int a_k_major;                 // A is stored A[k][i], i contiguous
 };
 struct Update2Args {
   const __bf16 *XT; long ldx;    // [I = coded columns][batch padded to 64]
@@ -88,8 +87,7 @@ struct Update2Args {
   int reverse;                   // walk the tiles in the opposite order (alternates from call to call)
 };
 constexpr int kMaxSplits = 8;
-void plan_gemm2(int I, int J, int K, int max_splits, int *tile, int *splits);
-hipError_t launch_gemm2(Gemm2Args g, int tile, float *workspace, hipStream_t s);
+hipError_t launch_product(Gemm2Args g, hipStream_t s);
 hipError_t launch_update2(Update2Args g, hipStream_t s);
 hipError_t launch_shadow(const float *Wt, int Mr, int Nc, void *Wb, long ldWb, hipStream_t s);
 

@@ -9,14 +9,12 @@
 //              B = [delta; delta~] batch-major (k contiguous)
 //   update   : i = coded column, j = coded row, k = batch;          A = [x; x~], B = [delta; delta~]
 //              (both k strided), C = W~ accumulated in place.
-// All operands are float32 in memory.  In the bf16 variant they are rounded to
-// bf16 (round to nearest even) on their way into LDS and multiplied with
-// v_mfma_f32_32x32x16_bf16; the f32 variant uses v_mfma_f32_32x32x2_f32.
-// Accumulation is float32 in both.
+// All operands are float32 in memory and are multiplied with v_mfma_f32_32x32x2_f32
+// (the bf16 mode has kernels of its own, gemm_bf16.hip).
 //
 // Tiling: 256 threads = 4 wavefronts in a 2 x 2 arrangement, each owning
 // FM x FN MFMA tiles of 32 x 32, so a workgroup computes (64 FM) x (64 FN).
-// A k-slab is 8 chunks of 16 bytes per operand row (64 bf16 or 32 f32); LDS
+// A k-slab is 8 chunks of 16 bytes per operand row (32 floats); LDS
 // rows are 128 bytes, chunk c of row r sits at slot c ^ swz(r), which keeps
 // both the 16-byte fragment reads (32 consecutive rows, one chunk) and the
 // transposing writes (rows 4 apart, one chunk) free of bank conflicts.
@@ -28,7 +26,6 @@
 
 namespace codenet {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
 __device__ __forceinline__ int swz(int row) { return ((row & 7) + (row >> 3)) & 7; }
@@ -37,23 +34,15 @@ __device__ __forceinline__ float f4get(const float4 &v, int e) {
   return e == 0 ? v.x : e == 1 ? v.y : e == 2 ? v.z : v.w;
 }
 
-__device__ __forceinline__ uint4 pack_bf16x8(float a0, float a1, float a2, float a3,
-                                             float a4, float a5, float a6, float a7) {
-  bf16x8 t;
-  t[0] = (__bf16)a0; t[1] = (__bf16)a1; t[2] = (__bf16)a2; t[3] = (__bf16)a3;
-  t[4] = (__bf16)a4; t[5] = (__bf16)a5; t[6] = (__bf16)a6; t[7] = (__bf16)a7;
-  return __builtin_bit_cast(uint4, t);
-}
-
 __device__ __forceinline__ uint4 pack_f32x4(float a0, float a1, float a2, float a3) {
   float4 t = make_float4(a0, a1, a2, a3);
   return __builtin_bit_cast(uint4, t);
 }
 
 // Stages one operand slab (T rows x 8 chunks) from global memory to LDS.
-template <bool BF16, int T, bool KC>
+template <int T, bool KC>
 struct Loader {
-  static constexpr int EPC = BF16 ? 8 : 4;                 // elements per 16-byte chunk
+  static constexpr int EPC = 4;                            // elements per 16-byte chunk
   static constexpr int NTASK = KC ? T * 8 : (T / 4) * 8;   // KC: (row, chunk); else (4 rows, chunk)
   static constexpr int PER = (NTASK + 255) / 256;
   static constexpr int NF4 = KC ? EPC / 4 : EPC;           // float4 loads per task
@@ -95,37 +84,24 @@ struct Loader {
       if (!((NTASK % 256 == 0) || q < NTASK)) continue;
       if (KC) {
         const int row = q >> 3, c = q & 7;
-        uint4 chunk;
-        if (BF16)
-          chunk = pack_bf16x8(st[p][0].x, st[p][0].y, st[p][0].z, st[p][0].w,
-                              st[p][NF4 - 1].x, st[p][NF4 - 1].y, st[p][NF4 - 1].z, st[p][NF4 - 1].w);
-        else
-          chunk = __builtin_bit_cast(uint4, st[p][0]);
-        lds[row * 8 + (c ^ swz(row))] = chunk;
+        lds[row * 8 + (c ^ swz(row))] = __builtin_bit_cast(uint4, st[p][0]);
       } else {
         const int ig = q % (T / 4), kg = q / (T / 4);
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int row = ig * 4 + e;
-          uint4 chunk;
-          if (BF16)
-            chunk = pack_bf16x8(f4get(st[p][0], e), f4get(st[p][1], e), f4get(st[p][2], e),
-                                f4get(st[p][3], e), f4get(st[p][NF4 - 4], e), f4get(st[p][NF4 - 3], e),
-                                f4get(st[p][NF4 - 2], e), f4get(st[p][NF4 - 1], e));
-          else
-            chunk = pack_f32x4(f4get(st[p][0], e), f4get(st[p][1], e), f4get(st[p][2], e),
-                               f4get(st[p][3], e));
-          lds[row * 8 + (kg ^ swz(row))] = chunk;
+          lds[row * 8 + (kg ^ swz(row))] = pack_f32x4(f4get(st[p][0], e), f4get(st[p][1], e), f4get(st[p][2], e),
+                                                       f4get(st[p][3], e));
         }
       }
     }
   }
 };
 
-template <bool BF16, int FM, int FN, bool AKC, bool BKC, bool ACCUM>
+template <int FM, int FN, bool AKC, bool BKC, bool ACCUM>
 __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
   constexpr int TI = 64 * FM, TJ = 64 * FN;
-  constexpr int EPC = BF16 ? 8 : 4, KT = 8 * EPC;
+  constexpr int EPC = 4, KT = 8 * EPC;
   constexpr int STAGE = (TI + TJ) * 8;                     // chunks per LDS stage
   extern __shared__ uint4 lds[];
 
@@ -145,8 +121,8 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
   const int wi = wave & 1, wj = wave >> 1;
   const int l32 = lane & 31, h = lane >> 5;
 
-  Loader<BF16, TI, AKC> la;
-  Loader<BF16, TJ, BKC> lb;
+  Loader<TI, AKC> la;
+  Loader<TJ, BKC> lb;
 
   floatx16 acc[FM][FN];
 #pragma unroll
@@ -191,17 +167,12 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
       for (int a = 0; a < FM; ++a)
 #pragma unroll
         for (int b = 0; b < FN; ++b) {
-          if (BF16) {
-            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                __builtin_bit_cast(bf16x8, av[a]), __builtin_bit_cast(bf16x8, bv[b]), acc[a][b], 0, 0, 0);
-          } else {
-            const float4 af = __builtin_bit_cast(float4, av[a]);
-            const float4 bf = __builtin_bit_cast(float4, bv[b]);
-            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af.x, bf.x, acc[a][b], 0, 0, 0);
-            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af.y, bf.y, acc[a][b], 0, 0, 0);
-            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af.z, bf.z, acc[a][b], 0, 0, 0);
-            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af.w, bf.w, acc[a][b], 0, 0, 0);
-          }
+          const float4 af = __builtin_bit_cast(float4, av[a]);
+          const float4 bf = __builtin_bit_cast(float4, bv[b]);
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af.x, bf.x, acc[a][b], 0, 0, 0);
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af.y, bf.y, acc[a][b], 0, 0, 0);
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af.z, bf.z, acc[a][b], 0, 0, 0);
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af.w, bf.w, acc[a][b], 0, 0, 0);
         }
     }
     if (kt + 1 < nk) {
@@ -284,8 +255,6 @@ const TileChoice kTiles[] = {{4, 2, 1.00}, {2, 2, 0.95}, {2, 1, 0.80}, {1, 2, 0.
 
 int pick_tile(const GemmArgs &g, bool accum) {
   // Cheapest estimated time: rounds of resident workgroups x tile area / tile efficiency.
-  const char *env = getenv("CODENET_GEMM_TILE");
-  if (env && env[0] >= '0' && env[0] <= '4') return env[0] - '0';
   // A short contraction into a large C (the update of a thin batch) is a read-modify-write of C:
   // 128 x 128 tiles, two workgroups per CU, so that one's contraction hides the other's memory
   // latency (18432 x 18432, batch 64: 733 us against 922 us with 256 x 128 and 813 us with 64 x 64).
@@ -304,7 +273,7 @@ int pick_tile(const GemmArgs &g, bool accum) {
   return best;
 }
 
-template <bool BF16, int FM, int FN, bool AKC, bool BKC, bool ACCUM>
+template <int FM, int FN, bool AKC, bool BKC, bool ACCUM>
 hipError_t launch_one(GemmArgs g, hipStream_t s) {
   constexpr int TI = 64 * FM, TJ = 64 * FN;
   constexpr int stages = 2 * (TI + TJ) * 128, ctile = ACCUM ? TJ * (TI + 4) * 4 : 0;
@@ -318,7 +287,7 @@ hipError_t launch_one(GemmArgs g, hipStream_t s) {
   float *final_out = g.C;
   g.splits = 1;
   g.split_stride = 0;
-  constexpr int KT = BF16 ? 64 : 32;
+  constexpr int KT = 32;
   const int tiles = g.tiles_i * g.tiles_j, slabs = (g.K + KT - 1) / KT;
   if (!ACCUM && g.workspace != nullptr && tiles < 512 && slabs >= 64) {
     int sp = (2048 + tiles - 1) / tiles;
@@ -332,7 +301,7 @@ hipError_t launch_one(GemmArgs g, hipStream_t s) {
   }
   const int nt = tiles * g.splits;
   const int grid = ((nt + 7) / 8) * 8;
-  auto kern = gemm_kernel<BF16, FM, FN, AKC, BKC, ACCUM>;
+  auto kern = gemm_kernel<FM, FN, AKC, BKC, ACCUM>;
   static LdsOnce attr_done;
   hipError_t e = allow_lds(kern, lds, &attr_done);
   if (e != hipSuccess) return e;
@@ -342,34 +311,29 @@ hipError_t launch_one(GemmArgs g, hipStream_t s) {
   return launch_reduce_partials(g.workspace, g.split_stride, g.splits, final_out, g.split_stride, s);
 }
 
-template <bool BF16, bool AKC, bool BKC, bool ACCUM>
+template <bool AKC, bool BKC, bool ACCUM>
 hipError_t launch_layout(const GemmArgs &g, hipStream_t s) {
   switch (pick_tile(g, ACCUM)) {
-    case 0: return launch_one<BF16, 4, 2, AKC, BKC, ACCUM>(g, s);
-    case 1: return launch_one<BF16, 2, 2, AKC, BKC, ACCUM>(g, s);
-    case 2: return launch_one<BF16, 2, 1, AKC, BKC, ACCUM>(g, s);
-    case 3: return launch_one<BF16, 1, 2, AKC, BKC, ACCUM>(g, s);
-    default: return launch_one<BF16, 1, 1, AKC, BKC, ACCUM>(g, s);
-  }
-}
-
-template <bool BF16>
-hipError_t launch_dtype(GemmLayout layout, const GemmArgs &g, hipStream_t s) {
-  switch (layout) {
-    case kFwd: return launch_layout<BF16, true, true, false>(g, s);
-    case kBwd: return launch_layout<BF16, false, true, false>(g, s);
-    default: return launch_layout<BF16, false, false, true>(g, s);
+    case 0: return launch_one<4, 2, AKC, BKC, ACCUM>(g, s);
+    case 1: return launch_one<2, 2, AKC, BKC, ACCUM>(g, s);
+    case 2: return launch_one<2, 1, AKC, BKC, ACCUM>(g, s);
+    case 3: return launch_one<1, 2, AKC, BKC, ACCUM>(g, s);
+    default: return launch_one<1, 1, AKC, BKC, ACCUM>(g, s);
   }
 }
 
 }  // namespace
 
-hipError_t launch_gemm(GemmLayout layout, bool bf16, const GemmArgs &args, hipStream_t stream) {
+hipError_t launch_gemm(GemmLayout layout, const GemmArgs &args, hipStream_t stream) {
   // The kernels use 16-byte accesses along every contiguous dimension.
   if ((args.lda & 3) || (args.ldb & 3) || (args.ldc & 3) || (args.I & 3)) return hipErrorInvalidValue;
   if (layout != kUpd && (args.K & 3)) return hipErrorInvalidValue;
   if (layout == kUpd && (args.J & 3)) return hipErrorInvalidValue;
-  return bf16 ? launch_dtype<true>(layout, args, stream) : launch_dtype<false>(layout, args, stream);
+  switch (layout) {
+    case kFwd: return launch_layout<true, true, false>(args, stream);
+    case kBwd: return launch_layout<false, true, false>(args, stream);
+    default: return launch_layout<false, false, true>(args, stream);
+  }
 }
 
 }  // namespace codenet

@@ -21,11 +21,9 @@
 //    by choosing which global chunk each lane fetches;
 //  * workgroup ids are dealt to the 8 XCDs round-robin by the hardware; the
 //    id -> tile maps give every XCD tiles that share operand panels, hence an L2.
-// Kernels: gemm2_kernel (4 wavefronts, templated tile, split-k with an ordered
-// reduction of partial tiles -- fp32 atomics at L2 were several times slower than the
-// whole product and are order dependent), product_kernel (8 wavefronts with separate
-// roles, the default for the two products), update2_kernel (update, one tile per workgroup),
-// update3_kernel (update, persistent and wave-specialised), shadow_kernel.
+// Kernels: product_kernel (8 wavefronts with separate roles, the two products),
+// update2_kernel (update, one tile per workgroup), update3_kernel (update, persistent and
+// wave-specialised), shadow_kernel.
 #include "codenet_internal.h"
 
 namespace codenet {
@@ -121,7 +119,7 @@ __device__ __forceinline__ int swizzle_of_row(int r) { return (r >> 1) & 7; }
 // Main loop shared by the product and the update kernels: acc[a][b] += A-tile x B-tile^T
 // over slabs [kb, kb + nk) of 64.  acc rows (MFMA row index) run over j (B rows),
 // acc columns (lane % 32) over i (A rows): the B-side fragment is the first MFMA operand.
-template <int FM, int FN, int NS, int DBG = 0>
+template <int FM, int FN, int NS>
 __device__ __forceinline__ void mainloop(const __bf16 *__restrict__ A, long lda, const __bf16 *__restrict__ B,
                                          long ldb, int I, int J, int i0, int j0, int kb, int nk, char *lds_c,
                                          floatx16 (&acc)[FM][FN]) {
@@ -181,7 +179,7 @@ __device__ __forceinline__ void mainloop(const __bf16 *__restrict__ A, long lda,
 
 #pragma unroll
   for (int s = 0; s < NS - 1; ++s)
-    if (s < nk && !(DBG & 1)) issue(s);
+    if (s < nk) issue(s);
 
   for (int kt = 0; kt < nk; ++kt) {
     // slab kt must have landed; up to NS-2 younger slabs stay in flight
@@ -193,24 +191,16 @@ __device__ __forceinline__ void mainloop(const __bf16 *__restrict__ A, long lda,
     // The loads of slab kt + NS - 1 are issued a few at a time between the MFMAs
     // of this slab: a wavefront issues in order, and a burst of direct-to-LDS
     // loads would hold back its own MFMAs while the memory pipeline accepts them.
-    const bool prefetch = kt + NS - 1 < nk && !(DBG & 1);
+    const bool prefetch = kt + NS - 1 < nk;
 
     const unsigned sb = (unsigned)((kt % NS) * STAGE);
     u32x4 fa[2][FM], fb[2][FN];
-    if (DBG & 2) {
-#pragma unroll
-      for (int a = 0; a < FM; ++a) fa[0][a] = fa[1][a] = u32x4{(unsigned)kt, 1u, 2u, 3u};
-#pragma unroll
-      for (int b = 0; b < FN; ++b) fb[0][b] = fb[1][b] = u32x4{(unsigned)kt, 1u, 2u, 3u};
-    } else {
-      read_frags<FM>(fa[0], sb + offA[0]);
-      read_frags<FN>(fb[0], sb + offB[0]);
-    }
+    read_frags<FM>(fa[0], sb + offA[0]);
+    read_frags<FN>(fb[0], sb + offB[0]);
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
       const int cur = s & 1, nxt = cur ^ 1;
-      if (DBG & 2) {
-      } else if (s < 3) {
+      if (s < 3) {
         read_frags<FM>(fa[nxt], sb + offA[s + 1]);
         read_frags<FN>(fb[nxt], sb + offB[s + 1]);
         wait_lgkm<FM + FN>();      // LDS returns in order: the older step's fragments are in
@@ -221,13 +211,6 @@ __device__ __forceinline__ void mainloop(const __bf16 *__restrict__ A, long lda,
       for (int a = 0; a < FM; ++a) pin(fa[cur][a]);
 #pragma unroll
       for (int b = 0; b < FN; ++b) pin(fb[cur][b]);
-      if (DBG & 4) {
-#pragma unroll
-        for (int a = 0; a < FM; ++a) acc[a][0][0] += __builtin_bit_cast(float, fa[cur][a][0]);
-#pragma unroll
-        for (int b = 0; b < FN; ++b) acc[0][b][1] += __builtin_bit_cast(float, fb[cur][b][0]);
-        continue;
-      }
       constexpr int LQ = LPS / 4;            // loads issued during one k-step
       constexpr int MPL = (FM * FN) / LQ;    // MFMAs between two loads
 #pragma unroll
@@ -252,50 +235,6 @@ __device__ __forceinline__ int logical_workgroup(int total) {
   const int per = (total + 7) >> 3;
   const int logical = (int)(blockIdx.x & 7) * per + (int)(blockIdx.x >> 3);
   return logical < total ? logical : -1;
-}
-
-template <int FM, int FN, int NS, int DBG = 0>
-__global__ __launch_bounds__(256) void gemm2_kernel(Gemm2Args g) {
-  constexpr int TI = 64 * FM, TJ = 64 * FN;
-  extern __shared__ uint4 lds[];
-  const int logical = logical_workgroup(g.tiles_i * g.tiles_j * g.splits);
-  if (logical < 0) return;
-  const int tj = logical % g.tiles_j;
-  const int rest = logical / g.tiles_j;
-  const int split = rest % g.splits, ti = rest / g.splits;
-  const int i0 = ti * TI, j0 = tj * TJ;
-  const int kslabs = g.K >> 6;
-  const int kb = (int)((long)split * kslabs / g.splits);
-  const int ke = (int)((long)(split + 1) * kslabs / g.splits);
-
-  floatx16 acc[FM][FN];
-#pragma unroll
-  for (int a = 0; a < FM; ++a)
-#pragma unroll
-    for (int b = 0; b < FN; ++b)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.f;
-  mainloop<FM, FN, NS, DBG>(g.A, g.lda, g.B, g.ldb, g.I, g.J, i0, j0, kb, ke - kb, reinterpret_cast<char *>(lds), acc);
-
-  // Accumulator element 4 q + e of a 32 x 32 tile is (j = 8 q + 4 h + e, i = lane % 32):
-  // for one (q, e) the 32 lanes of a half-wavefront write 128 contiguous bytes of a row.
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int wi = wave & 1, wj = wave >> 1, l32 = lane & 31, h = lane >> 5;
-  float *C = g.C + (long)split * g.split_stride;
-#pragma unroll
-  for (int a = 0; a < FM; ++a)
-#pragma unroll
-    for (int b = 0; b < FN; ++b) {
-      const int i = i0 + (wi * FM + a) * 32 + l32;
-      if (i >= g.I) continue;
-#pragma unroll
-      for (int q = 0; q < 4; ++q)
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int j = j0 + (wj * FN + b) * 32 + 8 * q + 4 * h + e;
-          if (j < g.J) C[(long)j * g.ldc + i] = acc[a][b][4 * q + e];
-        }
-    }
 }
 
 // ---------------------------------------------------------------------------
@@ -497,7 +436,7 @@ __device__ __forceinline__ unsigned pack2_bf16(float lo, float hi) {
   return (unsigned)__builtin_bit_cast(unsigned short, a) | ((unsigned)__builtin_bit_cast(unsigned short, b) << 16);
 }
 
-template <int FM, int FN, int NS, int DBG = 0>
+template <int FM, int FN, int NS>
 __global__ __launch_bounds__(256, (FM * FN <= 4 ? 2 : 1)) void update2_kernel(Update2Args g) {
   constexpr int TI = 64 * FM, TJ = 64 * FN;
   constexpr int PR = TI * 2 + 16;       // pitch of the staging tile [j][i], bytes
@@ -524,7 +463,7 @@ __global__ __launch_bounds__(256, (FM * FN <= 4 ? 2 : 1)) void update2_kernel(Up
 #pragma unroll
       for (int x = 0; x < 16; ++x) {
         const int j = j0 + (wj * FN + b) * 32 + 8 * (x >> 2) + 4 * h + (x & 3);
-        old[a][b][x] = (i < g.I && j < g.J && !(DBG & 1)) ? g.W[(long)j * g.ldw + i] : 0.f;
+        old[a][b][x] = (i < g.I && j < g.J) ? g.W[(long)j * g.ldw + i] : 0.f;
       }
     }
 
@@ -535,7 +474,7 @@ __global__ __launch_bounds__(256, (FM * FN <= 4 ? 2 : 1)) void update2_kernel(Up
     for (int b = 0; b < FN; ++b)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.f;
-  if (!(DBG & 8)) mainloop<FM, FN, NS>(g.XT, g.ldx, g.DT, g.ldd, g.I, g.J, i0, j0, 0, g.K >> 6, lds_c, acc);
+  mainloop<FM, FN, NS>(g.XT, g.ldx, g.DT, g.ldd, g.I, g.J, i0, j0, 0, g.K >> 6, lds_c, acc);
 
   __syncthreads();                       // every wavefront is done with the operand stages
 #pragma unroll
@@ -550,7 +489,7 @@ __global__ __launch_bounds__(256, (FM * FN <= 4 ? 2 : 1)) void update2_kernel(Up
         const int j = j0 + (wj * FN + b) * 32 + 8 * (x >> 2) + 4 * h + (x & 3);
         const bool in = i < g.I && j < g.J;
         const float w = in ? fmaf(g.eta, acc[a][b][x], old[a][b][x]) : 0.f;
-        if (in && !(DBG & 2)) g.W[(long)j * g.ldw + i] = w;
+        if (in) g.W[(long)j * g.ldw + i] = w;
         acc[a][b][x] = w;
       }
       // 2. stage the bf16 value of w, row-major [j][i]
@@ -562,7 +501,6 @@ __global__ __launch_bounds__(256, (FM * FN <= 4 ? 2 : 1)) void update2_kernel(Up
       }
     }
   __syncthreads();
-  if (DBG & 4) return;
   // 3. the copy leaves as rows of 16-byte chunks (the pitch is a multiple of 64
   //    elements: whole chunks fit, and entries beyond the matrix are zeros)
   for (int id = tid; id < TJ * (TI / 8); id += 256) {
@@ -644,9 +582,6 @@ struct TileWalk {
   }
 };
 
-// DBG (ablation builds): 1 loaders and storers idle, 2 MMA role idles, 4 no stores at all,
-// 16 no stores of the bf16 copy, 32 no fp32 stores
-template <int DBG = 0>
 __global__ __launch_bounds__(512) void update3_kernel(Update2Args g) {
   constexpr int STAGE = 256 * 128;            // bytes: 128 A rows + 128 B rows of 128 bytes
   constexpr int TILE = 3 * STAGE;             // fp32 tile of the matrix, 64 KB: 160 KB in all
@@ -710,12 +645,10 @@ __global__ __launch_bounds__(512) void update3_kernel(Update2Args g) {
         for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.f;
 
     point_at(ti, tj);
-    if (!(DBG & 2)) {
 #pragma unroll
-      for (int u = 0; u < 8; ++u) issue_one(0, 0, u);
+    for (int u = 0; u < 8; ++u) issue_one(0, 0, u);
 #pragma unroll
-      for (int u = 0; u < 8; ++u) issue_one(1, 1, u);
-    }
+    for (int u = 0; u < 8; ++u) issue_one(1, 1, u);
     int nti = 0, ntj = 0;
     bool more = walk.next(nti, ntj);
     int stage = 0;                            // stage of the slab being consumed; the pipeline is flat across tiles
@@ -725,7 +658,6 @@ __global__ __launch_bounds__(512) void update3_kernel(Update2Args g) {
         if (kt + 1 < KS || more) wait_vm<8>();
         else wait_vm<0>();
         lds_barrier();
-        if (DBG & 2) continue;
         // requested during this slab: two slabs ahead, in this tile or at the start of the next one
         const bool wraps = kt + 2 >= KS;
         const bool prefetch = !wraps || more;
@@ -814,13 +746,10 @@ __global__ __launch_bounds__(512) void update3_kernel(Update2Args g) {
     // request that group of the next tile: the HBM latency has a whole tile period.
     const int v = tid - 256;
     f32x4 old[32];                            // native vectors: an array of HIP's float4 struct ends up in scratch here
-    if (DBG & 128)
-      for (int n = 0; n < 32; ++n) old[n] = f32x4{0.f, 0.f, 0.f, 0.f};
     // item n goes to row 4 n + v / 32, piece (v % 32) ^ (row % 32) = ((v % 32) ^ (v / 32)) ^ (4 n % 32)
     char *const wbase = lds_c + TILE + (v >> 5) * 512;
     int wpiece = (((v & 31) ^ (v >> 5)) << 4);
     auto request_group = [&](int gq, int rti, int rtj) {
-      if (DBG & 129) return;
       if ((rti + 1) * 128 <= g.I && (rtj + 1) * 128 <= g.J) {
         // whole tile inside the matrix: one base address, uniform strides
         const float *src = g.W + (long)(rtj * 128 + (v >> 5)) * g.ldw + rti * 128 + (v & 31) * 4;
@@ -842,7 +771,6 @@ __global__ __launch_bounds__(512) void update3_kernel(Update2Args g) {
       }
     };
     auto write_group = [&](int gq) {
-      if (DBG & 257) return;
 #if CN_DEVICE_ASM
       // recompute the addresses of a group here: hoisted out of the tile loop they cost 32 registers
       asm volatile("" : "+v"(wpiece));
@@ -895,7 +823,6 @@ __global__ __launch_bounds__(512) void update3_kernel(Update2Args g) {
   int rpiece = (((2 * (v & 15)) ^ (v >> 4)) << 4);
   // qt: rows 64 qt .. 64 qt + 63 of the tile; hsel: -1 all of them, 0 / 1 one half (four of the eight row groups)
   auto quarter = [&](int qt, int hsel = -1) {
-    if (DBG & 513) return;
     // a tile that lies inside the matrix takes the branch-free path: all LDS reads of the
     // quarter first, then the stores; an edge tile masks every access
     const bool interior = (pti + 1) * 128 <= g.I && (ptj + 1) * 128 <= g.J;
@@ -924,11 +851,9 @@ __global__ __launch_bounds__(512) void update3_kernel(Update2Args g) {
             const int k = qt * 8 + half * 4 + k4;
             const f32x4 w0 = c[k4][0], w1 = c[k4][1];
             const u32x4 pk = {pack2_bf16(w0[0], w0[1]), pack2_bf16(w0[2], w0[3]), pack2_bf16(w1[0], w1[1]), pack2_bf16(w1[2], w1[3])};
-            if (!(DBG & 36)) {
-              *reinterpret_cast<f32x4 *>(pw + (long)(8 * k) * g.ldw) = w0;
-              *reinterpret_cast<f32x4 *>(pw + (long)(8 * k) * g.ldw + 4) = w1;
-            }
-            if (!(DBG & 20) || pk[0] == 0x12345u) *reinterpret_cast<u32x4 *>(pb + (long)(8 * k) * g.ldWb) = pk;
+            *reinterpret_cast<f32x4 *>(pw + (long)(8 * k) * g.ldw) = w0;
+            *reinterpret_cast<f32x4 *>(pw + (long)(8 * k) * g.ldw + 4) = w1;
+            *reinterpret_cast<u32x4 *>(pb + (long)(8 * k) * g.ldWb) = pk;
           }
         }
         return;
@@ -944,13 +869,12 @@ __global__ __launch_bounds__(512) void update3_kernel(Update2Args g) {
         const bool in0 = j < g.J && i < g.I, in1 = j < g.J && i + 4 < g.I;
         if (!in0) w0 = make_float4(0.f, 0.f, 0.f, 0.f);
         if (!in1) w1 = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (in0 && !(DBG & 36)) *reinterpret_cast<float4 *>(pw + (long)(8 * k) * g.ldw) = w0;
-        if (in1 && !(DBG & 36)) *reinterpret_cast<float4 *>(pw + (long)(8 * k) * g.ldw + 4) = w1;
+        if (in0) *reinterpret_cast<float4 *>(pw + (long)(8 * k) * g.ldw) = w0;
+        if (in1) *reinterpret_cast<float4 *>(pw + (long)(8 * k) * g.ldw + 4) = w1;
         uint4 pk;
         pk.x = pack2_bf16(w0.x, w0.y); pk.y = pack2_bf16(w0.z, w0.w);
         pk.z = pack2_bf16(w1.x, w1.y); pk.w = pack2_bf16(w1.z, w1.w);
-        if (j < g.J && i < g.ldWb && (!(DBG & 20) || pk.x == 0x12345u))
-          *reinterpret_cast<uint4 *>(pb + (long)(8 * k) * g.ldWb) = pk;
+        if (j < g.J && i < g.ldWb) *reinterpret_cast<uint4 *>(pb + (long)(8 * k) * g.ldWb) = pk;
       }
     }
   };
@@ -985,23 +909,7 @@ __global__ __launch_bounds__(512) void update3_kernel(Update2Args g) {
 
 namespace {
 
-struct Tile2 { int fm, fn, ns; };
-const Tile2 kTiles2[] = {{4, 2, 3}, {2, 2, 4}, {2, 2, 2}, {4, 4, 2}, {2, 4, 3}};
-constexpr int kNumTiles2 = 5;
-
-template <int FM, int FN, int NS, int DBG = 0>
-hipError_t launch2(Gemm2Args g, hipStream_t s) {
-  constexpr int lds = NS * (64 * FM + 64 * FN) * 128;
-  const int nt = g.tiles_i * g.tiles_j * g.splits;
-  const int grid = ((nt + 7) / 8) * 8;
-  static LdsOnce attr_done;
-  hipError_t e = allow_lds(gemm2_kernel<FM, FN, NS, DBG>, lds, &attr_done);
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((gemm2_kernel<FM, FN, NS, DBG>), dim3(grid), dim3(256), lds, s, g);
-  return hipGetLastError();
-}
-
-template <int FM, int FN, int NS, int DBG = 0>
+template <int FM, int FN, int NS>
 hipError_t launch_upd2(Update2Args g, hipStream_t s) {
   constexpr int TI = 64 * FM, TJ = 64 * FN;
   constexpr int stage = NS * (TI + TJ) * 128, st = TJ * (TI * 2 + 16);
@@ -1012,100 +920,42 @@ hipError_t launch_upd2(Update2Args g, hipStream_t s) {
   const int nt = g.tiles_i * g.tiles_j;
   const int grid = ((nt + 7) / 8) * 8;
   static LdsOnce attr_done;
-  hipError_t e = allow_lds(update2_kernel<FM, FN, NS, DBG>, lds, &attr_done);
+  hipError_t e = allow_lds(update2_kernel<FM, FN, NS>, lds, &attr_done);
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL((update2_kernel<FM, FN, NS, DBG>), dim3(grid), dim3(256), lds, s, g);
+  hipLaunchKernelGGL((update2_kernel<FM, FN, NS>), dim3(grid), dim3(256), lds, s, g);
+  return hipGetLastError();
+}
+
+hipError_t launch_upd3(Update2Args g, hipStream_t s) {
+  constexpr int lds = 3 * 256 * 128 + 128 * 128 * 4;   // 160 KB
+  g.tiles_i = (g.I + 127) / 128;
+  g.tiles_j = (g.J + 127) / 128;
+  static LdsOnce attr_done;
+  hipError_t e = allow_lds(update3_kernel, lds, &attr_done);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(update3_kernel, dim3(256), dim3(512), lds, s, g);
   return hipGetLastError();
 }
 
 }  // namespace
 
-// Picks tile and split count for an (I x J x K) product.  Measured on MI355X at
-// 5120 x 512 x 4096: 128 x 128 tiles, 4 stages, no split 41 us; 256 x 128 tiles
-// with 3 splits 34 us + 7 us for the ordered reduction.  The fixed cost of a
-// workgroup (launch, 64 barriers, epilogue) is of the order of the contraction
-// itself at this size, so splitting buys nothing: one split unless asked.
-void plan_gemm2(int I, int J, int K, int max_splits, int *tile, int *splits) {
-  (void)I; (void)J;
-  int best = 1, best_sp = 1;
-  const int kslabs = K / 64;
-  const char *env = getenv("CODENET_GEMM2");    // "tile,splits" override for tuning runs
-  if (env && env[0] >= '0' && env[0] < '0' + kNumTiles2) {
-    best = env[0] - '0';
-    if (env[1] == ',' && atoi(env + 2) > 0) best_sp = atoi(env + 2);
-    if (best_sp > kslabs) best_sp = kslabs;
-    if (best_sp > max_splits) best_sp = max_splits;
-  }
-  *tile = best;
-  *splits = best_sp;
-}
-
-// C = A B^T.  With g.splits > 1 the partial results go to `workspace`
-// (splits x J x ldc floats) and are then added into g.C in split order.
-hipError_t launch_gemm2(Gemm2Args g, int tile, float *workspace, hipStream_t s) {
-  if ((g.K & 63) || (g.lda & 7) || (g.ldb & 7) || (g.ldc & 3) || (g.I & 3) || g.splits < 1 || g.I < 1 || g.J < 1)
+// C = A B^T for bf16 operands (k contiguous and zero padded to a multiple of 64, or A stored
+// k-major), fp32 result.
+hipError_t launch_product(Gemm2Args g, hipStream_t s) {
+  if ((g.K & 63) || (g.lda & 7) || (g.ldb & 7) || (g.ldc & 3) || (g.I & 3) || g.I < 1 || g.J < 1)
     return hipErrorInvalidValue;
-  // only product_kernel reads a k-major A: the tuning switches below do not apply to such a product
-  if (g.a_k_major) { tile = 1; g.splits = 1; }
-  const int ti = 64 * kTiles2[tile].fm, tj = 64 * kTiles2[tile].fn;
-  g.tiles_i = (g.I + ti - 1) / ti;
-  g.tiles_j = (g.J + tj - 1) / tj;
-  float *final_out = g.C;
-  g.split_stride = 0;
-  if (g.splits > 1) {
-    if (workspace == nullptr) return hipErrorInvalidValue;
-    g.split_stride = (long)g.J * g.ldc;
-    g.C = workspace;
-  }
-  hipError_t e;
-  {
-    // CODENET_GEMM3=0: the generic kernel below also for this tile, for comparison
-    const char *env3 = getenv("CODENET_GEMM3");
-    if (g.a_k_major || (tile == 1 && g.splits == 1 && !(env3 && env3[0] == '0'))) {
-      constexpr int lds = 5 * (96 + 128) * 128;
-      static LdsOnce attr_done;
-      static LdsOnce attr_t_done;
-      e = g.a_k_major ? allow_lds(product_kernel<true>, lds, &attr_t_done) : allow_lds(product_kernel<false>, lds, &attr_done);
-      if (e != hipSuccess) return e;
-      g.tiles_i = (g.I + 95) / 96;
-      g.tiles_j = (g.J + 127) / 128;
-      const int total = g.tiles_i * g.tiles_j;
-      const dim3 grid((unsigned)(((total + 7) / 8) * 8));
-      if (g.a_k_major) hipLaunchKernelGGL(product_kernel<true>, grid, dim3(512), lds, s, g);
-      else hipLaunchKernelGGL(product_kernel<false>, grid, dim3(512), lds, s, g);
-      return hipGetLastError();
-    }
-  }
-#ifdef CODENET_ABLATION
-  const char *dbg_env = getenv("CODENET_GEMM2_DBG");
-  const int dbg = dbg_env ? atoi(dbg_env) : 0;
-  if (dbg && tile <= 1) {
-    switch (tile * 8 + dbg) {
-      case 1: return launch2<4, 2, 3, 1>(g, s);
-      case 2: return launch2<4, 2, 3, 2>(g, s);
-      case 3: return launch2<4, 2, 3, 3>(g, s);
-      case 4: return launch2<4, 2, 3, 4>(g, s);
-      case 6: return launch2<4, 2, 3, 6>(g, s);
-      case 7: return launch2<4, 2, 3, 7>(g, s);
-      case 9: return launch2<2, 2, 4, 1>(g, s);
-      case 10: return launch2<2, 2, 4, 2>(g, s);
-      case 11: return launch2<2, 2, 4, 3>(g, s);
-      case 12: return launch2<2, 2, 4, 4>(g, s);
-      case 14: return launch2<2, 2, 4, 6>(g, s);
-      case 15: return launch2<2, 2, 4, 7>(g, s);
-      default: break;
-    }
-  }
-#endif
-  switch (tile) {
-    case 0: e = launch2<4, 2, 3>(g, s); break;
-    case 1: e = launch2<2, 2, 4>(g, s); break;
-    case 2: e = launch2<2, 2, 2>(g, s); break;
-    case 3: e = launch2<4, 4, 2>(g, s); break;
-    default: e = launch2<2, 4, 3>(g, s); break;
-  }
-  if (e != hipSuccess || g.splits == 1) return e;
-  return launch_reduce_partials(workspace, g.split_stride, g.splits, final_out, g.split_stride, s);
+  constexpr int lds = 5 * (96 + 128) * 128;
+  static LdsOnce attr_done;
+  static LdsOnce attr_t_done;
+  hipError_t e = g.a_k_major ? allow_lds(product_kernel<true>, lds, &attr_t_done) : allow_lds(product_kernel<false>, lds, &attr_done);
+  if (e != hipSuccess) return e;
+  g.tiles_i = (g.I + 95) / 96;
+  g.tiles_j = (g.J + 127) / 128;
+  const int total = g.tiles_i * g.tiles_j;
+  const dim3 grid((unsigned)(((total + 7) / 8) * 8));
+  if (g.a_k_major) hipLaunchKernelGGL(product_kernel<true>, grid, dim3(512), lds, s, g);
+  else hipLaunchKernelGGL(product_kernel<false>, grid, dim3(512), lds, s, g);
+  return hipGetLastError();
 }
 
 hipError_t launch_reduce_partials(const float *part, long stride, int splits, float *out, long count, hipStream_t s) {
@@ -1116,60 +966,12 @@ hipError_t launch_reduce_partials(const float *part, long stride, int splits, fl
   return hipGetLastError();
 }
 
-template <int DBG = 0>
-hipError_t launch_upd3(Update2Args g, hipStream_t s) {
-  constexpr int lds = 3 * 256 * 128 + 128 * 128 * 4;   // 160 KB
-  g.tiles_i = (g.I + 127) / 128;
-  g.tiles_j = (g.J + 127) / 128;
-  static LdsOnce attr_done;
-  hipError_t e = allow_lds(update3_kernel<DBG>, lds, &attr_done);
-  if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(update3_kernel<DBG>, dim3(256), dim3(512), lds, s, g);
-  return hipGetLastError();
-}
-
-hipError_t launch_update3(Update2Args g, hipStream_t s) {
-#ifdef CODENET_ABLATION
-  const char *denv = getenv("CODENET_UPD3_DBG");
-  switch (denv ? atoi(denv) : 0) {
-    case 1: return launch_upd3<1>(g, s);
-    case 2: return launch_upd3<2>(g, s);
-    case 3: return launch_upd3<3>(g, s);
-    case 4: return launch_upd3<4>(g, s);
-    case 6: return launch_upd3<6>(g, s);
-    case 16: return launch_upd3<16>(g, s);
-    case 32: return launch_upd3<32>(g, s);
-    case 128: return launch_upd3<128>(g, s);
-    case 256: return launch_upd3<256>(g, s);
-    case 512: return launch_upd3<512>(g, s);
-    default: break;
-  }
-#endif
-  return launch_upd3<0>(g, s);
-}
-
+// The coded update: the persistent kernel for batches of 256 and more (its slab pipeline needs at
+// least four slabs per tile), one tile per workgroup below.
 hipError_t launch_update2(Update2Args g, hipStream_t s) {
   if ((g.K & 63) || (g.ldx & 7) || (g.ldd & 7) || (g.ldWb & 63) || g.I < 1 || g.J < 1)
     return hipErrorInvalidValue;
-  const char *env3 = getenv("CODENET_UPD3");
-  if (g.K >= 256 && (g.I & 3) == 0 && (g.J & 3) == 0 && !(env3 && env3[0] == '0')) return launch_update3(g, s);
-  const char *env = getenv("CODENET_UPD2");
-  const int which = env ? atoi(env) : 0;
-  if (which == 1) return launch_upd2<2, 2, 2>(g, s);
-#ifdef CODENET_ABLATION
-  const char *denv = getenv("CODENET_UPD2_DBG");
-  switch (denv ? atoi(denv) : 0) {
-    case 1: return launch_upd2<4, 2, 2, 1>(g, s);
-    case 2: return launch_upd2<4, 2, 2, 2>(g, s);
-    case 3: return launch_upd2<4, 2, 2, 3>(g, s);
-    case 4: return launch_upd2<4, 2, 2, 4>(g, s);
-    case 7: return launch_upd2<4, 2, 2, 7>(g, s);
-    case 8: return launch_upd2<4, 2, 2, 8>(g, s);
-    case 12: return launch_upd2<4, 2, 2, 12>(g, s);
-    case 15: return launch_upd2<4, 2, 2, 15>(g, s);
-    default: break;
-  }
-#endif
+  if (g.K >= 256 && (g.I & 3) == 0 && (g.J & 3) == 0) return launch_upd3(g, s);
   return launch_upd2<4, 2, 2>(g, s);
 }
 

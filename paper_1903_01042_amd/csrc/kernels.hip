@@ -279,20 +279,14 @@ hipError_t launch_encode_vector_bf16(const float *V, const DevCode *code_dev, co
                                      int b, void *Vb, long ldVb, void *VTb, long ldVT, hipStream_t s) {
   const int Rpad = (b + 63) & ~63;
   const int aligned = (code_host.N % 4 == 0) && (code_host.B0 % 4 == 0) && ((reinterpret_cast<uintptr_t>(V) & 15) == 0);
-  // tile width in positions (CODENET_ENCODE_TP: 16, 32 or 64, for tuning runs)
-  const char *env = getenv("CODENET_ENCODE_TP");
-  const int tp = env ? atoi(env) : 32;
-#define CODENET_ENCODE(AL, TPV)                                                                                       \
-  hipLaunchKernelGGL((encode_vector_bf16_kernel<AL, TPV>),                                                             \
-                     dim3((unsigned)((code_host.B + TPV - 1) / TPV), (unsigned)(Rpad / 64),                            \
-                          (unsigned)(code_host.a + code_host.r)),                                                      \
-                     dim3(256), 0, s, V, code_dev, b, (__bf16 *)Vb, ldVb, (__bf16 *)VTb, ldVT, Rpad, geometry_of(code_host))
-  if (aligned) {
-    if (tp == 16) CODENET_ENCODE(true, 16); else if (tp == 64) CODENET_ENCODE(true, 64); else CODENET_ENCODE(true, 32);
-  } else {
-    if (tp == 16) CODENET_ENCODE(false, 16); else if (tp == 64) CODENET_ENCODE(false, 64); else CODENET_ENCODE(false, 32);
-  }
-#undef CODENET_ENCODE
+  // 64 x 32 tiles (see the kernel's comment for the other widths measured)
+  const dim3 grid((unsigned)((code_host.B + 31) / 32), (unsigned)(Rpad / 64), (unsigned)(code_host.a + code_host.r));
+  if (aligned)
+    hipLaunchKernelGGL((encode_vector_bf16_kernel<true, 32>), grid, dim3(256), 0, s, V, code_dev, b, (__bf16 *)Vb, ldVb,
+                       (__bf16 *)VTb, ldVT, Rpad, geometry_of(code_host));
+  else
+    hipLaunchKernelGGL((encode_vector_bf16_kernel<false, 32>), grid, dim3(256), 0, s, V, code_dev, b, (__bf16 *)Vb, ldVb,
+                       (__bf16 *)VTb, ldVT, Rpad, geometry_of(code_host));
   return hipGetLastError();
 }
 
@@ -960,7 +954,7 @@ __global__ __launch_bounds__(256) void regen_kernel(RegenArgs g, const DevCode *
                                                     const codenet_report *__restrict__ report) {
   __shared__ float coef[CODENET_MAX_L];
   __shared__ int src_blk[CODENET_MAX_L];
-  __shared__ int s_target, s_n_src;
+  __shared__ int s_target, s_n_src;      // s_n_src < 0: the located blocks cannot be rebuilt (singular system)
   const int t = threadIdx.x;
   const int slot = blockIdx.z;
   if (report->verdict != CODENET_CORRECTED || slot >= report->n_located) return;
@@ -1001,10 +995,14 @@ __global__ __launch_bounds__(256) void regen_kernel(RegenArgs g, const DevCode *
         M[x][y] = code->H[Q[x]][As[y]];
         M[x][ks + y] = x == y ? 1.0 : 0.0;
       }
-    for (int c = 0; c < ks; ++c) {
+    bool singular = false;
+    for (int c = 0; c < ks && !singular; ++c) {
       int piv = c;
       for (int x = c + 1; x < ks; ++x)
         if (fabs(M[x][c]) > fabs(M[piv][c])) piv = x;
+      // a generator that passed the MDS check has no vanishing pivot here; one that was only
+      // sampled might: nothing is rebuilt then (the matrix stays as it is, the next check reports it)
+      if (!(fabs(M[piv][c]) > 1e-12)) { singular = true; break; }
       for (int y = 0; y < 2 * ks; ++y) { const double tmp = M[c][y]; M[c][y] = M[piv][y]; M[piv][y] = tmp; }
       const double inv = 1.0 / M[c][c];
       for (int y = 0; y < 2 * ks; ++y) M[c][y] *= inv;
@@ -1041,10 +1039,11 @@ __global__ __launch_bounds__(256) void regen_kernel(RegenArgs g, const DevCode *
     int n = 0;
     for (int i = 0; i < L; ++i)
       if (coef[i] != 0.f) src_blk[n++] = i;
-    s_n_src = n;
+    s_n_src = singular ? -1 : n;
   }
   __syncthreads();
   const int target = s_target, n_src = s_n_src;
+  if (n_src < 0) return;
   const int B = code->B;
   // tile (r0, c0) of the located block; along the code's axis the block offset is target * B
   constexpr int P = TR / 16;
@@ -1116,13 +1115,9 @@ hipError_t launch_regen(RegenArgs g, const DevCode *code_dev, const DevCode &ch,
   const int tcap = ch.r / 2 < CODENET_MAX_T ? ch.r / 2 : CODENET_MAX_T;
   if (tcap < 1) return hipSuccess;
   const int rows = g.axis == 0 ? ch.B : g.Mr, cols = g.axis == 0 ? g.Nc : ch.B;
-  // tile height (CODENET_REGEN_TR: 16, 32 or 64, for tuning runs)
-  const char *env = getenv("CODENET_REGEN_TR");
-  const int tr = env ? atoi(env) : 32;      // 20.3 us at cfg3 against 20.9 (64) and 21.2 (16)
-  const unsigned gx = (unsigned)((cols + 63) / 64);
-  if (tr == 16) hipLaunchKernelGGL(regen_kernel<16>, dim3(gx, (unsigned)((rows + 15) / 16), (unsigned)tcap), dim3(256), 0, s, g, code_dev, report);
-  else if (tr == 32) hipLaunchKernelGGL(regen_kernel<32>, dim3(gx, (unsigned)((rows + 31) / 32), (unsigned)tcap), dim3(256), 0, s, g, code_dev, report);
-  else hipLaunchKernelGGL(regen_kernel<64>, dim3(gx, (unsigned)((rows + 63) / 64), (unsigned)tcap), dim3(256), 0, s, g, code_dev, report);
+  // 32 x 64 tiles: 20.3 us at 5120 x 5120 against 20.9 (64 rows) and 21.2 (16 rows)
+  hipLaunchKernelGGL(regen_kernel<32>, dim3((unsigned)((cols + 63) / 64), (unsigned)((rows + 31) / 32), (unsigned)tcap), dim3(256), 0, s,
+                     g, code_dev, report);
   return hipGetLastError();
 }
 

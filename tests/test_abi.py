@@ -11,6 +11,11 @@ from paper_1903_01042_amd import binding as B
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
+def _has_gpu():
+    import torch
+    return torch.cuda.is_available()
+
+
 def _declared():
     text = open(os.path.join(ROOT, "include", "codenet.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
@@ -66,6 +71,25 @@ def test_argument_errors_without_a_gpu(lib):
     # rows 0 and 1 of P are equal: a zero 2x2 minor, not MDS
     P = (ctypes.c_double * 6)(1.0, 2.0, 1.0, 2.0, 1.0, 3.0)
     d = B.Desc(9, 9, 3, 3, 2, 2, P, P, B.F32, 4, 1e-3, 1e-2)
+    assert lib.codenet_encode(ctypes.byref(d), fake, None, ctypes.byref(h)) == B.E_CODE
+    # the MDS test is relative to the scale of the generator (Hadamard's bound on each minor): a tiny
+    # but well conditioned P is accepted (the call then goes on to the GPU, which answers differently
+    # with and without one -- anything but E_CODE), a huge one with nearly dependent rows is refused
+    good = [1.0, 1.0, 1.0, 2.0, 1.0, 3.0]
+    tiny = (ctypes.c_double * 6)(*[1e-6 * v for v in good])
+    d = B.Desc(9, 9, 3, 3, 2, 2, tiny, tiny, B.F32, 4, 1e-3, 2e-3)
+    if not _has_gpu():
+        assert lib.codenet_encode(ctypes.byref(d), fake, None, ctypes.byref(h)) != B.E_CODE
+    huge = (ctypes.c_double * 6)(1e6, 2e6, 1e6, 2e6 * (1 + 1e-12), 1e6, 3e6)
+    d = B.Desc(9, 9, 3, 3, 2, 2, huge, huge, B.F32, 4, 1e-3, 2e-3)
+    assert lib.codenet_encode(ctypes.byref(d), fake, None, ctypes.byref(h)) == B.E_CODE
+    # a code too long to enumerate (C(32, k) C(8, k) minors per order) is checked by sampling: a
+    # generator with two equal rows is still refused (every order k >= 2 has minors on those rows)
+    rng = __import__("numpy").random.default_rng(1)
+    big = rng.standard_normal((32, 8))
+    big[7] = big[19]
+    arr = (ctypes.c_double * 256)(*big.reshape(-1))
+    d = B.Desc(64, 64, 32, 32, 8, 8, arr, arr, B.F32, 4, 1e-3, 2e-3)
     assert lib.codenet_encode(ctypes.byref(d), fake, None, ctypes.byref(h)) == B.E_CODE
     assert lib.codenet_forward(None, None, 1, None, None) == B.E_NULL
     assert lib.codenet_update(None, 0.1, None) == B.E_NULL

@@ -457,30 +457,24 @@ def test_ragged_shapes(n_out, n_in, m, n, r, b, dtype):
     pair.close()
 
 
-# ------------------------------------------------------------- the library's other bf16 kernels
-@pytest.mark.parametrize("env", [
-    {"CODENET_GEMM3": "0"},                            # generic product kernel (four wavefronts, mixed roles)
-    {"CODENET_GEMM3": "0", "CODENET_GEMM2": "1,4"},    # the same with split-k and the ordered reduction
-    {"CODENET_UPD3": "0"},                             # one-tile-per-workgroup update kernel at batch >= 256
-])
-def test_alternative_bf16_kernels_agree_with_the_oracle(env, monkeypatch):
-    """The product and update kernels that the launchers fall back to (or that tuning switches select)
-    go through the same parity bar as the default ones.  The switches are read at every launch."""
-    say("alternative kernels", env)
-    for k, v in env.items():
-        monkeypatch.setenv(k, v)
-    n_out, n_in, m, n, r, b = 700, 452, 3, 7, 2, 512
+# ------------------------------------------------------------- both bf16 update kernels
+@pytest.mark.parametrize("b", [64, 192, 255, 256, 320])
+def test_bf16_update_kernels_on_either_side_of_their_batch_boundary(b):
+    """The coded update of the bf16 mode has two kernels: one tile per workgroup below a batch of
+    256 (padded: 192 and 255 contract over 192 and 256 columns), the persistent one from 256 on.
+    The same ragged layer through both, two steps each."""
+    say("update kernels, batch", b)
+    n_out, n_in, m, n, r = 700, 452, 3, 7, 2
     pair = Pair(WL.layer_weights(n_out, n_in), WL.vandermonde_like(m, r), WL.vandermonde_like(n, r), "bf16", b,
                 2e-2, 2e-2)
-    X, D = WL.normal((b, n_in), 21), WL.normal((b, n_out), 22)
-    _, rep, _ = pair.product(FWD, X, [WL.make_fault(FWD, 1, 0, 1)])
-    assert rep["verdict"] == CORRECTED and rep["located"] == [1]
-    _, rep, _ = pair.product(BWD, D, [WL.make_fault(BWD, 0, n, 1)])
-    assert rep["verdict"] == CORRECTED and rep["located"] == [n]
-    pair.update(0.02)
-    pair.check_weights()
-    pair.product(FWD, X)
-    pair.product(BWD, D)
+    for step in range(2):
+        X, D = WL.normal((b, n_in), 21 + step), WL.normal((b, n_out), 31 + step)
+        _, rep, _ = pair.product(FWD, X, [WL.make_fault(FWD, 1, 0, step)])
+        assert rep["verdict"] == CORRECTED and rep["located"] == [1]
+        _, rep, _ = pair.product(BWD, D, [WL.make_fault(BWD, 0, n, step)])
+        assert rep["verdict"] == CORRECTED and rep["located"] == [n]
+        pair.update(0.02)
+        pair.check_weights()
     pair.close()
 
 
