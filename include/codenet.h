@@ -164,6 +164,21 @@ int codenet_inject(codenet_layer *layer, const codenet_fault *faults_host, int n
                    float *coded_out_dev, int b, void *stream);
 
 /*
+ * codenet_inject for callers that cannot allocate device memory or have the library use memory
+ * it allocated earlier for its intermediate results: code under HIP graph capture, serving loops
+ * and harnesses that forbid hipMalloc.  Same arguments, same results, bit for bit.  The partial
+ * sums that the noise scale is taken from (128 per fault) live in a fixed array inside the
+ * library's device code instead of in the layer: 64 KB per GPU, held until the process ends, enough
+ * for CODENET_MAX_FAULTS faults -- more faults than that are refused with CODENET_E_SHAPE, as by
+ * codenet_inject.  The call allocates and frees nothing, on the host or on the device.  All layers
+ * on one GPU share the array: calls of this function that overlap in time on one GPU race (calls
+ * on one stream are ordered and safe); nothing has to be cleared between calls, every call
+ * writes the sums it reads.
+ */
+int codenet_inject_noalloc(codenet_layer *layer, const codenet_fault *faults_host, int n_faults,
+                           float *coded_out_dev, int b, void *stream);
+
+/*
  * Error detection and decoding (General Error-Detection Method; Lemma 2 and
  * the decoding algorithm of the appendix): syndromes (H (x) I) out with
  * H = [P^T | -I]; clean iff all relative syndrome norms <= tau_detect;

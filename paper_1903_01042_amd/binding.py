@@ -22,7 +22,7 @@ EPI_NONE, EPI_RELU, EPI_MASK_POS, EPI_MUL = 0, 1, 2, 3
 E_NULL, E_SHAPE, E_BATCH, E_ORDER, E_CODE, E_FAULT, E_HIP, E_DTYPE, E_ALLOC = range(-1, -10, -1)
 
 EXPORTS = ["codenet_encode", "codenet_layer_geometry", "codenet_forward", "codenet_backward",
-           "codenet_inject", "codenet_detect_decode", "codenet_detect_decode_act",
+           "codenet_inject", "codenet_inject_noalloc", "codenet_detect_decode", "codenet_detect_decode_act",
            "codenet_detect_decode_verified", "codenet_update", "codenet_regenerate", "codenet_export_coded",
            "codenet_export_weights", "codenet_destroy", "codenet_timestamp", "codenet_strerror"]
 
@@ -70,6 +70,7 @@ def load_library(path=LIB_PATH):
     lib.codenet_forward.argtypes = [vp, vp, ci, vp, vp]
     lib.codenet_backward.argtypes = [vp, vp, ci, vp, vp]
     lib.codenet_inject.argtypes = [vp, ctypes.POINTER(Fault), ci, vp, ci, vp]
+    lib.codenet_inject_noalloc.argtypes = [vp, ctypes.POINTER(Fault), ci, vp, ci, vp]
     lib.codenet_detect_decode.argtypes = [vp, ci, vp, ci, vp, vp, vp]
     lib.codenet_detect_decode_act.argtypes = [vp, ci, vp, ci, vp, vp, ci, vp, vp]
     lib.codenet_detect_decode_verified.argtypes = [vp, ci, vp, ci, vp, vp, ci, vp, vp]
@@ -183,7 +184,9 @@ class CodedLayer:
         _check(load_library().codenet_backward(self._h, _ptr(D), b, _ptr(C_coded), _stream()), "codenet_backward")
         return C_coded
 
-    def inject(self, faults, coded_out=None):
+    def inject(self, faults, coded_out=None, noalloc=False):
+        """noalloc: through codenet_inject_noalloc (the library's fixed scratch array instead of the
+        layer's buffer)."""
         if not faults:
             return
         phase = int(faults[0]["phase"])
@@ -195,6 +198,10 @@ class CodedLayer:
             b = int(coded_out.shape[0])
             _dev_f32(coded_out, (b, width), "coded_out")
         arr = pack_faults(faults)
+        if noalloc:
+            _check(load_library().codenet_inject_noalloc(self._h, arr, len(faults), _ptr(coded_out), b, _stream()),
+                   "codenet_inject_noalloc")
+            return
         _check(load_library().codenet_inject(self._h, arr, len(faults), _ptr(coded_out), b, _stream()),
                "codenet_inject")
 

@@ -189,6 +189,12 @@ void free_layer(codenet_layer *l) {
 
 }  // namespace
 
+// Scratch of codenet_inject_noalloc: the partial sums of squares of up to CODENET_MAX_FAULTS faults
+// (kFaultParts doubles each, 64 KB).  Every GPU holds its own copy of the array at its own address
+// for the life of the process; that address is looked up once per device (scratch_address below)
+// and is what host code passes around -- the array's name is only a handle on the host side.
+static __device__ __align__(256) double scratch[CODENET_MAX_FAULTS * kFaultParts];
+
 extern "C" {
 
 const char *codenet_strerror(int code) {
@@ -465,8 +471,30 @@ int check_call(codenet_layer *l, int phase, float *coded_out_dev, int b, float *
 }
 }  // namespace
 
-int codenet_inject(codenet_layer *l, const codenet_fault *faults, int n_faults, float *coded_out_dev, int b,
-                   void *stream) {
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::atomic<double *> scratch_of_device[kMaxDevices];
+
+// Device address of `scratch` on the current device; the first call on a device asks the runtime.
+int scratch_address(double **out) {
+  int dev = 0;
+  CN_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return CODENET_E_HIP;
+  double *p = scratch_of_device[dev].load(std::memory_order_acquire);
+  if (p == nullptr) {
+    CN_HIP(hipGetSymbolAddress(reinterpret_cast<void **>(&p), HIP_SYMBOL(scratch)));
+    if (p == nullptr) return CODENET_E_HIP;
+    scratch_of_device[dev].store(p, std::memory_order_release);
+  }
+  *out = p;
+  return CODENET_OK;
+}
+
+// Both injection entry points.  partials: kFaultParts doubles per fault, written by the first pass
+// of every call before the second pass reads them (nothing has to be cleared between calls).
+int inject_faults(codenet_layer *l, const codenet_fault *faults, int n_faults, float *coded_out_dev, int b,
+                  double *partials, void *stream) {
   if (!l) return CODENET_E_NULL;
   if (n_faults == 0) return CODENET_OK;
   if (!faults) return CODENET_E_NULL;
@@ -488,7 +516,7 @@ int codenet_inject(codenet_layer *l, const codenet_fault *faults, int n_faults, 
     if (b < 1 || b > l->desc.max_batch) return CODENET_E_BATCH;
   }
   const DevCode &cr = l->code_r, &cc = l->code_c;
-  std::vector<FaultArgs> fa((size_t)n_faults);
+  FaultArgs fa[CODENET_MAX_FAULTS];
   for (int f = 0; f < n_faults; ++f) {
     const codenet_fault &ft = faults[f];
     if (ft.phase != phase) return CODENET_E_FAULT;
@@ -504,7 +532,7 @@ int codenet_inject(codenet_layer *l, const codenet_fault *faults, int n_faults, 
     a.lo = ft.lo; a.hi = ft.hi; a.mode = ft.mode;
     double hb = std::floor((double)ft.density * 4294967296.0);
     a.hit_below = hb <= 0.0 ? 0u : (hb >= 4294967295.0 ? 4294967295u : (unsigned int)hb);
-    a.partials = l->fault_partials + (size_t)f * kFaultParts;
+    a.partials = partials + (size_t)f * kFaultParts;
     if (phase == CODENET_FWD) {
       a.base = coded_out_dev + (size_t)ft.bi * cr.B;
       a.stride_outer = l->Mr; a.n_outer = b; a.n_inner = real_entries(cr, ft.bi);
@@ -540,6 +568,23 @@ int codenet_inject(codenet_layer *l, const codenet_fault *faults, int n_faults, 
   if (phase == CODENET_WEIGHT && l->bf16)
     CN_HIP(launch_shadow(l->Wt, l->Mr, l->Nc, l->Wb, l->ldWb, s));
   return CODENET_OK;
+}
+
+}  // namespace
+
+int codenet_inject(codenet_layer *l, const codenet_fault *faults, int n_faults, float *coded_out_dev, int b,
+                   void *stream) {
+  if (!l) return CODENET_E_NULL;
+  return inject_faults(l, faults, n_faults, coded_out_dev, b, l->fault_partials, stream);
+}
+
+int codenet_inject_noalloc(codenet_layer *l, const codenet_fault *faults, int n_faults, float *coded_out_dev, int b,
+                           void *stream) {
+  if (!l) return CODENET_E_NULL;
+  double *partials = nullptr;
+  const int rc = scratch_address(&partials);
+  if (rc != CODENET_OK) return rc;
+  return inject_faults(l, faults, n_faults, coded_out_dev, b, partials, stream);
 }
 
 int codenet_regenerate(codenet_layer *l, int phase, const codenet_report *report_dev, void *stream) {
