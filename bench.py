@@ -7,6 +7,12 @@ fault injection, check + decode, coded update.  Inputs are resident in HBM
 before the timed region.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg3]
+
+Single-layer workloads (cfg1, cfg3, cfg5) time that layer's step.  The MLP workloads (cfg2:
+784-1024-1024-10; cfg4: 8 layers of width 8192) time whole training iterations -- feedforward
+through all layers with the activation fused into each check, loss head, backpropagation with
+g(x) (.) c fused into each check, update of every layer -- and report layer-steps per second
+(iterations x layers).  `--workload cfg4 --layers 1` is one layer of that network.
 """
 import argparse
 import ctypes
@@ -23,6 +29,8 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
+SAMPLED_STEPS = 8          # timed steps on which a kernel is bracketed, whatever --steps is
+PREWARM_SECONDS = 0.3      # untimed steps before the warm-up: the chip reaches its steady clocks
 
 
 def parse():
@@ -30,16 +38,24 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=1000)
     ap.add_argument("--warmup", type=int, default=50)
-    ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg3", "cfg4", "cfg5"],
-                    help="cfg4: one layer (the first) of that 8-layer workload")
-    ap.add_argument("--cpu-steps", type=int, default=40, help="oracle layer-steps timed for cpu_baseline (0 = skip)")
+    ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--layers", type=int, default=0, help="MLP workloads: only the first LAYERS layers (0 = all)")
+    ap.add_argument("--cpu-steps", type=int, default=-1,
+                    help="oracle layer-steps timed for cpu_baseline (0 = skip, -1 = sized to the workload)")
     ap.add_argument("--no-faults", action="store_true", help="run the coded path without injecting faults")
     ap.add_argument("--coded-only", action="store_true", help="skip the uncoded baseline and the CPU oracle (profiling runs)")
+    ap.add_argument("--no-prewarm", action="store_true", help="skip the untimed steps that precede the warm-up")
     ap.add_argument("--graph", action="store_true",
-                    help="replay one hipGraph per step instead of launching every call from Python (a kernel node of a "
-                         "graph takes about 3 us longer than the same kernel launched into the stream; the step is not "
-                         "launch bound, so the default is the plain stream)")
+                    help="single-layer workloads: replay one hipGraph per step instead of launching every call from "
+                         "Python (a kernel node of a graph takes about 3 us longer than the same kernel launched into "
+                         "the stream; the step is not launch bound, so the default is the plain stream)")
     return ap.parse_args()
+
+
+def sampled(steps, warmup, count=SAMPLED_STEPS, phase=0.5):
+    """`count` step indices spread evenly over the timed region [warmup, warmup + steps)."""
+    count = min(count, steps)
+    return sorted({warmup + min(steps - 1, int((k + phase) * steps / count)) for k in range(count)})
 
 
 class Runner:
@@ -73,7 +89,8 @@ class Runner:
         self.Ct = torch.empty((self.b, L.coded_cols), dtype=torch.float32, device=dev)
         self.S = torch.empty((self.b, n_out), dtype=torch.float32, device=dev)
         self.C = torch.empty((self.b, n_in), dtype=torch.float32, device=dev)
-        self.reports = torch.zeros((total_steps, 2, B.REPORT_BYTES), dtype=torch.uint8, device=dev)
+        self.reports = torch.zeros((total_steps + 1, 2, B.REPORT_BYTES), dtype=torch.uint8, device=dev)
+        self.total_steps = total_steps
         self.faults = []
         for s in range(total_steps):
             ff = wl.product_faults(WL.PHASE_FWD, s) if (coded and faults_on) else []
@@ -90,10 +107,12 @@ class Runner:
                           upd=2.0 * L.coded_rows * L.coded_cols * self.b)
         self.weight_bytes = 4.0 * L.coded_rows * L.coded_cols
 
-    def pre_update(self, s, stream):
-        """forward, faults, check, backward, faults, check of step s (everything but the update)."""
+    def pre_update(self, s, stream, slot=None):
+        """forward, faults, check, backward, faults, check of step s (everything but the update);
+        the two reports go to row `slot` of self.reports (default: the step's own)."""
         lib, h, b = self.lib, self.h, self.b
         k = s % self.RING
+        slot = s if slot is None else slot
         if self.verified:
             def check(phase, coded_out, decoded, report):
                 return lib.codenet_detect_decode_verified(h, phase, coded_out, b, decoded, report, 0, None, stream)
@@ -102,25 +121,23 @@ class Runner:
                 return lib.codenet_detect_decode(h, phase, coded_out, b, decoded, report, stream)
         rc = lib.codenet_forward(h, self.pX[k], b, self.pSt, stream)
         if self.coded:
-            (ff, nf), (fb, nb) = self.faults[s]
+            (ff, nf), (fb, nb) = self.faults[s % self.total_steps]
             if nf:
                 rc |= lib.codenet_inject(h, ff, nf, self.pSt, b, stream)
-            rc |= check(0, self.pSt, self.pS, ctypes.c_void_p(self.reports[s, 0].data_ptr()))
+            rc |= check(0, self.pSt, self.pS, ctypes.c_void_p(self.reports[slot, 0].data_ptr()))
         rc |= lib.codenet_backward(h, self.pD[k], b, self.pCt, stream)
         if self.coded:
             if nb:
                 rc |= lib.codenet_inject(h, fb, nb, self.pCt, b, stream)
-            rc |= check(1, self.pCt, self.pC, ctypes.c_void_p(self.reports[s, 1].data_ptr()))
+            rc |= check(1, self.pCt, self.pC, ctypes.c_void_p(self.reports[slot, 1].data_ptr()))
         if rc:
             raise RuntimeError("a codenet call failed in step %d (rc=%d)" % (s, rc))
 
-    STAMP_EVERY = 4     # steps whose update kernel is bracketed by two device time stamps
+    STAMP_EVERY = 4     # graph replay: steps whose update kernel is bracketed by two device time stamps
     EVENT_EVERY = 20    # graph replay: steps (s % EVENT_EVERY == 10) whose update is launched on its own between two HIP events
-    EAGER_EVENT_EVERY = 16  # plain stream: steps (s % EAGER_EVENT_EVERY == 2) whose update sits between two HIP events
-                            # (a pair of records costs the stream several us: see roofline.empty_event_pair_ms)
 
     def update(self, s, stream):
-        """The update of step s; on every STAMP_EVERY-th step between two device time stamps."""
+        """Graph replay: the update of step s; on every STAMP_EVERY-th step between two device time stamps."""
         stamped = s % self.STAMP_EVERY == 0
         rc = 0
         if stamped:
@@ -133,8 +150,8 @@ class Runner:
             raise RuntimeError("codenet_update failed (rc=%d)" % rc)
 
     def split(self, s):
-        """Steps whose graph ends before the update: the update kernel is then launched directly,
-        between two HIP events on the same stream (costs about 19 us of launch gaps on that step)."""
+        """Graph replay: steps whose graph ends before the update: the update kernel is then launched
+        directly, between two HIP events on the same stream (costs about 19 us of launch gaps on that step)."""
         return s % self.EVENT_EVERY == 10
 
     def capture(self, total_steps):
@@ -161,18 +178,57 @@ class Runner:
             self.graphs.append(g)
         torch.cuda.synchronize()
 
-    def run(self, steps, warmup, eager):
+    def prewarm(self, stream, seconds):
+        """Untimed steps until `seconds` have passed (reports go to the spare row)."""
+        torch = self.torch
+        t0 = time.perf_counter()
+        done = 0
+        while time.perf_counter() - t0 < seconds:
+            for _ in range(20):
+                self.pre_update(done, stream, slot=self.total_steps)
+                if self.lib.codenet_update(self.h, self.eta, stream):
+                    raise RuntimeError("codenet_update failed")
+                done += 1
+            torch.cuda.synchronize()
+        return done
+
+    def run(self, steps, warmup, eager, prewarm_seconds=0.0):
         torch = self.torch
         stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
         self.stamps = torch.zeros((steps + warmup, 2), dtype=torch.int64, device="cuda:0")
+        self.product_stamps = torch.zeros((steps + warmup, 4), dtype=torch.int64, device="cuda:0")
         self.ticks_per_us = ctypes.c_int(0)
+        self.prewarm_steps = self.prewarm(stream, prewarm_seconds) if (eager and prewarm_seconds > 0) else 0
         if not eager:
             self.capture(steps + warmup)
-
+        # plain stream: the update sits between two HIP events on SAMPLED_STEPS steps of the timed region, between
+        # two device time stamps on as many others, and on a third set the products are stamped
+        # (short runs: fewer of the other two kinds, every bracket costs the step a few microseconds)
+        few = 2 if steps < 64 else SAMPLED_STEPS
+        event_steps = set(sampled(steps, warmup)) if eager else set()
+        rest = [s for s in range(warmup, warmup + steps) if s not in event_steps] if eager else []
+        product_steps = {rest[i] for i in sampled(len(rest), 0, 2 * few)} if rest else set()
+        rest = [s for s in rest if s not in product_steps]
+        stamp_steps = {rest[i] for i in sampled(len(rest), 0, few)} if rest else set()
         events = {}
+        # every event that the timed region records exists and has been recorded once before it, and the
+        # time stamp kernel has run once: first uses cost hundreds of microseconds, a tenth of a 20-step run
+        pool = {s: (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for s in event_steps}
+        for a, b in pool.values():
+            a.record()
+            b.record()
+        self.lib.codenet_profile_stamps(self.h, ctypes.c_void_p(self.product_stamps[0].data_ptr()))
+        self.pre_update(0, stream, slot=self.total_steps)
+        self.lib.codenet_profile_stamps(self.h, None)
+        self.lib.codenet_timestamp(ctypes.c_void_p(self.stamps[0, 0].data_ptr()), stream, ctypes.byref(self.ticks_per_us))
+        if self.lib.codenet_update(self.h, self.eta, stream):
+            raise RuntimeError("codenet_update failed")
+        torch.cuda.synchronize()
+        self.product_stamps.zero_()
+        self.stamps.zero_()
 
         def timed_update(s):
-            ev = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+            ev = pool.get(s) or (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
             ev[0].record()
             rc = self.lib.codenet_update(self.h, self.eta, stream)
             ev[1].record()
@@ -191,10 +247,14 @@ class Runner:
 
         def one(s):
             if eager:
+                if s in product_steps:
+                    self.lib.codenet_profile_stamps(self.h, ctypes.c_void_p(self.product_stamps[s].data_ptr()))
                 self.pre_update(s, stream)
-                if s % self.EAGER_EVENT_EVERY == 2:
+                if s in product_steps:
+                    self.lib.codenet_profile_stamps(self.h, None)
+                if s in event_steps:
                     timed_update(s)
-                elif s % self.EAGER_EVENT_EVERY == 10:
+                elif s in stamp_steps:
                     stamped_update(s)       # a second clock on other steps: the GPU's own, read by two tiny kernels
                 elif self.lib.codenet_update(self.h, self.eta, stream):
                     raise RuntimeError("codenet_update failed")
@@ -219,9 +279,15 @@ class Runner:
         torch.cuda.synchronize()
         t1 = time.perf_counter()
         st = self.stamps[warmup:].cpu().numpy()
-        st = st[st[:, 0] != 0]
-        upd_ms = float(np.mean(st[:, 1] - st[:, 0])) / self.ticks_per_us.value * 1e-3 if len(st) else None
+        st = st[(st[:, 0] != 0) & (st[:, 1] != 0)]
+        tick = self.ticks_per_us.value or 100
+        upd_ms = float(np.mean(st[:, 1] - st[:, 0])) / tick * 1e-3 if len(st) else None
         self.upd_ms_events = float(np.mean([a.elapsed_time(b) for a, b in events.values()])) if events else None
+        self.upd_event_samples = len(events)
+        ps = self.product_stamps[warmup:].cpu().numpy()
+        ps = ps[ps[:, 0] != 0]
+        self.product_ms = (float(np.mean(ps[:, 1] - ps[:, 0])) / tick * 1e-3, float(np.mean(ps[:, 3] - ps[:, 2])) / tick * 1e-3,
+                           len(ps)) if len(ps) else None
         return (t1 - t0) * 1e3 / steps, upd_ms
 
     def update_by_events(self, reps=50):
@@ -277,15 +343,207 @@ class Runner:
                 "what": "one located block-row of the coded matrix rebuilt from the good systematic rows and a parity row"}
 
     def verdict_counts(self, lo, hi):
-        B = self.B
+        return count_verdicts(self.B, self.reports[lo:hi].cpu().numpy().reshape(-1, self.B.REPORT_BYTES))
+
+
+def count_verdicts(B, raw):
+    counts = {"clean": 0, "corrected": 0, "uncorrectable": 0}
+    for row in raw:
+        v = B.Report.from_buffer_copy(row.tobytes()).verdict
+        name = ["clean", "corrected", "uncorrectable", "disagree"][v]   # the last from verified checks only
+        counts[name] = counts.get(name, 0) + 1
+    return counts
+
+
+class MlpRunner:
+    """Whole training iterations of an MLP workload through the library: every activation, error and
+    weight stays on the GPU; the loss head (a few elementwise kernels) is PyTorch's.
+
+    Faults follow the workload's law.  The host knows which nodes it corrupts, hence whether a product
+    is beyond what the code corrects (more than t erroneous blocks; any fault at all with one parity
+    block): such a product is computed again right away, without its faults, as the step's roll-back
+    (transient errors), so nothing corrupted propagates and no verdict has to be read back inside the
+    timed loop.  The verdicts are read after the run and must be the ones the fault lists imply.
+    Update-stage (weight) faults are planted after the update where the workload has them and the code
+    can correct them (one block-row / block-column hit); every check is then followed by the
+    regeneration call, which acts on the device-side report alone."""
+
+    def __init__(self, wl, coded, faults_on, total_iters, n_layers):
+        import torch
+        from paper_1903_01042_amd import binding as B
+        from paper_1903_01042_amd import workloads as WL
+        self.torch, self.B, self.wl, self.WL = torch, B, wl, WL
+        self.lib = B.load_library()
+        dev = torch.device("cuda:0")
+        self.widths = wl.widths[: n_layers + 1]
+        self.Ln = n_layers
+        self.b = b = wl.batch
+        self.coded = coded
+        self.faults_on = coded and faults_on
+        self.t = wl.r // 2
+        m, n = wl.grid
+        self.layers = []
+        for l in range(n_layers):
+            W = torch.from_numpy(WL.layer_weights(self.widths[l + 1], self.widths[l], l)).to(dev)
+            P_r, P_c = wl.generators(l) if coded else (np.zeros((m, 0)), np.zeros((n, 0)))
+            self.layers.append(B.CodedLayer(W, P_r, P_c, dtype=B.F32, max_batch=b, tau_detect=wl.tau_detect,
+                                            tau_resid=wl.tau_resid))
+        f32 = dict(dtype=torch.float32, device=dev)
+        self.X = [torch.from_numpy(wl.inputs(s)[:, : self.widths[0]].copy()).to(dev) for s in range(4)]
+        self.act = [None] + [torch.empty((b, self.widths[l + 1]), **f32) for l in range(n_layers)]
+        self.St = [torch.empty((b, lay.coded_rows), **f32) for lay in self.layers]
+        self.Ct = [torch.empty((b, lay.coded_cols), **f32) for lay in self.layers]
+        self.err = [torch.empty((b, self.widths[l]), **f32) for l in range(n_layers)] + [torch.empty((b, self.widths[-1]), **f32)]
+        classes = self.widths[-1]
+        if wl.name.startswith("cfg2"):
+            labels = [np.random.default_rng(WL.SEED_DELTAS + s).integers(0, classes, size=b) for s in range(4)]
+            self.Y = [torch.nn.functional.one_hot(torch.from_numpy(y), classes).to(**f32) for y in labels]
+            self.head = "softmax cross-entropy on random labels"
+        else:
+            self.Y = [torch.from_numpy(WL.normal((b, classes), WL.SEED_DELTAS + s)).to(dev) for s in range(4)]
+            self.head = "squared error against random targets"
+        self.reports = torch.zeros((total_iters + 1, n_layers, 4, B.REPORT_BYTES), dtype=torch.uint8, device=dev)
+        self.total_iters = total_iters
+        self.eta = ctypes.c_float(wl.eta)
+        self.expected = {"clean": 0, "corrected": 0, "uncorrectable": 0}
+        self.plan = [self._plan(it) for it in range(total_iters)]
+        self.flops = sum(2.0 * self.b * (lay.coded_rows * (n * lay.B_c) + (m * lay.B_r) * lay.coded_cols
+                                         + lay.coded_rows * lay.coded_cols) for lay in self.layers)
+        self.stamps = torch.zeros((total_iters + 1, 4), dtype=torch.int64, device=dev)
+        self.ticks_per_us = ctypes.c_int(0)
+
+    def _plan(self, it):
+        """Marshalled fault lists of iteration `it`: per layer (fwd faults, redo?, bwd faults, redo?, weight faults)."""
+        B, WL, wl = self.B, self.WL, self.wl
+        rows = []
+        for l in range(self.Ln):
+            entry = []
+            for phase in (WL.PHASE_FWD, WL.PHASE_BWD):
+                ff = wl.product_faults(phase, it, l) if self.faults_on else []
+                hit = {f["bi"] if phase == WL.PHASE_FWD else f["bj"] for f in ff}
+                redo = len(hit) > self.t
+                entry += [(B.pack_faults(ff), len(ff)), redo]
+            wf = wl.update_faults(it, l) if self.faults_on else []
+            lines_r, lines_c = {f["bi"] for f in wf}, {f["bj"] for f in wf}
+            # plantable: the next forward product sees one erroneous block-row at most, the next backward one one block-column
+            ok = len(wf) > 0 and len(lines_r) <= self.t and len(lines_c) <= self.t
+            entry.append((B.pack_faults(wf), len(wf)) if ok else (None, 0))
+            rows.append(entry)
+        return rows
+
+    def iteration(self, it, stream, slot=None, stamp=False):
+        lib, B, b = self.lib, self.B, self.b
+        L = self.Ln
+        slot = it if slot is None else slot
+        plan = self.plan[it % self.total_iters]
+        vp = ctypes.c_void_p
+        rc = 0
+        regen = self.faults_on and self.wl.weight_faults
+        x = self.X[it % 4]
+        for l in range(L):
+            lay = self.layers[l]
+            (ff, nf), redo = plan[l][0], plan[l][1]
+            epi = B.EPI_RELU if l < L - 1 else B.EPI_NONE
+            pS, pA = vp(self.St[l].data_ptr()), vp(self.act[l + 1].data_ptr())
+            if stamp and l == 0:
+                rc |= lib.codenet_profile_stamps(lay._h, vp(self.stamps[slot].data_ptr()))
+            rc |= lib.codenet_forward(lay._h, vp(x.data_ptr()), b, pS, stream)
+            if self.coded:
+                if nf:
+                    rc |= lib.codenet_inject(lay._h, ff, nf, pS, b, stream)
+                rc |= lib.codenet_detect_decode_act(lay._h, 0, pS, b, pA, vp(self.reports[slot, l, 0].data_ptr()), epi, None, stream)
+                if redo:        # beyond the code's capability: the product again, without the transient faults
+                    rc |= lib.codenet_forward(lay._h, vp(x.data_ptr()), b, pS, stream)
+                    rc |= lib.codenet_detect_decode_act(lay._h, 0, pS, b, pA, vp(self.reports[slot, l, 1].data_ptr()), epi, None, stream)
+                if regen:
+                    rc |= lib.codenet_regenerate(lay._h, 0, vp(self.reports[slot, l, 1 if redo else 0].data_ptr()), stream)
+            else:
+                rc |= lib.codenet_detect_decode_act(lay._h, 0, pS, b, pA, None, epi, None, stream)
+            x = self.act[l + 1]
+        # loss head (PyTorch elementwise kernels): delta^L = -dLoss/ds^L
+        if self.head.startswith("softmax"):
+            self.torch.sub(self.Y[it % 4], self.torch.softmax(x, dim=1), out=self.err[L])
+            self.err[L].mul_(1.0 / b)
+        else:
+            self.torch.sub(self.Y[it % 4], x, out=self.err[L])
+            self.err[L].mul_(1.0 / b)
+        d = self.err[L]
+        for l in range(L - 1, -1, -1):
+            lay = self.layers[l]
+            (fb, nb), redo = plan[l][2], plan[l][3]
+            epi = B.EPI_MASK_POS if l > 0 else B.EPI_NONE
+            aux = vp(self.act[l].data_ptr()) if l > 0 else None
+            pC, pE = vp(self.Ct[l].data_ptr()), vp(self.err[l].data_ptr())
+            rc |= lib.codenet_backward(lay._h, vp(d.data_ptr()), b, pC, stream)
+            if self.coded:
+                if nb:
+                    rc |= lib.codenet_inject(lay._h, fb, nb, pC, b, stream)
+                rc |= lib.codenet_detect_decode_act(lay._h, 1, pC, b, pE, vp(self.reports[slot, l, 2].data_ptr()), epi, aux, stream)
+                if redo:
+                    rc |= lib.codenet_backward(lay._h, vp(d.data_ptr()), b, pC, stream)
+                    rc |= lib.codenet_detect_decode_act(lay._h, 1, pC, b, pE, vp(self.reports[slot, l, 3].data_ptr()), epi, aux, stream)
+                if regen:
+                    rc |= lib.codenet_regenerate(lay._h, 1, vp(self.reports[slot, l, 3 if redo else 2].data_ptr()), stream)
+            else:
+                rc |= lib.codenet_detect_decode_act(lay._h, 1, pC, b, pE, None, epi, aux, stream)
+            d = self.err[l]
+        if stamp:
+            rc |= lib.codenet_profile_stamps(self.layers[0]._h, None)
+        for l in range(L):
+            rc |= lib.codenet_update(self.layers[l]._h, self.eta, stream)
+            wf, nw = plan[l][4]
+            if nw:
+                rc |= lib.codenet_inject(self.layers[l]._h, wf, nw, None, 0, stream)
+        if rc:
+            raise RuntimeError("a codenet call failed in iteration %d (rc=%d)" % (it, rc))
+
+    def run(self, iters, warmup, prewarm_seconds=0.0):
+        torch = self.torch
+        stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+        self.prewarm_iters = 0
+        if prewarm_seconds > 0:
+            t0 = time.perf_counter()
+            while time.perf_counter() - t0 < prewarm_seconds:
+                for _ in range(4):
+                    self.iteration(self.prewarm_iters, stream, slot=self.total_iters)
+                    self.prewarm_iters += 1
+                torch.cuda.synchronize()
+            # the pre-warm has trained the network a little and planted weight faults: harmless, its reports are dropped
+        self.lib.codenet_timestamp(ctypes.c_void_p(self.stamps[self.total_iters].data_ptr()), stream, ctypes.byref(self.ticks_per_us))
+        stamp_at = set(sampled(iters, warmup))
+        for it in range(warmup):
+            self.iteration(it, stream)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for it in range(warmup, warmup + iters):
+            self.iteration(it, stream, stamp=it in stamp_at)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        st = self.stamps[warmup:warmup + iters].cpu().numpy()
+        st = st[st[:, 0] != 0]
+        tick = self.ticks_per_us.value or 100
+        self.product_ms = (float(np.mean(st[:, 1] - st[:, 0])) / tick * 1e-3, float(np.mean(st[:, 3] - st[:, 2])) / tick * 1e-3,
+                           len(st)) if len(st) else None
+        return (t1 - t0) * 1e3 / iters
+
+    def verdict_counts(self, lo, hi):
+        """Counts over the reports that were written (a product's second slot only when it was computed again)."""
         raw = self.reports[lo:hi].cpu().numpy()
-        counts = {"clean": 0, "corrected": 0, "uncorrectable": 0}
-        for s in range(raw.shape[0]):
-            for p in range(2):
-                v = B.Report.from_buffer_copy(raw[s, p].tobytes()).verdict
-                name = ["clean", "corrected", "uncorrectable", "disagree"][v]   # the last from verified checks only
-                counts[name] = counts.get(name, 0) + 1
-        return counts
+        rows = []
+        for it in range(lo, hi):
+            plan = self.plan[it % self.total_iters]
+            for l in range(self.Ln):
+                rows.append(raw[it - lo, l, 0])
+                if plan[l][1]:
+                    rows.append(raw[it - lo, l, 1])
+                rows.append(raw[it - lo, l, 2])
+                if plan[l][3]:
+                    rows.append(raw[it - lo, l, 3])
+        return count_verdicts(self.B, rows)
+
+    def destroy(self):
+        for lay in self.layers:
+            lay.destroy()
 
 
 def measured_traffic(workload_key):
@@ -301,31 +559,105 @@ def measured_traffic(workload_key):
     return None
 
 
-def cpu_baseline(wl, steps):
-    """The float64 oracle as it stands, timed on the host for a few layer-steps of
-    the same workload (encoding excluded, as on the GPU)."""
-    from oracle import codenet_oracle as O
-    from paper_1903_01042_amd import workloads as WL
+def host_threads():
     try:
         from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        return max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
     except Exception:
-        cores = os.cpu_count() or 1
+        return os.cpu_count() or 1
+
+
+def cpu_baseline(wl, steps):
+    """The float64 oracle as it stands, timed on the host for a few layer-steps of the first layer of
+    the workload at full size (encoding excluded, as on the GPU; inputs and fault lists are drawn
+    before the clock starts, as the GPU leg has them resident)."""
+    from oracle import codenet_oracle as O
+    from paper_1903_01042_amd import workloads as WL
     n_in, n_out = wl.widths[0], wl.widths[1]
     P_r, P_c = wl.generators()
     lay = O.CodedLayer(WL.layer_weights(n_out, n_in), P_r, P_c, tau_detect=wl.tau_detect, tau_resid=wl.tau_resid)
-    t0 = time.perf_counter()
+    work = []
     for s in range(steps):
-        X = wl.inputs(s).T.astype(np.float64)
-        D = wl.deltas(s).T.astype(np.float64)
-        out = lay.inject(wl.product_faults(WL.PHASE_FWD, s), lay.forward(X))
+        work.append((wl.inputs(s)[:, :n_in].T.astype(np.float64), WL.normal((wl.batch, n_out), WL.SEED_DELTAS + s).T.astype(np.float64),
+                     wl.product_faults(WL.PHASE_FWD, s), wl.product_faults(WL.PHASE_BWD, s)))
+    t0 = time.perf_counter()
+    for X, D, ff, fb in work:
+        out = lay.inject(ff, lay.forward(X))
         lay.detect_decode(O.PHASE_FWD, out)
-        out = lay.inject(wl.product_faults(WL.PHASE_BWD, s), lay.backward(D))
+        out = lay.inject(fb, lay.backward(D))
         lay.detect_decode(O.PHASE_BWD, out)
         lay.update(wl.eta)
     dt = time.perf_counter() - t0
-    return {"value": steps / dt, "unit": "coded layer-steps/s", "cores": int(cores), "kind": "oracle",
-            "sample": "%d full-size layer-steps of %s (float64 numpy, encoding excluded)" % (steps, wl.name)}
+    return {"value": steps / dt, "unit": "coded layer-steps/s", "cores": int(host_threads()), "kind": "oracle",
+            "sample": "%d full-size layer-steps of layer 0 of %s (%d x %d, float64 numpy, encoding and input generation excluded)"
+                      % (steps, wl.name, n_out, n_in)}
+
+
+def product_roofline(wl, flops, product_ms, kernel):
+    """The coded products against the MFMA peak of their arithmetic: flops of one product / its time on
+    the GPU (device time stamps around the kernel: its duration plus one kernel boundary)."""
+    if product_ms is None:
+        return None
+    fwd_ms, bwd_ms, n = product_ms
+    peak = MFMA_PEAK_TFLOPS[wl.dtype]
+    ach = 0.5 * (flops["fwd"] / (fwd_ms * 1e-3) + flops["bwd"] / (bwd_ms * 1e-3)) / 1e12
+    return {"kernel": kernel, "bound": "mfma", "achieved": ach, "peak": peak, "unit": "TFLOP/s", "frac": ach / peak,
+            "forward_ms": fwd_ms, "backward_ms": bwd_ms, "flops_forward": flops["fwd"], "flops_backward": flops["bwd"],
+            "frac_forward": flops["fwd"] / (fwd_ms * 1e-3) / 1e12 / peak, "frac_backward": flops["bwd"] / (bwd_ms * 1e-3) / 1e12 / peak,
+            "samples": n, "timed_by": "device time stamps (the GPU's 100 MHz clock) before and after the product kernel on %d "
+                                      "steps of the timed region: the kernel plus one kernel boundary" % n}
+
+
+def main_mlp(args, wl):
+    import torch
+    L_all = len(wl.widths) - 1
+    L = args.layers if 0 < args.layers <= L_all else L_all
+    total = args.steps + args.warmup
+    pre = 0.0 if args.no_prewarm else PREWARM_SECONDS
+    coded = MlpRunner(wl, True, not args.no_faults, total, L)
+    ms_coded = coded.run(args.steps, args.warmup, pre)
+    counts = coded.verdict_counts(args.warmup, total)
+    lay0 = coded.layers[0]
+    m, n = wl.grid
+    flops0 = dict(fwd=2.0 * lay0.coded_rows * (n * lay0.B_c) * coded.b, bwd=2.0 * (m * lay0.B_r) * lay0.coded_cols * coded.b)
+    out = {
+        "metric": "coded layer-steps/s (fwd+bwd+detect/decode+update)",
+        "value": 1e3 * L / ms_coded, "unit": "coded layer-steps/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_coded / L,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": wl.name, "layers": L, "widths": list(coded.widths), "grid": "%dx%d+%d" % (m, n, wl.r),
+                   "batch": wl.batch, "fault_law": "%s p=%g per node and product" % (wl.fault_law, wl.fault_p),
+                   "step": "one training iteration of the whole MLP = %d layer-steps; `steps` counts iterations" % L,
+                   "loss_head": coded.head, "launch": "every call launched into one stream",
+                   "roll_back": "a product with more erroneous blocks than the code corrects is computed again inside the timed loop"},
+        "ms_per_iteration": ms_coded,
+        "tflops": coded.flops / (ms_coded * 1e-3) / 1e12,
+        "mfma_frac_of_peak_whole_step": coded.flops / (ms_coded * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS[wl.dtype],
+        "verdicts": counts,
+        "prewarm_iterations": coded.prewarm_iters,
+        "roofline": product_roofline(wl, flops0, coded.product_ms, "gemm_kernel (coded products of layer 0, float32 MFMA)"),
+    }
+    coded.destroy()
+    if not args.coded_only:
+        unc = MlpRunner(wl, False, False, total, L)
+        ms_unc = unc.run(args.steps, args.warmup, pre)
+        floor = coded.flops / unc.flops - 1.0
+        unc.destroy()
+        out.update({"uncoded_ms_per_step": ms_unc / L, "coding_overhead": ms_coded / ms_unc - 1.0,
+                    "algorithmic_overhead_floor": floor, "excess_over_floor": (ms_coded / ms_unc) / (1.0 + floor) - 1.0})
+        if not args.no_faults:
+            clean = MlpRunner(wl, True, False, total, L)
+            ms_clean = clean.run(args.steps, args.warmup, pre)
+            clean.destroy()
+            out.update({"ms_per_step_without_faults": ms_clean / L,
+                        "coding_overhead_without_faults": ms_clean / ms_unc - 1.0,
+                        "excess_over_floor_without_faults": (ms_clean / ms_unc) / (1.0 + floor) - 1.0})
+        cpu_steps = args.cpu_steps if args.cpu_steps >= 0 else (40 if wl.widths[1] <= 2048 else 2)
+        if cpu_steps > 0:
+            out["cpu_baseline"] = cpu_baseline(wl, cpu_steps)
+    print(json.dumps(out))
 
 
 def main():
@@ -338,10 +670,13 @@ def main():
     from paper_1903_01042_amd import workloads as WL
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     wl = WL.WORKLOADS[args.workload]
+    if len(wl.widths) > 2 and args.layers != 1:
+        return main_mlp(args, wl)
     total = args.steps + args.warmup
+    pre = 0.0 if args.no_prewarm else PREWARM_SECONDS
 
     coded = Runner(wl, True, not args.no_faults, total)
-    ms_coded, upd_ms = coded.run(args.steps, args.warmup, not args.graph)
+    ms_coded, upd_ms = coded.run(args.steps, args.warmup, not args.graph, pre)
     counts = coded.verdict_counts(args.warmup, total)
     if args.coded_only:
         # a plain device-to-device copy of known size (the coded matrix) next to the kernels:
@@ -349,20 +684,21 @@ def main():
         for _ in range(3):
             coded.layer.export_coded()
         torch.cuda.synchronize()
-        print(json.dumps({"ms_per_step": ms_coded, "update_kernel_ms": upd_ms if args.graph else coded.upd_ms_events, "verdicts": counts, "workload": wl.name,
+        print(json.dumps({"ms_per_step": ms_coded, "update_kernel_ms": upd_ms if args.graph else coded.upd_ms_events,
+                          "product_kernels_ms": coded.product_ms, "verdicts": counts, "workload": wl.name,
                           "calibration_copy_bytes": coded.weight_bytes}))
         return
     uncoded = Runner(wl, False, False, total)
-    ms_uncoded, upd_ms_unc = uncoded.run(args.steps, args.warmup, not args.graph)
+    ms_uncoded, upd_ms_unc = uncoded.run(args.steps, args.warmup, not args.graph, pre)
     ms_clean = None
     if not args.no_faults:
         # the coded path without the injection kernels (scaffolding of the experiment, not of the method)
         clean = Runner(wl, True, False, total)
-        ms_clean, _ = clean.run(args.steps, args.warmup, not args.graph)
+        ms_clean, _ = clean.run(args.steps, args.warmup, not args.graph, pre)
         clean.layer.destroy()
     # the coded step with both verification steps of Error Model 2 in every check
     ver = Runner(wl, True, not args.no_faults, total, verified=True)
-    ms_verified, _ = ver.run(args.steps, args.warmup, not args.graph)
+    ms_verified, _ = ver.run(args.steps, args.warmup, not args.graph, pre)
     counts_verified = ver.verdict_counts(args.warmup, total)
     ver.layer.destroy()
 
@@ -393,6 +729,7 @@ def main():
                    "grid": "%dx%d+%d" % (m, n, wl.r), "batch": wl.batch, "fault_law": wl.fault_law,
                    "launch": "hipGraph replay, one graph per step, one stream" if args.graph
                    else "every call launched into one stream"},
+        "prewarm_steps": coded.prewarm_steps,
         "tflops": flops_step / (ms_coded * 1e-3) / 1e12,
         "mfma_frac_of_peak_whole_step": flops_step / (ms_coded * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS[wl.dtype],
         "uncoded_ms_per_step": ms_uncoded,
@@ -412,29 +749,33 @@ def main():
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(args.workload),
                      "avg_launch_ms": launch_ms,
+                     "avg_launch_samples": coded.upd_event_samples,
                      "empty_event_pair_ms": coded.event_pair_ms,
                      "avg_launch_ms_by": ("HIP events around the kernel on every %d-th step of the timed region, "
                                           "where the step's graph ends before the update and the kernel is launched "
                                           "on its own" % Runner.EVENT_EVERY) if args.graph else
-                     ("HIP events around the kernel, on its stream, on every %d-th step of the timed region"
-                      % Runner.EAGER_EVENT_EVERY),
+                     ("HIP events around the kernel, on its stream, on %d steps spread over the timed region"
+                      % coded.upd_event_samples),
                      "in_graph_ms": upd_ms if args.graph else None,
                      "in_graph_ms_by": ("device time stamps before and after the kernel inside the graph of every "
                                         "%d-th step of the timed region" % Runner.STAMP_EVERY) if args.graph else None,
                      "device_stamp_ms": upd_ms,
                      "device_stamp_ms_by": "codenet_timestamp kernels (the GPU's 100 MHz wall clock) before and after the "
-                                           "update on %s of the timed region: the kernel plus one kernel boundary"
-                                           % ("every %d-th step" % (Runner.STAMP_EVERY if args.graph
-                                                                     else Runner.EAGER_EVENT_EVERY)),
+                                           "update on other steps of the timed region: the kernel plus one kernel boundary",
                      "back_to_back_ms_hip_events": upd_events_ms,
                      "algorithmic_bytes": upd_bytes,
                      "tflops": coded.flops["upd"] / (launch_ms * 1e-3) / 1e12},
+        "roofline_products": product_roofline(
+            wl, coded.flops, coded.product_ms,
+            "product_kernel (coded forward and backward products, bf16 MFMA)" if wl.dtype == "bf16"
+            else "gemm_kernel (coded forward and backward products, float32 MFMA)"),
     }
     out["regeneration"] = coded.time_regeneration()
     coded.layer.destroy()
     uncoded.layer.destroy()
-    if args.cpu_steps > 0:
-        out["cpu_baseline"] = cpu_baseline(wl, args.cpu_steps)
+    cpu_steps = args.cpu_steps if args.cpu_steps >= 0 else 40
+    if cpu_steps > 0:
+        out["cpu_baseline"] = cpu_baseline(wl, cpu_steps)
     print(json.dumps(out))
 
 

@@ -282,6 +282,15 @@ int codenet_destroy(codenet_layer *layer);
  */
 int codenet_timestamp(uint64_t *dst_dev, void *stream, int *ticks_per_us);
 
+/*
+ * Profiling aid.  While stamps_dev is not NULL, codenet_forward and codenet_backward on this layer
+ * put a device time stamp (as codenet_timestamp) before and after the kernel(s) of their coded
+ * product: stamps_dev[0], [1] around the forward product, [2], [3] around the backward one (four
+ * 64-bit counts, device memory of the caller's).  The vector encoding that the same calls run
+ * first is outside the stamps.  NULL switches the stamps off again.
+ */
+int codenet_profile_stamps(codenet_layer *layer, uint64_t *stamps_dev);
+
 const char *codenet_strerror(int code);
 
 #ifdef __cplusplus

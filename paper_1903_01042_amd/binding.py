@@ -24,7 +24,7 @@ E_NULL, E_SHAPE, E_BATCH, E_ORDER, E_CODE, E_FAULT, E_HIP, E_DTYPE, E_ALLOC = ra
 EXPORTS = ["codenet_encode", "codenet_layer_geometry", "codenet_forward", "codenet_backward",
            "codenet_inject", "codenet_inject_noalloc", "codenet_detect_decode", "codenet_detect_decode_act",
            "codenet_detect_decode_verified", "codenet_update", "codenet_regenerate", "codenet_export_coded",
-           "codenet_export_weights", "codenet_destroy", "codenet_timestamp", "codenet_strerror"]
+           "codenet_export_weights", "codenet_destroy", "codenet_timestamp", "codenet_profile_stamps", "codenet_strerror"]
 
 
 class Desc(ctypes.Structure):
@@ -80,6 +80,7 @@ def load_library(path=LIB_PATH):
     lib.codenet_export_weights.argtypes = [vp, vp, vp]
     lib.codenet_destroy.argtypes = [vp]
     lib.codenet_timestamp.argtypes = [vp, vp, pi]
+    lib.codenet_profile_stamps.argtypes = [vp, vp]
     lib.codenet_strerror.argtypes = [ci]
     lib.codenet_strerror.restype = ctypes.c_char_p
     for name in EXPORTS[:-1]:

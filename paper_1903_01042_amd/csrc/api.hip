@@ -40,6 +40,7 @@ struct codenet_layer {
   long ldXb = 0, ldDb = 0, ldT = 0; // pitches of Xb, Db and of XTb / DTb
   int fwd_b = 0, bwd_b = 0;     // batch of the cached vectors (0 = none)
   unsigned long updates = 0;    // number of updates enqueued so far
+  unsigned long long *stamps = nullptr;   // profiling aid: four device time stamps around the product kernels (caller's memory)
   bool bf16 = false;
 };
 
@@ -336,7 +337,9 @@ int codenet_forward(codenet_layer *l, const float *X_dev, int b, float *S_coded_
     g2.B = l->Xb; g2.ldb = l->ldXb;
     g2.C = S_coded_dev; g2.ldc = l->Mr;
     g2.I = l->Mr; g2.J = b; g2.K = l->KpX;
+    if (l->stamps) CN_HIP(launch_timestamp(l->stamps + 0, s));
     CN_HIP(launch_product(g2, s));
+    if (l->stamps) CN_HIP(launch_timestamp(l->stamps + 1, s));
     l->fwd_b = b;
     return CODENET_OK;
   }
@@ -348,7 +351,9 @@ int codenet_forward(codenet_layer *l, const float *X_dev, int b, float *S_coded_
   g.I = l->Mr; g.J = b; g.K = l->code_c.a * l->code_c.B;
   g.alpha = 1.f;
   g.workspace = l->part; g.max_splits = kMaxSplits;
+  if (l->stamps) CN_HIP(launch_timestamp(l->stamps + 0, s));
   CN_HIP(launch_gemm(kFwd, g, s));
+  if (l->stamps) CN_HIP(launch_timestamp(l->stamps + 1, s));
   l->fwd_b = b;
   return CODENET_OK;
 }
@@ -366,7 +371,9 @@ int codenet_backward(codenet_layer *l, const float *D_dev, int b, float *C_coded
     g2.B = l->Db; g2.ldb = l->ldDb;
     g2.C = C_coded_dev; g2.ldc = l->Nc;
     g2.I = l->Nc; g2.J = b; g2.K = l->KpD;
+    if (l->stamps) CN_HIP(launch_timestamp(l->stamps + 2, s));
     CN_HIP(launch_product(g2, s));
+    if (l->stamps) CN_HIP(launch_timestamp(l->stamps + 3, s));
     l->bwd_b = b;
     return CODENET_OK;
   }
@@ -378,7 +385,9 @@ int codenet_backward(codenet_layer *l, const float *D_dev, int b, float *C_coded
   g.I = l->Nc; g.J = b; g.K = l->code_r.a * l->code_r.B;
   g.alpha = 1.f;
   g.workspace = l->part; g.max_splits = kMaxSplits;
+  if (l->stamps) CN_HIP(launch_timestamp(l->stamps + 2, s));
   CN_HIP(launch_gemm(kBwd, g, s));
+  if (l->stamps) CN_HIP(launch_timestamp(l->stamps + 3, s));
   l->bwd_b = b;
   return CODENET_OK;
 }
@@ -619,6 +628,12 @@ int codenet_destroy(codenet_layer *l) {
   if (!l) return CODENET_E_NULL;
   (void)hipDeviceSynchronize();
   free_layer(l);
+  return CODENET_OK;
+}
+
+int codenet_profile_stamps(codenet_layer *l, uint64_t *stamps_dev) {
+  if (!l) return CODENET_E_NULL;
+  l->stamps = reinterpret_cast<unsigned long long *>(stamps_dev);
   return CODENET_OK;
 }
 

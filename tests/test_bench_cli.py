@@ -55,3 +55,29 @@ def test_the_bench_line_keeps_its_contract():
     c = d["cpu_baseline"]
     assert c["kind"] == "oracle" and c["cores"] >= 1 and c["value"] > 0 and c["unit"] == d["unit"] and c["sample"]
     assert sum(d["verdicts"].values()) == 60 and d["verified_checks_agree"] is True
+    assert r["avg_launch_samples"] >= 8                      # the dominant kernel is bracketed on 8 timed steps at least
+    p = d["roofline_products"]                               # the coded GEMMs against the MFMA peak of their arithmetic
+    assert p["bound"] == "mfma" and p["unit"] == "TFLOP/s" and p["peak"] == 2500.0 and p["samples"] >= 2
+    assert abs(p["frac"] - p["achieved"] / p["peak"]) < 1e-9 and 0.02 < p["frac"] < 1.0
+    assert abs(p["frac_forward"] - p["flops_forward"] / (p["forward_ms"] * 1e-3) / 1e12 / p["peak"]) < 1e-9
+
+
+@pytest.mark.gpu
+def test_the_mlp_bench_line():
+    """cfg2 (784-1024-1024-10) as whole training iterations: layer-steps per second, the verdicts
+    that the fault lists imply (one parity block only detects: every faulty product is reported
+    UNCORRECTABLE and computed again, clean the second time), overhead against the uncoded run."""
+    p = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--workload", "cfg2", "--steps", "6", "--warmup", "2",
+                        "--cpu-steps", "2"], capture_output=True, text=True, timeout=600, cwd=ROOT)
+    assert p.returncode == 0, p.stderr[-2000:]
+    lines = [l for l in p.stdout.splitlines() if l.strip()]
+    assert len(lines) == 1, lines
+    d = json.loads(lines[0])
+    assert d["unit"] == "coded layer-steps/s" and d["config"]["layers"] == 3 and d["steps"] == 6
+    assert abs(d["value"] * d["ms_per_step"] - 1000.0) < 1e-6 * 1000.0
+    assert abs(d["ms_per_iteration"] - 3 * d["ms_per_step"]) < 1e-9
+    v = d["verdicts"]
+    assert v["corrected"] == 0 and v["uncorrectable"] > 0
+    assert v["clean"] == 6 * 6                               # every product ends clean: 3 layers x 2 products x 6 iterations
+    assert d["coding_overhead"] > d["coding_overhead_without_faults"] > 0.0
+    assert d["roofline"]["bound"] == "mfma" and d["cpu_baseline"]["kind"] == "oracle"
