@@ -45,6 +45,11 @@ def parse():
     ap.add_argument("--no-faults", action="store_true", help="run the coded path without injecting faults")
     ap.add_argument("--coded-only", action="store_true", help="skip the uncoded baseline and the CPU oracle (profiling runs)")
     ap.add_argument("--no-prewarm", action="store_true", help="skip the untimed steps that precede the warm-up")
+    ap.add_argument("--strategies", action="store_true",
+                    help="strategy comparison on the cfg2 network: CodeNet (t = 1), replication (two replicas, compare, "
+                         "roll back) and uncoded (errors ignored), time to --steps iterations over a sweep of checkpoint "
+                         "periods, next to the expected-time model of Theorem 2")
+    ap.add_argument("--fault-p", type=float, default=0.002, help="--strategies: failure probability per node and product")
     ap.add_argument("--graph", action="store_true",
                     help="single-layer workloads: replay one hipGraph per step instead of launching every call from "
                          "Python (a kernel node of a graph takes about 3 us longer than the same kernel launched into "
@@ -546,6 +551,220 @@ class MlpRunner:
             lay.destroy()
 
 
+class StrategyRun:
+    """One strategy training the cfg2 network for M iterations under transient soft errors in the
+    node outputs of both products (Bernoulli per node and product), with a checkpoint every I0
+    iterations (the weights of all layers copied to host memory) and the paper's roll-back rule: an
+    iteration whose errors the strategy cannot correct is thrown away and the network is restored
+    from the last checkpoint (host copy -> device, encoded afresh), from where the iterations are
+    repeated.  The verdicts of an iteration are read once, at its end.
+      codenet      coded layers with 2 parity block-rows / columns (t = 1): corrects one erroneous
+                   block per product and goes on (every check is followed by the regeneration call)
+      replication  two uncoded replicas compute every product; outputs are compared on the device,
+                   any difference means roll back (detection only)
+      uncoded      one uncoded network, errors are neither detected nor corrected, no checkpoints"""
+
+    def __init__(self, strategy, wl, p, period, iters, seed=0):
+        import torch
+        from paper_1903_01042_amd import binding as B
+        from paper_1903_01042_amd import workloads as WL
+        self.torch, self.B, self.WL, self.wl = torch, B, WL, wl
+        self.lib = B.load_library()
+        self.dev = torch.device("cuda:0")
+        self.strategy, self.p, self.period, self.iters, self.seed = strategy, p, period, iters, seed
+        self.Ln = len(wl.widths) - 1
+        self.b = wl.batch
+        m, n = wl.grid
+        self.r = 2 if strategy == "codenet" else 0
+        self.P = (WL.vandermonde_like(m, self.r), WL.vandermonde_like(n, self.r))
+        self.replicas = 2 if strategy == "replication" else 1
+        W0 = [WL.layer_weights(wl.widths[l + 1], wl.widths[l], l) for l in range(self.Ln)]
+        self.ckpt = [torch.from_numpy(w) for w in W0]             # host copies
+        self.nets = [[self._encode(self.ckpt[l]) for l in range(self.Ln)] for _ in range(self.replicas)]
+        f32 = dict(dtype=torch.float32, device=self.dev)
+        self.X = [torch.from_numpy(wl.inputs(s)).to(self.dev) for s in range(8)]
+        classes = wl.widths[-1]
+        self.Y = [torch.nn.functional.one_hot(torch.from_numpy(np.random.default_rng(WL.SEED_DELTAS + s).integers(0, classes, size=self.b)),
+                                              classes).to(**f32) for s in range(8)]
+        lay = self.nets[0]
+        self.St = [[torch.empty((self.b, l.coded_rows), **f32) for l in net] for net in self.nets]
+        self.Ct = [[torch.empty((self.b, l.coded_cols), **f32) for l in net] for net in self.nets]
+        self.act = [None] + [torch.empty((self.b, wl.widths[l + 1]), **f32) for l in range(self.Ln)]
+        self.err = [torch.empty((self.b, wl.widths[l]), **f32) for l in range(self.Ln + 1)]
+        self.reports = torch.zeros((self.Ln, 2, B.REPORT_BYTES), dtype=torch.uint8, device=self.dev)
+        self.mismatch = torch.zeros(1, dtype=torch.int32, device=self.dev)
+        self.classes = {"clean": 0, "corrected": 0, "rolled_back": 0}
+        self.t_iter = {"clean": [], "corrected": [], "rolled_back": []}
+        self.t_ckpt = []
+
+    def _encode(self, W_host):
+        return self.B.CodedLayer(W_host.to(self.dev), self.P[0], self.P[1], dtype=self.B.F32, max_batch=self.b,
+                                 tau_detect=self.wl.tau_detect, tau_resid=self.wl.tau_resid)
+
+    def _faults(self, phase, attempt, layer, replica):
+        WL = self.WL
+        m, n = self.wl.grid
+        ff = WL.bernoulli_faults(phase, m, n, self.r, self.r, self.p, attempt, layer, seed=WL.SEED_FAULTS + 17 * replica + 1000 * self.seed)
+        return self.B.pack_faults(ff), len(ff)
+
+    def _iteration(self, it, attempt, stream):
+        """Iteration `it` of the training (inputs it % 8); `attempt` numbers every try, so that a repeated
+        iteration draws new errors."""
+        lib, B, b, L = self.lib, self.B, self.b, self.Ln
+        vp = ctypes.c_void_p
+        coded = self.strategy == "codenet"
+        rc = 0
+        self.mismatch.zero_()
+        x = self.X[it % 8]
+        for l in range(L):
+            epi = B.EPI_RELU if l < L - 1 else B.EPI_NONE
+            for k, net in enumerate(self.nets):
+                lay, pS = net[l], vp(self.St[k][l].data_ptr())
+                rc |= lib.codenet_forward(lay._h, vp(x.data_ptr()), b, pS, stream)
+                ff, nf = self._faults(self.WL.PHASE_FWD, attempt, l, k)
+                if nf:
+                    rc |= lib.codenet_inject(lay._h, ff, nf, pS, b, stream)
+            if self.replicas == 2:
+                self.mismatch.add_((self.St[0][l] != self.St[1][l]).any().to(self.torch.int32))
+            lay = self.nets[0][l]
+            rep = vp(self.reports[l, 0].data_ptr()) if coded else None
+            rc |= lib.codenet_detect_decode_act(lay._h, 0, vp(self.St[0][l].data_ptr()), b, vp(self.act[l + 1].data_ptr()), rep, epi, None, stream)
+            if coded:
+                rc |= lib.codenet_regenerate(lay._h, 0, rep, stream)
+            x = self.act[l + 1]
+        self.torch.sub(self.Y[it % 8], self.torch.softmax(x, dim=1), out=self.err[L])
+        self.err[L].mul_(1.0 / b)
+        d = self.err[L]
+        for l in range(L - 1, -1, -1):
+            epi = B.EPI_MASK_POS if l > 0 else B.EPI_NONE
+            aux = vp(self.act[l].data_ptr()) if l > 0 else None
+            for k, net in enumerate(self.nets):
+                lay, pC = net[l], vp(self.Ct[k][l].data_ptr())
+                rc |= lib.codenet_backward(lay._h, vp(d.data_ptr()), b, pC, stream)
+                fb, nb = self._faults(self.WL.PHASE_BWD, attempt, l, k)
+                if nb:
+                    rc |= lib.codenet_inject(lay._h, fb, nb, pC, b, stream)
+            if self.replicas == 2:
+                self.mismatch.add_((self.Ct[0][l] != self.Ct[1][l]).any().to(self.torch.int32))
+            lay = self.nets[0][l]
+            rep = vp(self.reports[l, 1].data_ptr()) if coded else None
+            rc |= lib.codenet_detect_decode_act(lay._h, 1, vp(self.Ct[0][l].data_ptr()), b, vp(self.err[l].data_ptr()), rep, epi, aux, stream)
+            if coded:
+                rc |= lib.codenet_regenerate(lay._h, 1, rep, stream)
+            d = self.err[l]
+        for net in self.nets:
+            for lay in net:
+                rc |= lib.codenet_update(lay._h, ctypes.c_float(self.wl.eta), stream)
+        if rc:
+            raise RuntimeError("a codenet call failed (rc=%d)" % rc)
+        # the iteration's verdict, read once
+        if coded:
+            v = [self.B.Report.from_buffer_copy(row.tobytes()).verdict for row in self.reports.cpu().numpy().reshape(-1, B.REPORT_BYTES)]
+            return "rolled_back" if B.UNCORRECTABLE in v else ("corrected" if B.CORRECTED in v else "clean")
+        if self.replicas == 2:
+            return "rolled_back" if int(self.mismatch.item()) else "clean"
+        self.torch.cuda.synchronize()
+        return "clean"
+
+    def run(self):
+        torch = self.torch
+        stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+        for w in range(3):                      # warm-up on the first input (state restored below)
+            self._iteration(0, 10 ** 6 + w, stream)
+        self._restore()
+        torch.cuda.synchronize()
+        t_start = time.perf_counter()
+        done, attempt, last_ckpt = 0, 0, 0
+        self.finished = True
+        while done < self.iters:
+            if attempt >= 10 * self.iters:      # this period is hopeless at this error rate (the chain's expected time explodes)
+                self.finished = False
+                break
+            t0 = time.perf_counter()
+            kind = self._iteration(done, attempt, stream)
+            attempt += 1
+            if kind == "rolled_back" and self.strategy != "uncoded":
+                self._restore()
+                torch.cuda.synchronize()
+                done = last_ckpt
+            else:
+                done += 1
+            self.classes[kind] += 1
+            self.t_iter[kind].append(time.perf_counter() - t0)
+            if self.strategy != "uncoded" and done - last_ckpt == self.period and done < self.iters:
+                t0 = time.perf_counter()
+                self.ckpt = [lay.export_weights().cpu() for lay in self.nets[0]]
+                last_ckpt = done
+                self.t_ckpt.append(time.perf_counter() - t0)
+        total = time.perf_counter() - t_start
+        self.final = [lay.export_weights().cpu().numpy() for lay in self.nets[0]]
+        for net in self.nets:
+            for lay in net:
+                lay.destroy()
+        return total, attempt
+
+    def _restore(self):
+        for net in self.nets:
+            for lay in net:
+                lay.destroy()
+        self.nets = [[self._encode(self.ckpt[l]) for l in range(self.Ln)] for _ in range(self.replicas)]
+
+
+def main_strategies(args):
+    """Time to M iterations of CodeNet, replication and uncoded over a sweep of checkpoint periods,
+    next to the expected-time model (Theorem 2; the chain's own solution and the formula as printed)
+    evaluated at the measured tau_f, tau_b, tau_cpt and at the class frequencies of the drawn errors."""
+    from oracle import strategy_model as S
+    from paper_1903_01042_amd import workloads as WL
+    wl = WL.WORKLOADS["cfg2"]
+    M, p = args.steps if args.steps != 1000 else 200, args.fault_p
+    periods = [q for q in (5, 10, 20, 50, 100) if q <= M]
+    out = {"metric": "time to M training iterations under soft errors", "unit": "s", "M": M, "fault_p_per_node_and_product": p,
+           "network": list(wl.widths), "grid": "%dx%d" % wl.grid, "batch": wl.batch, "data": "synthetic",
+           "strategies": {}}
+    ref = StrategyRun("uncoded", wl, 0.0, M, M)
+    t_ref, _ = ref.run()
+    for name in ("codenet", "replication"):
+        rows = []
+        for I0 in periods:
+            run = StrategyRun(name, wl, p, I0, M)
+            total, attempts = run.run()
+            n = sum(run.classes.values())
+            med = lambda v: float(np.median(v)) if v else None
+            tau_f, tau_b = med(run.t_iter["clean"]), med(run.t_iter["rolled_back"]) or med(run.t_iter["corrected"])
+            tau_c = med(run.t_iter["corrected"])
+            tau_cpt = med(run.t_ckpt) or 0.0
+            p0, p1 = run.classes["clean"] / n, run.classes["corrected"] / n
+            row = {"I0": I0, "seconds": total if run.finished else float("inf"), "finished": run.finished, "attempts": attempts, "classes": run.classes, "tau_f": tau_f, "tau_corrected": tau_c,
+                   "tau_b": tau_b, "tau_cpt": tau_cpt, "p0": p0, "p1": p1,
+                   # relative distance of every layer's final weights from those of a run without errors
+                   "distance_from_fault_free_run": [float(np.linalg.norm(a - b) / np.linalg.norm(b))
+                                                    for a, b in zip(run.final, ref.final)] if run.finished else None}
+            if tau_f and tau_b:
+                # the paper charges tau_b to a corrected iteration as well (its pessimistic assumption); measured
+                # corrected iterations cost tau_corrected, so the model is given the mixture it assumes
+                row["model_seconds_chain"] = S.expected_total_time(M, I0, p0, p1, tau_f, tau_b, tau_cpt)
+                row["model_seconds_as_printed"] = S.expected_total_time(M, I0, p0, p1, tau_f, tau_b, tau_cpt, printed=True)
+            rows.append(row)
+        best = min(rows, key=lambda r: r["seconds"])
+        out["strategies"][name] = {"sweep": rows, "best_I0": best["I0"], "best_seconds": best["seconds"]}
+    unc = StrategyRun("uncoded", wl, p, M, M)
+    t_unc, _ = unc.run()
+    dist = [float(np.linalg.norm(a - b) / np.linalg.norm(b)) for a, b in zip(unc.final, ref.final)]
+    out["strategies"]["uncoded"] = {"seconds": t_unc, "fault_free_seconds": t_ref,
+                                    "relative_distance_of_final_weights_from_the_fault_free_run": dist}
+    rep, cod = out["strategies"]["replication"], out["strategies"]["codenet"]
+    out["replication_over_codenet_measured"] = rep["best_seconds"] / cod["best_seconds"]
+    rb, cb = min(rep["sweep"], key=lambda r: r["seconds"]), min(cod["sweep"], key=lambda r: r["seconds"])
+    if cb.get("model_seconds_chain") and rb.get("model_seconds_chain"):
+        out["replication_over_codenet_model_chain"] = rb["model_seconds_chain"] / cb["model_seconds_chain"]
+        out["replication_over_codenet_model_as_printed"] = rb["model_seconds_as_printed"] / cb["model_seconds_as_printed"]
+    out["value"] = out["replication_over_codenet_measured"]
+    out["note"] = ("one GPU: both replicas, and CodeNet's redundant blocks, run on the same device, so an error-free iteration "
+                   "costs each strategy its own tau_f (the paper gives the redundancy extra nodes and one tau_f to both)")
+    print(json.dumps(out))
+
+
 def measured_traffic(workload_key):
     """HBM bytes per launch of the dominant kernel, from the committed rocprofv3 counter summary
     (FETCH_SIZE + WRITE_SIZE, scaled by a copy of known size); None when no summary exists."""
@@ -669,6 +888,8 @@ def main():
     import torch
     from paper_1903_01042_amd import workloads as WL
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.strategies:
+        return main_strategies(args)
     wl = WL.WORKLOADS[args.workload]
     if len(wl.widths) > 2 and args.layers != 1:
         return main_mlp(args, wl)

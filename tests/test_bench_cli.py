@@ -81,3 +81,24 @@ def test_the_mlp_bench_line():
     assert v["clean"] == 6 * 6                               # every product ends clean: 3 layers x 2 products x 6 iterations
     assert d["coding_overhead"] > d["coding_overhead_without_faults"] > 0.0
     assert d["roofline"]["bound"] == "mfma" and d["cpu_baseline"]["kind"] == "oracle"
+
+
+@pytest.mark.gpu
+def test_the_strategy_comparison_leg():
+    """CodeNet, replication and uncoded on the cfg2 network for 20 iterations each: CodeNet and
+    replication end with the weights of a run without errors (to float32 accuracy / exactly), uncoded
+    does not; the expected-time model is quoted both ways next to the measured times."""
+    p = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--strategies", "--steps", "20", "--fault-p", "0.004"],
+                       capture_output=True, text=True, timeout=600, cwd=ROOT)
+    assert p.returncode == 0, p.stderr[-2000:]
+    d = json.loads([l for l in p.stdout.splitlines() if l.strip()][0])
+    cod, rep, unc = (d["strategies"][k] for k in ("codenet", "replication", "uncoded"))
+    done = [r for r in cod["sweep"] if r["finished"]]
+    assert done and all(max(r["distance_from_fault_free_run"]) < 1e-3 for r in done)
+    assert any(r["classes"]["corrected"] > 0 for r in done)
+    done = [r for r in rep["sweep"] if r["finished"]]
+    assert done and all(max(r["distance_from_fault_free_run"]) == 0.0 for r in done)
+    assert all(r["classes"]["corrected"] == 0 for r in rep["sweep"])
+    assert max(unc["relative_distance_of_final_weights_from_the_fault_free_run"]) > 1e-3
+    assert d["replication_over_codenet_measured"] > 1.0
+    assert all("model_seconds_chain" in r and "model_seconds_as_printed" in r for r in done)
