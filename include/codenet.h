@@ -188,11 +188,27 @@ int codenet_inject_noalloc(codenet_layer *layer, const codenet_fault *faults_hos
  * place in coded_out_dev.  More errors than t: verdict UNCORRECTABLE,
  * coded_out_dev untouched (the caller rolls back; not an API error).
  * phase: CODENET_FWD or CODENET_BWD.  decoded_dev: [b][n_out] (FWD) or
- * [b][n_in] (BWD), receives the systematic part without padding; may be NULL.
- * report_dev: written by the GPU; may be NULL.  decoded_dev must not overlap coded_out_dev.
+ * [b][n_in] (BWD), receives the systematic part without padding; may be NULL, or
+ * coded_out_dev itself ("in place": nothing is copied, the systematic part stays
+ * where it is -- block i in columns [i * B, i * B + real entries) of each row of
+ * coded_out_dev -- and a clean check writes nothing at all); any other overlap of
+ * the two buffers is not allowed.  report_dev: written by the GPU; may be NULL.
+ *
+ * Where the consistency checks are evaluated.  In the bf16 mode, for codes of at most ten
+ * blocks and four parity blocks, the coded product computes them in its epilogue, while the
+ * outputs of a codeword still sit side by side in registers, and leaves them with the layer;
+ * this call then starts from them instead of reading the output again.  They are used only if
+ * coded_out_dev is the buffer that the layer's last product of this phase wrote, with the same
+ * b, and no codenet_inject or check has touched it since (both discard them, as does a
+ * verified check, which evaluates the checks twice itself).  A caller that changes that buffer
+ * by any other means between the product and the check must say so with
+ * codenet_output_modified(), or the change goes unchecked.
  */
 int codenet_detect_decode(codenet_layer *layer, int phase, float *coded_out_dev, int b,
                           float *decoded_dev, codenet_report *report_dev, void *stream);
+
+/* The coded output of the last product of `phase` was modified by the caller: the check reads it afresh. */
+int codenet_output_modified(codenet_layer *layer, int phase);
 
 /*
  * The same with the elementwise primary step that follows the product applied
@@ -204,7 +220,9 @@ int codenet_detect_decode(codenet_layer *layer, int phase, float *coded_out_dev,
  *   CODENET_EPI_MUL       decoded = decoded * aux                    (any f', supplied by the caller)
  * aux_dev has the shape of decoded_dev ([b][n_out] for FWD, [b][n_in] for BWD) and
  * is required by the last two; decoded_dev is required by all three.  The coded
- * output buffer keeps the (corrected) values before the elementwise step.
+ * output buffer keeps the (corrected) values before the elementwise step -- unless
+ * decoded_dev is coded_out_dev, where the step is applied in place to the real entries
+ * of the systematic blocks.
  */
 typedef enum { CODENET_EPI_NONE = 0, CODENET_EPI_RELU = 1, CODENET_EPI_MASK_POS = 2, CODENET_EPI_MUL = 3 } codenet_epilogue;
 int codenet_detect_decode_act(codenet_layer *layer, int phase, float *coded_out_dev, int b,

@@ -23,7 +23,7 @@ E_NULL, E_SHAPE, E_BATCH, E_ORDER, E_CODE, E_FAULT, E_HIP, E_DTYPE, E_ALLOC = ra
 
 EXPORTS = ["codenet_encode", "codenet_layer_geometry", "codenet_forward", "codenet_backward",
            "codenet_inject", "codenet_inject_noalloc", "codenet_detect_decode", "codenet_detect_decode_act",
-           "codenet_detect_decode_verified", "codenet_update", "codenet_regenerate", "codenet_export_coded",
+           "codenet_detect_decode_verified", "codenet_output_modified", "codenet_update", "codenet_regenerate", "codenet_export_coded",
            "codenet_export_weights", "codenet_destroy", "codenet_timestamp", "codenet_profile_stamps", "codenet_strerror"]
 
 
@@ -74,6 +74,7 @@ def load_library(path=LIB_PATH):
     lib.codenet_detect_decode.argtypes = [vp, ci, vp, ci, vp, vp, vp]
     lib.codenet_detect_decode_act.argtypes = [vp, ci, vp, ci, vp, vp, ci, vp, vp]
     lib.codenet_detect_decode_verified.argtypes = [vp, ci, vp, ci, vp, vp, ci, vp, vp]
+    lib.codenet_output_modified.argtypes = [vp, ci]
     lib.codenet_update.argtypes = [vp, cf, vp]
     lib.codenet_regenerate.argtypes = [vp, ci, vp, vp]
     lib.codenet_export_coded.argtypes = [vp, vp, vp]
@@ -217,7 +218,7 @@ class CodedLayer:
         _dev_f32(coded_out, (b, width), "coded_out")
         if decoded is None and want_decoded:
             decoded = torch.empty((b, n_logical), dtype=torch.float32, device=self.device)
-        if decoded is not None:
+        if decoded is not None and decoded.data_ptr() != coded_out.data_ptr():
             _dev_f32(decoded, (b, n_logical), "decoded")
         if report is not None and (report.dtype != torch.uint8 or report.numel() < REPORT_BYTES):
             raise ValueError("report must be a uint8 tensor of at least %d bytes" % REPORT_BYTES)
@@ -237,6 +238,9 @@ class CodedLayer:
         _check(load_library().codenet_detect_decode(self._h, int(phase), _ptr(coded_out), b, _ptr(decoded),
                                                     _ptr(report), _stream()), "codenet_detect_decode")
         return decoded
+
+    def output_modified(self, phase):
+        _check(load_library().codenet_output_modified(self._h, int(phase)), "codenet_output_modified")
 
     def update(self, eta):
         _check(load_library().codenet_update(self._h, float(eta), _stream()), "codenet_update")

@@ -21,6 +21,12 @@ struct codenet_layer {
   float *Dt = nullptr;          // [max_batch][Mr]   cached [delta; delta~]  (f32 mode only)
   float *syn = nullptr;         // [max r][max_batch][max B]
   double *partials = nullptr;   // [kDetectParts][kMaxEntries]
+  // pass 1 of the check as the product's epilogue left it (bf16 mode, codes that fit the kernel), per phase:
+  // syndromes, records, and which output buffer / batch / number of records they describe (null: none)
+  float *syn_p[2] = {nullptr, nullptr};
+  double *partials_p[2] = {nullptr, nullptr};
+  const float *rec_out[2] = {nullptr, nullptr};
+  int rec_b[2] = {0, 0}, rec_parts[2] = {0, 0};
   double *fault_partials = nullptr;   // [CODENET_MAX_FAULTS][kFaultParts]
   double *partials_b = nullptr; // records of the second evaluation of the checks (verified check), as partials
   unsigned long long *votes = nullptr;  // one decision word per workgroup of the finishing kernel (verified check)
@@ -182,6 +188,7 @@ void free_layer(codenet_layer *l) {
   (void)hipFree(l->Wt); (void)hipFree(l->Xt); (void)hipFree(l->Dt); (void)hipFree(l->syn);
   (void)hipFree(l->partials); (void)hipFree(l->fault_partials);
   (void)hipFree(l->partials_b); (void)hipFree(l->votes);
+  for (int ph = 0; ph < 2; ++ph) { (void)hipFree(l->syn_p[ph]); (void)hipFree(l->partials_p[ph]); }
   (void)hipFree(l->code_r_dev); (void)hipFree(l->code_c_dev);
   (void)hipFree(l->Wb); (void)hipFree(l->Xb); (void)hipFree(l->Db);
   (void)hipFree(l->XTb); (void)hipFree(l->DTb); (void)hipFree(l->part);
@@ -279,6 +286,13 @@ int codenet_encode(const codenet_desc *d, const float *W_dev, void *stream, code
     l->ldT = pitch(l->bpad);
     alloc((void **)&l->XTb, 2 * (size_t)l->Nc * l->ldT);
     alloc((void **)&l->DTb, 2 * (size_t)l->Mr * l->ldT);
+    for (int ph = 0; ph < 2; ++ph) {
+      const DevCode &cd = ph == 0 ? l->code_r : l->code_c;
+      if (product_check_fits(cd.L, cd.B, cd.r, 1)) {
+        alloc((void **)&l->syn_p[ph], sizeof(float) * (size_t)cd.r * mb * cd.B);
+        alloc((void **)&l->partials_p[ph], sizeof(double) * (size_t)kDetectParts * kMaxEntries);
+      }
+    }
     alloc((void **)&l->Wb, szWb);
     alloc((void **)&l->Xb, szXb);
     alloc((void **)&l->Db, szDb);
@@ -324,6 +338,33 @@ int codenet_layer_geometry(const codenet_layer *l, int *B_r, int *B_c, int *code
   return CODENET_OK;
 }
 
+namespace {
+// The bf16 product of a phase: on tiles of whole codewords with the check's first pass in the
+// epilogue where the code fits that kernel, else the plain product (the check then reads the output).
+int bf16_product(codenet_layer *l, int phase, Gemm2Args g2, const float *out, int b, hipStream_t s) {
+  const DevCode &cd = phase == CODENET_FWD ? l->code_r : l->code_c;
+  l->rec_out[phase] = nullptr;
+  if (l->stamps) CN_HIP(launch_timestamp(l->stamps + 2 * phase, s));
+  if (l->syn_p[phase] && product_check_fits(cd.L, cd.B, cd.r, b)) {
+    CheckArgs c{};
+    c.syn = l->syn_p[phase];
+    c.partials = l->partials_p[phase];
+    c.L = cd.L; c.Bp = cd.B; c.r = cd.r;
+    for (int k = 0; k < cd.r; ++k)
+      for (int i = 0; i < cd.L; ++i) c.Hf[k][i] = cd.Hf[k][i];
+    int n_parts = 0;
+    CN_HIP(launch_product_check(g2, c, &n_parts, s));
+    l->rec_out[phase] = out;
+    l->rec_b[phase] = b;
+    l->rec_parts[phase] = n_parts;
+  } else {
+    CN_HIP(launch_product(g2, s));
+  }
+  if (l->stamps) CN_HIP(launch_timestamp(l->stamps + 2 * phase + 1, s));
+  return CODENET_OK;
+}
+}  // namespace
+
 int codenet_forward(codenet_layer *l, const float *X_dev, int b, float *S_coded_dev, void *stream) {
   if (!l || !X_dev || !S_coded_dev) return CODENET_E_NULL;
   if (b < 1 || b > l->desc.max_batch) return CODENET_E_BATCH;
@@ -337,9 +378,8 @@ int codenet_forward(codenet_layer *l, const float *X_dev, int b, float *S_coded_
     g2.B = l->Xb; g2.ldb = l->ldXb;
     g2.C = S_coded_dev; g2.ldc = l->Mr;
     g2.I = l->Mr; g2.J = b; g2.K = l->KpX;
-    if (l->stamps) CN_HIP(launch_timestamp(l->stamps + 0, s));
-    CN_HIP(launch_product(g2, s));
-    if (l->stamps) CN_HIP(launch_timestamp(l->stamps + 1, s));
+    const int rc = bf16_product(l, CODENET_FWD, g2, S_coded_dev, b, s);
+    if (rc != CODENET_OK) return rc;
     l->fwd_b = b;
     return CODENET_OK;
   }
@@ -371,9 +411,8 @@ int codenet_backward(codenet_layer *l, const float *D_dev, int b, float *C_coded
     g2.B = l->Db; g2.ldb = l->ldDb;
     g2.C = C_coded_dev; g2.ldc = l->Nc;
     g2.I = l->Nc; g2.J = b; g2.K = l->KpD;
-    if (l->stamps) CN_HIP(launch_timestamp(l->stamps + 2, s));
-    CN_HIP(launch_product(g2, s));
-    if (l->stamps) CN_HIP(launch_timestamp(l->stamps + 3, s));
+    const int rc = bf16_product(l, CODENET_BWD, g2, C_coded_dev, b, s);
+    if (rc != CODENET_OK) return rc;
     l->bwd_b = b;
     return CODENET_OK;
   }
@@ -450,6 +489,7 @@ int check_call(codenet_layer *l, int phase, float *coded_out_dev, int b, float *
   if (!l || !coded_out_dev) return CODENET_E_NULL;
   if (epilogue < CODENET_EPI_NONE || epilogue > CODENET_EPI_MUL) return CODENET_E_DTYPE;
   if (epilogue != CODENET_EPI_NONE && !decoded_dev) return CODENET_E_NULL;
+  if (aux_dev && aux_dev == decoded_dev) return CODENET_E_SHAPE;
   if ((epilogue == CODENET_EPI_MASK_POS || epilogue == CODENET_EPI_MUL) && !aux_dev) return CODENET_E_NULL;
   if (phase != CODENET_FWD && phase != CODENET_BWD) return CODENET_E_DTYPE;
   if (b < 1 || b > l->desc.max_batch) return CODENET_E_BATCH;
@@ -457,7 +497,15 @@ int check_call(codenet_layer *l, int phase, float *coded_out_dev, int b, float *
   const DevCode &ch = phase == CODENET_FWD ? l->code_r : l->code_c;
   const DevCode *cd = phase == CODENET_FWD ? l->code_r_dev : l->code_c_dev;
   int n_parts = 0;
-  if (ch.r > 0) {
+  // The product of this phase may have left the first pass behind (its records describe this very
+  // buffer as the product wrote it: nothing but this call has touched it since).  Whatever happens
+  // now, they are used up: the check may correct the buffer in place.
+  const bool taken = !verified && ch.r > 0 && l->rec_out[phase] == coded_out_dev && l->rec_b[phase] == b;
+  const float *syn = taken ? l->syn_p[phase] : l->syn;
+  const double *partials = taken ? l->partials_p[phase] : l->partials;
+  if (taken) n_parts = l->rec_parts[phase];
+  l->rec_out[phase] = nullptr;
+  if (ch.r > 0 && !taken) {
     CN_HIP(launch_detect(coded_out_dev, l->syn, l->partials, &n_parts, cd, ch, b, false, s));
   }
   if (verified && ch.r > 0) {
@@ -474,7 +522,7 @@ int check_call(codenet_layer *l, int phase, float *coded_out_dev, int b, float *
     return CODENET_OK;
   }
   // with r = 0 there is nothing to check: zero records make the decision CLEAN
-  CN_HIP(launch_finish(coded_out_dev, l->syn, l->partials, n_parts, cd, ch, b, decoded_dev, report_dev, epilogue,
+  CN_HIP(launch_finish(coded_out_dev, syn, partials, n_parts, cd, ch, b, decoded_dev, report_dev, epilogue,
                        aux_dev, nullptr, s));
   return CODENET_OK;
 }
@@ -523,6 +571,7 @@ int inject_faults(codenet_layer *l, const codenet_fault *faults, int n_faults, f
   if (phase != CODENET_WEIGHT) {
     if (!coded_out_dev) return CODENET_E_NULL;
     if (b < 1 || b > l->desc.max_batch) return CODENET_E_BATCH;
+    l->rec_out[phase] = nullptr;      // the output changes: what the product recorded about it is stale
   }
   const DevCode &cr = l->code_r, &cc = l->code_c;
   FaultArgs fa[CODENET_MAX_FAULTS];
@@ -628,6 +677,13 @@ int codenet_destroy(codenet_layer *l) {
   if (!l) return CODENET_E_NULL;
   (void)hipDeviceSynchronize();
   free_layer(l);
+  return CODENET_OK;
+}
+
+int codenet_output_modified(codenet_layer *l, int phase) {
+  if (!l) return CODENET_E_NULL;
+  if (phase != CODENET_FWD && phase != CODENET_BWD) return CODENET_E_DTYPE;
+  l->rec_out[phase] = nullptr;
   return CODENET_OK;
 }
 

@@ -86,8 +86,17 @@ struct Update2Args {
   int tiles_i, tiles_j;
   int reverse;                   // walk the tiles in the opposite order (alternates from call to call)
 };
+// pass 1 of the check, taken in the epilogue of the product (launch_product_check)
+struct CheckArgs {
+  float *syn;                    // syndromes [r][J][Bp], written for the correction pass
+  double *partials;              // one record per tile, entry-major as detect_kernel's
+  float Hf[4][10];               // H[k][block], zero beyond the code
+  int L, Bp, r;                  // blocks per codeword, block pitch, parity blocks
+};
 constexpr int kMaxSplits = 8;
 hipError_t launch_product(Gemm2Args g, hipStream_t s);
+bool product_check_fits(int L, int Bp, int r, int J);
+hipError_t launch_product_check(Gemm2Args g, CheckArgs c, int *n_parts, hipStream_t s);
 hipError_t launch_update2(Update2Args g, hipStream_t s);
 hipError_t launch_shadow(const float *Wt, int Mr, int Nc, void *Wb, long ldWb, hipStream_t s);
 

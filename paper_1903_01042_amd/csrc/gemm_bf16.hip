@@ -33,6 +33,7 @@ typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 #define CN_LDS_PTR(p) ((__attribute__((address_space(3))) void *)(p))
 
@@ -408,6 +409,286 @@ __global__ __launch_bounds__(512) void product_kernel(Gemm2Args g) {
         const int j = j0 + (wj * 2 + b) * 32 + 8 * q + 4 * h + e;
         if (j < g.J) g.C[(long)j * g.ldc + i] = acc[b][4 * q + e];
       }
+}
+
+// ---------------------------------------------------------------------------
+// The coded product with the check's first pass in its epilogue (General Error-Detection
+// Method: every consistency check is a linear combination of block outputs that sit side by
+// side once the tile holds whole codewords).
+//
+// Tile: 160 rows x 64 batch columns, the rows being the same 16 positions of up to ten blocks
+// (row a of the tile is position p0 + a % 16 of block a / 16), so that a workgroup owns
+// 16 x 64 complete codewords.  With L = 10 blocks of 512 positions and a batch of 512 that is
+// 32 x 8 = 256 tiles: one per compute unit, none idle.  Eight wavefronts: four issue MFMAs
+// (v_mfma_f32_16x16x32_bf16, 2 x 2 wavefronts of 80 rows x 32 columns: five blocks times two
+// column groups = ten accumulators), four only issue the direct-to-LDS loads.  What limits this
+// product is the 64 bytes per clock at which a compute unit takes data in (measured: 57 B/clk
+// with 28 KB per wavefront in flight): (160 + 64) x 128 bytes per 64-deep slab are 500 clocks,
+// the ten MFMAs of a wavefront and k-step 160 clocks, 320 per slab -- MFMAs, loads and LDS
+// fragment reads run concurrently without slowing each other (measured with a kernel that
+// only issues them), so the MFMA wavefronts simply read a slab's fragments after its barrier.
+//
+// Epilogue: the accumulators are stored as the coded output and, from the same registers, each
+// lane forms its share of the r syndromes (a lane holds one position of five blocks for four
+// batch columns; the two wavefronts that share a column group exchange their halves through
+// LDS), writes them for the correction pass, and the workgroup leaves one record of partial sums
+// -- squared norms of the blocks, Gram matrix of the syndromes, float64, fixed order -- exactly
+// what detect_kernel leaves per workgroup.  The decision kernel then runs on these records.
+// AT: the A operand stored k-major (the backward product), tile columns gathered as 32-byte
+// pieces, fragments through the transposing LDS read.
+// ---------------------------------------------------------------------------
+template <bool AT, int R>
+__global__ __launch_bounds__(512) void product_check_kernel(Gemm2Args g, CheckArgs c) {
+  constexpr int NS = 5;
+  constexpr int A_BYTES = 160 * 128, STAGE = A_BYTES + 64 * 128;      // 28 KB
+  constexpr int NG = R * (R + 1) / 2;
+  extern __shared__ uint4 lds[];
+  char *const lds_c = reinterpret_cast<char *>(lds);
+  const int logical = logical_workgroup(g.tiles_i * g.tiles_j);
+  if (logical < 0) return;
+  const int tj = logical % g.tiles_j, tp = logical / g.tiles_j;
+  const int p0 = tp * 16, j0 = tj * 64;
+  const int nk = g.K >> 6;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, hw = tid >> 6;
+  const int L = c.L, Bp = c.Bp;
+
+  if (hw >= 4) {
+    // ------------------------------------------------------------------ loaders
+    // 28 wavefront-loads of 1 KB per slab (20 of A, 8 of B); loader lw takes loads lw, lw + 4, ...
+    const int lw = hw - 4;
+    const int lrow = lane >> 3;
+    const __bf16 *src[7];
+    long step[7];
+#pragma unroll
+    for (int u = 0; u < 7; ++u) {
+      const int grp = 4 * u + lw;
+      if (grp < 20) {
+        if (AT) {
+          // bytes 1024 grp + 16 lane of the slab: rows of 320 bytes (k), 16-byte pieces = (block, half)
+          const int o = 1024 * grp + 16 * lane;
+          const int k = o / 320, piece = (o % 320) >> 4;
+          const int blk = piece >> 1, pos = p0 + 8 * (piece & 1);
+          const bool ok = blk < L && pos < Bp;            // Bp is a multiple of 8 here: whole pieces are in or out
+          src[u] = g.A + (long)k * g.lda + (ok ? (long)blk * Bp + pos : 0);
+          step[u] = 64 * g.lda;
+        } else {
+          const int a = 8 * grp + lrow;                    // tile row
+          const int blk = a >> 4, pos = p0 + (a & 15);
+          const bool ok = blk < L && pos < Bp;
+          const int chunk = (lane & 7) ^ swizzle_of_row(a);
+          src[u] = g.A + (ok ? (long)blk * Bp + pos : 0) * g.lda + chunk * 8;
+          step[u] = 64;
+        }
+      } else {
+        const int row = 8 * (grp - 20) + lrow;
+        int j = j0 + row;
+        j = j < g.J ? j : g.J - 1;
+        const int chunk = (lane & 7) ^ swizzle_of_row(row);
+        src[u] = g.B + (long)j * g.ldb + chunk * 8;
+        step[u] = 64;
+      }
+    }
+    auto issue = [&](int kt) {
+#if CN_DEVICE_ASM
+      char *stage = lds_c + (kt % NS) * STAGE;
+#pragma unroll
+      for (int u = 0; u < 7; ++u)
+        __builtin_amdgcn_global_load_lds(src[u] + (long)kt * step[u], CN_LDS_PTR(stage + (4 * u + lw) * 1024), 16, 0, 0);
+#else
+      (void)kt;
+#endif
+    };
+#pragma unroll
+    for (int s = 0; s < NS - 1; ++s)
+      if (s < nk) issue(s);
+    for (int kt = 0; kt < nk; ++kt) {
+      const int later = nk - 1 - kt;
+      if (later >= 3) wait_vm<21>();
+      else if (later >= 2) wait_vm<14>();
+      else if (later >= 1) wait_vm<7>();
+      else wait_vm<0>();
+      __builtin_amdgcn_s_barrier();
+      if (kt + NS - 1 < nk) issue(kt + NS - 1);
+    }
+    // the epilogue's barriers: one before LDS is reused, one for the exchange, three per reduction round
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_s_barrier();
+#pragma unroll
+    for (int c0 = 0; c0 < 10 + NG; c0 += 16) {
+      __builtin_amdgcn_s_barrier();
+      __builtin_amdgcn_s_barrier();
+      __builtin_amdgcn_s_barrier();
+    }
+    return;
+  }
+
+  // ------------------------------------------------------------------ MFMA wavefronts
+  const int wi = hw & 1, wj = hw >> 1;
+  const int l16 = lane & 15, gq = lane >> 4;
+  // fragment addresses inside a stage for the two k-steps of a slab (block s5 adds 2048 / 32 bytes)
+  unsigned offA[2], offB[2];
+#pragma unroll
+  for (int ks = 0; ks < 2; ++ks) {
+    const unsigned slot = (unsigned)((((4 * ks + gq) ^ (l16 >> 1)) & 7) * 16);
+    offB[ks] = (unsigned)(A_BYTES + (32 * wj) * 128 + l16 * 128) + slot;
+    if (AT) offA[ks] = (unsigned)((32 * ks + 8 * gq + (l16 >> 2)) * 320 + (80 * wi + 4 * (l16 & 3)) * 2);
+    else offA[ks] = (unsigned)((80 * wi) * 128 + l16 * 128) + slot;
+  }
+  floatx4 acc[5][2];
+#pragma unroll
+  for (int s5 = 0; s5 < 5; ++s5)
+#pragma unroll
+    for (int bj = 0; bj < 2; ++bj) acc[s5][bj] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+  for (int kt = 0; kt < nk; ++kt) {
+    __builtin_amdgcn_s_barrier();
+    const unsigned sb = (unsigned)((kt % NS) * STAGE);
+    u32x4 fa[2][5], fb[2][2];
+    u32x2 alo[2][5], ahi[2][5];
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      const unsigned a = sb + offA[ks], b = sb + offB[ks];
+      if constexpr (AT) {
+        alo[ks][0] = lds_read_tr8<0>(a);   ahi[ks][0] = lds_read_tr8<1280>(a);
+        alo[ks][1] = lds_read_tr8<32>(a);  ahi[ks][1] = lds_read_tr8<1312>(a);
+        alo[ks][2] = lds_read_tr8<64>(a);  ahi[ks][2] = lds_read_tr8<1344>(a);
+        alo[ks][3] = lds_read_tr8<96>(a);  ahi[ks][3] = lds_read_tr8<1376>(a);
+        alo[ks][4] = lds_read_tr8<128>(a); ahi[ks][4] = lds_read_tr8<1408>(a);
+      } else {
+        fa[ks][0] = lds_read16<0>(a);
+        fa[ks][1] = lds_read16<2048>(a);
+        fa[ks][2] = lds_read16<4096>(a);
+        fa[ks][3] = lds_read16<6144>(a);
+        fa[ks][4] = lds_read16<8192>(a);
+      }
+      fb[ks][0] = lds_read16<0>(b);
+      fb[ks][1] = lds_read16<2048>(b);
+    }
+    constexpr int READS = AT ? 12 : 7;           // LDS reads of one k-step
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      if (ks == 0) wait_lgkm<READS>(); else wait_lgkm<0>();
+#pragma unroll
+      for (int s5 = 0; s5 < 5; ++s5) {
+        if constexpr (AT) {
+          pin(alo[ks][s5]); pin(ahi[ks][s5]);
+          fa[ks][s5] = u32x4{alo[ks][s5][0], alo[ks][s5][1], ahi[ks][s5][0], ahi[ks][s5][1]};
+        } else {
+          pin(fa[ks][s5]);
+        }
+      }
+      pin(fb[ks][0]); pin(fb[ks][1]);
+#pragma unroll
+      for (int s5 = 0; s5 < 5; ++s5)
+#pragma unroll
+        for (int bj = 0; bj < 2; ++bj)
+          acc[s5][bj] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, fb[ks][bj]),
+                                                               __builtin_bit_cast(bf16x8, fa[ks][s5]), acc[s5][bj], 0, 0, 0);
+    }
+  }
+  __builtin_amdgcn_s_barrier();                  // every wavefront is done with the operand stages
+
+  // element e of accumulator (s5, bj): block 5 wi + s5, position p0 + lane % 16,
+  // batch column j0 + 32 wj + 16 bj + 4 (lane / 16) + e
+  const int pos = p0 + l16;
+  float sq[5];
+  float ps[R][2][4];
+#pragma unroll
+  for (int k = 0; k < R; ++k)
+#pragma unroll
+    for (int bj = 0; bj < 2; ++bj)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) ps[k][bj][e] = 0.f;
+#pragma unroll
+  for (int s5 = 0; s5 < 5; ++s5) {
+    const int blk = 5 * wi + s5;
+    const bool row_ok = blk < L && pos < Bp;
+    float ssum = 0.f;
+#pragma unroll
+    for (int bj = 0; bj < 2; ++bj)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int j = j0 + 32 * wj + 16 * bj + 4 * gq + e;
+        const bool ok = row_ok && j < g.J;
+        const float v = ok ? acc[s5][bj][e] : 0.f;
+        if (ok) g.C[(long)j * g.ldc + (long)blk * Bp + pos] = v;
+        ssum = fmaf(v, v, ssum);
+#pragma unroll
+        for (int k = 0; k < R; ++k) ps[k][bj][e] = fmaf(c.Hf[k][blk < 10 ? blk : 9], v, ps[k][bj][e]);
+      }
+    sq[s5] = ssum;
+  }
+  // the halves of the syndromes meet: wavefronts with wi = 1 hand theirs over
+  float *const exch = reinterpret_cast<float *>(lds_c + 40960) + wj * (R * 8 * 64);
+  if (wi == 1) {
+#pragma unroll
+    for (int k = 0; k < R; ++k)
+#pragma unroll
+      for (int bj = 0; bj < 2; ++bj)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) exch[(k * 8 + bj * 4 + e) * 64 + lane] = ps[k][bj][e];
+  }
+  __syncthreads();
+  float gram[NG];
+#pragma unroll
+  for (int q = 0; q < NG; ++q) gram[q] = 0.f;
+  if (wi == 0) {
+#pragma unroll
+    for (int k = 0; k < R; ++k)
+#pragma unroll
+      for (int bj = 0; bj < 2; ++bj)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) ps[k][bj][e] += exch[(k * 8 + bj * 4 + e) * 64 + lane];
+#pragma unroll
+    for (int bj = 0; bj < 2; ++bj)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int j = j0 + 32 * wj + 16 * bj + 4 * gq + e;
+        if (pos < Bp && j < g.J) {
+#pragma unroll
+          for (int k = 0; k < R; ++k) c.syn[((long)k * g.J + j) * Bp + pos] = ps[k][bj][e];
+        }
+        int q = 0;
+#pragma unroll
+        for (int k = 0; k < R; ++k)
+#pragma unroll
+          for (int k2 = k; k2 < R; ++k2, ++q) gram[q] = fmaf(ps[k][bj][e], ps[k2][bj][e], gram[q]);
+      }
+  }
+  // The workgroup's record: ten block norms, then the Gram entries; float64, a 16 x 16 tree per
+  // entry over the 256 lanes of the MFMA wavefronts, the same order on every run.
+  double (*red)[256] = reinterpret_cast<double (*)[256]>(lds_c);
+  double (*red2)[16] = reinterpret_cast<double (*)[16]>(lds_c + 16 * 256 * 8);
+#pragma unroll
+  for (int c0 = 0; c0 < 10 + NG; c0 += 16) {
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      const int en = c0 + u;                       // compile-time after unrolling
+      float v = 0.f;
+      if (en < 10) v = (en / 5 == wi) ? sq[en % 5] : 0.f;
+      else if (en - 10 < NG) v = wi == 0 ? gram[en - 10 < NG ? en - 10 : 0] : 0.f;
+      red[u][tid] = (double)v;
+    }
+    __syncthreads();
+    {
+      const int u = tid >> 4, part = tid & 15;
+      double a = 0.0;
+#pragma unroll
+      for (int q = 0; q < 16; ++q) a += red[u][part + 16 * q];
+      red2[u][part] = a;
+    }
+    __syncthreads();
+    if (tid < 16 && c0 + tid < 10 + NG) {
+      double a = 0.0;
+#pragma unroll
+      for (int q = 0; q < 16; ++q) a += red2[tid][q];
+      const int en = c0 + tid;
+      const int entry = en < 10 ? en : CODENET_MAX_L + (en - 10);
+      if (en >= 10 || en < L) c.partials[(long)entry * kDetectParts + logical] = a;
+    }
+    __syncthreads();
+  }
 }
 
 // out = sum over splits of the partial results, in split order
@@ -956,6 +1237,43 @@ hipError_t launch_product(Gemm2Args g, hipStream_t s) {
   if (g.a_k_major) hipLaunchKernelGGL(product_kernel<true>, grid, dim3(512), lds, s, g);
   else hipLaunchKernelGGL(product_kernel<false>, grid, dim3(512), lds, s, g);
   return hipGetLastError();
+}
+
+// Whether launch_product_check takes a product: whole codewords of at most ten blocks in a tile, at
+// most four parity blocks, block pitch a multiple of 8 (the k-major operand is gathered in 16-byte
+// pieces), one record per tile within the check's record buffer.
+bool product_check_fits(int L, int Bp, int r, int J) {
+  if (L < 1 || L > 10 || r < 1 || r > 4 || (Bp & 7) || J < 1) return false;
+  const long tiles = (long)((Bp + 15) / 16) * ((J + 63) / 64);
+  return tiles <= kDetectParts;
+}
+
+// C = A B^T as launch_product, on tiles of whole codewords, with the pass-1 records of the check
+// and the syndromes left behind (*n_parts records).
+hipError_t launch_product_check(Gemm2Args g, CheckArgs c, int *n_parts, hipStream_t s) {
+  if ((g.K & 63) || (g.lda & 7) || (g.ldb & 7) || (g.ldc & 3) || !product_check_fits(c.L, c.Bp, c.r, g.J) ||
+      g.I != c.L * c.Bp)
+    return hipErrorInvalidValue;
+  constexpr int lds = 5 * (160 + 64) * 128;
+  g.tiles_i = (c.Bp + 15) / 16;
+  g.tiles_j = (g.J + 63) / 64;
+  const int total = g.tiles_i * g.tiles_j;
+  *n_parts = total;
+  const dim3 grid((unsigned)(((total + 7) / 8) * 8));
+#define CODENET_PC(ATV, RV)                                                                            \
+  {                                                                                                    \
+    static LdsOnce once;                                                                               \
+    hipError_t e = allow_lds(product_check_kernel<ATV, RV>, lds, &once);                               \
+    if (e != hipSuccess) return e;                                                                     \
+    hipLaunchKernelGGL((product_check_kernel<ATV, RV>), grid, dim3(512), lds, s, g, c);                \
+    return hipGetLastError();                                                                          \
+  }
+  if (g.a_k_major) {
+    switch (c.r) { case 1: CODENET_PC(true, 1) case 2: CODENET_PC(true, 2) case 3: CODENET_PC(true, 3) default: CODENET_PC(true, 4) }
+  } else {
+    switch (c.r) { case 1: CODENET_PC(false, 1) case 2: CODENET_PC(false, 2) case 3: CODENET_PC(false, 3) default: CODENET_PC(false, 4) }
+  }
+#undef CODENET_PC
 }
 
 hipError_t launch_reduce_partials(const float *part, long stride, int splits, float *out, long count, hipStream_t s) {

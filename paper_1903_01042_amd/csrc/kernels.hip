@@ -752,7 +752,7 @@ template <bool GENERIC, bool VERIFY>
 __global__ __launch_bounds__(256) void finish_kernel(float *__restrict__ out, const float *__restrict__ syn,
                                                      const double *__restrict__ partials, int n_parts,
                                                      const DevCode *__restrict__ code, int b,
-                                                     float *__restrict__ decoded, int aligned,
+                                                     float *__restrict__ decoded, int aligned, int in_place,
                                                      codenet_report *__restrict__ report, int epi,
                                                      const float *__restrict__ aux, VerifyArgs ver, Geometry geo) {
   __shared__ DevPlan plan;
@@ -807,7 +807,10 @@ __global__ __launch_bounds__(256) void finish_kernel(float *__restrict__ out, co
     __syncthreads();
   }
   const int corrected = plan.verdict == CODENET_CORRECTED ? plan.n_located : 0;
-  if (corrected == 0 && decoded == nullptr) return;
+  // in_place: the caller reads the systematic part where it is (decoded is null then); only an
+  // elementwise step still has work to do on a clean output
+  const bool act_in_place = in_place && epi != CODENET_EPI_NONE;
+  if (corrected == 0 && decoded == nullptr && !act_in_place) return;
   const int quads = B >> 2;
   const long idx = (long)blockIdx.x * 256 + threadIdx.x;
   if (idx >= (long)b * quads) return;
@@ -827,8 +830,8 @@ __global__ __launch_bounds__(256) void finish_kernel(float *__restrict__ out, co
     v.x -= e.x; v.y -= e.y; v.z -= e.z; v.w -= e.w;
     *reinterpret_cast<float4 *>(row + i * B) = v;
   }
-  if (decoded == nullptr) return;
-  float *dst = decoded + (long)beta * N;
+  if (decoded == nullptr && !act_in_place) return;
+  float *dst = decoded ? decoded + (long)beta * N : nullptr;
   const float *ax = aux ? aux + (long)beta * N : nullptr;
   // the elementwise primary step that follows the product, applied to the decoded copy only:
   // activation f = ReLU (feedforward), or the diagonal post-multiplication by g(x) (backpropagation)
@@ -838,6 +841,20 @@ __global__ __launch_bounds__(256) void finish_kernel(float *__restrict__ out, co
     if (epi == CODENET_EPI_MUL) return v * ax[g];
     return v;
   };
+  if (act_in_place) {
+    // the elementwise step on the real entries of the systematic blocks, where they are
+    for (int i = 0; i < a; ++i) {
+      float4 v = *reinterpret_cast<const float4 *>(row + i * B);
+      float vv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int g = i * B0 + rho + e;
+        if (rho + e < B0 && g < N) vv[e] = act(vv[e], g);
+      }
+      *reinterpret_cast<float4 *>(row + i * B) = make_float4(vv[0], vv[1], vv[2], vv[3]);
+    }
+    return;
+  }
   // eight blocks at a time: all loads first, then the stores (one block at a time would
   // expose a load latency per block)
   for (int i0 = 0; i0 < a; i0 += 8) {
@@ -916,12 +933,14 @@ long finish_workgroups(const DevCode &ch, int b, bool verified) {
 hipError_t launch_finish(float *out, const float *syn, const double *partials, int n_parts, const DevCode *code_dev,
                          const DevCode &ch, int b, float *decoded, codenet_report *report, int epi, const float *aux,
                          const VerifyArgs *ver, hipStream_t s) {
+  const int in_place = decoded != nullptr && decoded == out;
+  if (in_place) decoded = nullptr;
   const int aligned = (ch.N % 4 == 0) && (ch.B0 % 4 == 0) && ((reinterpret_cast<uintptr_t>(decoded) & 15) == 0);
   dim3 grid((unsigned)finish_workgroups(ch, b, ver != nullptr)), block(256);
   const VerifyArgs none{};
 #define CODENET_FINISH(GEN, VER)                                                                                    \
   hipLaunchKernelGGL((finish_kernel<GEN, VER>), grid, block, 0, s, out, syn, partials, n_parts, code_dev, b, decoded, \
-                     aligned, report, epi, aux, ver ? *ver : none, geometry_of(ch))
+                     aligned, in_place, report, epi, aux, ver ? *ver : none, geometry_of(ch))
   if (ver) {
     if (ch.r >= 4) CODENET_FINISH(true, true); else CODENET_FINISH(false, true);
   } else {

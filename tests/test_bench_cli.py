@@ -88,7 +88,7 @@ def test_the_strategy_comparison_leg():
     """CodeNet, replication and uncoded on the cfg2 network for 20 iterations each: CodeNet and
     replication end with the weights of a run without errors (to float32 accuracy / exactly), uncoded
     does not; the expected-time model is quoted both ways next to the measured times."""
-    p = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--strategies", "--steps", "20", "--fault-p", "0.004"],
+    p = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--strategies", "--steps", "20", "--fault-p", "0.0015"],
                        capture_output=True, text=True, timeout=600, cwd=ROOT)
     assert p.returncode == 0, p.stderr[-2000:]
     d = json.loads([l for l in p.stdout.splitlines() if l.strip()][0])
