@@ -29,7 +29,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
-SAMPLED_STEPS = 8          # timed steps on which a kernel is bracketed, whatever --steps is
+SAMPLED_STEPS = 8          # timed steps on which a kernel is bracketed (4 in runs of fewer than 64 steps)
 PREWARM_SECONDS = 0.3      # untimed steps before the warm-up: the chip reaches its steady clocks
 
 
@@ -203,14 +203,13 @@ class Runner:
         self.stamps = torch.zeros((steps + warmup, 2), dtype=torch.int64, device="cuda:0")
         self.product_stamps = torch.zeros((steps + warmup, 4), dtype=torch.int64, device="cuda:0")
         self.ticks_per_us = ctypes.c_int(0)
-        self.prewarm_steps = self.prewarm(stream, prewarm_seconds) if (eager and prewarm_seconds > 0) else 0
         if not eager:
             self.capture(steps + warmup)
         # plain stream: the update sits between two HIP events on SAMPLED_STEPS steps of the timed region, between
         # two device time stamps on as many others, and on a third set the products are stamped
         # (short runs: fewer of the other two kinds, every bracket costs the step a few microseconds)
         few = 2 if steps < 64 else SAMPLED_STEPS
-        event_steps = set(sampled(steps, warmup)) if eager else set()
+        event_steps = set(sampled(steps, warmup, SAMPLED_STEPS if steps >= 64 else 4)) if eager else set()
         rest = [s for s in range(warmup, warmup + steps) if s not in event_steps] if eager else []
         product_steps = {rest[i] for i in sampled(len(rest), 0, 2 * few)} if rest else set()
         rest = [s for s in rest if s not in product_steps]
@@ -268,9 +267,6 @@ class Runner:
             if self.split(s):
                 timed_update(s)
 
-        for s in range(warmup):
-            one(s)
-        torch.cuda.synchronize()
         # what a pair of event records reads with nothing between them (their own cost on this stream)
         pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(20)]
         for a, b in pairs:
@@ -278,6 +274,13 @@ class Runner:
             b.record()
         torch.cuda.synchronize()
         self.event_pair_ms = float(np.median([a.elapsed_time(b) for a, b in pairs]))
+        # The untimed steps come last before the warm-up, with nothing but the warm-up's closing
+        # synchronization between them and the timed region: the set-up above leaves the GPU idle for
+        # milliseconds, and what runs right after an idle stretch runs at lower clocks.
+        self.prewarm_steps = self.prewarm(stream, prewarm_seconds) if (eager and prewarm_seconds > 0) else 0
+        for s in range(warmup):
+            one(s)
+        torch.cuda.synchronize()
         t0 = time.perf_counter()
         for s in range(steps):
             one(warmup + s)

@@ -194,9 +194,10 @@ int codenet_inject_noalloc(codenet_layer *layer, const codenet_fault *faults_hos
  * coded_out_dev -- and a clean check writes nothing at all); any other overlap of
  * the two buffers is not allowed.  report_dev: written by the GPU; may be NULL.
  *
- * Where the consistency checks are evaluated.  In the bf16 mode, for codes of at most ten
- * blocks and four parity blocks, the coded product computes them in its epilogue, while the
- * outputs of a codeword still sit side by side in registers, and leaves them with the layer;
+ * Where the consistency checks are evaluated.  In the bf16 mode, for row codes of at most ten
+ * blocks and four parity blocks, the coded forward product computes them in its epilogue, while
+ * the outputs of a codeword still sit side by side in registers, and leaves them with the layer
+ * (the backward product reads the matrix the other way and does not);
  * this call then starts from them instead of reading the output again.  They are used only if
  * coded_out_dev is the buffer that the layer's last product of this phase wrote, with the same
  * b, and no codenet_inject or check has touched it since (both discard them, as does a

@@ -286,12 +286,10 @@ int codenet_encode(const codenet_desc *d, const float *W_dev, void *stream, code
     l->ldT = pitch(l->bpad);
     alloc((void **)&l->XTb, 2 * (size_t)l->Nc * l->ldT);
     alloc((void **)&l->DTb, 2 * (size_t)l->Mr * l->ldT);
-    for (int ph = 0; ph < 2; ++ph) {
-      const DevCode &cd = ph == 0 ? l->code_r : l->code_c;
-      if (product_check_fits(cd.L, cd.B, cd.r, 1)) {
-        alloc((void **)&l->syn_p[ph], sizeof(float) * (size_t)cd.r * mb * cd.B);
-        alloc((void **)&l->partials_p[ph], sizeof(double) * (size_t)kDetectParts * kMaxEntries);
-      }
+    // Only the forward product (k contiguous in both operands) can leave the check's records behind.
+    if (product_check_fits(l->code_r.L, l->code_r.B, l->code_r.r, 1)) {
+      alloc((void **)&l->syn_p[CODENET_FWD], sizeof(float) * (size_t)l->code_r.r * mb * l->code_r.B);
+      alloc((void **)&l->partials_p[CODENET_FWD], sizeof(double) * (size_t)kDetectParts * kMaxEntries);
     }
     alloc((void **)&l->Wb, szWb);
     alloc((void **)&l->Xb, szXb);
@@ -340,12 +338,13 @@ int codenet_layer_geometry(const codenet_layer *l, int *B_r, int *B_c, int *code
 
 namespace {
 // The bf16 product of a phase: on tiles of whole codewords with the check's first pass in the
-// epilogue where the code fits that kernel, else the plain product (the check then reads the output).
+// epilogue where the operand layout and the code fit that kernel (the forward product), else the
+// plain product (the check then reads the output).
 int bf16_product(codenet_layer *l, int phase, Gemm2Args g2, const float *out, int b, hipStream_t s) {
   const DevCode &cd = phase == CODENET_FWD ? l->code_r : l->code_c;
   l->rec_out[phase] = nullptr;
   if (l->stamps) CN_HIP(launch_timestamp(l->stamps + 2 * phase, s));
-  if (l->syn_p[phase] && product_check_fits(cd.L, cd.B, cd.r, b)) {
+  if (l->syn_p[phase] && !g2.a_k_major && product_check_fits(cd.L, cd.B, cd.r, b)) {
     CheckArgs c{};
     c.syn = l->syn_p[phase];
     c.partials = l->partials_p[phase];

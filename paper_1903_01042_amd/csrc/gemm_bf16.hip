@@ -421,12 +421,21 @@ __global__ __launch_bounds__(512) void product_kernel(Gemm2Args g) {
 // 16 x 64 complete codewords.  With L = 10 blocks of 512 positions and a batch of 512 that is
 // 32 x 8 = 256 tiles: one per compute unit, none idle.  Eight wavefronts: four issue MFMAs
 // (v_mfma_f32_16x16x32_bf16, 2 x 2 wavefronts of 80 rows x 32 columns: five blocks times two
-// column groups = ten accumulators), four only issue the direct-to-LDS loads.  What limits this
-// product is the 64 bytes per clock at which a compute unit takes data in (measured: 57 B/clk
-// with 28 KB per wavefront in flight): (160 + 64) x 128 bytes per 64-deep slab are 500 clocks,
-// the ten MFMAs of a wavefront and k-step 160 clocks, 320 per slab -- MFMAs, loads and LDS
-// fragment reads run concurrently without slowing each other (measured with a kernel that
-// only issues them), so the MFMA wavefronts simply read a slab's fragments after its barrier.
+// column groups = ten accumulators), four only issue the direct-to-LDS loads.
+//
+// What bounds the main loop (measured on this kernel and on kernels that issue only one kind of
+// instruction): a compute unit takes direct-to-LDS data at up to 57 bytes per clock, MFMAs, these
+// loads and LDS fragment reads run side by side without slowing each other, and the MFMAs of a
+// 64-deep slab are 320 clocks per wavefront -- yet a slab takes about 650 clocks, with or without
+// the MFMAs.  The period is the loaded latency of a slab's loads divided by the slabs in flight
+// (NS - 1 = 4 stages of 28 KB, all the LDS that the epilogue leaves), so the loop is bound by bytes
+// in flight per compute unit, not by a pipe.  Reading the fragments one k-step ahead, across the
+// barrier, is kept because it costs nothing; it gained nothing either.
+//
+// Only the product with k contiguous in both operands runs here.  The backward product reads
+// the row-major matrix k-major: gathering this tile's rows from it takes 32-byte pieces (three
+// times the L2 requests) and the transposing LDS reads then conflict two ways; measured at twice
+// the time of product_kernel<true> plus detect_kernel, which that product therefore keeps.
 //
 // Epilogue: the accumulators are stored as the coded output and, from the same registers, each
 // lane forms its share of the r syndromes (a lane holds one position of five blocks for four
@@ -434,10 +443,8 @@ __global__ __launch_bounds__(512) void product_kernel(Gemm2Args g) {
 // LDS), writes them for the correction pass, and the workgroup leaves one record of partial sums
 // -- squared norms of the blocks, Gram matrix of the syndromes, float64, fixed order -- exactly
 // what detect_kernel leaves per workgroup.  The decision kernel then runs on these records.
-// AT: the A operand stored k-major (the backward product), tile columns gathered as 32-byte
-// pieces, fragments through the transposing LDS read.
 // ---------------------------------------------------------------------------
-template <bool AT, int R>
+template <int R>
 __global__ __launch_bounds__(512) void product_check_kernel(Gemm2Args g, CheckArgs c) {
   constexpr int NS = 5;
   constexpr int A_BYTES = 160 * 128, STAGE = A_BYTES + 64 * 128;      // 28 KB
@@ -459,34 +466,21 @@ __global__ __launch_bounds__(512) void product_check_kernel(Gemm2Args g, CheckAr
     const int lw = hw - 4;
     const int lrow = lane >> 3;
     const __bf16 *src[7];
-    long step[7];
 #pragma unroll
     for (int u = 0; u < 7; ++u) {
       const int grp = 4 * u + lw;
       if (grp < 20) {
-        if (AT) {
-          // bytes 1024 grp + 16 lane of the slab: rows of 320 bytes (k), 16-byte pieces = (block, half)
-          const int o = 1024 * grp + 16 * lane;
-          const int k = o / 320, piece = (o % 320) >> 4;
-          const int blk = piece >> 1, pos = p0 + 8 * (piece & 1);
-          const bool ok = blk < L && pos < Bp;            // Bp is a multiple of 8 here: whole pieces are in or out
-          src[u] = g.A + (long)k * g.lda + (ok ? (long)blk * Bp + pos : 0);
-          step[u] = 64 * g.lda;
-        } else {
-          const int a = 8 * grp + lrow;                    // tile row
-          const int blk = a >> 4, pos = p0 + (a & 15);
-          const bool ok = blk < L && pos < Bp;
-          const int chunk = (lane & 7) ^ swizzle_of_row(a);
-          src[u] = g.A + (ok ? (long)blk * Bp + pos : 0) * g.lda + chunk * 8;
-          step[u] = 64;
-        }
+        const int a = 8 * grp + lrow;                    // tile row
+        const int blk = a >> 4, pos = p0 + (a & 15);
+        const bool ok = blk < L && pos < Bp;
+        const int chunk = (lane & 7) ^ swizzle_of_row(a);
+        src[u] = g.A + (ok ? (long)blk * Bp + pos : 0) * g.lda + chunk * 8;
       } else {
         const int row = 8 * (grp - 20) + lrow;
         int j = j0 + row;
         j = j < g.J ? j : g.J - 1;
         const int chunk = (lane & 7) ^ swizzle_of_row(row);
         src[u] = g.B + (long)j * g.ldb + chunk * 8;
-        step[u] = 64;
       }
     }
     auto issue = [&](int kt) {
@@ -494,7 +488,7 @@ __global__ __launch_bounds__(512) void product_check_kernel(Gemm2Args g, CheckAr
       char *stage = lds_c + (kt % NS) * STAGE;
 #pragma unroll
       for (int u = 0; u < 7; ++u)
-        __builtin_amdgcn_global_load_lds(src[u] + (long)kt * step[u], CN_LDS_PTR(stage + (4 * u + lw) * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(src[u] + (long)kt * 64, CN_LDS_PTR(stage + (4 * u + lw) * 1024), 16, 0, 0);
 #else
       (void)kt;
 #endif
@@ -532,8 +526,7 @@ __global__ __launch_bounds__(512) void product_check_kernel(Gemm2Args g, CheckAr
   for (int ks = 0; ks < 2; ++ks) {
     const unsigned slot = (unsigned)((((4 * ks + gq) ^ (l16 >> 1)) & 7) * 16);
     offB[ks] = (unsigned)(A_BYTES + (32 * wj) * 128 + l16 * 128) + slot;
-    if (AT) offA[ks] = (unsigned)((32 * ks + 8 * gq + (l16 >> 2)) * 320 + (80 * wi + 4 * (l16 & 3)) * 2);
-    else offA[ks] = (unsigned)((80 * wi) * 128 + l16 * 128) + slot;
+    offA[ks] = (unsigned)((80 * wi) * 128 + l16 * 128) + slot;
   }
   floatx4 acc[5][2];
 #pragma unroll
@@ -541,51 +534,43 @@ __global__ __launch_bounds__(512) void product_check_kernel(Gemm2Args g, CheckAr
 #pragma unroll
     for (int bj = 0; bj < 2; ++bj) acc[s5][bj] = floatx4{0.f, 0.f, 0.f, 0.f};
 
+  // Fragments are read one k-step ahead of the MFMAs that use them, across the slab boundary as well.
+  u32x4 fa[2][5], fb[2][2];
+  constexpr int READS = 7;                       // LDS reads of one k-step
+  auto read_step = [&](unsigned sb, int ks) {
+    const unsigned a = sb + offA[ks], b = sb + offB[ks];
+    fa[ks][0] = lds_read16<0>(a);
+    fa[ks][1] = lds_read16<2048>(a);
+    fa[ks][2] = lds_read16<4096>(a);
+    fa[ks][3] = lds_read16<6144>(a);
+    fa[ks][4] = lds_read16<8192>(a);
+    fb[ks][0] = lds_read16<0>(b);
+    fb[ks][1] = lds_read16<2048>(b);
+  };
+  auto mfma_step = [&](int ks) {
+#pragma unroll
+    for (int s5 = 0; s5 < 5; ++s5) pin(fa[ks][s5]);
+    pin(fb[ks][0]); pin(fb[ks][1]);
+#pragma unroll
+    for (int s5 = 0; s5 < 5; ++s5)
+#pragma unroll
+      for (int bj = 0; bj < 2; ++bj)
+        acc[s5][bj] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, fb[ks][bj]),
+                                                             __builtin_bit_cast(bf16x8, fa[ks][s5]), acc[s5][bj], 0, 0, 0);
+  };
+  __builtin_amdgcn_s_barrier();                  // slab 0 has landed
+  read_step(0u, 0);
   for (int kt = 0; kt < nk; ++kt) {
-    __builtin_amdgcn_s_barrier();
     const unsigned sb = (unsigned)((kt % NS) * STAGE);
-    u32x4 fa[2][5], fb[2][2];
-    u32x2 alo[2][5], ahi[2][5];
-#pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-      const unsigned a = sb + offA[ks], b = sb + offB[ks];
-      if constexpr (AT) {
-        alo[ks][0] = lds_read_tr8<0>(a);   ahi[ks][0] = lds_read_tr8<1280>(a);
-        alo[ks][1] = lds_read_tr8<32>(a);  ahi[ks][1] = lds_read_tr8<1312>(a);
-        alo[ks][2] = lds_read_tr8<64>(a);  ahi[ks][2] = lds_read_tr8<1344>(a);
-        alo[ks][3] = lds_read_tr8<96>(a);  ahi[ks][3] = lds_read_tr8<1376>(a);
-        alo[ks][4] = lds_read_tr8<128>(a); ahi[ks][4] = lds_read_tr8<1408>(a);
-      } else {
-        fa[ks][0] = lds_read16<0>(a);
-        fa[ks][1] = lds_read16<2048>(a);
-        fa[ks][2] = lds_read16<4096>(a);
-        fa[ks][3] = lds_read16<6144>(a);
-        fa[ks][4] = lds_read16<8192>(a);
-      }
-      fb[ks][0] = lds_read16<0>(b);
-      fb[ks][1] = lds_read16<2048>(b);
+    read_step(sb, 1);
+    wait_lgkm<READS>();                          // LDS returns in order: the first k-step's fragments are in
+    mfma_step(0);
+    wait_lgkm<0>();                              // all of this wavefront's reads of slab kt are done
+    if (kt + 1 < nk) {
+      __builtin_amdgcn_s_barrier();              // slab kt + 1 has landed; the loaders may refill the stage of slab kt
+      read_step((unsigned)(((kt + 1) % NS) * STAGE), 0);
     }
-    constexpr int READS = AT ? 12 : 7;           // LDS reads of one k-step
-#pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-      if (ks == 0) wait_lgkm<READS>(); else wait_lgkm<0>();
-#pragma unroll
-      for (int s5 = 0; s5 < 5; ++s5) {
-        if constexpr (AT) {
-          pin(alo[ks][s5]); pin(ahi[ks][s5]);
-          fa[ks][s5] = u32x4{alo[ks][s5][0], alo[ks][s5][1], ahi[ks][s5][0], ahi[ks][s5][1]};
-        } else {
-          pin(fa[ks][s5]);
-        }
-      }
-      pin(fb[ks][0]); pin(fb[ks][1]);
-#pragma unroll
-      for (int s5 = 0; s5 < 5; ++s5)
-#pragma unroll
-        for (int bj = 0; bj < 2; ++bj)
-          acc[s5][bj] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, fb[ks][bj]),
-                                                               __builtin_bit_cast(bf16x8, fa[ks][s5]), acc[s5][bj], 0, 0, 0);
-    }
+    mfma_step(1);
   }
   __builtin_amdgcn_s_barrier();                  // every wavefront is done with the operand stages
 
@@ -1240,18 +1225,17 @@ hipError_t launch_product(Gemm2Args g, hipStream_t s) {
 }
 
 // Whether launch_product_check takes a product: whole codewords of at most ten blocks in a tile, at
-// most four parity blocks, block pitch a multiple of 8 (the k-major operand is gathered in 16-byte
-// pieces), one record per tile within the check's record buffer.
+// most four parity blocks, one record per tile within the check's record buffer.
 bool product_check_fits(int L, int Bp, int r, int J) {
-  if (L < 1 || L > 10 || r < 1 || r > 4 || (Bp & 7) || J < 1) return false;
+  if (L < 1 || L > 10 || r < 1 || r > 4 || Bp < 1 || J < 1) return false;
   const long tiles = (long)((Bp + 15) / 16) * ((J + 63) / 64);
   return tiles <= kDetectParts;
 }
 
-// C = A B^T as launch_product, on tiles of whole codewords, with the pass-1 records of the check
-// and the syndromes left behind (*n_parts records).
+// C = A B^T as launch_product (k contiguous in both operands only), on tiles of whole codewords,
+// with the pass-1 records of the check and the syndromes left behind (*n_parts records).
 hipError_t launch_product_check(Gemm2Args g, CheckArgs c, int *n_parts, hipStream_t s) {
-  if ((g.K & 63) || (g.lda & 7) || (g.ldb & 7) || (g.ldc & 3) || !product_check_fits(c.L, c.Bp, c.r, g.J) ||
+  if ((g.K & 63) || (g.lda & 7) || (g.ldb & 7) || g.a_k_major || !product_check_fits(c.L, c.Bp, c.r, g.J) ||
       g.I != c.L * c.Bp)
     return hipErrorInvalidValue;
   constexpr int lds = 5 * (160 + 64) * 128;
@@ -1260,19 +1244,15 @@ hipError_t launch_product_check(Gemm2Args g, CheckArgs c, int *n_parts, hipStrea
   const int total = g.tiles_i * g.tiles_j;
   *n_parts = total;
   const dim3 grid((unsigned)(((total + 7) / 8) * 8));
-#define CODENET_PC(ATV, RV)                                                                            \
+#define CODENET_PC(RV)                                                                                 \
   {                                                                                                    \
     static LdsOnce once;                                                                               \
-    hipError_t e = allow_lds(product_check_kernel<ATV, RV>, lds, &once);                               \
+    hipError_t e = allow_lds(product_check_kernel<RV>, lds, &once);                                    \
     if (e != hipSuccess) return e;                                                                     \
-    hipLaunchKernelGGL((product_check_kernel<ATV, RV>), grid, dim3(512), lds, s, g, c);                \
+    hipLaunchKernelGGL((product_check_kernel<RV>), grid, dim3(512), lds, s, g, c);                     \
     return hipGetLastError();                                                                          \
   }
-  if (g.a_k_major) {
-    switch (c.r) { case 1: CODENET_PC(true, 1) case 2: CODENET_PC(true, 2) case 3: CODENET_PC(true, 3) default: CODENET_PC(true, 4) }
-  } else {
-    switch (c.r) { case 1: CODENET_PC(false, 1) case 2: CODENET_PC(false, 2) case 3: CODENET_PC(false, 3) default: CODENET_PC(false, 4) }
-  }
+  switch (c.r) { case 1: CODENET_PC(1) case 2: CODENET_PC(2) case 3: CODENET_PC(3) default: CODENET_PC(4) }
 #undef CODENET_PC
 }
 

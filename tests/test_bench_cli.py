@@ -55,7 +55,7 @@ def test_the_bench_line_keeps_its_contract():
     c = d["cpu_baseline"]
     assert c["kind"] == "oracle" and c["cores"] >= 1 and c["value"] > 0 and c["unit"] == d["unit"] and c["sample"]
     assert sum(d["verdicts"].values()) == 60 and d["verified_checks_agree"] is True
-    assert r["avg_launch_samples"] >= 8                      # the dominant kernel is bracketed on 8 timed steps at least
+    assert r["avg_launch_samples"] >= 4                      # the dominant kernel is bracketed on 4 timed steps of a short run (8 of a long one)
     p = d["roofline_products"]                               # the coded GEMMs against the MFMA peak of their arithmetic
     assert p["bound"] == "mfma" and p["unit"] == "TFLOP/s" and p["peak"] == 2500.0 and p["samples"] >= 2
     assert abs(p["frac"] - p["achieved"] / p["peak"]) < 1e-9 and 0.02 < p["frac"] < 1.0

@@ -894,24 +894,26 @@ def test_verified_check_agrees_or_reports_the_disagreement(n_out, n_in, m, n, r,
 
 # ------------------------------------------------------------------ checks evaluated in the product's epilogue
 def test_checks_taken_in_the_product_epilogue():
-    """bf16 layers whose code fits the codeword-interleaved product kernel (at most ten blocks, four
-    parity blocks, block pitch a multiple of 8) evaluate the consistency checks in the product's
-    epilogue; the check call then starts from those records.  Same verdicts, syndromes' effect and
-    outputs as the stand-alone first pass (which a second layer is forced to use by checking a copy of
-    the output in another buffer); records are dropped by injection and by a check; a buffer changed
-    behind the library's back needs codenet_output_modified(); the decoded output may stay in place."""
+    """bf16 layers whose row code fits the codeword-interleaved product kernel (at most ten blocks,
+    four parity blocks) evaluate the consistency checks of the forward product in its epilogue; the
+    check call then starts from those records.  Same verdicts, syndromes' effect and outputs as the
+    stand-alone first pass (which is forced by checking a copy of the output in another buffer);
+    records are dropped by injection and by a check; a buffer changed behind the library's back needs
+    codenet_output_modified(); the decoded output may stay in place.  The backward product leaves no
+    records: its check always reads the output."""
     import torch
     from paper_1903_01042_amd import binding as B
-    for (n_out, n_in, m, n, r, b) in ((512, 384, 8, 6, 2, 96), (192, 320, 3, 5, 4, 70), (1024, 1024, 8, 8, 2, 200)):
+    for (n_out, n_in, m, n, r, b) in ((512, 384, 8, 6, 2, 96), (192, 320, 3, 5, 4, 70), (1024, 1024, 8, 8, 2, 200),
+                                      (200, 150, 8, 6, 2, 130), (77, 90, 7, 3, 1, 64)):
         say("fused checks", n_out, n_in, m, n, r, b)
         P_r = WL.vandermonde_like(m, r) if r <= 2 else WL.gaussian_generator(m, r, 8)
         P_c = WL.vandermonde_like(n, r) if r <= 2 else WL.gaussian_generator(n, r, 9)
         pair = Pair(WL.layer_weights(n_out, n_in), P_r, P_c, "bf16", b, 2e-2, 2e-2)
         lay = pair.gpu
-        assert lay.B_r % 8 == 0 and lay.B_c % 8 == 0
         X, D = WL.normal((b, n_in), 61), WL.normal((b, n_out), 62)
         # through the harness: clean products use the epilogue's records, faulty ones the stand-alone pass
-        for faults_f, faults_b in (((), ()), ([WL.make_fault(FWD, 1, 0, 3)], [WL.make_fault(BWD, 0, n, 3)]), ((), ())):
+        campaign = (((), ()), ([WL.make_fault(FWD, 1, 0, 3)], [WL.make_fault(BWD, 0, n, 3)]), ((), ()))
+        for faults_f, faults_b in (campaign if r >= 2 else campaign[:1]):
             pair.product(FWD, X, faults_f, check_margins=True if r <= 2 else 2.0)
             pair.product(BWD, D, faults_b, check_margins=True if r <= 2 else 2.0)
             pair.update(0.02)
@@ -931,17 +933,19 @@ def test_checks_taken_in_the_product_epilogue():
             blk = lay.B_r if phase == FWD else lay.B_c
             out = lay.forward(Vd) if phase == FWD else lay.backward(Vd)
             out[:, blk:2 * blk] += 5.0 * out[:, blk:2 * blk].std()
-            lay.detect_decode(phase, out, report=rep_a, want_decoded=False)
-            assert lay.read_report(rep_a)["verdict"] == CLEAN                 # stale records: documented hazard
+            want = CORRECTED if r >= 2 else UNCORRECTABLE
+            if phase == FWD:
+                lay.detect_decode(phase, out, report=rep_a, want_decoded=False)
+                assert lay.read_report(rep_a)["verdict"] == CLEAN             # stale records: documented hazard
             lay.detect_decode(phase, out, report=rep_a, want_decoded=False)   # the records are gone after one check
             got = lay.read_report(rep_a)
-            assert got["verdict"] == CORRECTED and got["located"] == [1]
+            assert got["verdict"] == want and (r < 2 or got["located"] == [1])
             out = lay.forward(Vd) if phase == FWD else lay.backward(Vd)
             out[:, blk:2 * blk] += 5.0 * out[:, blk:2 * blk].std()
             lay.output_modified(phase)
             lay.detect_decode(phase, out, report=rep_a, want_decoded=False)
             got = lay.read_report(rep_a)
-            assert got["verdict"] == CORRECTED and got["located"] == [1]
+            assert got["verdict"] == want and (r < 2 or got["located"] == [1])
             # decoded in place: nothing copied; with ReLU the systematic part is rectified where it is
             out = lay.forward(Vd) if phase == FWD else lay.backward(Vd)
             ref = out.clone()
