@@ -969,7 +969,8 @@ def main():
         "verdicts": counts,
         "update_kernel_ms_uncoded": upd_ms_unc if args.graph else uncoded.upd_ms_events,
         "roofline": {"kernel": "update3_kernel (W~ += eta [d;d~][x;x~]^T, fp32 RMW + bf16 copy)"
-                     if wl.dtype == "bf16" else "gemm_kernel (update, W~ += eta [d;d~][x;x~]^T)", "bound": "hbm",
+                     if wl.dtype == "bf16" else ("update_thin_kernel" if wl.batch <= 256 and min(L.coded_rows, L.coded_cols) >= 1024
+                                                 else "gemm_kernel") + " (update, W~ += eta [d;d~][x;x~]^T, fp32 RMW)", "bound": "hbm",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(args.workload),
                      "avg_launch_ms": launch_ms,

@@ -248,6 +248,174 @@ __global__ __launch_bounds__(256) void gemm_kernel(GemmArgs g) {
     }
 }
 
+// ---------------------------------------------------------------------------
+// Coded update of a thin batch in float32: C[j][i] += alpha * sum_k A[k][i] B[k][j] with a
+// contraction of a few dozen to a few hundred (the batch), which makes it a read-modify-write of
+// the coded matrix with the rate of v_mfma_f32_32x32x2_f32 next to it: at a batch of 64 the MFMAs
+// of the 18432 x 18432 update take 277 us at the chip's fp32 matrix peak (525 us measured for this
+// kernel's contraction alone, one or two wavefronts per SIMD), the 2.7 GB of the matrix about
+// 500 us at the rate a plain in-place pass reaches.
+//
+// One 128 (i) x 128 (j) tile per workgroup of four wavefronts (2 x 2, 64 x 64 each), two
+// workgroups per compute unit: while one contracts, the other's loads and stores are under way.
+// (One resident workgroup per compute unit that requests the next tile's operands and old values
+// during the contraction of the current one was slower, 805 us against 645 us: it is the second
+// wavefront on each SIMD that fills the gaps of the first.)
+// The operands are stored batch-major, which is k-major here: a k-row of a tile is 512 contiguous
+// bytes, and it goes to LDS as it is (direct-to-LDS loads, 64 k-rows per operand and stage).  The
+// MFMA takes one k per half wavefront and one row or column index per lane: the x~ side is the
+// column index (lane % 32) and a lane reads columns 2 (lane % 32) and the next with one
+// ds_read_b64 as its fragments a = 0, 1, the delta~ side is the row index, one ds_read_b32 per
+// fragment.  The matrix does not pass through LDS: a lane owns two adjacent columns of 32 rows;
+// their old values are requested (dwordx2, 256 contiguous bytes per half wavefront) before the
+// contraction and used after it, the new ones leave with dwordx2 stores.
+// ---------------------------------------------------------------------------
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+#if defined(__HIP_DEVICE_COMPILE__)
+#define CN_GEMM_ASM 1
+#else
+#define CN_GEMM_ASM 0
+#endif
+
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void update_thin_kernel(GemmArgs g) {
+  constexpr int KROWS = 64;                    // k-rows per stage
+  constexpr int OPB = KROWS * 512;             // bytes of one operand's stage
+  extern __shared__ uint4 lds[];
+  char *const lds_c = reinterpret_cast<char *>(lds);
+  const int nt = g.tiles_i * g.tiles_j;
+  const int per = (nt + 7) >> 3;
+  const int logical = (int)(blockIdx.x & 7) * per + (int)(blockIdx.x >> 3);
+  if (logical >= nt) return;
+  const int tj = logical % g.tiles_j, ti = logical / g.tiles_j;
+  const int i0 = ti * 128, j0 = tj * 128;
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wi = wave & 1, wj = wave >> 1;
+  const int l32 = lane & 31, h = lane >> 5;
+
+  // fill: load u of a wavefront brings k-rows 2 (4 u + wave) and the next of both operands, 16 bytes per lane
+  int ca = i0 + 4 * l32, cb = j0 + 4 * l32;
+  ca = ca < g.I ? ca : g.I - 4;
+  cb = cb < g.J ? cb : g.J - 4;
+  auto fill = [&](int k0) __attribute__((always_inline)) {
+#if CN_GEMM_ASM
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      int k = k0 + 2 * (4 * u + wave) + h;
+      k = k < g.K ? k : g.K - 1;
+      __builtin_amdgcn_global_load_lds(g.A + (long)k * g.lda + ca,
+                                       (__attribute__((address_space(3))) void *)(lds_c + (4 * u + wave) * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds(g.B + (long)k * g.ldb + cb,
+                                       (__attribute__((address_space(3))) void *)(lds_c + OPB + (4 * u + wave) * 1024), 16, 0, 0);
+    }
+#else
+    (void)k0;
+#endif
+  };
+  fill(0);
+#if CN_GEMM_ASM
+  asm volatile("" ::: "memory");            // the old values are requested after the fill: the first wait counts on it
+#endif
+  __builtin_amdgcn_sched_barrier(0);
+
+  // old values: element x = 4 q + e of fragment row b is row 64 wj + 32 b + 8 q + 4 h + e, columns 64 wi + 2 l32, + 1
+  const int ci = i0 + 64 * wi + 2 * l32, rj = j0 + 64 * wj + 4 * h;
+  const bool col_in = ci < g.I;
+  const float *const pold = g.C + (col_in ? ci : g.I - 2);
+  f32x2 old[2][16];
+#pragma unroll
+  for (int b = 0; b < 2; ++b)
+#pragma unroll
+    for (int x = 0; x < 16; ++x) {
+      int row = rj + 32 * b + 8 * (x >> 2) + (x & 3);
+      row = row < g.J ? row : g.J - 1;
+      old[b][x] = *reinterpret_cast<const f32x2 *>(pold + (long)row * g.ldc);
+    }
+
+  floatx16 acc[2][2];
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[a][b][e] = 0.f;
+
+  // LDS addresses of this lane's operands in k-row h of a pair
+  const unsigned addr_x = (unsigned)(h * 512 + (64 * wi + 2 * l32) * 4);
+  const unsigned addr_d = (unsigned)(OPB + h * 512 + (64 * wj + l32) * 4);
+  auto read_x = [&](unsigned at) __attribute__((always_inline)) {
+    f32x2 v = {0.f, 0.f};
+#if CN_GEMM_ASM
+    asm volatile("ds_read_b64 %0, %1" : "=v"(v) : "v"(at) : "memory");
+#endif
+    return v;
+  };
+  auto read_d = [&](unsigned at, int b) __attribute__((always_inline)) {
+    float v = 0.f;
+#if CN_GEMM_ASM
+    if (b == 0) asm volatile("ds_read_b32 %0, %1" : "=v"(v) : "v"(at) : "memory");
+    else asm volatile("ds_read_b32 %0, %1 offset:128" : "=v"(v) : "v"(at) : "memory");
+#endif
+    return v;
+  };
+
+  for (int k0 = 0; k0 < g.K; k0 += KROWS) {
+    // everything but the old values (issued after the first fill) has landed
+#if CN_GEMM_ASM
+    if (k0 == 0) asm volatile("s_waitcnt vmcnt(32)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#endif
+    __builtin_amdgcn_s_barrier();
+    const int left = g.K - k0;
+    const int steps = left >= KROWS ? KROWS / 2 : (left + 1) / 2;
+    f32x2 xv = read_x(addr_x);
+    float d0 = read_d(addr_d, 0), d1 = read_d(addr_d, 1);
+    for (int ks = 0; ks < steps; ++ks) {
+      const unsigned nxt = (unsigned)((ks + 1 < steps ? ks + 1 : ks) * 1024);
+      const f32x2 xn = read_x(addr_x + nxt);
+      const float e0 = read_d(addr_d + nxt, 0), e1 = read_d(addr_d + nxt, 1);
+#if CN_GEMM_ASM
+      asm volatile("s_waitcnt lgkmcnt(3)" : "+v"(xv), "+v"(d0), "+v"(d1)::"memory");
+#endif
+      const bool live = 2 * ks + h < left;        // a batch of odd size: its last k-row has no partner
+      const float a0 = live ? d0 : 0.f, a1 = live ? d1 : 0.f;
+      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, xv[0], acc[0][0], 0, 0, 0);
+      acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, xv[1], acc[1][0], 0, 0, 0);
+      acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, xv[0], acc[0][1], 0, 0, 0);
+      acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, xv[1], acc[1][1], 0, 0, 0);
+      xv = xn; d0 = e0; d1 = e1;
+    }
+#if CN_GEMM_ASM
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(xv), "+v"(d0), "+v"(d1)::"memory");
+#endif
+    if (k0 + KROWS < g.K) {
+      __builtin_amdgcn_s_barrier();              // every wavefront is done with the stage (its reads have returned)
+      fill(k0 + KROWS);
+    }
+  }
+
+  // The old values pass through an empty asm statement: the compiler waits for them once, here, and
+  // not before each of the 32 uses below (with a direct-to-LDS load behind it, it waits for everything
+  // outstanding every time: each store would wait for the one before it).
+#if CN_GEMM_ASM
+#pragma unroll
+  for (int b = 0; b < 2; ++b)
+#pragma unroll
+    for (int x = 0; x < 16; ++x) asm volatile("" : "+v"(old[b][x]));
+#endif
+  float *const pnew = g.C + ci;
+#pragma unroll
+  for (int b = 0; b < 2; ++b)
+#pragma unroll
+    for (int x = 0; x < 16; ++x) {
+      const int row = rj + 32 * b + 8 * (x >> 2) + (x & 3);
+      if (col_in && row < g.J)
+        *reinterpret_cast<f32x2 *>(pnew + (long)row * g.ldc) =
+            f32x2{fmaf(g.alpha, acc[0][b][x], old[b][x][0]), fmaf(g.alpha, acc[1][b][x], old[b][x][1])};
+    }
+}
+
 namespace {
 
 struct TileChoice { int fm, fn; double eff; };
@@ -255,10 +423,6 @@ const TileChoice kTiles[] = {{4, 2, 1.00}, {2, 2, 0.95}, {2, 1, 0.80}, {1, 2, 0.
 
 int pick_tile(const GemmArgs &g, bool accum) {
   // Cheapest estimated time: rounds of resident workgroups x tile area / tile efficiency.
-  // A short contraction into a large C (the update of a thin batch) is a read-modify-write of C:
-  // 128 x 128 tiles, two workgroups per CU, so that one's contraction hides the other's memory
-  // latency (18432 x 18432, batch 64: 733 us against 922 us with 256 x 128 and 813 us with 64 x 64).
-  if (accum && g.K <= 256 && g.I >= 1024 && g.J >= 1024) return 1;
   int best = 0;
   double best_cost = 1e300;
   for (int t = 0; t < 5; ++t) {
@@ -311,8 +475,24 @@ hipError_t launch_one(GemmArgs g, hipStream_t s) {
   return launch_reduce_partials(g.workspace, g.split_stride, g.splits, final_out, g.split_stride, s);
 }
 
+// The update of a thin batch: one 128 x 128 tile per workgroup, 64 KB of LDS (two per compute unit).
+hipError_t launch_update_thin(GemmArgs g, hipStream_t s) {
+  constexpr int lds = 2 * 64 * 512;
+  g.tiles_i = (g.I + 127) / 128;
+  g.tiles_j = (g.J + 127) / 128;
+  const int nt = g.tiles_i * g.tiles_j;
+  const int grid = ((nt + 7) / 8) * 8;
+  static LdsOnce attr_done;
+  hipError_t e = allow_lds(update_thin_kernel, lds, &attr_done);
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(update_thin_kernel, dim3(grid), dim3(256), lds, s, g);
+  return hipGetLastError();
+}
+
 template <bool AKC, bool BKC, bool ACCUM>
 hipError_t launch_layout(const GemmArgs &g, hipStream_t s) {
+  // A short contraction into a large C is a read-modify-write of C with the contraction next to it.
+  if (ACCUM && g.K <= 256 && g.I >= 1024 && g.J >= 1024 && (g.ldc & 1) == 0) return launch_update_thin(g, s);
   switch (pick_tile(g, ACCUM)) {
     case 0: return launch_one<4, 2, AKC, BKC, ACCUM>(g, s);
     case 1: return launch_one<2, 2, AKC, BKC, ACCUM>(g, s);

@@ -458,11 +458,13 @@ def test_ragged_shapes(n_out, n_in, m, n, r, b, dtype):
 
 
 # ------------------------------------------------------------- both bf16 update kernels
-@pytest.mark.parametrize("b", [64, 192, 255, 256, 320])
+@pytest.mark.parametrize("b", [64, 192, 255, 256, 257, 320, 512, 700])
 def test_bf16_update_kernels_on_either_side_of_their_batch_boundary(b):
-    """The coded update of the bf16 mode has two kernels: one tile per workgroup below a batch of
-    256 (padded: 192 and 255 contract over 192 and 256 columns), the persistent one from 256 on.
-    The same ragged layer through both, two steps each."""
+    """The coded update of the bf16 mode has two kernels: one tile per workgroup up to a batch of
+    192, the persistent one from 193 on (batches are padded to 64: 255 and 256 contract over 256
+    columns, four slabs of 64, the fewest that its pipeline takes; 257 and 320 over five).  The same
+    layer through both, two steps each: 1180 x 612 coded entries, ragged against the 128 x 128 tiles
+    of the persistent kernel in both directions."""
     say("update kernels, batch", b)
     n_out, n_in, m, n, r = 700, 452, 3, 7, 2
     pair = Pair(WL.layer_weights(n_out, n_in), WL.vandermonde_like(m, r), WL.vandermonde_like(n, r), "bf16", b,
@@ -473,6 +475,65 @@ def test_bf16_update_kernels_on_either_side_of_their_batch_boundary(b):
         assert rep["verdict"] == CORRECTED and rep["located"] == [1]
         _, rep, _ = pair.product(BWD, D, [WL.make_fault(BWD, 0, n, step)])
         assert rep["verdict"] == CORRECTED and rep["located"] == [n]
+        pair.update(0.02)
+        pair.check_weights()
+    pair.close()
+
+
+def test_bf16_persistent_update_with_several_tiles_per_workgroup():
+    """4120 x 4120 coded entries are 33 x 33 tiles of the persistent update kernel on 256 workgroups:
+    every workgroup walks over four or five tiles, tiles inside the matrix and tiles that stick out of
+    it in either direction following each other in both orders (the walk alternates its direction from
+    one update to the next).  Batches of 200 (four slabs per tile, the fewest) and 448 (seven)."""
+    for b in (200, 448):
+        say("persistent update over several tiles per workgroup, batch", b)
+        n = 3282
+        pair = Pair(WL.layer_weights(n, n), WL.vandermonde_like(8, 2), WL.vandermonde_like(8, 2), "bf16", b, 2e-2, 2e-2)
+        assert pair.gpu.coded_rows == pair.gpu.coded_cols == 4120
+        for step in range(3):
+            X, D = WL.normal((b, n), 51 + step), WL.normal((b, n), 61 + step)
+            pair.product(FWD, X)
+            pair.product(BWD, D)
+            pair.update(0.02)
+            pair.check_weights()
+        pair.close()
+
+
+# ------------------------------------------------------------- float32 update of a thin batch
+@pytest.mark.parametrize("b", [1, 7, 64, 65, 130, 256, 257])
+def test_f32_update_of_a_thin_batch(b):
+    """Float32 layers of more than 1024 coded rows and columns update through a kernel of their own
+    up to a batch of 256 (the matrix read and written straight from the accumulators, 64 batch rows
+    per LDS stage: 65 and 130 leave a ragged second or third stage, odd batches a k-row without a
+    partner); 257 goes through the general kernel.  1656 x 1820 coded entries: ragged against the
+    128 x 128 tiles in both directions.  Two steps each, with one corrected fault per product."""
+    say("f32 thin-batch update, batch", b)
+    n_out, n_in, m, n, r = 1100, 1300, 4, 5, 2
+    pair = Pair(WL.layer_weights(n_out, n_in), WL.vandermonde_like(m, r), WL.vandermonde_like(n, r), "f32", b,
+                1e-3, 2e-3)
+    assert pair.gpu.coded_rows == 1656 and pair.gpu.coded_cols == 1820
+    for step in range(2):
+        X, D = WL.normal((b, n_in), 71 + step), WL.normal((b, n_out), 81 + step)
+        _, rep, _ = pair.product(FWD, X, [WL.make_fault(FWD, 1, 0, step)])
+        assert rep["verdict"] == CORRECTED and rep["located"] == [1]
+        _, rep, _ = pair.product(BWD, D, [WL.make_fault(BWD, 0, n, step)])
+        assert rep["verdict"] == CORRECTED and rep["located"] == [n]
+        pair.update(0.02)
+        pair.check_weights()
+    pair.close()
+
+
+def test_f32_thin_batch_update_on_more_tiles_than_fit_the_chip():
+    """4120 x 4120 coded entries are 33 x 33 tiles of the thin-batch update kernel, more workgroups
+    than are resident at a time, edge tiles among them.  Batch 33."""
+    b, n = 33, 3282
+    say("f32 thin-batch update, 1089 tiles")
+    pair = Pair(WL.layer_weights(n, n), WL.vandermonde_like(8, 2), WL.vandermonde_like(8, 2), "f32", b, 1e-3, 2e-3)
+    assert pair.gpu.coded_rows == pair.gpu.coded_cols == 4120
+    for step in range(3):
+        X, D = WL.normal((b, n), 91 + step), WL.normal((b, n), 95 + step)
+        pair.product(FWD, X)
+        pair.product(BWD, D)
         pair.update(0.02)
         pair.check_weights()
     pair.close()
