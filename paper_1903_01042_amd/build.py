@@ -14,7 +14,6 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I" + os.path.join(ROOT, "include"), "-I" + CSRC, "-Wno-unused-command-line-argument"]
-FLAGS += os.environ.get("CODENET_CXXFLAGS", "").split()     # e.g. -DCODENET_ABLATION for the timing variants
 
 
 def _compile(src):

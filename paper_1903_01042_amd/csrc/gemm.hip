@@ -10,7 +10,8 @@
 //   update   : i = coded column, j = coded row, k = batch;          A = [x; x~], B = [delta; delta~]
 //              (both k strided), C = W~ accumulated in place.
 // All operands are float32 in memory and are multiplied with v_mfma_f32_32x32x2_f32
-// (the bf16 mode has kernels of its own, gemm_bf16.hip).
+// (the bf16 mode has kernels of its own, gemm_bf16.hip).  The update of a thin batch into a
+// large matrix has a kernel of its own as well (update_thin_kernel, below).
 //
 // Tiling: 256 threads = 4 wavefronts in a 2 x 2 arrangement, each owning
 // FM x FN MFMA tiles of 32 x 32, so a workgroup computes (64 FM) x (64 FN).

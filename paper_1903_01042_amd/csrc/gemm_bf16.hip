@@ -5,9 +5,8 @@
 // with zeros to a multiple of 64), fp32 accumulation, fp32 result.
 //
 // At the benchmark shape (5120 x 512 x 4096) the MFMA rate is not the bound: per CU the
-// 64 bytes per clock of the global -> LDS fill, the fragment reads and the MFMAs take
-// comparable times, and they only overlap when they run on different SIMDs (see
-// product_kernel).  Common to the kernels below:
+// global -> LDS fill of a slab takes longer than its MFMAs, and its rate is set by the bytes a
+// CU keeps in flight (see product_kernel and product_check_kernel).  Common to the kernels below:
 //  * slabs go global -> LDS directly (global_load_lds_dwordx4, no VGPR staging),
 //    NS stages deep; a stage is consumed NS-1 iterations after it was requested;
 //  * completion is tracked by hand: s_waitcnt vmcnt(n) leaves the younger
@@ -22,8 +21,9 @@
 //  * workgroup ids are dealt to the 8 XCDs round-robin by the hardware; the
 //    id -> tile maps give every XCD tiles that share operand panels, hence an L2.
 // Kernels: product_kernel (8 wavefronts with separate roles, the two products),
-// update2_kernel (update, one tile per workgroup), update3_kernel (update, persistent and
-// wave-specialised), shadow_kernel.
+// product_check_kernel (the forward product on tiles of whole codewords with the check's first
+// pass in its epilogue), update2_kernel (update, one tile per workgroup), update3_kernel (update,
+// persistent and wave-specialised), shadow_kernel.
 #include "codenet_internal.h"
 
 namespace codenet {
@@ -246,22 +246,24 @@ __device__ __forceinline__ int logical_workgroup(int total) {
 // 28 KB, five stages (four slabs in flight), one barrier per slab for all eight wavefronts.
 // Three quarters of the MFMA units work, on 216 instead of 160 tiles at 5120 x 512.
 //
-// Why: on wavefronts that share a SIMD the time of the loads, of the fragment reads and of the
-// MFMAs add up instead of overlapping; across SIMDs they overlap.  Measured at
-// 5120 x 512 x 4096 with ablation builds of a 128 x 128 kernel whose four MFMA wavefronts (one
-// per SIMD, 64 x 64 each) and four loader wavefronts are separate (shader clock 2.05 GHz under
-// this load): launch, barriers and the epilogue's 10.5 MB of stores 7.5 to 11 us; MFMAs alone
-// 10 to 14 us; fragment reads alone 6 us; fill alone 18 us, which is the 64 bytes per clock of
-// the CU's vector memory path, whether the weights come from HBM or, with every tile reading
-// one L2-resident panel, from L2.  Loads + MFMAs 37 us, reads + MFMAs 29 us, all three 42 us;
-// the same with the roles mixed in every wavefront (one or two per SIMD: 39 to 42 us), with
-// loaders that stage through registers (39 us), with a sixth wavefront that prefetches into
-// L2 (46 us), with fragments requested one, two or four k-steps ahead (42 to 45 us), and with
-// 160 x 64 tiles on all 256 CUs (41 us).  With the loaders on SIMDs 2 and 3 and the MFMA
-// wavefronts on SIMDs 0 and 1, loads + MFMAs take 38 us where the MFMAs alone take 36: they
-// overlap.  This kernel: 33.6 us (the 128 x 128 kernel with mixed roles: 41.3 us in the same
-// run; 192 x 64 tiles with three MFMA wavefronts of 64 x 64: 36 us; hipBLASLt's kernel for
-// this product, 160 x 64 x 128 tiles: 32 us).
+// Why this shape was chosen, and what is known since.  Measured at 5120 x 512 x 4096 with
+// ablation builds of a 128 x 128 kernel whose four MFMA wavefronts (one per SIMD, 64 x 64 each)
+// and four loader wavefronts are separate (shader clock 2.05 GHz under this load): launch,
+// barriers and the epilogue's 10.5 MB of stores 7.5 to 11 us; MFMAs alone 10 to 14 us; fragment
+// reads alone 6 us; fill alone 18 us, whether the weights come from HBM or, with every tile
+// reading one L2-resident panel, from L2.  Loads + MFMAs 37 us, reads + MFMAs 29 us, all three
+// 42 us; the same with the roles mixed in every wavefront (39 to 42 us), with loaders that stage
+// through registers (39 us), with a sixth wavefront that prefetches into L2 (46 us), with
+// fragments requested one, two or four k-steps ahead (42 to 45 us), and with 160 x 64 tiles on
+// all 256 CUs (41 us).  With the loaders on SIMDs 2 and 3 and the MFMA wavefronts on SIMDs 0 and
+// 1, loads + MFMAs take 38 us where the MFMAs alone take 36.  This kernel: 31 to 33 us (the
+// 128 x 128 kernel with mixed roles: 41.3 us in the same run; hipBLASLt's kernel for this
+// product, 160 x 64 x 128 tiles: 32 us).  Kernels that issue only one kind of instruction show
+// that the pipes themselves do not get in each other's way: one wavefront per SIMD keeps the
+// MFMA pipe 99.8 % busy, LDS reads run at up to 230 bytes per clock and CU, the direct-to-LDS
+// fill at up to 57 (50 from HBM), and all three at once at the same rates.  What the structure
+// above buys is bytes in flight: a slab period is the loaded latency of a slab's loads divided
+// by the slabs in flight, about 650 clocks with 4 x 28 KB here, whatever else the CU does.
 // ---------------------------------------------------------------------------
 // AT: the A operand is stored k-major, A[k][i] with i contiguous (the row-major bf16 copy of the
 // coded matrix seen from the backward product).  Its slab then sits in LDS as 64 rows (k) of
@@ -799,9 +801,12 @@ __global__ __launch_bounds__(256, (FM * FN <= 4 ? 2 : 1)) void update2_kernel(Up
 //    rate, not its bandwidth, is what this kernel runs into).  They only ever issue
 //    stores, so they never wait for memory.
 // Which piece follows which barrier is described at the roles' code below.
-// On gfx9 one counter covers loads and stores and stores return out of order:
-// a wavefront that mixes the two can only wait for everything, which is why
-// the roles are split this way.  Tiles are dealt so that every XCD owns one rectangle of a
+// One counter covers a wavefront's loads and stores, and with a direct-to-LDS load
+// outstanding the compiler waits for all of them wherever it places a wait of its own: a
+// wavefront that fills LDS, loads the matrix and stores it would drain everything at every
+// use of a loaded value, which is why the roles are split this way.  (A kernel in which eight
+// identical wavefronts read and write the matrix straight from the accumulators of 256 x 128
+// tiles, with hand-placed waits, ran no faster: 69 to 71 us.)  Tiles are dealt so that every XCD owns one rectangle of a
 // 2 x 4 partition of the tile grid and needs only the operand panels of that rectangle.
 // Streaming accesses stay ordinary cached ones: the matrix and its copy largely live in
 // the 256 MB memory-side cache from one step to the next, and non-temporal stores forfeit
