@@ -1088,10 +1088,13 @@ __global__ __launch_bounds__(512) void update3_kernel(Update2Args g) {
   const int v = tid - 384;                    // 0 .. 127
   int pti = 0, ptj = 0;                       // tile being stored (one behind the MMA role)
   // quarters 0, 1 (rows 0 .. 63 and 64 .. 127 of the tile): fp32 matrix and its bf16 copy;
-  // item k is row j = 8 k + v / 16, columns i = 8 (v % 16) .. + 7
-  // its two pieces are 2 (v % 16) and 2 (v % 16) + 1, at (piece ^ row % 32) = ((2 (v % 16)) ^ (v / 16)) ^ (8 k % 32) (^ 1)
+  // item k is row j = 8 k + v / 16, columns i = 4 (v % 16) .. + 3 and 64 + 4 (v % 16) .. + 3: sixteen lanes
+  // of one store instruction cover 256 contiguous bytes of a row (with eight adjacent columns per lane, as
+  // two stores, each instruction wrote every other 16-byte piece and every 64-byte write request left the
+  // L1 half full: 4.1 M write requests per launch for 2.46 M segments).
+  // The two pieces are v % 16 and 16 + v % 16, at (piece ^ row % 32) = ((v % 16) ^ (v / 16)) ^ (8 k % 32) (^ 16)
   const char *const rbase = lds_c + TILE + (v >> 4) * 512;
-  int rpiece = (((2 * (v & 15)) ^ (v >> 4)) << 4);
+  int rpiece = ((((v & 15)) ^ (v >> 4)) << 4);
   // qt: rows 64 qt .. 64 qt + 63 of the tile; hsel: -1 all of them, 0 / 1 one half (four of the eight row groups)
   auto quarter = [&](int qt, int hsel = -1) {
     // a tile that lies inside the matrix takes the branch-free path: all LDS reads of the
@@ -1101,9 +1104,9 @@ __global__ __launch_bounds__(512) void update3_kernel(Update2Args g) {
 #if CN_DEVICE_ASM
       asm volatile("" : "+v"(rpiece));
 #endif
-      // byte offset of item k's first piece from rbase; the second piece is that offset ^ 16
+      // byte offset of item k's first piece from rbase; the second piece is that offset ^ 256
       auto piece0 = [&](int k) -> int { return 4096 * k + (rpiece ^ (((8 * k) & 31) << 4)); };
-      const int j0 = ptj * 128 + (v >> 4), i = pti * 128 + (v & 15) * 8;
+      const int j0 = ptj * 128 + (v >> 4), i = pti * 128 + (v & 15) * 4;
       float *const pw = g.W + (long)j0 * g.ldw + i;
       __bf16 *const pb = g.Wb + (long)j0 * g.ldWb + i;
       if (interior) {
@@ -1115,16 +1118,16 @@ __global__ __launch_bounds__(512) void update3_kernel(Update2Args g) {
           for (int k4 = 0; k4 < 4; ++k4) {
             const int o = piece0(qt * 8 + half * 4 + k4);
             c[k4][0] = *reinterpret_cast<const f32x4 *>(rbase + o);
-            c[k4][1] = *reinterpret_cast<const f32x4 *>(rbase + (o ^ 16));
+            c[k4][1] = *reinterpret_cast<const f32x4 *>(rbase + (o ^ 256));
           }
 #pragma unroll
           for (int k4 = 0; k4 < 4; ++k4) {
             const int k = qt * 8 + half * 4 + k4;
             const f32x4 w0 = c[k4][0], w1 = c[k4][1];
-            const u32x4 pk = {pack2_bf16(w0[0], w0[1]), pack2_bf16(w0[2], w0[3]), pack2_bf16(w1[0], w1[1]), pack2_bf16(w1[2], w1[3])};
             *reinterpret_cast<f32x4 *>(pw + (long)(8 * k) * g.ldw) = w0;
-            *reinterpret_cast<f32x4 *>(pw + (long)(8 * k) * g.ldw + 4) = w1;
-            *reinterpret_cast<u32x4 *>(pb + (long)(8 * k) * g.ldWb) = pk;
+            *reinterpret_cast<f32x4 *>(pw + (long)(8 * k) * g.ldw + 64) = w1;
+            *reinterpret_cast<u32x2 *>(pb + (long)(8 * k) * g.ldWb) = u32x2{pack2_bf16(w0[0], w0[1]), pack2_bf16(w0[2], w0[3])};
+            *reinterpret_cast<u32x2 *>(pb + (long)(8 * k) * g.ldWb + 64) = u32x2{pack2_bf16(w1[0], w1[1]), pack2_bf16(w1[2], w1[3])};
           }
         }
         return;
@@ -1134,18 +1137,18 @@ __global__ __launch_bounds__(512) void update3_kernel(Update2Args g) {
         const int k = qt * 8 + k8;
         const int o = piece0(k);
         const f32x4 c0 = *reinterpret_cast<const f32x4 *>(rbase + o);
-        const f32x4 c1 = *reinterpret_cast<const f32x4 *>(rbase + (o ^ 16));
+        const f32x4 c1 = *reinterpret_cast<const f32x4 *>(rbase + (o ^ 256));
         float4 w0 = make_float4(c0[0], c0[1], c0[2], c0[3]), w1 = make_float4(c1[0], c1[1], c1[2], c1[3]);
         const int j = j0 + 8 * k;
-        const bool in0 = j < g.J && i < g.I, in1 = j < g.J && i + 4 < g.I;
+        const bool in0 = j < g.J && i < g.I, in1 = j < g.J && i + 64 < g.I;
         if (!in0) w0 = make_float4(0.f, 0.f, 0.f, 0.f);
         if (!in1) w1 = make_float4(0.f, 0.f, 0.f, 0.f);
         if (in0) *reinterpret_cast<float4 *>(pw + (long)(8 * k) * g.ldw) = w0;
-        if (in1) *reinterpret_cast<float4 *>(pw + (long)(8 * k) * g.ldw + 4) = w1;
-        uint4 pk;
-        pk.x = pack2_bf16(w0.x, w0.y); pk.y = pack2_bf16(w0.z, w0.w);
-        pk.z = pack2_bf16(w1.x, w1.y); pk.w = pack2_bf16(w1.z, w1.w);
-        if (j < g.J && i < g.ldWb) *reinterpret_cast<uint4 *>(pb + (long)(8 * k) * g.ldWb) = pk;
+        if (in1) *reinterpret_cast<float4 *>(pw + (long)(8 * k) * g.ldw + 64) = w1;
+        if (j < g.J && i < g.ldWb)
+          *reinterpret_cast<uint2 *>(pb + (long)(8 * k) * g.ldWb) = make_uint2(pack2_bf16(w0.x, w0.y), pack2_bf16(w0.z, w0.w));
+        if (j < g.J && i + 64 < g.ldWb)
+          *reinterpret_cast<uint2 *>(pb + (long)(8 * k) * g.ldWb + 64) = make_uint2(pack2_bf16(w1.x, w1.y), pack2_bf16(w1.z, w1.w));
       }
     }
   };
