@@ -429,7 +429,7 @@ namespace {
 struct TileChoice { int fm, fn; double eff; };
 const TileChoice kTiles[] = {{4, 2, 1.00}, {2, 2, 0.95}, {2, 1, 0.80}, {1, 2, 0.80}, {1, 1, 0.60}};
 
-int pick_tile(const GemmArgs &g, bool accum) {
+int pick_tile(const GemmArgs &g) {
   // Cheapest estimated time: rounds of resident workgroups x tile area / tile efficiency.
   int best = 0;
   double best_cost = 1e300;
@@ -501,7 +501,7 @@ template <bool AKC, bool BKC, bool ACCUM>
 hipError_t launch_layout(const GemmArgs &g, hipStream_t s) {
   // A short contraction into a large C is a read-modify-write of C with the contraction next to it.
   if (ACCUM && g.K <= 256 && g.I >= 1024 && g.J >= 1024 && (g.ldc & 1) == 0) return launch_update_thin(g, s);
-  switch (pick_tile(g, ACCUM)) {
+  switch (pick_tile(g)) {
     case 0: return launch_one<4, 2, AKC, BKC, ACCUM>(g, s);
     case 1: return launch_one<2, 2, AKC, BKC, ACCUM>(g, s);
     case 2: return launch_one<2, 1, AKC, BKC, ACCUM>(g, s);
