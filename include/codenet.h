@@ -142,6 +142,16 @@ int codenet_forward(codenet_layer *layer, const float *X_dev, int b, float *S_co
 int codenet_backward(codenet_layer *layer, const float *D_dev, int b, float *C_coded_dev, void *stream);
 
 /*
+ * The same two calls for an input whose rows are ldx (ldd) floats apart, ldx >= n_in (ldd >= n_out;
+ * else CODENET_E_SHAPE).  For inputs that are a part of wider rows: the decoded output of another
+ * layer's check left in place in its coded buffer (codenet_detect_decode with decoded_dev =
+ * coded_out_dev) is such an input when that layer's blocks carry no padding (its width a multiple of
+ * its block count and the block a multiple of 4 entries): X_dev = its coded buffer, ldx = its coded width.
+ */
+int codenet_forward_ld(codenet_layer *layer, const float *X_dev, long ldx, int b, float *S_coded_dev, void *stream);
+int codenet_backward_ld(codenet_layer *layer, const float *D_dev, long ldd, int b, float *C_coded_dev, void *stream);
+
+/*
  * Soft-error injection (Error Models 1 / 2; the experiment's sparse law is
  * mode SPARSE_ABS).  All faults of one call must have the same phase.
  * FWD: node (bi, bj), bi < m + r_rows, bj < n, adds noise to block-row bi of

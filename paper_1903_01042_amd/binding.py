@@ -22,6 +22,7 @@ EPI_NONE, EPI_RELU, EPI_MASK_POS, EPI_MUL = 0, 1, 2, 3
 E_NULL, E_SHAPE, E_BATCH, E_ORDER, E_CODE, E_FAULT, E_HIP, E_DTYPE, E_ALLOC = range(-1, -10, -1)
 
 EXPORTS = ["codenet_encode", "codenet_layer_geometry", "codenet_forward", "codenet_backward",
+           "codenet_forward_ld", "codenet_backward_ld",
            "codenet_inject", "codenet_inject_noalloc", "codenet_detect_decode", "codenet_detect_decode_act",
            "codenet_detect_decode_verified", "codenet_output_modified", "codenet_update", "codenet_regenerate", "codenet_export_coded",
            "codenet_export_weights", "codenet_destroy", "codenet_timestamp", "codenet_profile_stamps", "codenet_strerror"]
@@ -69,6 +70,8 @@ def load_library(path=LIB_PATH):
     lib.codenet_layer_geometry.argtypes = [vp, pi, pi, pi, pi]
     lib.codenet_forward.argtypes = [vp, vp, ci, vp, vp]
     lib.codenet_backward.argtypes = [vp, vp, ci, vp, vp]
+    lib.codenet_forward_ld.argtypes = [vp, vp, ctypes.c_long, ci, vp, vp]
+    lib.codenet_backward_ld.argtypes = [vp, vp, ctypes.c_long, ci, vp, vp]
     lib.codenet_inject.argtypes = [vp, ctypes.POINTER(Fault), ci, vp, ci, vp]
     lib.codenet_inject_noalloc.argtypes = [vp, ctypes.POINTER(Fault), ci, vp, ci, vp]
     lib.codenet_detect_decode.argtypes = [vp, ci, vp, ci, vp, vp, vp]
@@ -166,24 +169,42 @@ class CodedLayer:
         self.B_r, self.B_c, self.coded_rows, self.coded_cols = (x.value for x in g)
 
     # ---- the six calls -----------------------------------------------------------------
-    def forward(self, X, S_coded=None):
+    @staticmethod
+    def _rows(t, width, name):
+        """A float32 CUDA matrix [b][>= width] whose rows may be a part of wider rows (a column slice
+        of a contiguous tensor): returns (b, row pitch in elements)."""
         import torch
-        b = int(X.shape[0])
-        _dev_f32(X, (b, self.n_in), "X")
+        ok = (t.is_cuda and t.dtype == torch.float32 and t.dim() == 2 and int(t.shape[1]) == width
+              and t.stride(1) == 1 and t.stride(0) >= width)
+        if not ok:
+            raise ValueError("%s must be a float32 CUDA matrix with %d unit-stride columns, got %s %s strides %s"
+                             % (name, width, t.dtype, tuple(t.shape), tuple(t.stride())))
+        return int(t.shape[0]), int(t.stride(0))
+
+    def forward(self, X, S_coded=None):
+        """X: [b][n_in]; its rows may be a part of wider rows (a column slice of another tensor, e.g. of the
+        coded buffer in which another layer's check left its decoded output): codenet_forward_ld."""
+        import torch
+        b, ldx = self._rows(X, self.n_in, "X")
         if S_coded is None:
             S_coded = torch.empty((b, self.coded_rows), dtype=torch.float32, device=self.device)
         _dev_f32(S_coded, (b, self.coded_rows), "S_coded")
-        _check(load_library().codenet_forward(self._h, _ptr(X), b, _ptr(S_coded), _stream()), "codenet_forward")
+        if ldx == self.n_in:
+            _check(load_library().codenet_forward(self._h, _ptr(X), b, _ptr(S_coded), _stream()), "codenet_forward")
+        else:
+            _check(load_library().codenet_forward_ld(self._h, _ptr(X), ldx, b, _ptr(S_coded), _stream()), "codenet_forward_ld")
         return S_coded
 
     def backward(self, D, C_coded=None):
         import torch
-        b = int(D.shape[0])
-        _dev_f32(D, (b, self.n_out), "Delta")
+        b, ldd = self._rows(D, self.n_out, "Delta")
         if C_coded is None:
             C_coded = torch.empty((b, self.coded_cols), dtype=torch.float32, device=self.device)
         _dev_f32(C_coded, (b, self.coded_cols), "C_coded")
-        _check(load_library().codenet_backward(self._h, _ptr(D), b, _ptr(C_coded), _stream()), "codenet_backward")
+        if ldd == self.n_out:
+            _check(load_library().codenet_backward(self._h, _ptr(D), b, _ptr(C_coded), _stream()), "codenet_backward")
+        else:
+            _check(load_library().codenet_backward_ld(self._h, _ptr(D), ldd, b, _ptr(C_coded), _stream()), "codenet_backward_ld")
         return C_coded
 
     def inject(self, faults, coded_out=None, noalloc=False):

@@ -365,13 +365,18 @@ int bf16_product(codenet_layer *l, int phase, Gemm2Args g2, const float *out, in
 }  // namespace
 
 int codenet_forward(codenet_layer *l, const float *X_dev, int b, float *S_coded_dev, void *stream) {
+  return codenet_forward_ld(l, X_dev, l ? l->desc.n_in : 0, b, S_coded_dev, stream);
+}
+
+int codenet_forward_ld(codenet_layer *l, const float *X_dev, long ldx, int b, float *S_coded_dev, void *stream) {
   if (!l || !X_dev || !S_coded_dev) return CODENET_E_NULL;
   if (b < 1 || b > l->desc.max_batch) return CODENET_E_BATCH;
+  if (ldx < l->desc.n_in) return CODENET_E_SHAPE;
   hipStream_t s = (hipStream_t)stream;
   l->fwd_b = 0;
   if (l->bf16) {
     // coded input: batch-major bf16 x (product operand) and feature-major bf16 [x; x~] (update operand)
-    CN_HIP(launch_encode_vector_bf16(X_dev, l->code_c_dev, l->code_c, b, l->Xb, l->ldXb, l->XTb, l->ldT, s));
+    CN_HIP(launch_encode_vector_bf16(X_dev, ldx, l->code_c_dev, l->code_c, b, l->Xb, l->ldXb, l->XTb, l->ldT, s));
     Gemm2Args g2{};
     g2.A = l->Wb; g2.lda = l->ldWb;
     g2.B = l->Xb; g2.ldb = l->ldXb;
@@ -382,7 +387,7 @@ int codenet_forward(codenet_layer *l, const float *X_dev, int b, float *S_coded_
     l->fwd_b = b;
     return CODENET_OK;
   }
-  CN_HIP(launch_encode_vector(X_dev, l->Xt, l->code_c_dev, l->code_c, b, nullptr, 0, nullptr, 0, s));
+  CN_HIP(launch_encode_vector(X_dev, ldx, l->Xt, l->code_c_dev, l->code_c, b, nullptr, 0, nullptr, 0, s));
   GemmArgs g{};
   g.A = l->Wt; g.lda = l->Nc;                 // A[i][k] = W~[i][k], k over the base columns
   g.B = l->Xt; g.ldb = l->Nc;                 // B[j][k] = x[j][k]
@@ -398,12 +403,17 @@ int codenet_forward(codenet_layer *l, const float *X_dev, int b, float *S_coded_
 }
 
 int codenet_backward(codenet_layer *l, const float *D_dev, int b, float *C_coded_dev, void *stream) {
+  return codenet_backward_ld(l, D_dev, l ? l->desc.n_out : 0, b, C_coded_dev, stream);
+}
+
+int codenet_backward_ld(codenet_layer *l, const float *D_dev, long ldd, int b, float *C_coded_dev, void *stream) {
   if (!l || !D_dev || !C_coded_dev) return CODENET_E_NULL;
   if (b < 1 || b > l->desc.max_batch) return CODENET_E_BATCH;
+  if (ldd < l->desc.n_out) return CODENET_E_SHAPE;
   hipStream_t s = (hipStream_t)stream;
   l->bwd_b = 0;
   if (l->bf16) {
-    CN_HIP(launch_encode_vector_bf16(D_dev, l->code_r_dev, l->code_r, b, l->Db, l->ldDb, l->DTb, l->ldT, s));
+    CN_HIP(launch_encode_vector_bf16(D_dev, ldd, l->code_r_dev, l->code_r, b, l->Db, l->ldDb, l->DTb, l->ldT, s));
     Gemm2Args g2{};
     // A[i][k] = W~[k][i]: the row-major copy, read k-major (transposing LDS reads in the kernel)
     g2.A = l->Wb; g2.lda = l->ldWb; g2.a_k_major = 1;
@@ -415,7 +425,7 @@ int codenet_backward(codenet_layer *l, const float *D_dev, int b, float *C_coded
     l->bwd_b = b;
     return CODENET_OK;
   }
-  CN_HIP(launch_encode_vector(D_dev, l->Dt, l->code_r_dev, l->code_r, b, nullptr, 0, nullptr, 0, s));
+  CN_HIP(launch_encode_vector(D_dev, ldd, l->Dt, l->code_r_dev, l->code_r, b, nullptr, 0, nullptr, 0, s));
   GemmArgs g{};
   g.A = l->Wt; g.lda = l->Nc;                 // A[i][k] = W~[k][i], k over the base rows
   g.B = l->Dt; g.ldb = l->Mr;                 // B[j][k] = delta[j][k]

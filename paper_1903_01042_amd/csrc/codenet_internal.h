@@ -132,9 +132,9 @@ hipError_t launch_encode_matrix(const float *W, float *Wt, const DevCode *code_r
                                 int Mr, int Nc, int n_out, int n_in, hipStream_t s);
 // Vb (optional): bf16 batch-major copy of the systematic part, pitch ldVb.
 // zero (optional): zero_count4 float4 of a buffer to clear in the same pass.
-hipError_t launch_encode_vector(const float *V, float *Vt, const DevCode *code_dev, const DevCode &code_host,
+hipError_t launch_encode_vector(const float *V, long ldv, float *Vt, const DevCode *code_dev, const DevCode &code_host,
                                 int b, void *Vb, long ldVb, float *zero, long zero_count4, hipStream_t s);
-hipError_t launch_encode_vector_bf16(const float *V, const DevCode *code_dev, const DevCode &code_host,
+hipError_t launch_encode_vector_bf16(const float *V, long ldv, const DevCode *code_dev, const DevCode &code_host,
                                      int b, void *Vb, long ldVb, void *VTb, long ldVT, hipStream_t s);
 // pass 1 of a check.  second_evaluation: the same records computed by other workgroups (another
 // compute unit for every record); syn may then be null (the syndromes are not written again)

@@ -79,7 +79,7 @@ static inline Geometry geometry_of(const DevCode &c) { return Geometry{c.B, c.B0
 // the update read.  One thread per (batch row, 4 positions inside a block).
 // ---------------------------------------------------------------------------
 template <bool ALIGNED>
-__global__ __launch_bounds__(256) void encode_vector_kernel(const float *__restrict__ V, float *__restrict__ Vt,
+__global__ __launch_bounds__(256) void encode_vector_kernel(const float *__restrict__ V, long ldv, float *__restrict__ Vt,
                                                             const DevCode *__restrict__ code, int b,
                                                             __bf16 *__restrict__ Vb, long ldVb,
                                                             float4 *__restrict__ zero, long zero_count4,
@@ -92,7 +92,7 @@ __global__ __launch_bounds__(256) void encode_vector_kernel(const float *__restr
     for (long z = idx; z < zero_count4; z += (long)gridDim.x * 256) zero[z] = make_float4(0.f, 0.f, 0.f, 0.f);
   if (idx >= (long)b * quads) return;
   const int beta = (int)(idx / quads), rho = (int)(idx % quads) * 4;
-  const float *src = V + (long)beta * N;
+  const float *src = V + (long)beta * ldv;
   float *dst = Vt + (long)beta * (a + r) * B;
   // Entries rho .. rho + 3 of block i.  Unconditional loads (the address moves to the start of the
   // row where the entry is padding, and the value is dropped): a guarded load would wait for its
@@ -158,16 +158,16 @@ __global__ __launch_bounds__(256) void encode_vector_kernel(const float *__restr
 }
 
 
-hipError_t launch_encode_vector(const float *V, float *Vt, const DevCode *code_dev, const DevCode &code_host,
+hipError_t launch_encode_vector(const float *V, long ldv, float *Vt, const DevCode *code_dev, const DevCode &code_host,
                                 int b, void *Vb, long ldVb, float *zero, long zero_count4, hipStream_t s) {
   const long total = (long)b * (code_host.B >> 2);
   dim3 grid((unsigned)((total + 255) / 256), (unsigned)(code_host.a + 1));
-  const int aligned = (code_host.N % 4 == 0) && (code_host.B0 % 4 == 0) && ((reinterpret_cast<uintptr_t>(V) & 15) == 0);
+  const int aligned = (code_host.N % 4 == 0) && (code_host.B0 % 4 == 0) && (ldv % 4 == 0) && ((reinterpret_cast<uintptr_t>(V) & 15) == 0);
   if (aligned)
-    hipLaunchKernelGGL(encode_vector_kernel<true>, grid, dim3(256), 0, s, V, Vt, code_dev, b, (__bf16 *)Vb, ldVb,
+    hipLaunchKernelGGL(encode_vector_kernel<true>, grid, dim3(256), 0, s, V, ldv, Vt, code_dev, b, (__bf16 *)Vb, ldVb,
                        reinterpret_cast<float4 *>(zero), zero_count4, geometry_of(code_host));
   else
-    hipLaunchKernelGGL(encode_vector_kernel<false>, grid, dim3(256), 0, s, V, Vt, code_dev, b, (__bf16 *)Vb, ldVb,
+    hipLaunchKernelGGL(encode_vector_kernel<false>, grid, dim3(256), 0, s, V, ldv, Vt, code_dev, b, (__bf16 *)Vb, ldVb,
                        reinterpret_cast<float4 *>(zero), zero_count4, geometry_of(code_host));
   return hipGetLastError();
 }
@@ -182,7 +182,7 @@ hipError_t launch_encode_vector(const float *V, float *Vt, const DevCode *code_d
 // batch columns b .. Rpad-1 of the latter are written as zeros.  Jobs 0 .. a-1 copy
 // a systematic block, job a + k computes parity block k.
 template <bool ALIGNED, int TP>
-__global__ __launch_bounds__(256) void encode_vector_bf16_kernel(const float *__restrict__ V,
+__global__ __launch_bounds__(256) void encode_vector_bf16_kernel(const float *__restrict__ V, long ldv,
                                                                  const DevCode *__restrict__ code, int b,
                                                                  __bf16 *__restrict__ Vb, long ldVb,
                                                                  __bf16 *__restrict__ VTb, long ldVT, int Rpad,
@@ -203,7 +203,7 @@ __global__ __launch_bounds__(256) void encode_vector_bf16_kernel(const float *__
   // ALIGNED: N and B0 multiples of 4, V 16-byte aligned -- whole quads are real or padding.
   auto fetch = [&](int beta, int i, float (&v)[4]) {
     const bool row_ok = beta < b && rho < B;
-    const float *src = V + (long)(beta < b ? beta : b - 1) * N;
+    const float *src = V + (long)(beta < b ? beta : b - 1) * ldv;
     if constexpr (ALIGNED) {
       const int g = i * B0 + rho;
       const bool ok = row_ok && rho < B0 && g < N;
@@ -275,17 +275,17 @@ __global__ __launch_bounds__(256) void encode_vector_bf16_kernel(const float *__
   }
 }
 
-hipError_t launch_encode_vector_bf16(const float *V, const DevCode *code_dev, const DevCode &code_host,
+hipError_t launch_encode_vector_bf16(const float *V, long ldv, const DevCode *code_dev, const DevCode &code_host,
                                      int b, void *Vb, long ldVb, void *VTb, long ldVT, hipStream_t s) {
   const int Rpad = (b + 63) & ~63;
-  const int aligned = (code_host.N % 4 == 0) && (code_host.B0 % 4 == 0) && ((reinterpret_cast<uintptr_t>(V) & 15) == 0);
+  const int aligned = (code_host.N % 4 == 0) && (code_host.B0 % 4 == 0) && (ldv % 4 == 0) && ((reinterpret_cast<uintptr_t>(V) & 15) == 0);
   // 64 x 32 tiles (see the kernel's comment for the other widths measured)
   const dim3 grid((unsigned)((code_host.B + 31) / 32), (unsigned)(Rpad / 64), (unsigned)(code_host.a + code_host.r));
   if (aligned)
-    hipLaunchKernelGGL((encode_vector_bf16_kernel<true, 32>), grid, dim3(256), 0, s, V, code_dev, b, (__bf16 *)Vb, ldVb,
+    hipLaunchKernelGGL((encode_vector_bf16_kernel<true, 32>), grid, dim3(256), 0, s, V, ldv, code_dev, b, (__bf16 *)Vb, ldVb,
                        (__bf16 *)VTb, ldVT, Rpad, geometry_of(code_host));
   else
-    hipLaunchKernelGGL((encode_vector_bf16_kernel<false, 32>), grid, dim3(256), 0, s, V, code_dev, b, (__bf16 *)Vb, ldVb,
+    hipLaunchKernelGGL((encode_vector_bf16_kernel<false, 32>), grid, dim3(256), 0, s, V, ldv, code_dev, b, (__bf16 *)Vb, ldVb,
                        (__bf16 *)VTb, ldVT, Rpad, geometry_of(code_host));
   return hipGetLastError();
 }

@@ -1020,6 +1020,54 @@ def test_checks_taken_in_the_product_epilogue():
         pair.close()
 
 
+def test_a_decoded_output_left_in_place_feeds_the_next_layer():
+    """Two layers in a row, both arithmetic modes: the first layer's check leaves its decoded output in
+    the coded buffer (with the activation applied where it is) and the second layer's forward product
+    takes it from there as an input with a row pitch (codenet_forward_ld); on the way back the second
+    layer's decoded backward output stays in place and feeds the first layer's backward product
+    (codenet_backward_ld).  Bit for bit the results of the same chain through dense decoded copies."""
+    import torch
+    from paper_1903_01042_amd import binding as B
+    for dtype, taus in ((B.F32, (1e-3, 2e-3)), (B.BF16_F32ACC, (2e-2, 2e-2))):
+        say("in-place chain, dtype", dtype)
+        n0, n1, n2, b = 320, 512, 256, 96
+        dev = torch.device("cuda")
+        P4, P8 = WL.vandermonde_like(4, 2), WL.vandermonde_like(8, 2)
+        l1 = B.CodedLayer(torch.from_numpy(WL.layer_weights(n1, n0)).to(dev), P8, P4, dtype=dtype, max_batch=b,
+                          tau_detect=taus[0], tau_resid=taus[1])
+        l2 = B.CodedLayer(torch.from_numpy(WL.layer_weights(n2, n1, 1)).to(dev), P4, P8, dtype=dtype, max_batch=b,
+                          tau_detect=taus[0], tau_resid=taus[1])
+        assert l1.B_r * 8 == n1 and l2.B_c * 8 == n1          # no padding inside the blocks of the shared width
+        X = torch.from_numpy(WL.normal((b, n0), 5)).to(dev)
+        D = torch.from_numpy(WL.normal((b, n2), 6)).to(dev)
+        rep = l1.new_report()
+        # dense chain
+        s1 = l1.forward(X)
+        l1.inject([WL.make_fault(FWD, 2, 1, 0)], s1)
+        x1 = l1.detect_decode(FWD, s1, report=rep, epilogue=B.EPI_RELU)
+        s2 = l2.forward(x1)
+        c2 = l2.backward(D)
+        l2.inject([WL.make_fault(BWD, 1, 3, 0)], c2)
+        d1 = l2.detect_decode(BWD, c2, report=rep)
+        c1 = l1.backward(d1)
+        # the same chain in place
+        t1 = l1.forward(X)
+        l1.inject([WL.make_fault(FWD, 2, 1, 0)], t1)
+        l1.detect_decode(FWD, t1, decoded=t1, report=rep, epilogue=B.EPI_RELU)
+        assert l1.read_report(rep)["verdict"] == CORRECTED
+        t2 = l2.forward(t1[:, :n1])
+        e2 = l2.backward(D)
+        l2.inject([WL.make_fault(BWD, 1, 3, 0)], e2)
+        l2.detect_decode(BWD, e2, decoded=e2, report=rep)
+        assert l2.read_report(rep)["verdict"] == CORRECTED
+        e1 = l1.backward(e2[:, :n1])
+        assert torch.equal(t1[:, :n1], x1) and torch.equal(t2, s2) and torch.equal(e2[:, :n1], d1) and torch.equal(e1, c1)
+        with pytest.raises(ValueError):
+            l2.forward(t1[:, 1:n1 + 1].t())
+        l1.destroy()
+        l2.destroy()
+
+
 # ------------------------------------------------------------------ API error paths
 def test_api_errors_on_the_gpu():
     import torch
